@@ -1,0 +1,275 @@
+"""Pins for the CPU oracle: everything here runs without a GPU and compares the
+oracle with things other than itself - exact rational arithmetic, hand-worked
+closed forms (tests/golden), numpy library routines on special cases, and
+invariants of the definitions in section 3.7 / 4.2 of the paper."""
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+import oracle
+from paper_2505_00232_amd import synth
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden", "handworked_cases.txt")
+
+
+def _golden():
+    cases, cur = {}, None
+    for line in open(GOLDEN):
+        line = line.strip()
+        if not line or line.startswith("#"):
+            continue
+        key, val = line.split(":", 1)
+        if key == "case":
+            cur = cases.setdefault(val.strip(), {})
+        else:
+            cur[key.strip()] = val.split()
+    return cases
+
+
+def _frac_f16(v: np.float16) -> Fraction:
+    return Fraction(float(v))  # float16 -> python float is exact
+
+
+# ---------------------------------------------------------------- binary16
+def test_f16_decode_all_bit_patterns():
+    bits = np.arange(65536, dtype=np.uint16)
+    ref = bits.view(np.float16).astype(np.float64)
+    got = np.array([oracle.f16_bits_to_f64(int(b)) for b in bits])
+    nan = np.isnan(ref)
+    assert np.array_equal(np.isnan(got), nan)
+    assert np.array_equal(got[~nan], ref[~nan])
+    assert np.array_equal(np.signbit(got[~nan]), np.signbit(ref[~nan]))
+
+
+# ---------------------------------------------------------------- golden, hand-worked
+def test_golden_activation_quantization():
+    g = _golden()
+    for name in ("actquant_ties", "actquant_pow2", "actquant_zero_row", "actquant_unit"):
+        c = g[name]
+        x = np.array([[float(v) for v in c["x"]]], dtype=np.float16)
+        xq, sx = oracle.quantize_activations(x)
+        assert xq[0].tolist() == [int(v) for v in c["xq"]], name
+        want = Fraction(c["sx"][0])
+        got = Fraction(float(sx[0]))
+        ulp = Fraction(float(np.spacing(sx[0]))) if sx[0] != 0 else Fraction(0)
+        assert abs(got - want) <= ulp / 2, name  # correctly rounded fp32 quotient
+
+
+def test_golden_fc_per_channel():
+    c = _golden()["fc_per_channel"]
+    x = np.array([[float(v) for v in c["x"]]], dtype=np.float16)
+    wq = np.array([[int(v) for v in c["w0"]], [int(v) for v in c["w1"]]], dtype=np.int8)
+    s = np.array([float(v) for v in c["s"]], dtype=np.float32)
+    y = oracle.fc_weight_only(x, wq, s)
+    assert y[0].tolist() == [float(v) for v in c["y"]]
+
+
+def test_golden_fc_group32():
+    c = _golden()["fc_group32"]
+    xv = [float(v) for v in c["x_group_values"]]
+    x = np.repeat(np.array(xv, dtype=np.float16), 32)[None, :]
+    wq = np.stack([np.repeat(np.array([int(v) for v in c[k]], dtype=np.int8), 32)
+                   for k in ("w0_group_values", "w1_group_values")])
+    s = np.array([[float(v) for v in c["s0"]], [float(v) for v in c["s1"]]], dtype=np.float16)
+    y = oracle.fc_weight_only(x, wq, s, group_size=32)
+    assert y[0].tolist() == [float(v) for v in c["y"]]
+
+
+# ---------------------------------------------------------------- exact rational brute force
+def _brute_fp(x, wq, s, group):
+    M, K = x.shape
+    N = wq.shape[0]
+    out = [[Fraction(0)] * N for _ in range(M)]
+    for m in range(M):
+        for n in range(N):
+            acc = Fraction(0)
+            for k in range(K):
+                sc = Fraction(float(s[n])) if group == 0 else Fraction(float(s[n, k // group]))
+                acc += _frac_f16(x[m, k]) * sc * int(wq[n, k])
+            out[m][n] = acc
+    return out
+
+
+@pytest.mark.parametrize("fmt,M,N,K", [("w8c", 1, 1, 32), ("w8c", 3, 17, 96), ("w8c", 4, 5, 64),
+                                       ("w4g32", 1, 1, 32), ("w4g32", 2, 17, 96), ("w4g32", 4, 7, 64)])
+def test_weight_only_matches_exact_rationals(fmt, M, N, K):
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(77, M, N, fc)
+    # include the extreme codes
+    wq.flat[0] = -128 if fmt == "w8c" else -8
+    wq.flat[-1] = 127 if fmt == "w8c" else 7
+    x = synth.activations(77, M, N, M, K)
+    group = 0 if fmt == "w8c" else 32
+    y = oracle.fc_weight_only(x, wq, s, group)
+    exact = _brute_fp(x, wq, s, group)
+    scale = max(abs(float(v)) for row in exact for v in row)
+    for m in range(M):
+        for n in range(N):
+            assert abs(Fraction(float(y[m, n])) - exact[m][n]) <= Fraction(scale) * Fraction(1, 10**13)
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 32), (3, 9, 96), (4, 17, 64)])
+def test_int_path_matches_exact_rationals(M, N, K):
+    fc = synth.FC("t", K, N, "w8c")
+    wq, sw = synth.weights(78, M, N, fc)
+    wq.flat[0] = -128
+    x = synth.activations(78, M, N, M, K)
+    xq, sx, acc, y = oracle.fc_int8_act(x, wq, sw)
+    for m in range(M):
+        for n in range(N):
+            a = sum(int(xq[m, k]) * int(wq[n, k]) for k in range(K))
+            assert int(acc[m, n]) == a
+            exact = Fraction(a) * Fraction(float(sx[m])) * Fraction(float(sw[n]))
+            assert abs(Fraction(float(y[m, n])) - exact) <= abs(exact) * Fraction(1, 10**15)
+
+
+# ---------------------------------------------------------------- library special cases
+def test_unit_scales_reduce_to_numpy_matmul():
+    rng = np.random.default_rng(5)
+    M, N, K = 5, 40, 160
+    x = rng.standard_normal((M, K)).astype(np.float16)
+    wq = rng.integers(-8, 8, size=(N, K), dtype=np.int8)
+    ref = x.astype(np.float64) @ wq.astype(np.float64).T
+    y8 = oracle.fc_weight_only(x, wq, np.ones(N, np.float32))
+    y4 = oracle.fc_weight_only(x, wq, np.ones((N, K // 32), np.float16), 32)
+    np.testing.assert_allclose(y8, ref, rtol=0, atol=1e-12)
+    np.testing.assert_allclose(y4, ref, rtol=0, atol=1e-12)
+
+
+def test_int_contraction_is_numpy_int64_matmul():
+    rng = np.random.default_rng(6)
+    xq = rng.integers(-127, 128, size=(7, 256), dtype=np.int8)
+    wq = rng.integers(-128, 128, size=(33, 256), dtype=np.int8)
+    assert np.array_equal(oracle.int_contract(xq, wq), xq.astype(np.int64) @ wq.astype(np.int64).T)
+
+
+# ---------------------------------------------------------------- closed forms and structure
+def test_identity_weights_return_x_exactly():
+    K = 64
+    x = synth.activations(79, 0, 0, 3, K)
+    eye = np.eye(K, dtype=np.int8)
+    y8 = oracle.fc_weight_only(x, eye, np.ones(K, np.float32))
+    y4 = oracle.fc_weight_only(x, eye, np.ones((K, K // 32), np.float16), 32)
+    assert np.array_equal(y8, x.astype(np.float64))
+    assert np.array_equal(y4, x.astype(np.float64))
+    xq, sx, acc, y = oracle.fc_int8_act(x, eye, np.ones(K, np.float32))
+    assert np.array_equal(acc, xq.astype(np.int64))
+    assert np.all(np.abs(y - x.astype(np.float64)) <= sx[:, None].astype(np.float64) / 2 * (1 + 2.0**-22))
+
+
+def test_one_hot_rows_pick_permuted_inputs():
+    rng = np.random.default_rng(7)
+    N, K = 48, 96
+    perm = rng.integers(0, K, size=N)
+    q = rng.integers(-8, 8, size=N)
+    q[q == 0] = 3
+    wq = np.zeros((N, K), np.int8)
+    wq[np.arange(N), perm] = q
+    x = synth.activations(80, 0, 0, 2, K)
+    s8 = (2.0 ** rng.integers(-6, 3, size=N)).astype(np.float32)
+    y = oracle.fc_weight_only(x, wq, s8)
+    want = x.astype(np.float64)[:, perm] * (s8.astype(np.float64) * q)[None, :]
+    assert np.array_equal(y, want)
+    s4 = (2.0 ** rng.integers(-6, 3, size=(N, K // 32))).astype(np.float16)
+    y = oracle.fc_weight_only(x, wq, s4, 32)
+    want = x.astype(np.float64)[:, perm] * (s4.astype(np.float64)[np.arange(N), perm // 32] * q)[None, :]
+    assert np.array_equal(y, want)
+
+
+def test_constant_and_ramp_closed_forms():
+    N, K = 6, 128
+    x = np.ones((1, K), np.float16)
+    y = oracle.fc_weight_only(x, np.full((N, K), 5, np.int8), np.full(N, 0.25, np.float32))
+    assert np.array_equal(y, np.full((1, N), K * 5 * 0.25))
+    n, k = np.meshgrid(np.arange(N), np.arange(K), indexing="ij")
+    ramp = (((n + k) % 15) - 7).astype(np.int8)
+    y = oracle.fc_weight_only(x, ramp, np.ones((N, K // 32), np.float16), 32)
+    assert y[0].tolist() == [float(sum(((i + j) % 15) - 7 for j in range(K))) for i in range(N)]
+
+
+def test_scaling_and_permutation_invariances():
+    fc = synth.FC("t", 128, 20, "w4g32")
+    wq, s = synth.weights(81, 0, 0, fc)
+    x = synth.activations(81, 0, 0, 3, fc.K)
+    y = oracle.fc_weight_only(x, wq, s, 32)
+    y2 = oracle.fc_weight_only(x, wq, (s.astype(np.float32) * 2).astype(np.float16), 32)
+    assert np.array_equal(y2, 2 * y)
+    # permuting whole groups of K jointly in x, Wq and the scales changes only the summation order
+    gp = np.random.default_rng(8).permutation(fc.K // 32)
+    kp = (gp[:, None] * 32 + np.arange(32)[None, :]).ravel()
+    y3 = oracle.fc_weight_only(x[:, kp], wq[:, kp], s[:, gp], 32)
+    np.testing.assert_allclose(y3, y, rtol=1e-12, atol=1e-12)
+    # integer accumulators are exactly invariant under any joint K permutation
+    fc8 = synth.FC("t", 128, 20, "w8c")
+    w8, _ = synth.weights(82, 0, 0, fc8)
+    xq, _ = oracle.quantize_activations(x)
+    p = np.random.default_rng(9).permutation(fc.K)
+    assert np.array_equal(oracle.int_contract(xq[:, p], w8[:, p]), oracle.int_contract(xq, w8))
+    # rows of a batch are independent
+    y_rows = np.concatenate([oracle.fc_weight_only(x[i:i + 1], wq, s, 32) for i in range(3)])
+    assert np.array_equal(y_rows, y)
+
+
+# ---------------------------------------------------------------- activation quantization invariants
+def test_activation_quantization_invariants():
+    x = synth.activations(83, 0, 0, 16, 512)
+    x[3] = 0
+    x[4, :] = np.float16(65504.0) * np.sign(x[4].astype(np.float32)).astype(np.float16)  # largest finite
+    x[5] *= np.float16(2.0**-10)  # small magnitudes
+    xq, sx = oracle.quantize_activations(x)
+    xf = x.astype(np.float64)
+    a = np.abs(xf).max(axis=1)
+    # scale is the correctly rounded fp32 quotient a/127
+    for m in range(x.shape[0]):
+        want = Fraction(float(a[m])) / 127
+        ulp = Fraction(float(np.spacing(sx[m]))) if sx[m] else Fraction(0)
+        assert abs(Fraction(float(sx[m])) - want) <= ulp / 2
+    # round trip within half a step (plus the fp32 rounding of 127/a and of the product)
+    assert np.all(np.abs(xf - sx[:, None].astype(np.float64) * xq) <= sx[:, None].astype(np.float64) / 2 * (1 + 2.0**-20))
+    # the largest element of a non-zero row maps to +-127, nothing exceeds it
+    assert np.all(np.abs(xq).max(axis=1)[a > 0] == 127) and np.abs(xq.astype(np.int32)).max() <= 127
+    assert np.all(xq[3] == 0) and sx[3] == 0
+    # odd symmetry, and exact invariance of the codes under power-of-two scaling
+    xq_neg, sx_neg = oracle.quantize_activations(-x)
+    assert np.array_equal(xq_neg, -xq) and np.array_equal(sx_neg, sx)
+    keep = [0, 1, 2, 6, 7]
+    xq_h, sx_h = oracle.quantize_activations((x[keep].astype(np.float32) * 0.25).astype(np.float16))
+    assert np.array_equal(xq_h, xq[keep]) and np.array_equal(sx_h, sx[keep] * np.float32(0.25))
+    # independent brute force of the rounding rule with exact rationals:
+    # code = nearest integer to fl32(x * fl32(127/a)), ties to even
+    for m in (0, 5):
+        inv = np.float32(127.0) / np.float32(a[m])
+        for k in range(0, 512, 7):
+            p = np.float32(x[m, k]) * inv
+            fr = Fraction(float(p))
+            lo = fr.numerator // fr.denominator
+            d = fr - lo
+            r = lo + (1 if d > Fraction(1, 2) or (d == Fraction(1, 2) and lo % 2 == 1) else 0)
+            assert int(xq[m, k]) == max(-127, min(127, r))
+
+
+def test_weight_quantizer_round_trip_half_step():
+    """Helper quantizer used only by tests: |w - s*q| <= s/2 (the round-trip
+    invariant of symmetric quantization), checked through the oracle's dequantizer."""
+    rng = np.random.default_rng(10)
+    w = rng.standard_normal((12, 64))
+    s = (np.abs(w).max(axis=1) / 127).astype(np.float32)
+    q = np.clip(np.rint(w / s[:, None].astype(np.float64)), -127, 127).astype(np.int8)
+    what = oracle.dequantize(q, s)
+    assert np.all(np.abs(w - what) <= s[:, None].astype(np.float64) / 2 * (1 + 1e-6))
+    sg = (np.abs(w.reshape(12, 2, 32)).max(axis=2) / 7).astype(np.float16)
+    sg = np.maximum(sg, np.float16(1e-4))
+    qg = np.clip(np.rint(w.reshape(12, 2, 32) / sg[:, :, None].astype(np.float64)), -8, 7).astype(np.int8).reshape(12, 64)
+    whatg = oracle.dequantize(qg, sg, 32)
+    err = np.abs(w - whatg).reshape(12, 2, 32)
+    inside = np.abs(w.reshape(12, 2, 32) / sg[:, :, None].astype(np.float64)) <= 7
+    assert np.all(err[inside] <= (sg[:, :, None].astype(np.float64) / 2 * (1 + 1e-6) * np.ones_like(err))[inside])
+
+
+def test_error_metric():
+    y = np.array([[1.0, -2.0, 0.0, 1e-9]])
+    assert oracle.floored_rel_error(y, y) == 0.0
+    rho = np.sqrt(np.mean(y * y))
+    assert abs(oracle.floored_rel_error(y + np.array([[0, 0, 1e-3, 0]]), y) - 1e-3 / rho) < 1e-15
