@@ -1,0 +1,142 @@
+/*
+ * qfc - weight-only-quantized fully-connected layer for MI355X (gfx950).
+ *
+ * C ABI of the hot path of LLM inference as the paper states it (section 3.7,
+ * "Stage-Aware Optimizations for LLM Inference", and the weight formats of
+ * section 4.2): the same quantized weights, resident in GPU memory, serve
+ *   - decode  (M <= 8 token rows): a bandwidth-bound fully connected kernel
+ *     that streams the packed weights once and dequantizes them in registers;
+ *   - prefill (M > 8): either a quantization kernel that turns the float
+ *     activations into int8 plus one scale per token, an int8 x int8 -> int32
+ *     matrix product on the matrix cores and a dequantizing epilogue, or an
+ *     fp16 matrix product over weights dequantized on the fly.
+ * Weights are converted once, at load time, from their logical [N, K] form to
+ * a physical layout chosen for the kernels (section 3.1 weight layouts,
+ * section 3.4 "weights conversion").
+ *
+ * Conventions
+ *   - Every pointer is a DEVICE pointer unless its comment says "host".
+ *   - `stream` is a hipStream_t passed as void* (NULL = the null stream).
+ *     All work is enqueued on it; no call synchronizes, allocates device
+ *     memory or changes the current device.
+ *   - The caller owns every buffer.  A handle is a small host object that
+ *     borrows `packed` and the bound workspace: keep both alive, and do not
+ *     write to them, until qfc_destroy.
+ *   - Every call returns a qfc_status_t.  Argument errors are detected on the
+ *     host before anything is launched; a failed launch gives QFC_ERR_HIP.
+ *     No exception crosses this boundary.
+ *   - Device pointers must be 16-byte aligned.  K must be a multiple of 32.
+ *   - Calls that share a workspace must not overlap in time (same stream, or
+ *     ordered by the caller).
+ */
+#ifndef QFC_H
+#define QFC_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct qfc_weights_s *qfc_handle_t;
+
+typedef enum {
+    QFC_OK = 0,
+    QFC_ERR_INVALID_ARG = 1,      /* null pointer, bad enum, non-positive size, K % 32 != 0 */
+    QFC_ERR_UNSUPPORTED = 2,      /* a valid combination this library has no kernel for */
+    QFC_ERR_BUFFER_TOO_SMALL = 3, /* packed buffer or workspace smaller than required */
+    QFC_ERR_ALIGNMENT = 4,        /* a device pointer is not 16-byte aligned */
+    QFC_ERR_HIP = 5               /* the HIP runtime reported an error */
+} qfc_status_t;
+
+enum { QFC_SCALE_F32 = 0, QFC_SCALE_F16 = 1 };
+enum { QFC_COMPUTE_FP16_DEQUANT = 0, QFC_COMPUTE_INT8_ACT = 1 };
+
+/* Description of one quantized linear layer, y[M,N] = x[M,K] . W[N,K]^T.
+ * Supported formats (section 4.2 per-channel schemes; group scales are the
+ * sub-channel quantization the paper names as its next step):
+ *   wbits 8, group_size 0,  scale_dtype F32: int8 codes, one fp32 scale per output channel;
+ *   wbits 4, group_size 32, scale_dtype F16: int4 codes in [-8,7], one binary16 scale per
+ *                                            32 consecutive k of a row, scales [N, K/32].
+ * Any other combination returns QFC_ERR_UNSUPPORTED.
+ * compute_mode selects the M > 8 path: QFC_COMPUTE_INT8_ACT (needs 8-bit per-channel weights)
+ * or QFC_COMPUTE_FP16_DEQUANT.  It has no effect for M <= 8. */
+typedef struct {
+    int32_t N;
+    int32_t K;
+    int32_t wbits;
+    int32_t group_size;
+    int32_t scale_dtype;
+    int32_t compute_mode;
+} qfc_desc_t;
+
+/* Bytes of the physical (packed) form of a layer, padding included.
+ * `desc` and `bytes` are host pointers. */
+qfc_status_t qfc_packed_size(const qfc_desc_t *desc, size_t *bytes);
+
+/* Weights conversion (section 3.4): rearrange the logical quantized weights
+ * into the physical layout and create a handle.
+ *   wq_logical  int8 [N, K], row-major, one code per byte (int4 codes in [-8, 7];
+ *               only the low four bits of an int4 code are kept);
+ *   scales      fp32 [N] or binary16 [N, K/32] as `desc` says;
+ *   packed      caller-owned destination of at least qfc_packed_size bytes, borrowed
+ *               by the handle afterwards;
+ *   out         host pointer receiving the handle.
+ * The inputs may be freed once the stream has run the conversion. */
+qfc_status_t qfc_pack_weights(const qfc_desc_t *desc, const int8_t *wq_logical,
+                              const void *scales, void *packed, size_t packed_bytes,
+                              void *stream, qfc_handle_t *out);
+
+/* Inverse of the conversion (test aid): writes back the logical codes and
+ * scales, bit for bit what qfc_pack_weights was given. */
+qfc_status_t qfc_unpack_weights(qfc_handle_t h, int8_t *wq_logical, void *scales, void *stream);
+
+/* Scratch a forward call with up to M token rows needs (partial sums of a
+ * K-split, quantized activations).  `bytes` is a host pointer. */
+qfc_status_t qfc_workspace_size(qfc_handle_t h, int32_t M, size_t *bytes);
+
+/* Lend a workspace to the handle.  Enqueues the one-time clearing of its
+ * counters on `stream`.  One workspace may be bound to many handles as long as
+ * their calls do not overlap. */
+qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes, void *stream);
+
+/* Activation quantization kernel of the prefill stage (section 3.7): per token
+ * row m, a = max|x[m,:]|, sx[m] = a/127 (fp32), xq[m,k] = clamp(rne(x[m,k] * (127/a)), +-127);
+ * an all-zero row gives sx = 0, xq = 0.
+ *   x_f16 binary16 [M, K] row-major; xq int8 [M, K] row-major; sx fp32 [M]. */
+qfc_status_t qfc_quantize_activations(const void *x_f16, int32_t M, int32_t K,
+                                      int8_t *xq, float *sx, void *stream);
+
+/* y[M,N] = x[M,K] . dequant(W)^T, binary16 in, fp32 accumulation, binary16 out.
+ * M <= 8: decode kernel (weights dequantized in registers).  M > 8: the path
+ * `compute_mode` names; QFC_COMPUTE_INT8_ACT quantizes x per token into the
+ * bound workspace first.  Needs a bound workspace of qfc_workspace_size(h, M). */
+qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream);
+
+/* Prefill product on already quantized activations (int8 per-channel weights
+ * only): y[m,n] = fp16(float(sum_k xq[m,k] Wq[n,k]) * sx[m] * sw[n]).
+ *   xq int8 [M, K] row-major, sx fp32 [M], y binary16 [M, N].  Any M >= 1. */
+qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M,
+                            void *y_f16, void *stream);
+
+/* The raw int32 accumulators of the same product (parity aid): acc int32 [M, N]. */
+qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc,
+                                 void *stream);
+
+/* `count` forward calls issued in order on one stream: handles, xs and ys are
+ * host arrays of `count` entries; every call uses the same M.  Stops at the
+ * first error and returns it. */
+qfc_status_t qfc_forward_batch(const qfc_handle_t *handles, const void *const *xs, int32_t M,
+                               void *const *ys, int32_t count, void *stream);
+
+/* Free the host object.  Device buffers stay with the caller. */
+qfc_status_t qfc_destroy(qfc_handle_t h);
+
+/* Static, host string for a status code. */
+const char *qfc_status_string(qfc_status_t s);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QFC_H */

@@ -1,0 +1,193 @@
+"""Thin ctypes binding of libqfc.so: same names as include/qfc.h, argument
+marshalling only.  PyTorch supplies device memory and the stream; every step of
+the path runs in the library's HIP kernels.  There is no fallback: if the
+library is missing or a call fails, an exception is raised."""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libqfc.so")
+
+QFC_OK = 0
+QFC_SCALE_F32, QFC_SCALE_F16 = 0, 1
+QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT = 0, 1
+
+EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
+           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_q8",
+           "qfc_forward_acc_i32", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
+
+
+class Desc(ctypes.Structure):
+    _fields_ = [("N", ctypes.c_int32), ("K", ctypes.c_int32), ("wbits", ctypes.c_int32),
+                ("group_size", ctypes.c_int32), ("scale_dtype", ctypes.c_int32),
+                ("compute_mode", ctypes.c_int32)]
+
+
+class QfcError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {status_string(code)} (status {code})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """The loaded library; built beforehand by paper_2505_00232_amd.build."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(f"{LIB_PATH} is missing: run `python -m paper_2505_00232_amd.build` first")
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32, sz = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t
+        L.qfc_packed_size.argtypes = [ctypes.POINTER(Desc), ctypes.POINTER(sz)]
+        L.qfc_pack_weights.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, sz, vp, ctypes.POINTER(vp)]
+        L.qfc_unpack_weights.argtypes = [vp, vp, vp, vp]
+        L.qfc_workspace_size.argtypes = [vp, i32, ctypes.POINTER(sz)]
+        L.qfc_bind_workspace.argtypes = [vp, vp, sz, vp]
+        L.qfc_quantize_activations.argtypes = [vp, i32, i32, vp, vp, vp]
+        L.qfc_forward.argtypes = [vp, vp, i32, vp, vp]
+        L.qfc_forward_q8.argtypes = [vp, vp, vp, i32, vp, vp]
+        L.qfc_forward_acc_i32.argtypes = [vp, vp, i32, vp, vp]
+        L.qfc_forward_batch.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, vp]
+        L.qfc_destroy.argtypes = [vp]
+        L.qfc_status_string.argtypes = [ctypes.c_int]
+        L.qfc_status_string.restype = ctypes.c_char_p
+        L.qfc_tune.argtypes = [i32, i32]
+        L.qfc_tune.restype = None
+        for name in EXPORTS:
+            if name != "qfc_status_string":
+                getattr(L, name).restype = ctypes.c_int
+        _lib = L
+    return _lib
+
+
+def status_string(code: int) -> str:
+    return lib().qfc_status_string(int(code)).decode()
+
+
+def _check(code: int, where: str):
+    if code != QFC_OK:
+        raise QfcError(code, where)
+
+
+def _ptr(t):
+    return ctypes.c_void_p(t.data_ptr() if t is not None else 0)
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def make_desc(N: int, K: int, fmt: str, compute_mode: int | None = None) -> Desc:
+    if fmt == "w8c":
+        mode = QFC_COMPUTE_INT8_ACT if compute_mode is None else compute_mode
+        return Desc(N, K, 8, 0, QFC_SCALE_F32, mode)
+    if fmt == "w4g32":
+        mode = QFC_COMPUTE_FP16_DEQUANT if compute_mode is None else compute_mode
+        return Desc(N, K, 4, 32, QFC_SCALE_F16, mode)
+    raise ValueError(fmt)
+
+
+def qfc_packed_size(desc: Desc) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().qfc_packed_size(ctypes.byref(desc), ctypes.byref(out)), "qfc_packed_size")
+    return out.value
+
+
+def qfc_pack_weights(desc: Desc, wq_logical: torch.Tensor, scales: torch.Tensor, packed: torch.Tensor):
+    h = ctypes.c_void_p(0)
+    _check(lib().qfc_pack_weights(ctypes.byref(desc), _ptr(wq_logical), _ptr(scales), _ptr(packed),
+                                  packed.numel() * packed.element_size(), _stream(), ctypes.byref(h)),
+           "qfc_pack_weights")
+    return h
+
+
+def qfc_unpack_weights(h, wq_logical: torch.Tensor, scales: torch.Tensor):
+    _check(lib().qfc_unpack_weights(h, _ptr(wq_logical), _ptr(scales), _stream()), "qfc_unpack_weights")
+
+
+def qfc_workspace_size(h, M: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().qfc_workspace_size(h, M, ctypes.byref(out)), "qfc_workspace_size")
+    return out.value
+
+
+def qfc_bind_workspace(h, ws: torch.Tensor):
+    _check(lib().qfc_bind_workspace(h, _ptr(ws), ws.numel() * ws.element_size(), _stream()), "qfc_bind_workspace")
+
+
+def qfc_quantize_activations(x: torch.Tensor, xq: torch.Tensor, sx: torch.Tensor):
+    M, K = x.shape
+    _check(lib().qfc_quantize_activations(_ptr(x), M, K, _ptr(xq), _ptr(sx), _stream()), "qfc_quantize_activations")
+
+
+def qfc_forward(h, x: torch.Tensor, y: torch.Tensor):
+    _check(lib().qfc_forward(h, _ptr(x), x.shape[0], _ptr(y), _stream()), "qfc_forward")
+
+
+def qfc_forward_q8(h, xq: torch.Tensor, sx: torch.Tensor, y: torch.Tensor):
+    _check(lib().qfc_forward_q8(h, _ptr(xq), _ptr(sx), xq.shape[0], _ptr(y), _stream()), "qfc_forward_q8")
+
+
+def qfc_forward_acc_i32(h, xq: torch.Tensor, acc: torch.Tensor):
+    _check(lib().qfc_forward_acc_i32(h, _ptr(xq), xq.shape[0], _ptr(acc), _stream()), "qfc_forward_acc_i32")
+
+
+class ForwardBatch:
+    """Pre-marshalled argument arrays for qfc_forward_batch."""
+
+    def __init__(self, handles, xs, ys, M: int):
+        n = len(handles)
+        arr = ctypes.c_void_p * n
+        self.h = arr(*[h.value for h in handles])
+        self.x = arr(*[x.data_ptr() for x in xs])
+        self.y = arr(*[y.data_ptr() for y in ys])
+        self.n, self.M = n, M
+        self._keep = (list(xs), list(ys))
+
+    def run(self):
+        _check(lib().qfc_forward_batch(self.h, self.x, self.M, self.y, self.n, _stream()), "qfc_forward_batch")
+
+
+def qfc_destroy(h):
+    _check(lib().qfc_destroy(h), "qfc_destroy")
+
+
+def qfc_tune(key: int, value: int):
+    lib().qfc_tune(key, value)
+
+
+class QuantLinear:
+    """Convenience owner of one packed layer: device buffers + handle."""
+
+    def __init__(self, wq, scales, fmt: str, compute_mode: int | None = None, device="cuda", max_m: int = 8,
+                 workspace: torch.Tensor | None = None):
+        wq_d = torch.as_tensor(wq).to(device).contiguous()
+        s_d = torch.as_tensor(scales).to(device).contiguous()
+        N, K = wq_d.shape
+        self.N, self.K, self.fmt = N, K, fmt
+        self.desc = make_desc(N, K, fmt, compute_mode)
+        self.packed = torch.empty(qfc_packed_size(self.desc), dtype=torch.uint8, device=device)
+        self.handle = qfc_pack_weights(self.desc, wq_d, s_d, self.packed)
+        need = max(qfc_workspace_size(self.handle, m) for m in sorted({1, min(max_m, 8), max_m}))
+        if workspace is None or workspace.numel() < need:
+            workspace = torch.empty(need, dtype=torch.uint8, device=device)
+        self.workspace = workspace
+        qfc_bind_workspace(self.handle, self.workspace)
+        torch.cuda.current_stream().synchronize()  # inputs of the conversion may now be freed
+
+    def forward(self, x: torch.Tensor, y: torch.Tensor | None = None) -> torch.Tensor:
+        if y is None:
+            y = torch.empty((x.shape[0], self.N), dtype=torch.float16, device=x.device)
+        qfc_forward(self.handle, x, y)
+        return y
+
+    def close(self):
+        if self.handle is not None:
+            qfc_destroy(self.handle)
+            self.handle = None

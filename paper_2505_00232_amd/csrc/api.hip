@@ -1,0 +1,239 @@
+// C ABI of libqfc.so: argument checking, handle bookkeeping and dispatch
+// (decode kernel for M <= 8, prefill kernels above; section 3.7 of the paper:
+// the stage decides the kernel).  All arithmetic is in the kernels' files.
+#include <new>
+
+#include "qfc_internal.h"
+
+using namespace qfc;
+
+struct qfc_weights_s {
+    uint32_t magic;
+    qfc_desc_t desc;
+    Geometry geo;
+    void *packed;
+    void *workspace;
+    size_t workspace_bytes;
+    int num_cus;
+};
+
+namespace {
+
+constexpr uint32_t kMagic = 0x51464331u;  // "QFC1"
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+qfc_status_t check_desc(const qfc_desc_t *d, int *fmt) {
+    if (!d) return QFC_ERR_INVALID_ARG;
+    if (d->N < 1 || d->K < 1 || d->K % 32 != 0) return QFC_ERR_INVALID_ARG;
+    if (d->wbits != 8 && d->wbits != 4) return QFC_ERR_INVALID_ARG;
+    if (d->group_size < 0) return QFC_ERR_INVALID_ARG;
+    if (d->scale_dtype != QFC_SCALE_F32 && d->scale_dtype != QFC_SCALE_F16) return QFC_ERR_INVALID_ARG;
+    if (d->compute_mode != QFC_COMPUTE_FP16_DEQUANT && d->compute_mode != QFC_COMPUTE_INT8_ACT)
+        return QFC_ERR_INVALID_ARG;
+    if (d->wbits == 8 && d->group_size == 0 && d->scale_dtype == QFC_SCALE_F32) {
+        *fmt = kW8C;
+    } else if (d->wbits == 4 && d->group_size == 32 && d->scale_dtype == QFC_SCALE_F16) {
+        *fmt = kW4G32;
+        if (d->compute_mode == QFC_COMPUTE_INT8_ACT) return QFC_ERR_UNSUPPORTED;
+    } else {
+        return QFC_ERR_UNSUPPORTED;
+    }
+    // int32 accumulators must hold K * 127 * 128
+    if ((int64_t)d->K * 127 * 128 > INT32_MAX) return QFC_ERR_UNSUPPORTED;
+    return QFC_OK;
+}
+
+bool valid(qfc_handle_t h) { return h && h->magic == kMagic; }
+
+int prefill_rows(int M) { return round_up(M, 256); }
+
+size_t ticket_region(const Geometry &g) { return (size_t)round_up(g.RB * 4, 256); }
+
+size_t int8_region(const Geometry &g, int M) {
+    const size_t Mp = (size_t)prefill_rows(M);
+    return Mp * (size_t)g.Kp + Mp * sizeof(float);
+}
+
+size_t workspace_need(qfc_handle_t h, int M) {
+    size_t need = ticket_region(h->geo);
+    size_t body = 0;
+    if (M <= kMaxDecodeM) body = gemv_workspace_bytes(h->geo, M, h->num_cus) - ticket_region(h->geo);
+    if (h->geo.fmt == kW8C) {
+        const size_t b = int8_region(h->geo, M);
+        if (b > body) body = b;
+    }
+    return need + body;
+}
+
+qfc_status_t hip_status(hipError_t e) { return e == hipSuccess ? QFC_OK : QFC_ERR_HIP; }
+
+// Common checks of the int8 entry points; on success the tiled activations are in the workspace.
+qfc_status_t stage_xq(qfc_handle_t h, const int8_t *xq, int M, int8_t **tiled, float **sx_ws,
+                      hipStream_t st) {
+    if (!valid(h) || !xq || M < 1) return QFC_ERR_INVALID_ARG;
+    if (h->geo.fmt != kW8C) return QFC_ERR_UNSUPPORTED;
+    if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
+    if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
+    const int Mp = prefill_rows(M);
+    char *body = static_cast<char *>(h->workspace) + ticket_region(h->geo);
+    *tiled = reinterpret_cast<int8_t *>(body);
+    *sx_ws = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
+    return hip_status(launch_retile_xq(xq, M, h->geo.K, *tiled, Mp, h->geo.Kp, st));
+}
+
+}  // namespace
+
+extern "C" {
+
+qfc_status_t qfc_packed_size(const qfc_desc_t *desc, size_t *bytes) {
+    int fmt = 0;
+    if (!bytes) return QFC_ERR_INVALID_ARG;
+    const qfc_status_t s = check_desc(desc, &fmt);
+    if (s != QFC_OK) return s;
+    *bytes = make_geometry(desc->N, desc->K, fmt).total_bytes;
+    return QFC_OK;
+}
+
+qfc_status_t qfc_pack_weights(const qfc_desc_t *desc, const int8_t *wq_logical, const void *scales,
+                              void *packed, size_t packed_bytes, void *stream, qfc_handle_t *out) {
+    int fmt = 0;
+    if (!out) return QFC_ERR_INVALID_ARG;
+    *out = nullptr;
+    const qfc_status_t s = check_desc(desc, &fmt);
+    if (s != QFC_OK) return s;
+    if (!wq_logical || !scales || !packed) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(wq_logical) || !aligned16(scales) || !aligned16(packed)) return QFC_ERR_ALIGNMENT;
+    const Geometry g = make_geometry(desc->N, desc->K, fmt);
+    if (packed_bytes < g.total_bytes) return QFC_ERR_BUFFER_TOO_SMALL;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return QFC_ERR_HIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return QFC_ERR_HIP;
+    if (launch_pack(g, wq_logical, scales, packed, static_cast<hipStream_t>(stream)) != hipSuccess)
+        return QFC_ERR_HIP;
+    qfc_weights_s *h = new (std::nothrow) qfc_weights_s;
+    if (!h) return QFC_ERR_HIP;
+    h->magic = kMagic;
+    h->desc = *desc;
+    h->geo = g;
+    h->packed = packed;
+    h->workspace = nullptr;
+    h->workspace_bytes = 0;
+    h->num_cus = cus;
+    *out = h;
+    return QFC_OK;
+}
+
+qfc_status_t qfc_unpack_weights(qfc_handle_t h, int8_t *wq_logical, void *scales, void *stream) {
+    if (!valid(h) || !wq_logical || !scales) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(wq_logical) || !aligned16(scales)) return QFC_ERR_ALIGNMENT;
+    return hip_status(launch_unpack(h->geo, h->packed, wq_logical, scales, static_cast<hipStream_t>(stream)));
+}
+
+qfc_status_t qfc_workspace_size(qfc_handle_t h, int32_t M, size_t *bytes) {
+    if (!valid(h) || !bytes || M < 1) return QFC_ERR_INVALID_ARG;
+    *bytes = workspace_need(h, M);
+    return QFC_OK;
+}
+
+qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes, void *stream) {
+    if (!valid(h) || !workspace) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(workspace)) return QFC_ERR_ALIGNMENT;
+    const size_t t = ticket_region(h->geo);
+    if (bytes < t) return QFC_ERR_BUFFER_TOO_SMALL;
+    if (hipMemsetAsync(workspace, 0, t, static_cast<hipStream_t>(stream)) != hipSuccess) return QFC_ERR_HIP;
+    h->workspace = workspace;
+    h->workspace_bytes = bytes;
+    return QFC_OK;
+}
+
+qfc_status_t qfc_quantize_activations(const void *x_f16, int32_t M, int32_t K, int8_t *xq, float *sx,
+                                      void *stream) {
+    if (!x_f16 || !xq || !sx || M < 1 || K < 1 || K % 32 != 0) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(x_f16) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return QFC_ERR_ALIGNMENT;
+    return hip_status(launch_act_quant(x_f16, M, K, xq, sx, 0, M, K, static_cast<hipStream_t>(stream)));
+}
+
+qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream) {
+    if (!valid(h) || !x_f16 || !y_f16 || M < 1) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(x_f16) || !aligned16(y_f16)) return QFC_ERR_ALIGNMENT;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    if (M > kMaxDecodeM && h->desc.compute_mode == QFC_COMPUTE_FP16_DEQUANT) {
+        if (h->geo.fmt != kW4G32) return QFC_ERR_UNSUPPORTED;
+        return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, st));
+    }
+    if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
+    if (M <= kMaxDecodeM)
+        return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, h->workspace, h->num_cus, st));
+    // int8 activations: quantize into the workspace (tiled), multiply, rescale
+    const int Mp = prefill_rows(M);
+    char *body = static_cast<char *>(h->workspace) + ticket_region(h->geo);
+    int8_t *tiled = reinterpret_cast<int8_t *>(body);
+    float *sx = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
+    if (launch_act_quant(x_f16, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, st) != hipSuccess) return QFC_ERR_HIP;
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, st));
+}
+
+qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M, void *y_f16,
+                            void *stream) {
+    if (!sx || !y_f16) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(y_f16) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return QFC_ERR_ALIGNMENT;
+    int8_t *tiled = nullptr;
+    float *sx_ws = nullptr;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
+    if (s != QFC_OK) return s;
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, prefill_rows(M), y_f16, 0, st));
+}
+
+qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc, void *stream) {
+    if (!acc) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(acc)) return QFC_ERR_ALIGNMENT;
+    int8_t *tiled = nullptr;
+    float *sx_ws = nullptr;
+    hipStream_t st = static_cast<hipStream_t>(stream);
+    const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
+    if (s != QFC_OK) return s;
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, st));
+}
+
+qfc_status_t qfc_forward_batch(const qfc_handle_t *handles, const void *const *xs, int32_t M,
+                               void *const *ys, int32_t count, void *stream) {
+    if (!handles || !xs || !ys || count < 0) return QFC_ERR_INVALID_ARG;
+    for (int32_t i = 0; i < count; ++i) {
+        const qfc_status_t s = qfc_forward(handles[i], xs[i], M, ys[i], stream);
+        if (s != QFC_OK) return s;
+    }
+    return QFC_OK;
+}
+
+qfc_status_t qfc_destroy(qfc_handle_t h) {
+    if (!valid(h)) return QFC_ERR_INVALID_ARG;
+    h->magic = 0;
+    delete h;
+    return QFC_OK;
+}
+
+const char *qfc_status_string(qfc_status_t s) {
+    switch (s) {
+        case QFC_OK: return "ok";
+        case QFC_ERR_INVALID_ARG: return "invalid argument";
+        case QFC_ERR_UNSUPPORTED: return "unsupported combination";
+        case QFC_ERR_BUFFER_TOO_SMALL: return "buffer too small";
+        case QFC_ERR_ALIGNMENT: return "pointer not 16-byte aligned";
+        case QFC_ERR_HIP: return "HIP runtime error";
+    }
+    return "unknown status";
+}
+
+// Tuning knob for experiments (not part of the documented interface):
+// key 0 = target wavefronts of a decode launch, 1 = max wavefronts per
+// workgroup, 2 = prefill kernel variant.
+void qfc_tune(int32_t key, int32_t value) {
+    Tuning &t = tuning();
+    if (key == 0) t.gemv_target_waves = value;
+    if (key == 1) t.gemv_max_waves_per_wg = value;
+    if (key == 2) t.gemm_variant = value;
+}
+
+}  // extern "C"

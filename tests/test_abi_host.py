@@ -1,0 +1,79 @@
+"""Host-side checks of the C ABI that need no GPU: the library loads, exports
+every symbol the header declares, and rejects bad arguments before touching a
+device."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2505_00232_amd import binding, build
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(binding.LIB_PATH):
+        build.build()
+    return binding.lib()
+
+
+def test_header_symbols_are_exported(L):
+    header = open(os.path.join(ROOT, "include", "qfc.h")).read()
+    declared = set(re.findall(r"\b(qfc_[a-z0-9_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    for name in declared:
+        assert hasattr(L, name), name
+
+
+def test_status_strings(L):
+    seen = {binding.status_string(c) for c in range(6)}
+    assert len(seen) == 6 and binding.status_string(0) == "ok"
+    assert binding.status_string(99) == "unknown status"
+
+
+def test_packed_size_and_descriptor_checks(L):
+    d = binding.make_desc(1024, 512, "w8c")
+    # 1024 x 512 codes + 1024 fp32 scales, no padding needed
+    assert binding.qfc_packed_size(d) == 1024 * 512 + 4 * 1024
+    d = binding.make_desc(4096, 2304, "w4g32")
+    # 9 KiB per (64 rows x 256 k)
+    assert binding.qfc_packed_size(d) == (4096 // 64) * (2304 // 256) * 9216
+    d = binding.make_desc(1, 32, "w4g32")
+    assert binding.qfc_packed_size(d) == 4 * 9216  # padded to 256 rows x 256 k
+    out = ctypes.c_size_t(0)
+    bad = [binding.Desc(0, 512, 8, 0, 0, 1), binding.Desc(8, 48, 8, 0, 0, 1), binding.Desc(8, 64, 3, 0, 0, 1),
+           binding.Desc(8, 64, 8, -1, 0, 1), binding.Desc(8, 64, 8, 0, 7, 1), binding.Desc(8, 64, 8, 0, 0, 5)]
+    for d in bad:
+        assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 1
+    unsupported = [binding.Desc(8, 64, 8, 32, 0, 1), binding.Desc(8, 64, 4, 32, 1, 1),
+                   binding.Desc(8, 64, 4, 0, 0, 0), binding.Desc(8, 64, 8, 0, 1, 1)]
+    for d in unsupported:
+        assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 2
+    assert L.qfc_packed_size(None, ctypes.byref(out)) == 1
+    assert L.qfc_packed_size(ctypes.byref(binding.make_desc(8, 64, "w8c")), None) == 1
+
+
+def test_argument_errors_before_any_launch(L):
+    d = binding.make_desc(64, 64, "w8c")
+    h = ctypes.c_void_p(0)
+    a = ctypes.c_void_p(0x1000)   # never dereferenced: checks fail first
+    odd = ctypes.c_void_p(0x1008)
+    s = ctypes.c_void_p(0)
+    assert L.qfc_pack_weights(ctypes.byref(d), None, a, a, 1 << 20, s, ctypes.byref(h)) == 1
+    assert L.qfc_pack_weights(ctypes.byref(d), a, a, a, 1 << 20, s, None) == 1
+    assert L.qfc_pack_weights(ctypes.byref(d), odd, a, a, 1 << 20, s, ctypes.byref(h)) == 4
+    assert L.qfc_pack_weights(ctypes.byref(d), a, a, a, 16, s, ctypes.byref(h)) == 3
+    assert h.value is None
+    for fn, args in [(L.qfc_forward, (None, a, 1, a, s)), (L.qfc_unpack_weights, (None, a, a, s)),
+                     (L.qfc_bind_workspace, (None, a, 1024, s)), (L.qfc_forward_q8, (None, a, a, 1, a, s)),
+                     (L.qfc_forward_acc_i32, (None, a, 1, a, s)), (L.qfc_destroy, (None,))]:
+        assert fn(*args) == 1
+    out = ctypes.c_size_t(0)
+    assert L.qfc_workspace_size(None, 1, ctypes.byref(out)) == 1
+    assert L.qfc_quantize_activations(a, 0, 64, a, a, s) == 1
+    assert L.qfc_quantize_activations(a, 4, 40, a, a, s) == 1
+    assert L.qfc_quantize_activations(odd, 4, 64, a, a, s) == 4
+    assert L.qfc_quantize_activations(None, 4, 64, a, a, s) == 1
+    assert L.qfc_forward_batch(None, None, 1, None, 0, s) == 1

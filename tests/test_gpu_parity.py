@@ -1,0 +1,291 @@
+"""Parity of the HIP path (through the C ABI) against the CPU oracle, element by
+element on the same seeded inputs.  Integer work (packing, quantized
+activations, int32 accumulators) must match bit for bit; floating-point outputs
+must satisfy the floored relative error bound 2e-3 (fp32 accumulation, binary16
+output)."""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from paper_2505_00232_amd import binding, synth
+
+pytestmark = pytest.mark.gpu
+TOL = 2e-3
+DEV = "cuda"
+
+
+def _layer(wq, s, fmt, max_m=8, mode=None):
+    return binding.QuantLinear(wq, s, fmt, compute_mode=mode, max_m=max_m)
+
+
+def _group(fmt):
+    return 0 if fmt == "w8c" else 32
+
+
+def _forward(layer, x):
+    xd = torch.from_numpy(x).to(DEV)
+    y = layer.forward(xd)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+# ------------------------------------------------------------------ A1 pack / unpack
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+@pytest.mark.parametrize("N,K", [(1, 32), (17, 96), (64, 256), (300, 512), (1000, 2304)])
+def test_pack_unpack_round_trip_bit_exact(fmt, N, K):
+    print(f"pack/unpack {fmt} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(N * 7919 + K)
+    if fmt == "w8c":
+        wq = rng.integers(-128, 128, size=(N, K), dtype=np.int8)
+        wq.flat[: min(256, wq.size)] = np.arange(-128, 128, dtype=np.int16).astype(np.int8)[: min(256, wq.size)]
+        s = rng.integers(0, 2**32, size=N, dtype=np.uint32).view(np.float32)  # any bit pattern
+    else:
+        wq = rng.integers(-8, 8, size=(N, K), dtype=np.int8)
+        wq.flat[:16] = np.arange(-8, 8, dtype=np.int8)
+        s = rng.integers(0, 2**16, size=(N, K // 32), dtype=np.uint16).view(np.float16)
+    layer = _layer(wq, s, fmt)
+    wq_back = torch.full((N, K), 99, dtype=torch.int8, device=DEV)
+    s_back = torch.zeros(s.shape, dtype=torch.float32 if fmt == "w8c" else torch.float16, device=DEV)
+    binding.qfc_unpack_weights(layer.handle, wq_back, s_back)
+    torch.cuda.synchronize()
+    assert np.array_equal(wq_back.cpu().numpy(), wq)
+    sb = s_back.cpu().numpy()
+    assert np.array_equal(sb.view(np.uint32 if fmt == "w8c" else np.uint16),
+                          s.view(np.uint32 if fmt == "w8c" else np.uint16))
+    layer.close()
+
+
+# ------------------------------------------------------------------ A2 decode
+DECODE_SHAPES = [(1, 32), (17, 96), (130, 256), (1000, 2304), (96, 14336), (1024, 512)]
+
+
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+@pytest.mark.parametrize("N,K", DECODE_SHAPES)
+def test_decode_matches_oracle(fmt, N, K):
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(2000, N, K, fc)
+    wq.flat[0] = -128 if fmt == "w8c" else -8
+    layer = _layer(wq, s, fmt)
+    for M in range(1, 9):
+        print(f"decode {fmt} N={N} K={K} M={M}", flush=True)
+        x = synth.activations(2000, N, K + M, M, K)
+        y = _forward(layer, x)
+        ref = oracle.fc_weight_only(x, wq, s, _group(fmt))
+        err = oracle.floored_rel_error(y, ref)
+        assert err <= TOL, (M, err)
+        y2 = _forward(layer, x)
+        assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))  # deterministic
+    layer.close()
+
+
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+def test_decode_config1_and_structure_cases(fmt):
+    print(f"decode structure cases {fmt}", flush=True)
+    # identity weights with unit scales return x bit for bit (one non-zero term per output)
+    K = 512
+    eye = np.eye(K, dtype=np.int8)
+    ones = np.ones(K, np.float32) if fmt == "w8c" else np.ones((K, K // 32), np.float16)
+    layer = _layer(eye, ones, fmt)
+    x = synth.activations(2001, 0, 0, 4, K)
+    y = _forward(layer, x)
+    assert np.array_equal(y.view(np.uint16), x.view(np.uint16))
+    layer.close()
+    # one-hot rows with power-of-two scales: y[m,n] = s_n q_n x[m, perm(n)] exactly
+    rng = np.random.default_rng(11)
+    N, K = 700, 1024
+    perm = rng.integers(0, K, size=N)
+    q = rng.integers(1, 8, size=N) * rng.choice([-1, 1], size=N)
+    wq = np.zeros((N, K), np.int8)
+    wq[np.arange(N), perm] = q
+    if fmt == "w8c":
+        s = (2.0 ** rng.integers(-6, 3, size=N)).astype(np.float32)
+        sn = s.astype(np.float64)
+    else:
+        s = (2.0 ** rng.integers(-6, 3, size=(N, K // 32))).astype(np.float16)
+        sn = s.astype(np.float64)[np.arange(N), perm // 32]
+    layer = _layer(wq, s, fmt)
+    x = synth.activations(2002, 0, 0, 3, K)
+    y = _forward(layer, x)
+    want = (x.astype(np.float64)[:, perm] * (sn * q)[None, :]).astype(np.float16)
+    assert np.array_equal(y.view(np.uint16), want.view(np.uint16))
+    assert np.array_equal(oracle.fc_weight_only(x, wq, s, _group(fmt)).astype(np.float16).view(np.uint16),
+                          want.view(np.uint16))
+    layer.close()
+
+
+def test_decode_config1():
+    print("config 1", flush=True)
+    fc = synth.CFG1_FC
+    wq, s = synth.weights(1001, 0, 0, fc)
+    x = synth.activations(1001, 0, 0, 1, fc.K)
+    layer = _layer(wq, s, fc.fmt)
+    y = _forward(layer, x)
+    assert oracle.floored_rel_error(y, oracle.fc_weight_only(x, wq, s)) <= TOL
+    layer.close()
+
+
+def test_decode_config2_gemma_layer_full():
+    for i, fc in enumerate(synth.GEMMA_FCS_W4):
+        print(f"config 2 {fc.name} {fc.K}->{fc.N}", flush=True)
+        wq, s = synth.weights(1002, 0, i, fc)
+        x = synth.activations(1002, 0, i, 1, fc.K)
+        layer = _layer(wq, s, fc.fmt)
+        y = _forward(layer, x)
+        assert oracle.floored_rel_error(y, oracle.fc_weight_only(x, wq, s, 32)) <= TOL
+        layer.close()
+
+
+@pytest.mark.parametrize("M", [1, 4])
+def test_decode_config3_llama_shapes_sampled(M):
+    """Full-size Llama-3.1-8B FCs in the launch configuration the benchmark
+    uses; the oracle evaluates a random sample of output channels."""
+    rng = np.random.default_rng(3)
+    for i, fc in enumerate(synth.LLAMA_FCS_W4 + (synth.LLAMA_LM_HEAD,)):
+        print(f"config 3 {fc.name} {fc.K}->{fc.N} M={M}", flush=True)
+        wq, s = synth.weights(1003, 0, i, fc)
+        x = synth.activations(1003, 0, i, M, fc.K)
+        layer = _layer(wq, s, fc.fmt)
+        y = _forward(layer, x)
+        rows = np.sort(rng.choice(fc.N, size=1536, replace=False))
+        rows[:2] = (0, 1)
+        rows[-2:] = (fc.N - 2, fc.N - 1)
+        ref = oracle.fc_weight_only(x, wq[rows], s[rows], _group(fc.fmt))
+        assert oracle.floored_rel_error(y[:, rows], ref) <= TOL
+        assert np.all(np.isfinite(y.astype(np.float32)))
+        layer.close()
+        del wq, s
+
+
+# ------------------------------------------------------------------ A3 activation quantization
+@pytest.mark.parametrize("M,K", [(1, 32), (5, 96), (64, 14336), (1024, 4096)])
+def test_activation_quantization_bit_exact(M, K):
+    print(f"act quant M={M} K={K}", flush=True)
+    x = synth.activations(3000, M, K, M, K)
+    if M >= 5:
+        x[1] = 0
+        x[2] = (x[2].astype(np.float32) * 2.0**-12).astype(np.float16)
+        x[3, 0] = np.float16(65504.0)
+        x[4, :] = np.float16(-3.0)
+    xd = torch.from_numpy(x).to(DEV)
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    binding.qfc_quantize_activations(xd, xq, sx)
+    torch.cuda.synchronize()
+    xq_ref, sx_ref = oracle.quantize_activations(x)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+    assert np.array_equal(xq.cpu().numpy(), xq_ref)
+
+
+# ------------------------------------------------------------------ A4 / A5 int8 prefill
+@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (256, 1000, 2304), (130, 64, 14336)])
+def test_int8_prefill_matches_oracle(M, N, K):
+    print(f"int8 prefill M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, "w8c")
+    wq, sw = synth.weights(4000, M, N, fc)
+    wq.flat[0] = -128
+    x = synth.activations(4000, M, N, M, K)
+    xq_ref, sx_ref, acc_ref, y_ref = oracle.fc_int8_act(x, wq, sw)
+    layer = _layer(wq, sw, "w8c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    xq_d = torch.from_numpy(xq_ref).to(DEV)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    binding.qfc_forward_acc_i32(layer.handle, xq_d, acc)
+    torch.cuda.synchronize()
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref)
+    y = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    binding.qfc_forward_q8(layer.handle, xq_d, torch.from_numpy(sx_ref).to(DEV), y)
+    torch.cuda.synchronize()
+    assert oracle.floored_rel_error(y.cpu().numpy(), y_ref) <= TOL
+    y2 = _forward(layer, x)  # quantization kernel + product + epilogue in one call
+    assert oracle.floored_rel_error(y2, y_ref) <= TOL
+    layer.close()
+
+
+def test_int8_prefill_config4_shapes_sampled():
+    """Llama layer at M = 1024, int8 per-channel weights: accumulators of a
+    sample of (token, channel) pairs against the exact integer contraction."""
+    rng = np.random.default_rng(4)
+    M = 1024
+    for i, fc in enumerate(synth.LLAMA_FCS_W8):
+        print(f"config 4 {fc.name} {fc.K}->{fc.N}", flush=True)
+        wq, sw = synth.weights(1004, 0, i, fc)
+        x = synth.activations(1004, 0, i, M, fc.K)
+        layer = _layer(wq, sw, "w8c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+        xd = torch.from_numpy(x).to(DEV)
+        xq = torch.empty((M, fc.K), dtype=torch.int8, device=DEV)
+        sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+        binding.qfc_quantize_activations(xd, xq, sx)
+        acc = torch.empty((M, fc.N), dtype=torch.int32, device=DEV)
+        binding.qfc_forward_acc_i32(layer.handle, xq, acc)
+        y = layer.forward(xd)
+        torch.cuda.synchronize()
+        xq_ref, sx_ref = oracle.quantize_activations(x)
+        assert np.array_equal(xq.cpu().numpy(), xq_ref)
+        assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+        rows = np.sort(rng.choice(M, size=48, replace=False))
+        cols = np.sort(rng.choice(fc.N, size=384, replace=False))
+        rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, fc.N - 1
+        acc_ref = oracle.int_contract(xq_ref[rows], wq[cols])
+        got = acc.cpu().numpy()[np.ix_(rows, cols)].astype(np.int64)
+        assert np.array_equal(got, acc_ref)
+        y_ref = oracle.rescale(acc_ref, sx_ref[rows], sw[cols])
+        assert oracle.floored_rel_error(y.cpu().numpy()[np.ix_(rows, cols)], y_ref) <= TOL
+        layer.close()
+        del wq
+
+
+# ------------------------------------------------------------------ A6 fp16 MFMA prefill with in-LDS dequantization
+@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (130, 1000, 2304)])
+def test_fp16_prefill_matches_oracle(M, N, K):
+    print(f"fp16 prefill M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, "w4g32")
+    wq, s = synth.weights(5000, M, N, fc)
+    wq.flat[0] = -8
+    x = synth.activations(5000, M, N, M, K)
+    layer = _layer(wq, s, "w4g32", max_m=M)
+    y = _forward(layer, x)
+    ref = oracle.fc_weight_only(x, wq, s, 32)
+    assert oracle.floored_rel_error(y, ref) <= TOL
+    layer.close()
+
+
+def test_fp16_prefill_config5_shapes_sampled():
+    rng = np.random.default_rng(5)
+    M = 2048
+    for i, fc in enumerate(synth.GEMMA_FCS_W4):
+        print(f"config 5 {fc.name} {fc.K}->{fc.N}", flush=True)
+        wq, s = synth.weights(1005, 0, i, fc)
+        x = synth.activations(1005, 0, i, M, fc.K)
+        layer = _layer(wq, s, "w4g32", max_m=M)
+        y = _forward(layer, x)
+        rows = np.sort(rng.choice(M, size=64, replace=False))
+        cols = np.sort(rng.choice(fc.N, size=512, replace=False))
+        rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, fc.N - 1
+        ref = oracle.fc_weight_only(x[rows], wq[cols], s[cols], 32)
+        assert oracle.floored_rel_error(y[np.ix_(rows, cols)], ref) <= TOL
+        layer.close()
+
+
+def test_error_paths_on_device():
+    print("error paths", flush=True)
+    fc = synth.FC("t", 64, 64, "w4g32")
+    wq, s = synth.weights(6000, 0, 0, fc)
+    layer = _layer(wq, s, "w4g32")
+    x = torch.zeros((2, 64), dtype=torch.float16, device=DEV)
+    xq = torch.zeros((2, 64), dtype=torch.int8, device=DEV)
+    acc = torch.zeros((2, 64), dtype=torch.int32, device=DEV)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_forward_acc_i32(layer.handle, xq, acc)  # int8 product needs int8 per-channel weights
+    assert e.value.code == 2
+    small = torch.zeros(256, dtype=torch.uint8, device=DEV)
+    big = synth.FC("t", 14336, 64, "w4g32")
+    wq2, s2 = synth.weights(6001, 0, 0, big)
+    layer2 = _layer(wq2, s2, "w4g32")
+    binding.qfc_bind_workspace(layer2.handle, small)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_forward(layer2.handle, torch.zeros((1, 14336), dtype=torch.float16, device=DEV),
+                            torch.zeros((1, 64), dtype=torch.float16, device=DEV))
+    assert e.value.code == 3
+    layer.close()
+    layer2.close()
+    del x
