@@ -92,13 +92,14 @@ qfc_status_t qfc_pack_weights(const qfc_desc_t *desc, const int8_t *wq_logical,
  * scales, bit for bit what qfc_pack_weights was given. */
 qfc_status_t qfc_unpack_weights(qfc_handle_t h, int8_t *wq_logical, void *scales, void *stream);
 
-/* Scratch a forward call with up to M token rows needs (partial sums of a
- * K-split, quantized activations).  `bytes` is a host pointer. */
+/* Scratch a forward call with up to M token rows needs (the tiled int8
+ * activations and their scales of the int8 prefill path; at least 256 bytes).
+ * `bytes` is a host pointer. */
 qfc_status_t qfc_workspace_size(qfc_handle_t h, int32_t M, size_t *bytes);
 
-/* Lend a workspace to the handle.  Enqueues the one-time clearing of its
- * counters on `stream`.  One workspace may be bound to many handles as long as
- * their calls do not overlap. */
+/* Lend a workspace to the handle (nothing is enqueued; `stream` is reserved).
+ * One workspace may be bound to many handles as long as their calls do not
+ * overlap. */
 qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes, void *stream);
 
 /* Activation quantization kernel of the prefill stage (section 3.7): per token
@@ -111,7 +112,8 @@ qfc_status_t qfc_quantize_activations(const void *x_f16, int32_t M, int32_t K,
 /* y[M,N] = x[M,K] . dequant(W)^T, binary16 in, fp32 accumulation, binary16 out.
  * M <= 8: decode kernel (weights dequantized in registers).  M > 8: the path
  * `compute_mode` names; QFC_COMPUTE_INT8_ACT quantizes x per token into the
- * bound workspace first.  Needs a bound workspace of qfc_workspace_size(h, M). */
+ * bound workspace first: that path needs a bound workspace of
+ * qfc_workspace_size(h, M) bytes; the others use none. */
 qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream);
 
 /* Prefill product on already quantized activations (int8 per-channel weights

@@ -6,9 +6,9 @@
 // An all-zero row gives sx = 0 and xq = 0.
 //
 // Output either row-major [M, K] (the public entry point) or tiled for the
-// int8 product: rows in blocks of 64, K in chunks of 16, one KiB tile per
-// (row block, chunk) with row r of the block at bytes 16r..16r+15, tiles stored
-// [row block][chunk], padded with zeros to [Mp, Kp].
+// int8 product exactly like the int8 weights: KiB tiles of 16 token rows x 64 k,
+// lane (c, q) of a tile = the 16 codes (row c, k = 16q .. 16q+15), tiles stored
+// [row tile][k tile], padded with zeros to [Mp, Kp].
 #include "qfc_internal.h"
 
 namespace qfc {
@@ -77,7 +77,7 @@ __global__ __launch_bounds__(256) void act_quant_kernel(const uint4 *__restrict_
             out = make_uint4(quant4(v, inv), quant4(v + 4, inv), quant4(v + 8, inv), quant4(v + 12, inv));
         }
         if (kTiled)
-            xq[((size_t)(m >> 6) * (Kp / 16) + c) * 64 + (m & 63)] = out;
+            xq[((size_t)(m >> 4) * (Kp / 64) + (c >> 2)) * 64 + (c & 3) * 16 + (m & 15)] = out;
         else
             xq[(size_t)m * (K / 16) + c] = out;
     }
@@ -88,10 +88,11 @@ __global__ __launch_bounds__(256) void retile_xq_kernel(const uint4 *__restrict_
     const size_t total = (size_t)Mp * (Kp / 16);
     const size_t v = (size_t)blockIdx.x * 256 + threadIdx.x;
     if (v >= total) return;
-    const int r = (int)(v % 64);
+    const int lane = (int)(v % 64);
     const size_t tile = v / 64;
-    const int c = (int)(tile % (Kp / 16));
-    const int m = (int)(tile / (Kp / 16)) * 64 + r;
+    const int kt = (int)(tile % (Kp / 64));
+    const int m = (int)(tile / (Kp / 64)) * 16 + (lane & 15);
+    const int c = kt * 4 + (lane >> 4);
     uint4 out = make_uint4(0, 0, 0, 0);
     if (m < M && c * 16 < K) out = xq[(size_t)m * (K / 16) + c];
     tiled[v] = out;

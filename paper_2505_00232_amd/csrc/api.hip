@@ -48,22 +48,14 @@ bool valid(qfc_handle_t h) { return h && h->magic == kMagic; }
 
 int prefill_rows(int M) { return round_up(M, 256); }
 
-size_t ticket_region(const Geometry &g) { return (size_t)round_up(g.RB * 4, 256); }
-
+// Workspace: the tiled int8 activations and their scales (int8 weights only).
 size_t int8_region(const Geometry &g, int M) {
     const size_t Mp = (size_t)prefill_rows(M);
     return Mp * (size_t)g.Kp + Mp * sizeof(float);
 }
 
 size_t workspace_need(qfc_handle_t h, int M) {
-    size_t need = ticket_region(h->geo);
-    size_t body = 0;
-    if (M <= kMaxDecodeM) body = gemv_workspace_bytes(h->geo, M, h->num_cus) - ticket_region(h->geo);
-    if (h->geo.fmt == kW8C) {
-        const size_t b = int8_region(h->geo, M);
-        if (b > body) body = b;
-    }
-    return need + body;
+    return h->geo.fmt == kW8C ? int8_region(h->geo, M) : 256;
 }
 
 qfc_status_t hip_status(hipError_t e) { return e == hipSuccess ? QFC_OK : QFC_ERR_HIP; }
@@ -76,7 +68,7 @@ qfc_status_t stage_xq(qfc_handle_t h, const int8_t *xq, int M, int8_t **tiled, f
     if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
     if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     const int Mp = prefill_rows(M);
-    char *body = static_cast<char *>(h->workspace) + ticket_region(h->geo);
+    char *body = static_cast<char *>(h->workspace);
     *tiled = reinterpret_cast<int8_t *>(body);
     *sx_ws = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
     return hip_status(launch_retile_xq(xq, M, h->geo.K, *tiled, Mp, h->geo.Kp, st));
@@ -139,9 +131,8 @@ qfc_status_t qfc_workspace_size(qfc_handle_t h, int32_t M, size_t *bytes) {
 qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes, void *stream) {
     if (!valid(h) || !workspace) return QFC_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return QFC_ERR_ALIGNMENT;
-    const size_t t = ticket_region(h->geo);
-    if (bytes < t) return QFC_ERR_BUFFER_TOO_SMALL;
-    if (hipMemsetAsync(workspace, 0, t, static_cast<hipStream_t>(stream)) != hipSuccess) return QFC_ERR_HIP;
+    (void)stream;
+    if (bytes < 256) return QFC_ERR_BUFFER_TOO_SMALL;
     h->workspace = workspace;
     h->workspace_bytes = bytes;
     return QFC_OK;
@@ -162,12 +153,12 @@ qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f
         if (h->geo.fmt != kW4G32) return QFC_ERR_UNSUPPORTED;
         return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, st));
     }
-    if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     if (M <= kMaxDecodeM)
-        return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, h->workspace, h->num_cus, st));
+        return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
+    if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     // int8 activations: quantize into the workspace (tiled), multiply, rescale
     const int Mp = prefill_rows(M);
-    char *body = static_cast<char *>(h->workspace) + ticket_region(h->geo);
+    char *body = static_cast<char *>(h->workspace);
     int8_t *tiled = reinterpret_cast<int8_t *>(body);
     float *sx = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
     if (launch_act_quant(x_f16, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, st) != hipSuccess) return QFC_ERR_HIP;
@@ -227,12 +218,12 @@ const char *qfc_status_string(qfc_status_t s) {
 }
 
 // Tuning knob for experiments (not part of the documented interface):
-// key 0 = target wavefronts of a decode launch, 1 = max wavefronts per
-// workgroup, 2 = prefill kernel variant.
+// key 0 = target wavefronts of a decode launch, 1 = max row tiles per
+// decode workgroup, 2 = prefill kernel variant.
 void qfc_tune(int32_t key, int32_t value) {
     Tuning &t = tuning();
     if (key == 0) t.gemv_target_waves = value;
-    if (key == 1) t.gemv_max_waves_per_wg = value;
+    if (key == 1) t.gemv_max_row_tiles = value;
     if (key == 2) t.gemm_variant = value;
 }
 

@@ -4,11 +4,11 @@
 //   acc[m,n] = sum_k xq[m,k] * Wq[n,k]        (int32, exact)
 //   y[m,n]   = fp16(float(acc) * sx[m] * sw[n])
 //
-// Both operands arrive tiled the same way (64 rows x 16 k per KiB tile, lane r
-// of a wavefront load = row r), so a stage of the K loop is a verbatim,
-// fully coalesced copy of KiB tiles into LDS, and an MFMA operand fragment
-// (32 rows x 32 k, lane = row + 32 * (k / 16)) is two runs of 512 contiguous
-// LDS bytes: bank-conflict free without padding or swizzling.
+// Both operands arrive tiled the same way (KiB tiles of 16 rows x 64 k, lane
+// (c, q) = 16 codes of row c at k = 16q), so a stage of the K loop is a
+// verbatim, fully coalesced copy of KiB tiles into LDS, and an MFMA operand
+// fragment (32 rows x 32 k, lane = row + 32 * (k / 16)) is made of runs of 256
+// contiguous LDS bytes: bank-conflict free without padding or swizzling.
 //
 // Workgroup: 256 threads = 4 wavefronts in a 2 x 2 grid over a BN x BM tile
 // (weights rows x token rows); each wavefront owns (BN/2) x (BM/2) outputs as
@@ -27,8 +27,8 @@ constexpr int BK = 128;            // k per stage
 constexpr int KCH = BK / 16;       // 16-byte chunks per row per stage
 
 struct GemmI8Args {
-    const uint4 *w;      // packed weights, tiles [rb][Kp/16][64]
-    const uint4 *x;      // tiled activations, tiles [mb][Kp/16][64]
+    const uint4 *w;      // packed weights, tiles [row tile][Kp/64][64]
+    const uint4 *x;      // tiled activations, tiles [row tile][Kp/64][64]
     const float *sw;     // [Np]
     const float *sx;     // [Mp] (null for raw accumulators)
     void *out;
@@ -57,22 +57,24 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
     if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
     const int nt = logical / a.m_tiles;
     const int mt = logical % a.m_tiles;
-    const int KC = a.Kp / 16;
+    const int KT = a.Kp / 64;  // k tiles per row tile
+    constexpr int KTS = BK / 64;  // k tiles per stage
 
-    // global source of this thread's vectors for stage 0
+    // global source of this thread's vectors for stage 0 (LDS vector v = tile * 64 + lane,
+    // tile = row tile of the block * KTS + k tile of the stage)
     const uint4 *wsrc[W_LD];
     const uint4 *xsrc[X_LD];
 #pragma unroll
     for (int i = 0; i < W_LD; ++i) {
         const int v = tid + 256 * i;
-        const int rbl = v / (KCH * 64), c = (v / 64) % KCH, r = v % 64;
-        wsrc[i] = a.w + ((size_t)(nt * (BN / 64) + rbl) * KC + c) * 64 + r;
+        const int rtl = v / (KTS * 64), ktl = (v / 64) % KTS, ln = v % 64;
+        wsrc[i] = a.w + ((size_t)(nt * (BN / 16) + rtl) * KT + ktl) * 64 + ln;
     }
 #pragma unroll
     for (int i = 0; i < X_LD; ++i) {
         const int v = tid + 256 * i;
-        const int rbl = v / (KCH * 64), c = (v / 64) % KCH, r = v % 64;
-        xsrc[i] = a.x + ((size_t)(mt * (BM / 64) + rbl) * KC + c) * 64 + r;
+        const int rtl = v / (KTS * 64), ktl = (v / 64) % KTS, ln = v % 64;
+        xsrc[i] = a.x + ((size_t)(mt * (BM / 16) + rtl) * KT + ktl) * 64 + ln;
     }
 
     v16i acc[TN][TM];
@@ -98,7 +100,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
         for (int i = 0; i < X_LD; ++i) lds_x[tid + 256 * i] = xreg[i];
         __syncthreads();
         if (kt + 1 < stages) {
-            const size_t adv = (size_t)(kt + 1) * KCH * 64;
+            const size_t adv = (size_t)(kt + 1) * KTS * 64;
 #pragma unroll
             for (int i = 0; i < W_LD; ++i) wreg[i] = wsrc[i][adv];
 #pragma unroll
@@ -106,17 +108,18 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
         }
 #pragma unroll
         for (int ks = 0; ks < BK / 32; ++ks) {
-            const int c = 2 * ks + (lane >> 5);
+            const int kc = 2 * ks + (lane >> 5);           // 16-code chunk inside the stage
+            const int koff = (kc >> 2) * 64 + (kc & 3) * 16;  // k tile and quarter
             v4i fa[TN], fb[TM];
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
                 const int row = wn * WN + i * 32 + (lane & 31);
-                fa[i] = __builtin_bit_cast(v4i, lds_w[((row >> 6) * KCH + c) * 64 + (row & 63)]);
+                fa[i] = __builtin_bit_cast(v4i, lds_w[(row >> 4) * (KTS * 64) + koff + (row & 15)]);
             }
 #pragma unroll
             for (int j = 0; j < TM; ++j) {
                 const int row = wm * WM + j * 32 + (lane & 31);
-                fb[j] = __builtin_bit_cast(v4i, lds_x[((row >> 6) * KCH + c) * 64 + (row & 63)]);
+                fb[j] = __builtin_bit_cast(v4i, lds_x[(row >> 4) * (KTS * 64) + koff + (row & 15)]);
             }
 #pragma unroll
             for (int i = 0; i < TN; ++i)

@@ -3,16 +3,24 @@
 // the paper), here with binary16 activations and the weights dequantized in
 // registers.
 //
-// Mapping.  A wavefront owns 64 output rows (lane = row) and a contiguous range
-// of K.  Every 16-byte lane load is one contiguous KiB for the wavefront; the
-// activations of the current k range are the same for all 64 lanes, so they are
-// read through the scalar unit and used as scalar operands of v_dot2_f32_f16.
-// No lane ever needs another lane's data: there is no cross-lane reduction in
-// the streaming loop.  K is split over the wavefronts of a workgroup (summed in
-// LDS, fixed order) and, when there are too few row blocks to fill 256 CUs,
-// over several workgroups (fp32 partials in the workspace, summed in fixed
-// order by the workgroup that arrives last; no floating-point atomics, so the
-// result is deterministic).
+// Mapping.  A wavefront streams KiB tiles of 16 output rows (one 16-byte load
+// per lane, one contiguous KiB per wavefront load, several loads in flight),
+// converts the codes to binary16 in registers (exactly) and feeds them to
+// v_mfma_f32_16x16x32_f16 as the B operand; the A operand holds the token rows
+// (rows >= M are zero).  The MFMA does the reduction across the lanes of the
+// wavefront that a dot-product formulation would need DPP shuffles for, its
+// cost does not depend on M, and the matrix pipe is idle in a bandwidth-bound
+// kernel anyway.  For int4 group-quantized weights every MFMA covers exactly
+// one quantization group, and its fp32 result is scaled and accumulated with
+// one FMA per token row; int8 per-channel weights accumulate inside the MFMA
+// and are scaled once at the end.
+//
+// Activations of the k range a wavefront is working on are staged in a private
+// LDS region in A-operand order (no workgroup barrier in the streaming loop).
+// A workgroup owns 1..4 consecutive row tiles (which share the staged
+// activations) and splits K over its wavefronts; their partial sums meet in
+// LDS in fixed order, so results are deterministic.  There is no reduction
+// across workgroups and no atomics.
 #include "qfc_internal.h"
 
 namespace qfc {
@@ -22,315 +30,299 @@ Tuning &tuning() {
     return t;
 }
 
+static int wave_cap(int M) { return M > 4 ? 4 : 8; }
+
 GemvPlan plan_gemv(const Geometry &g, int M, int num_cus) {
-    (void)M;
     (void)num_cus;
-    GemvPlan p;
-    p.units = g.fmt == kW8C ? (g.K + 127) / 128 : (g.K + 255) / 256;
     const Tuning &t = tuning();
-    int per_rb = (t.gemv_target_waves + g.RB - 1) / g.RB;
-    if (per_rb < 1) per_rb = 1;
-    if (per_rb > p.units) per_rb = p.units;
-    int maxw = t.gemv_max_waves_per_wg;
-    if (maxw > 8) maxw = 8;  // LDS reduction buffer holds 8 wavefronts
-    if (maxw < 1) maxw = 1;
-    p.splits = (per_rb + maxw - 1) / maxw;
-    p.waves = (per_rb + p.splits - 1) / p.splits;
+    GemvPlan p;
+    const int cap = wave_cap(M);
+    const int per_wave = (g.KU + cap - 1) / cap;  // units per wavefront
+    p.waves = (g.KU + per_wave - 1) / per_wave;
+    const long waves_total = (long)g.RT * p.waves;
+    int r = (int)((waves_total + t.gemv_target_waves - 1) / t.gemv_target_waves);
+    if (r > t.gemv_max_row_tiles) r = t.gemv_max_row_tiles;
+    if (r > 4) r = 4;
+    if (r < 1) r = 1;
+    p.row_tiles = r;
     return p;
-}
-
-static size_t ticket_bytes(const Geometry &g) { return (size_t)round_up(g.RB * 4, 256); }
-
-size_t gemv_workspace_bytes(const Geometry &g, int M, int num_cus) {
-    const GemvPlan p = plan_gemv(g, M, num_cus);
-    size_t b = ticket_bytes(g);
-    if (p.splits > 1) b += (size_t)p.splits * M * g.RB * 64 * sizeof(float);
-    return b;
 }
 
 namespace {
 
 typedef _Float16 h2 __attribute__((ext_vector_type(2)));
+typedef _Float16 v8h __attribute__((ext_vector_type(8)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
+__device__ __forceinline__ uint32_t as_u32(h2 h) { return __builtin_bit_cast(uint32_t, h); }
 
-__device__ __forceinline__ float dot2(h2 a, h2 b, float c) {
-    return __builtin_amdgcn_fdot2(a, b, c, false);
+// Eight biased int4 codes of one dword -> eight binary16 values, k ascending,
+// exactly.  A byte permute puts a code byte under the high byte 0x64:
+// 0x6400 | u is 1024 + u and 0x6400 | (u << 4) is 1024 + 16 u, both exact in
+// binary16, as are the subtraction of 1032 and the fused (x / 16 - 72).
+// (Plain C only: hand-placed VALU instructions next to MFMAs would escape the
+// compiler's hazard tracking.)
+__device__ __forceinline__ v8h dequant8(uint32_t w) {
+    const h2 c1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
+    const h2 c72 = {(_Float16)72.0f, (_Float16)72.0f};
+    const h2 c16th = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const uint32_t lo = w & 0x0F0F0F0Fu, hi = w & 0xF0F0F0F0u;
+    const h2 p0 = as_h2(__builtin_amdgcn_perm(0x64646464u, lo, 0x04010400u)) - c1032;
+    const h2 p1 = as_h2(__builtin_amdgcn_perm(0x64646464u, lo, 0x04030402u)) - c1032;
+    const h2 p2 = as_h2(__builtin_amdgcn_perm(0x64646464u, hi, 0x04010400u)) * c16th - c72;
+    const h2 p3 = as_h2(__builtin_amdgcn_perm(0x64646464u, hi, 0x04030402u)) * c16th - c72;
+    const u32x4 r = {as_u32(p0), as_u32(p1), as_u32(p2), as_u32(p3)};
+    return __builtin_bit_cast(v8h, r);
 }
 
-__device__ __forceinline__ float f16_bits_to_f32(uint32_t bits) {
-    return (float)__builtin_bit_cast(_Float16, (uint16_t)bits);
+// Eight int8 codes (two dwords) -> eight binary16 values, exactly: flipping the
+// sign bit gives b + 128 in [0, 255]; 0x64 in the high byte makes 1024 + that.
+__device__ __forceinline__ v8h dequant_i8x8(uint32_t lo, uint32_t hi) {
+    const h2 c1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
+    const uint32_t a = lo ^ 0x80808080u, b = hi ^ 0x80808080u;
+    const h2 p0 = as_h2(__builtin_amdgcn_perm(0x64646464u, a, 0x04010400u)) - c1152;
+    const h2 p1 = as_h2(__builtin_amdgcn_perm(0x64646464u, a, 0x04030402u)) - c1152;
+    const h2 p2 = as_h2(__builtin_amdgcn_perm(0x64646464u, b, 0x04010400u)) - c1152;
+    const h2 p3 = as_h2(__builtin_amdgcn_perm(0x64646464u, b, 0x04030402u)) - c1152;
+    const u32x4 r = {as_u32(p0), as_u32(p1), as_u32(p2), as_u32(p3)};
+    return __builtin_bit_cast(v8h, r);
 }
 
 struct GemvArgs {
     const u32x4 *packed;
-    const uint32_t *x;  // binary16 pairs, [M, K/2]
+    const u32x4 *x;     // binary16 [M, K] as 16-byte vectors (8 values)
     _Float16 *y;        // [M, N]
     const float *sw;    // W8C scales [Np]
-    float *partial;     // [splits][M][RB*64]
-    unsigned *tickets;  // [RB]
-    int N, K, units_q, units_rem, waves, splits, units_stride, ld;
+    int N, K, RT, KT, KU, rt_stride;
+    int row_tiles;           // R: row tiles per workgroup
+    int units_q, units_rem;  // KU = units_q * waves + units_rem
 };
 
-// Sum the per-wavefront partials in LDS, then either store y or hand the
-// workgroup's partial to the cross-workgroup reduction.
-template <int M, bool kPerChannelScale>
-__device__ __forceinline__ void finish(const GemvArgs &a, float (&acc)[M], int rb, int split, int wave,
-                                       int lane) {
-    __shared__ float red[kMaxDecodeM * 8 * 64];
-    if (a.waves > 1) {
+// LDS view of one wavefront's staged activations: vector (slot * M + m).
+// W4G32 unit: 1024 k = 128 octets, slot = octet index (4 * group + q).
+// W8C unit:    512 k =  64 octets, slot = tile * 8 + j * 4 + q for octet 2q + j of the tile.
+template <int M, int FMT>
+__device__ __forceinline__ void stage_x(const GemvArgs &a, u32x4 *lds, int unit, int lane) {
+    constexpr int OCT = FMT == kW4G32 ? 128 : 64;  // octets per unit
+    const int K8 = a.K / 8;
+    const int o_base = unit * OCT;
 #pragma unroll
-        for (int m = 0; m < M; ++m) red[(wave * M + m) * 64 + lane] = acc[m];
-        __syncthreads();
-    }
-    if (wave != 0) return;
-    if (a.waves > 1) {
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            float s = red[m * 64 + lane];
-            for (int w = 1; w < a.waves; ++w) s += red[(w * M + m) * 64 + lane];
-            acc[m] = s;
-        }
-    }
-    const int n = rb * 64 + lane;
-    const int ld = a.ld;  // RB * 64
-    if (a.splits > 1) {
-        // Publish this workgroup's partial, then take a ticket; the workgroup that
-        // draws the last ticket of the row block sums all partials in split order.
-#pragma unroll
-        for (int m = 0; m < M; ++m) a.partial[(size_t)(split * M + m) * ld + n] = acc[m];
-        __threadfence();
-        unsigned last = 0;
-        if (lane == 0) last = atomicAdd(&a.tickets[rb], 1u) == (unsigned)(a.splits - 1) ? 1u : 0u;
-        last = __builtin_amdgcn_readfirstlane(last);
-        if (!last) return;
-        __threadfence();
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            float s = 0.0f;
-            for (int sp = 0; sp < a.splits; ++sp) s += a.partial[(size_t)(sp * M + m) * ld + n];
-            acc[m] = s;
-        }
-        if (lane == 0) a.tickets[rb] = 0u;  // ready for the next call on this workspace
-    }
-    if (n < a.N) {
-        float sc = 1.0f;
-        if (kPerChannelScale) sc = a.sw[n];
-#pragma unroll
-        for (int m = 0; m < M; ++m) a.y[(size_t)m * a.N + n] = (_Float16)(acc[m] * sc);
+    for (int i = 0; i < M * OCT / 64; ++i) {
+        const int p = i * 64 + lane;
+        const int m = p / OCT, o = p % OCT;
+        u32x4 v = {0, 0, 0, 0};
+        if (o_base + o < K8) v = a.x[(size_t)m * K8 + o_base + o];
+        int slot = o;
+        if (FMT == kW8C) slot = (o & ~7) | ((o & 1) << 2) | ((o >> 1) & 3);
+        lds[slot * M + m] = v;
     }
 }
 
-// ---------------------------------------------------------------- W4G32
-// Eight biased int4 codes of one dword -> four binary16 pairs (k-adjacent),
-// exactly: 0x6400 | u is 1024 + u, 0x6400 | (u << 4) is 1024 + 16 u.
-// (w & mask) | magic in one VALU instruction; the compiler emits two otherwise.
-__device__ __forceinline__ uint32_t and_or(uint32_t w, uint32_t mask, uint32_t magic) {
-    uint32_t r;
-    asm("v_and_or_b32 %0, %1, %2, %3" : "=v"(r) : "v"(w), "s"(mask), "v"(magic));
-    return r;
-}
+template <int M, int FMT>
+__global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
+    constexpr int TILES = 8;                    // weight tiles per unit
+    constexpr int NV = FMT == kW4G32 ? 12 : 8;  // 16-byte vectors per lane per (unit, row tile)
+    constexpr int OCT = FMT == kW4G32 ? 128 : 64;
+    constexpr int MI = M < 4 ? M : 4;           // accumulator rows that matter on a lane
+    extern __shared__ u32x4 lds_all[];
 
-__device__ __forceinline__ void dequant8(uint32_t w, h2 (&p)[4]) {
-    const uint32_t magic = 0x64006400u;
-    const h2 c1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
-    const h2 c72 = {(_Float16)72.0f, (_Float16)72.0f};
-    const h2 c16th = {(_Float16)0.0625f, (_Float16)0.0625f};
-    const uint32_t ws = w >> 8;
-    p[0] = as_h2(and_or(w, 0x000F000Fu, magic)) - c1032;
-    p[1] = as_h2(and_or(w, 0x00F000F0u, magic)) * c16th - c72;
-    p[2] = as_h2(and_or(ws, 0x000F000Fu, magic)) - c1032;
-    p[3] = as_h2(and_or(ws, 0x00F000F0u, magic)) * c16th - c72;
-}
-
-template <int M>
-__device__ __forceinline__ void w4_group(const u32x4 &wv, uint32_t scale_bits, const uint32_t *xg, int K2,
-                                         float (&acc)[M]) {
-    float part[M];
-#pragma unroll
-    for (int m = 0; m < M; ++m) part[m] = 0.0f;
-    const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        h2 p[4];
-        dequant8(wd[d], p);
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const uint32_t *xm = xg + (size_t)m * K2 + d * 4;
-#pragma unroll
-            for (int i = 0; i < 4; ++i) part[m] = dot2(p[i], as_h2(xm[i]), part[m]);
-        }
-    }
-    const float s = f16_bits_to_f32(scale_bits);
-#pragma unroll
-    for (int m = 0; m < M; ++m) acc[m] = fmaf(s, part[m], acc[m]);
-}
-
-template <int M>
-__global__ __launch_bounds__(512) void gemv_w4g32_kernel(GemvArgs a) {
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rb = blockIdx.y;
-    const int split = blockIdx.x;
-    const int t = split * a.waves + wave;
-    // units = q * slots + rem: the first rem slots take q + 1 units
-    const int u0 = t * a.units_q + (t < a.units_rem ? t : a.units_rem);
-    const int u1 = u0 + a.units_q + (t < a.units_rem ? 1 : 0);
-    const int Kg = a.K / 32;
-    const int K2 = a.K / 2;
+    const int nwaves = blockDim.x >> 6;
+    const int c = lane & 15, q = lane >> 4;
+    const int rt0 = blockIdx.x * a.row_tiles;
+    const int R = min(a.row_tiles, a.RT - rt0);
+    const int u0 = wave * a.units_q + min(wave, a.units_rem);
+    const int u1 = u0 + a.units_q + (wave < a.units_rem ? 1 : 0);
+    u32x4 *lds_x = lds_all + wave * (OCT * M);
 
-    float acc[M];
+    float acc[4][4];
 #pragma unroll
-    for (int m = 0; m < M; ++m) acc[m] = 0.0f;
+    for (int r = 0; r < 4; ++r)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) acc[r][i] = 0.0f;
 
-    const u32x4 *p = a.packed + ((size_t)rb * a.units_stride + u0) * kW4UnitVecs + lane;
-    u32x4 cur[9];
-    if (u0 < u1) {
+    // item = (unit, row tile); its vectors: weight tiles 0..nt-1, then (W4G32) 4 scale vectors
+    auto load_item = [&](u32x4(&buf)[NV], int u, int r) {
+        const int nt = min(TILES, a.KT - TILES * u);
+        const int pos = FMT == kW4G32 ? 9 * u : TILES * u;
+        const u32x4 *base = a.packed + ((size_t)(rt0 + r) * a.rt_stride + pos) * 64;
 #pragma unroll
-        for (int j = 0; j < 9; ++j) cur[j] = __builtin_nontemporal_load(p + j * 64);
-    }
-    for (int u = u0; u < u1; ++u) {
-        u32x4 nxt[9];
-        p += kW4UnitVecs;
-        if (u + 1 < u1) {
+        for (int t = 0; t < TILES; ++t)
+            if (t < nt) buf[t] = __builtin_nontemporal_load(base + t * 64 + lane);
+        if (FMT == kW4G32) {
 #pragma unroll
-            for (int j = 0; j < 9; ++j) nxt[j] = __builtin_nontemporal_load(p + j * 64);
+            for (int p = 0; p < 4; ++p)
+                buf[TILES + p] = __builtin_nontemporal_load(base + nt * 64 + p * 16 + c);
         }
-        const uint32_t sc[4] = {cur[8].x, cur[8].y, cur[8].z, cur[8].w};
-        const uint32_t *xu = a.x + (size_t)u * 128;  // 256 k = 128 pairs
-        if (u * 8 + 8 <= Kg) {
+    };
+
+    u32x4 cur[NV], nxt[NV];
+    const int items = (u1 - u0) * R;
+    if (items > 0) load_item(cur, u0, 0);
+    int u = u0, r = 0;
+    for (int it = 0; it < items; ++it) {
+        if (r == 0) {
+            // new unit: the wavefront's earlier LDS reads are done (same wavefront, in order)
+            stage_x<M, FMT>(a, lds_x, u, lane);
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        int un = u, rn = r + 1;
+        if (rn == R) {
+            rn = 0;
+            un = u + 1;
+        }
+        if (it + 1 < items) load_item(nxt, un, rn);
+
+        const int nt = min(TILES, a.KT - TILES * u);
+        float accr[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+        v4f accw = {0.0f, 0.0f, 0.0f, 0.0f};
+        // A operands (token rows) of one tile; lanes whose row index is >= M read
+        // row c % M instead: an A row only feeds the D row of the same index, and
+        // D rows >= M are never used, so no masking or zeroing is needed.
+        constexpr int XA = FMT == kW4G32 ? 4 : 2;
+        const u32x4 *xrow = lds_x + q * M + (c % M);
+        auto load_xa = [&](v8h(&xa)[XA], int t) {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                w4_group<M>(cur[j], (sc[j >> 1] >> (16 * (j & 1))) & 0xFFFFu, xu + j * 16, K2, acc);
+            for (int j = 0; j < XA; ++j)
+                xa[j] = __builtin_bit_cast(v8h, xrow[(FMT == kW4G32 ? (4 * t + j) * 4 : t * 8 + j * 4) * M]);
+        };
+        // The scaled accumulation of an MFMA result is issued one step late, after the
+        // next MFMA has been started, so that its latency is covered by the next
+        // step's dequantization instead of a stall.
+        v4f d_prev = {0.0f, 0.0f, 0.0f, 0.0f};
+        _Float16 s_prev = (_Float16)0.0f;
+        auto tile_math = [&](const v8h(&xa)[XA], int t) {
+            if (FMT == kW4G32) {
+                const uint32_t wd[4] = {cur[t].x, cur[t].y, cur[t].z, cur[t].w};
+#pragma unroll
+                for (int j = 0; j < 4; ++j) {
+                    const int gl = 4 * t + j;  // group inside the unit
+                    const v8h wb = dequant8(wd[j]);
+                    const v4f zero = {0.0f, 0.0f, 0.0f, 0.0f};
+                    const v4f d = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[j], wb, zero, 0, 0, 0);
+#pragma unroll
+                    for (int i = 0; i < MI; ++i) accr[i] = fmaf((float)s_prev, d_prev[i], accr[i]);
+                    const u32x4 sv = cur[TILES + gl / 8];
+                    const uint32_t sd = sv[(gl % 8) / 2];
+                    s_prev = __builtin_bit_cast(_Float16, (uint16_t)(sd >> (16 * (gl & 1))));
+                    d_prev = d;
+                }
+            } else {
+                accw = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[0], dequant_i8x8(cur[t].x, cur[t].y), accw, 0, 0, 0);
+                accw = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], dequant_i8x8(cur[t].z, cur[t].w), accw, 0, 0, 0);
+            }
+        };
+        if (nt == TILES) {
+            // full unit: straight-line code, A operands fetched one tile ahead
+            v8h xa[XA], xn[XA];
+            load_xa(xa, 0);
+#pragma unroll
+            for (int t = 0; t < TILES; ++t) {
+                if (t + 1 < TILES) load_xa(xn, t + 1);
+                tile_math(xa, t);
+#pragma unroll
+                for (int j = 0; j < XA; ++j) xa[j] = xn[j];
+            }
         } else {
 #pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (u * 8 + j < Kg)
-                    w4_group<M>(cur[j], (sc[j >> 1] >> (16 * (j & 1))) & 0xFFFFu, xu + j * 16, K2, acc);
+            for (int t = 0; t < TILES; ++t) {
+                if (t < nt) {
+                    v8h xa[XA];
+                    load_xa(xa, t);
+                    tile_math(xa, t);
+                }
+            }
         }
-        if (u + 1 < u1) {
+        if (FMT == kW4G32) {
 #pragma unroll
-            for (int j = 0; j < 9; ++j) cur[j] = nxt[j];
+            for (int i = 0; i < MI; ++i) accr[i] = fmaf((float)s_prev, d_prev[i], accr[i]);
+        }
+        // add this item's contribution to the accumulators of its row tile
+#pragma unroll
+        for (int rr = 0; rr < 4; ++rr)
+            if (rr == r) {
+#pragma unroll
+                for (int i = 0; i < MI; ++i) acc[rr][i] += FMT == kW4G32 ? accr[i] : accw[i];
+            }
+        if (it + 1 < items) {
+#pragma unroll
+            for (int v = 0; v < NV; ++v) cur[v] = nxt[v];
+        }
+        u = un;
+        r = rn;
+    }
+
+    // meet in LDS: red[wave][r][m][16 rows]; lane (c, q) holds token rows 4q .. 4q+3 of row c
+    __syncthreads();
+    float *red = reinterpret_cast<float *>(lds_all);
+#pragma unroll
+    for (int rr = 0; rr < 4; ++rr)
+#pragma unroll
+        for (int i = 0; i < MI; ++i) {
+            const int m = 4 * q + i;
+            if (rr < R && m < M) red[((wave * 4 + rr) * M + m) * 16 + c] = acc[rr][i];
+        }
+    __syncthreads();
+    for (int e = threadIdx.x; e < R * M * 16; e += blockDim.x) {
+        const int cc = e & 15, m = (e >> 4) % M, rr = (e >> 4) / M;
+        float s = 0.0f;
+        for (int w = 0; w < nwaves; ++w) s += red[((w * 4 + rr) * M + m) * 16 + cc];
+        const int n = (rt0 + rr) * 16 + cc;
+        if (n < a.N) {
+            if (FMT == kW8C) s *= a.sw[n];
+            a.y[(size_t)m * a.N + n] = (_Float16)s;
         }
     }
-    finish<M, false>(a, acc, rb, split, wave, lane);
-}
-
-// ---------------------------------------------------------------- W8C
-// Four int8 codes of one dword -> two binary16 pairs, exactly: flipping the
-// sign bit gives b + 128 in [0, 255]; 0x64 in the high byte makes 1024 + that.
-__device__ __forceinline__ void dequant4(uint32_t w, h2 (&p)[2]) {
-    const h2 c1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
-    const uint32_t wx = w ^ 0x80808080u;
-    p[0] = as_h2(__builtin_amdgcn_perm(0x64646464u, wx, 0x04010400u)) - c1152;
-    p[1] = as_h2(__builtin_amdgcn_perm(0x64646464u, wx, 0x04030402u)) - c1152;
-}
-
-template <int M>
-__device__ __forceinline__ void w8_chunk(const u32x4 &wv, const uint32_t *xc, int K2, float (&acc)[M]) {
-    const uint32_t wd[4] = {wv.x, wv.y, wv.z, wv.w};
-#pragma unroll
-    for (int d = 0; d < 4; ++d) {
-        h2 p[2];
-        dequant4(wd[d], p);
-#pragma unroll
-        for (int m = 0; m < M; ++m) {
-            const uint32_t *xm = xc + (size_t)m * K2 + d * 2;
-            acc[m] = dot2(p[0], as_h2(xm[0]), acc[m]);
-            acc[m] = dot2(p[1], as_h2(xm[1]), acc[m]);
-        }
-    }
-}
-
-template <int M>
-__global__ __launch_bounds__(512) void gemv_w8c_kernel(GemvArgs a) {
-    const int lane = threadIdx.x & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int rb = blockIdx.y;
-    const int split = blockIdx.x;
-    const int t = split * a.waves + wave;
-    // units = q * slots + rem: the first rem slots take q + 1 units
-    const int u0 = t * a.units_q + (t < a.units_rem ? t : a.units_rem);
-    const int u1 = u0 + a.units_q + (t < a.units_rem ? 1 : 0);
-    const int Kc = a.K / 16;
-    const int K2 = a.K / 2;
-
-    float acc[M];
-#pragma unroll
-    for (int m = 0; m < M; ++m) acc[m] = 0.0f;
-
-    // a unit is 8 chunks of 16 k; chunk tiles of one row block are contiguous
-    const u32x4 *p = a.packed + ((size_t)rb * a.units_stride + u0) * 8 * 64 + lane;
-    u32x4 cur[8];
-    if (u0 < u1) {
-#pragma unroll
-        for (int j = 0; j < 8; ++j) cur[j] = __builtin_nontemporal_load(p + j * 64);
-    }
-    for (int u = u0; u < u1; ++u) {
-        u32x4 nxt[8];
-        p += 8 * 64;
-        if (u + 1 < u1) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) nxt[j] = __builtin_nontemporal_load(p + j * 64);
-        }
-        const uint32_t *xu = a.x + (size_t)u * 64;  // 128 k = 64 pairs
-        if (u * 8 + 8 <= Kc) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) w8_chunk<M>(cur[j], xu + j * 8, K2, acc);
-        } else {
-#pragma unroll
-            for (int j = 0; j < 8; ++j)
-                if (u * 8 + j < Kc) w8_chunk<M>(cur[j], xu + j * 8, K2, acc);
-        }
-        if (u + 1 < u1) {
-#pragma unroll
-            for (int j = 0; j < 8; ++j) cur[j] = nxt[j];
-        }
-    }
-    finish<M, true>(a, acc, rb, split, wave, lane);
 }
 
 template <int M>
-hipError_t launch_m(const Geometry &g, const GemvArgs &a, dim3 grid, dim3 block, hipStream_t st) {
+hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t st) {
+    const dim3 grid((unsigned)((g.RT + a.row_tiles - 1) / a.row_tiles));
+    const dim3 block((unsigned)(waves * 64));
+    const int oct = g.fmt == kW4G32 ? 128 : 64;
+    size_t lds = (size_t)waves * oct * M * 16;
+    const size_t red = (size_t)waves * 4 * M * 16 * sizeof(float);
+    if (red > lds) lds = red;
     if (g.fmt == kW8C)
-        gemv_w8c_kernel<M><<<grid, block, 0, st>>>(a);
+        gemv_kernel<M, kW8C><<<grid, block, lds, st>>>(a);
     else
-        gemv_w4g32_kernel<M><<<grid, block, 0, st>>>(a);
+        gemv_kernel<M, kW4G32><<<grid, block, lds, st>>>(a);
     return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                       void *workspace, int num_cus, hipStream_t st) {
+                       int num_cus, hipStream_t st) {
     const GemvPlan p = plan_gemv(g, M, num_cus);
     GemvArgs a;
     a.packed = static_cast<const u32x4 *>(packed);
-    a.x = static_cast<const uint32_t *>(x);
+    a.x = static_cast<const u32x4 *>(x);
     a.y = static_cast<_Float16 *>(y);
     a.sw = reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off);
-    a.tickets = static_cast<unsigned *>(workspace);
-    a.partial = reinterpret_cast<float *>(static_cast<char *>(workspace) + ticket_bytes(g));
     a.N = g.N;
     a.K = g.K;
-    a.units_q = p.units / (p.splits * p.waves);
-    a.units_rem = p.units % (p.splits * p.waves);
-    a.ld = g.RB * 64;
-    a.waves = p.waves;
-    a.splits = p.splits;
-    a.units_stride = g.fmt == kW8C ? g.Kp / 128 : g.Kp / 256;
-    const dim3 grid((unsigned)p.splits, (unsigned)g.RB);
-    const dim3 block((unsigned)(p.waves * 64));
+    a.RT = g.RT;
+    a.KT = g.KT;
+    a.KU = g.KU;
+    a.rt_stride = g.rt_stride;
+    a.row_tiles = p.row_tiles;
+    a.units_q = g.KU / p.waves;
+    a.units_rem = g.KU % p.waves;
     switch (M) {
-        case 1: return launch_m<1>(g, a, grid, block, st);
-        case 2: return launch_m<2>(g, a, grid, block, st);
-        case 3: return launch_m<3>(g, a, grid, block, st);
-        case 4: return launch_m<4>(g, a, grid, block, st);
-        case 5: return launch_m<5>(g, a, grid, block, st);
-        case 6: return launch_m<6>(g, a, grid, block, st);
-        case 7: return launch_m<7>(g, a, grid, block, st);
-        case 8: return launch_m<8>(g, a, grid, block, st);
+        case 1: return launch_m<1>(g, a, p.waves, st);
+        case 2: return launch_m<2>(g, a, p.waves, st);
+        case 3: return launch_m<3>(g, a, p.waves, st);
+        case 4: return launch_m<4>(g, a, p.waves, st);
+        case 5: return launch_m<5>(g, a, p.waves, st);
+        case 6: return launch_m<6>(g, a, p.waves, st);
+        case 7: return launch_m<7>(g, a, p.waves, st);
+        case 8: return launch_m<8>(g, a, p.waves, st);
         default: return hipErrorInvalidValue;
     }
 }

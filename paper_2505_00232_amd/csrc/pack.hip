@@ -11,18 +11,17 @@ namespace {
 __global__ __launch_bounds__(256) void pack_w8c_kernel(const int8_t *__restrict__ wq,
                                                        const float *__restrict__ scales,
                                                        uint4 *__restrict__ packed, float *__restrict__ ps,
-                                                       int N, int K, int Np, int Kp) {
-    const int KC = Kp / 16;
-    const size_t total = (size_t)(Np / 64) * KC * 64;
+                                                       int N, int K, int Np, int KT) {
+    const size_t total = (size_t)(Np / 16) * KT * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (v < (size_t)Np) ps[v] = v < (size_t)N ? scales[v] : 0.0f;
     if (v >= total) return;
-    const int r = (int)(v % 64);
+    const int lane = (int)(v % 64);
     const size_t tile = v / 64;
-    const int kc = (int)(tile % KC);
-    const int rb = (int)(tile / KC);
-    const int n = rb * 64 + r;
-    const int k = kc * 16;
+    const int kt = (int)(tile % KT);
+    const int rt = (int)(tile / KT);
+    const int n = rt * 16 + (lane & 15);
+    const int k = kt * 64 + (lane >> 4) * 16;
     uint4 out = make_uint4(0, 0, 0, 0);
     if (n < N && k < K) out = *reinterpret_cast<const uint4 *>(wq + (size_t)n * K + k);
     packed[v] = out;
@@ -31,29 +30,29 @@ __global__ __launch_bounds__(256) void pack_w8c_kernel(const int8_t *__restrict_
 __global__ __launch_bounds__(256) void unpack_w8c_kernel(const uint4 *__restrict__ packed,
                                                          const float *__restrict__ ps,
                                                          int8_t *__restrict__ wq, float *__restrict__ scales,
-                                                         int N, int K, int Np, int Kp) {
-    const int KC = Kp / 16;
-    const size_t total = (size_t)(Np / 64) * KC * 64;
+                                                         int N, int K, int Np, int KT) {
+    const size_t total = (size_t)(Np / 16) * KT * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (v < (size_t)N) scales[v] = ps[v];
     if (v >= total) return;
-    const int r = (int)(v % 64);
+    const int lane = (int)(v % 64);
     const size_t tile = v / 64;
-    const int kc = (int)(tile % KC);
-    const int rb = (int)(tile / KC);
-    const int n = rb * 64 + r;
-    const int k = kc * 16;
+    const int kt = (int)(tile % KT);
+    const int rt = (int)(tile / KT);
+    const int n = rt * 16 + (lane & 15);
+    const int k = kt * 64 + (lane >> 4) * 16;
     if (n < N && k < K) *reinterpret_cast<uint4 *>(wq + (size_t)n * K + k) = packed[v];
 }
 
 // ---------------------------------------------------------------- W4G32
-// Eight consecutive codes -> one dword, biased by 8, code e in nibble (e>>1)+4*(e&1).
+// Eight consecutive codes -> one dword, biased by 8: byte i holds code i in its
+// low nibble and code 4 + i in its high nibble.
 __device__ inline uint32_t pack8(const int8_t *c) {
     uint32_t d = 0;
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
         const uint32_t u = ((uint32_t)(c[e] + 8)) & 0xFu;
-        d |= u << (4 * ((e >> 1) + 4 * (e & 1)));
+        d |= u << (8 * (e & 3) + 4 * (e >> 2));
     }
     return d;
 }
@@ -61,43 +60,59 @@ __device__ inline uint32_t pack8(const int8_t *c) {
 __device__ inline void unpack8(uint32_t d, int8_t *c) {
 #pragma unroll
     for (int e = 0; e < 8; ++e) {
-        const uint32_t u = (d >> (4 * ((e >> 1) + 4 * (e & 1)))) & 0xFu;
+        const uint32_t u = (d >> (8 * (e & 3) + 4 * (e >> 2))) & 0xFu;
         c[e] = (int8_t)((int)u - 8);
     }
+}
+
+// Position `pos` inside a row tile's sequence -> weight tile index (>= 0) or
+// scale tile of unit u (returned as -1 - u).
+__device__ inline int classify(int pos, int KT) {
+    const int u = pos / 9;
+    const int s = pos % 9;
+    const int nt = min(8, KT - 8 * u);
+    return s < nt ? 8 * u + s : -1 - u;
 }
 
 __global__ __launch_bounds__(256) void pack_w4g32_kernel(const int8_t *__restrict__ wq,
                                                          const uint16_t *__restrict__ scales,
                                                          uint4 *__restrict__ packed, int N, int K,
-                                                         int Np, int Kp) {
-    const int G8 = Kp / 256;
+                                                         int RTp, int KT, int stride) {
     const int Kg = K / 32;
-    const size_t total = (size_t)(Np / 64) * G8 * kW4UnitVecs;
+    const size_t total = (size_t)RTp * stride * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= total) return;
-    const int r = (int)(v % 64);
-    const int j = (int)((v / 64) % 9);
-    const size_t unit = v / kW4UnitVecs;
-    const int b = (int)(unit % G8);
-    const int rb = (int)(unit / G8);
-    const int n = rb * 64 + r;
+    const int lane = (int)(v % 64);
+    const size_t tile = v / 64;
+    const int pos = (int)(tile % stride);
+    const int rt = (int)(tile / stride);
+    const int what = classify(pos, KT);
     uint4 out;
-    if (j < 8) {
-        const int g = b * 8 + j;
-        if (n < N && g < Kg) {
-            alignas(16) int8_t c[32];
-            const uint4 *src = reinterpret_cast<const uint4 *>(wq + (size_t)n * K + (size_t)g * 32);
-            *reinterpret_cast<uint4 *>(c) = src[0];
-            *reinterpret_cast<uint4 *>(c + 16) = src[1];
-            out = make_uint4(pack8(c), pack8(c + 8), pack8(c + 16), pack8(c + 24));
-        } else {
-            out = make_uint4(0x88888888u, 0x88888888u, 0x88888888u, 0x88888888u);
+    if (what >= 0) {
+        const int n = rt * 16 + (lane & 15);
+        const int q = lane >> 4;
+        uint32_t d[4];
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int g = 4 * what + j;
+            if (n < N && g < Kg) {
+                alignas(8) int8_t c[8];
+                *reinterpret_cast<uint2 *>(c) =
+                    *reinterpret_cast<const uint2 *>(wq + (size_t)n * K + (size_t)g * 32 + 8 * q);
+                d[j] = pack8(c);
+            } else {
+                d[j] = 0x88888888u;
+            }
         }
+        out = make_uint4(d[0], d[1], d[2], d[3]);
     } else {
+        const int u = -1 - what;
+        const int n = rt * 16 + (lane & 15);
+        const int p = lane >> 4;
         uint32_t s[8];
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int g = b * 8 + i;
+            const int g = 32 * u + 8 * p + i;
             s[i] = (n < N && g < Kg) ? scales[(size_t)n * Kg + g] : 0u;
         }
         out = make_uint4(s[0] | (s[1] << 16), s[2] | (s[3] << 16), s[4] | (s[5] << 16), s[6] | (s[7] << 16));
@@ -108,36 +123,38 @@ __global__ __launch_bounds__(256) void pack_w4g32_kernel(const int8_t *__restric
 __global__ __launch_bounds__(256) void unpack_w4g32_kernel(const uint4 *__restrict__ packed,
                                                            int8_t *__restrict__ wq,
                                                            uint16_t *__restrict__ scales, int N, int K,
-                                                           int Np, int Kp) {
-    const int G8 = Kp / 256;
+                                                           int RTp, int KT, int stride) {
     const int Kg = K / 32;
-    const size_t total = (size_t)(Np / 64) * G8 * kW4UnitVecs;
+    const size_t total = (size_t)RTp * stride * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (v >= total) return;
-    const int r = (int)(v % 64);
-    const int j = (int)((v / 64) % 9);
-    const size_t unit = v / kW4UnitVecs;
-    const int b = (int)(unit % G8);
-    const int rb = (int)(unit / G8);
-    const int n = rb * 64 + r;
+    const int lane = (int)(v % 64);
+    const size_t tile = v / 64;
+    const int pos = (int)(tile % stride);
+    const int rt = (int)(tile / stride);
+    const int what = classify(pos, KT);
+    const int n = rt * 16 + (lane & 15);
     if (n >= N) return;
     const uint4 in = packed[v];
-    if (j < 8) {
-        const int g = b * 8 + j;
-        if (g >= Kg) return;
-        alignas(16) int8_t c[32];
-        unpack8(in.x, c);
-        unpack8(in.y, c + 8);
-        unpack8(in.z, c + 16);
-        unpack8(in.w, c + 24);
-        uint4 *dst = reinterpret_cast<uint4 *>(wq + (size_t)n * K + (size_t)g * 32);
-        dst[0] = *reinterpret_cast<uint4 *>(c);
-        dst[1] = *reinterpret_cast<uint4 *>(c + 16);
+    const uint32_t w[4] = {in.x, in.y, in.z, in.w};
+    if (what >= 0) {
+        const int q = lane >> 4;
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int g = 4 * what + j;
+            if (g < Kg) {
+                alignas(8) int8_t c[8];
+                unpack8(w[j], c);
+                *reinterpret_cast<uint2 *>(wq + (size_t)n * K + (size_t)g * 32 + 8 * q) =
+                    *reinterpret_cast<uint2 *>(c);
+            }
+        }
     } else {
-        const uint32_t w[4] = {in.x, in.y, in.z, in.w};
+        const int u = -1 - what;
+        const int p = lane >> 4;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
-            const int g = b * 8 + i;
+            const int g = 32 * u + 8 * p + i;
             if (g < Kg) scales[(size_t)n * Kg + g] = (uint16_t)((w[i / 2] >> (16 * (i & 1))) & 0xFFFFu);
         }
     }
@@ -150,14 +167,15 @@ inline unsigned blocks_for(size_t threads) { return (unsigned)((threads + 255) /
 hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, void *packed,
                        hipStream_t st) {
     if (g.fmt == kW8C) {
-        const size_t total = (size_t)g.RBp * (g.Kp / 16) * 64;
+        const size_t total = (size_t)g.RTp * g.KT * 64;
         pack_w8c_kernel<<<blocks_for(total), 256, 0, st>>>(
             wq, static_cast<const float *>(scales), static_cast<uint4 *>(packed),
-            reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.Kp);
+            reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.KT);
     } else {
-        const size_t total = (size_t)g.RBp * (g.Kp / 256) * kW4UnitVecs;
+        const size_t total = (size_t)g.RTp * g.rt_stride * 64;
         pack_w4g32_kernel<<<blocks_for(total), 256, 0, st>>>(
-            wq, static_cast<const uint16_t *>(scales), static_cast<uint4 *>(packed), g.N, g.K, g.Np, g.Kp);
+            wq, static_cast<const uint16_t *>(scales), static_cast<uint4 *>(packed), g.N, g.K, g.RTp, g.KT,
+            g.rt_stride);
     }
     return hipGetLastError();
 }
@@ -165,15 +183,16 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
 hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void *scales,
                          hipStream_t st) {
     if (g.fmt == kW8C) {
-        const size_t total = (size_t)g.RBp * (g.Kp / 16) * 64;
+        const size_t total = (size_t)g.RTp * g.KT * 64;
         unpack_w8c_kernel<<<blocks_for(total), 256, 0, st>>>(
             static_cast<const uint4 *>(packed),
             reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off), wq,
-            static_cast<float *>(scales), g.N, g.K, g.Np, g.Kp);
+            static_cast<float *>(scales), g.N, g.K, g.Np, g.KT);
     } else {
-        const size_t total = (size_t)g.RBp * (g.Kp / 256) * kW4UnitVecs;
+        const size_t total = (size_t)g.RTp * g.rt_stride * 64;
         unpack_w4g32_kernel<<<blocks_for(total), 256, 0, st>>>(
-            static_cast<const uint4 *>(packed), wq, static_cast<uint16_t *>(scales), g.N, g.K, g.Np, g.Kp);
+            static_cast<const uint4 *>(packed), wq, static_cast<uint16_t *>(scales), g.N, g.K, g.RTp, g.KT,
+            g.rt_stride);
     }
     return hipGetLastError();
 }

@@ -1,26 +1,36 @@
 // Internal declarations shared by the translation units of libqfc.so.
+//
 // Physical weight layouts (the "weights conversion" of section 3.4 of the
 // paper; the layouts themselves are this library's own, chosen for 64-lane
-// wavefronts and 16-byte lane loads):
+// wavefronts, 16-byte lane loads and the CDNA4 matrix-core operand shapes).
+// A wavefront load of 16 B per lane always covers one contiguous KiB "tile" of
+// 16 output rows; lane l = (c, q) with c = l % 16 the row inside the tile and
+// q = l / 16 a quarter of the tile's k range.  This is exactly the B-operand
+// shape of the 16x16 MFMA instructions, so a tile goes from HBM to a matrix
+// core without any cross-lane shuffle.
 //
-// W8C (int8 codes, fp32 scale per output channel)
-//   rows are grouped in blocks of 64, K in chunks of 16 codes.  One 1 KiB tile
-//   holds chunk kc of the 64 rows of row block rb: lane r owns the 16 bytes
-//   (rb*64 + r, kc*16 .. kc*16+15).  Tiles are stored [rb][kc].  A wavefront
-//   load of 16 B per lane is therefore one contiguous KiB, every lane works on
-//   its own output row (no cross-lane reduction), and the same tile is an MFMA
-//   int8 operand fragment when 16 rows x 4 chunks are read from LDS.
-//   K is padded to a multiple of 256 and N to a multiple of 256 with zero
-//   codes.  The fp32 scales [Np] follow the codes.
+// W8C (int8 codes, one fp32 scale per output channel)
+//   tile = 16 rows x 64 k; lane (c, q) holds the 16 codes (row c, k = 16q .. 16q+15).
+//   Tiles are stored [row tile][k tile].  N is padded to a multiple of 256 and
+//   K to a multiple of 256 with zero codes.  The fp32 scales [Np] follow.
+//   The 16 bytes of a lane are an int8 MFMA fragment as they are
+//   (v_mfma_i32_16x16x64_i8 / 32x32x32), and two fp16 MFMA fragments after
+//   conversion (k = 16q + 8j + e for j = 0, 1).
 //
-// W4G32 (int4 codes, binary16 scale per 32 consecutive k)
-//   a unit is 64 rows x 256 k = 9 KiB: eight 1 KiB tiles (tile j = quantization
-//   group j of the unit; lane r owns the 32 codes of (row r, group j) in 16
-//   bytes) followed by one 1 KiB tile of scales (lane r owns the eight binary16
-//   scales of its row).  Units are stored [rb][k/256].  Codes are stored biased
-//   (q + 8) and nibble-interleaved so that two mask operations per byte pair
-//   yield k-adjacent binary16 pairs: code e (0..7) of a dword sits in nibble
-//   (e >> 1) + 4 * (e & 1).  Padding codes are 8 (zero), padding scales 0.
+// W4G32 (int4 codes, one binary16 scale per 32 consecutive k)
+//   weight tile = 16 rows x 128 k (four quantization groups); lane (c, q) holds
+//   four dwords, dword j = the eight codes (row c, k = 32 (4t + j) + 8q .. + 7)
+//   of tile t: octet q of group j, i.e. one fp16 MFMA B fragment whose whole k
+//   range lies inside one quantization group, so the group scale can be applied
+//   to the MFMA result.  Codes are stored biased (q + 8); byte i of a dword holds
+//   code i in its low nibble and code 4 + i in its high nibble, so that one mask
+//   per nibble plane and one byte permute per pair yield k-adjacent binary16
+//   pairs.
+//   Up to eight weight tiles (1024 k) are followed by one scale tile holding the
+//   32 group scales of each of the 16 rows: 16-byte vector p * 16 + c = scales
+//   of row c for groups 8p .. 8p+7 of the unit.  A row tile is the sequence
+//   [8 tiles][scales][8 tiles][scales]...[last <= 8 tiles][scales].
+//   K is padded to a multiple of 128 (codes 8 = zero, scales 0), N to 256.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -30,10 +40,8 @@
 
 namespace qfc {
 
-constexpr int kRowsPerBlock = 64;
+constexpr int kTileRows = 16;
 constexpr int kPadN = 256;
-constexpr int kPadK = 256;
-constexpr int kW4UnitVecs = 9 * 64;  // 16-byte vectors per W4G32 unit
 constexpr int kMaxDecodeM = 8;
 
 enum Format { kW8C = 0, kW4G32 = 1 };
@@ -41,8 +49,11 @@ enum Format { kW8C = 0, kW4G32 = 1 };
 struct Geometry {
     int N, K;    // logical
     int Np, Kp;  // padded
-    int RB;      // row blocks holding real rows: ceil(N / 64)
-    int RBp;     // Np / 64
+    int RT;      // row tiles holding real rows: ceil(N / 16)
+    int RTp;     // Np / 16
+    int KT;      // k tiles per row tile (64 k for W8C, 128 k for W4G32)
+    int KU;      // units per row tile (W4G32: ceil(KT / 8); W8C: ceil(KT / 8))
+    int rt_stride;       // KiB tiles per row tile (W4G32: KT + KU, W8C: KT)
     int fmt;
     size_t code_bytes;   // bytes of the code (+ group scale) region
     size_t scale_off;    // W8C: byte offset of the fp32 scales
@@ -55,15 +66,22 @@ inline Geometry make_geometry(int N, int K, int fmt) {
     Geometry g;
     g.N = N; g.K = K; g.fmt = fmt;
     g.Np = round_up(N, kPadN);
-    g.Kp = round_up(K, kPadK);
-    g.RB = (N + kRowsPerBlock - 1) / kRowsPerBlock;
-    g.RBp = g.Np / kRowsPerBlock;
+    g.RT = (N + kTileRows - 1) / kTileRows;
+    g.RTp = g.Np / kTileRows;
     if (fmt == kW8C) {
+        g.Kp = round_up(K, 256);
+        g.KT = g.Kp / 64;
+        g.KU = (g.KT + 7) / 8;
+        g.rt_stride = g.KT;
         g.code_bytes = (size_t)g.Np * g.Kp;
         g.scale_off = g.code_bytes;
         g.total_bytes = g.code_bytes + (size_t)g.Np * 4;
     } else {
-        g.code_bytes = (size_t)g.RBp * (g.Kp / 256) * kW4UnitVecs * 16;
+        g.Kp = round_up(K, 128);
+        g.KT = g.Kp / 128;
+        g.KU = (g.KT + 7) / 8;
+        g.rt_stride = g.KT + g.KU;
+        g.code_bytes = (size_t)g.RTp * g.rt_stride * 1024;
         g.scale_off = 0;
         g.total_bytes = g.code_bytes;
     }
@@ -71,21 +89,19 @@ inline Geometry make_geometry(int N, int K, int fmt) {
 }
 
 struct GemvPlan {
-    int waves;   // wavefronts per workgroup
-    int splits;  // workgroups sharing one row block (K split)
-    int units;   // work units along K per row block
+    int waves;       // wavefronts per workgroup, each owning a range of units
+    int row_tiles;   // row tiles a workgroup walks through (shares staged x)
 };
 
 // Tunables (set through qfc_tune, used by the planners).
 struct Tuning {
     int gemv_target_waves = 4096;
-    int gemv_max_waves_per_wg = 8;
+    int gemv_max_row_tiles = 4;
     int gemm_variant = 0;
 };
 Tuning &tuning();
 
 GemvPlan plan_gemv(const Geometry &g, int M, int num_cus);
-size_t gemv_workspace_bytes(const Geometry &g, int M, int num_cus);
 
 // Launchers.  Every one validates nothing (the C ABI layer did) and returns
 // the hipError_t of the launch.
@@ -94,7 +110,7 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
 hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void *scales,
                          hipStream_t st);
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                       void *workspace, int num_cus, hipStream_t st);
+                       int num_cus, hipStream_t st);
 hipError_t launch_act_quant(const void *x, int M, int K, int8_t *xq, float *sx, int tiled,
                             int Mp, int Kp, hipStream_t st);
 hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp,

@@ -38,10 +38,10 @@ def test_packed_size_and_descriptor_checks(L):
     # 1024 x 512 codes + 1024 fp32 scales, no padding needed
     assert binding.qfc_packed_size(d) == 1024 * 512 + 4 * 1024
     d = binding.make_desc(4096, 2304, "w4g32")
-    # 9 KiB per (64 rows x 256 k)
-    assert binding.qfc_packed_size(d) == (4096 // 64) * (2304 // 256) * 9216
+    # per 16 rows: 18 KiB tiles of 128 k plus 3 scale tiles
+    assert binding.qfc_packed_size(d) == (4096 // 16) * (18 + 3) * 1024
     d = binding.make_desc(1, 32, "w4g32")
-    assert binding.qfc_packed_size(d) == 4 * 9216  # padded to 256 rows x 256 k
+    assert binding.qfc_packed_size(d) == 16 * 2 * 1024  # padded to 256 rows x 128 k, one scale tile each
     out = ctypes.c_size_t(0)
     bad = [binding.Desc(0, 512, 8, 0, 0, 1), binding.Desc(8, 48, 8, 0, 0, 1), binding.Desc(8, 64, 3, 0, 0, 1),
            binding.Desc(8, 64, 8, -1, 0, 1), binding.Desc(8, 64, 8, 0, 7, 1), binding.Desc(8, 64, 8, 0, 0, 5)]

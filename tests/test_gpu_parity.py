@@ -278,13 +278,13 @@ def test_error_paths_on_device():
         binding.qfc_forward_acc_i32(layer.handle, xq, acc)  # int8 product needs int8 per-channel weights
     assert e.value.code == 2
     small = torch.zeros(256, dtype=torch.uint8, device=DEV)
-    big = synth.FC("t", 14336, 64, "w4g32")
+    big = synth.FC("t", 512, 64, "w8c")
     wq2, s2 = synth.weights(6001, 0, 0, big)
-    layer2 = _layer(wq2, s2, "w4g32")
+    layer2 = _layer(wq2, s2, "w8c")
     binding.qfc_bind_workspace(layer2.handle, small)
-    with pytest.raises(binding.QfcError) as e:
-        binding.qfc_forward(layer2.handle, torch.zeros((1, 14336), dtype=torch.float16, device=DEV),
-                            torch.zeros((1, 64), dtype=torch.float16, device=DEV))
+    with pytest.raises(binding.QfcError) as e:  # int8 prefill needs room for the quantized activations
+        binding.qfc_forward(layer2.handle, torch.zeros((16, 512), dtype=torch.float16, device=DEV),
+                            torch.zeros((16, 64), dtype=torch.float16, device=DEV))
     assert e.value.code == 3
     layer.close()
     layer2.close()
