@@ -104,23 +104,37 @@ struct GemvArgs {
 // W4G32 unit: 1024 k = 128 octets, slot = octet index (4 * group + q).
 // W8C unit:    512 k =  64 octets, slot = tile * 8 + j * 4 + q for octet 2q + j of the tile.
 template <int M, int FMT>
-__device__ __forceinline__ void stage_x(const GemvArgs &a, u32x4 *lds, int unit, int lane) {
-    constexpr int OCT = FMT == kW4G32 ? 128 : 64;  // octets per unit
-    const int K8 = a.K / 8;
-    const int o_base = unit * OCT;
-#pragma unroll
-    for (int i = 0; i < M * OCT / 64; ++i) {
-        const int p = i * 64 + lane;
-        const int m = p / OCT, o = p % OCT;
-        u32x4 v = {0, 0, 0, 0};
-        if (o_base + o < K8) v = a.x[(size_t)m * K8 + o_base + o];
-        int slot = o;
-        if (FMT == kW8C) slot = (o & ~7) | ((o & 1) << 2) | ((o >> 1) & 3);
-        lds[slot * M + m] = v;
-    }
-}
+struct XStage {
+    static constexpr int OCT = FMT == kW4G32 ? 128 : 64;  // octets per unit
+    static constexpr int XV = M * OCT / 64;               // 16-byte vectors per lane per unit
+    u32x4 v[XV];
 
-template <int M, int FMT>
+    // global -> registers (zeros beyond K)
+    __device__ __forceinline__ void load(const GemvArgs &a, int unit, int lane) {
+        const int K8 = a.K / 8;
+        const int o_base = unit * OCT;
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int p = i * 64 + lane;
+            const int m = p / OCT, o = p % OCT;
+            const u32x4 zero = {0, 0, 0, 0};
+            v[i] = o_base + o < K8 ? a.x[(size_t)m * K8 + o_base + o] : zero;
+        }
+    }
+    // registers -> this wavefront's LDS region, A-operand order
+    __device__ __forceinline__ void store(u32x4 *lds, int lane) const {
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int p = i * 64 + lane;
+            const int m = p / OCT, o = p % OCT;
+            int slot = o;
+            if (FMT == kW8C) slot = (o & ~7) | ((o & 1) << 2) | ((o >> 1) & 3);
+            lds[slot * M + m] = v[i];
+        }
+    }
+};
+
+template <int M, int FMT, bool DB>
 __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     constexpr int TILES = 8;                    // weight tiles per unit
     constexpr int NV = FMT == kW4G32 ? 12 : 8;  // 16-byte vectors per lane per (unit, row tile)
@@ -159,24 +173,33 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
         }
     };
 
-    u32x4 cur[NV], nxt[NV];
+    // Two variants.  DB = false: latency is hidden by occupancy, a wavefront
+    // requests the activations and all weight vectors of an item at once, waits,
+    // computes and moves on; the low register count (no second weight buffer)
+    // buys extra resident wavefronts.  This suits launches whose wavefronts have
+    // one or two items.  DB = true: the next item's vectors are requested before
+    // the current item is computed, for long-lived wavefronts.  Vector loads
+    // return in order, so the (small) activation loads are issued first.
+    XStage<M, FMT> xs;
+    u32x4 cur[NV];
+    u32x4 nxt[DB ? NV : 1];
     const int items = (u1 - u0) * R;
-    if (items > 0) load_item(cur, u0, 0);
     int u = u0, r = 0;
+    if (items > 0) {
+        xs.load(a, u0, lane);
+        load_item(cur, u0, 0);
+        if constexpr (DB) {
+            if (items > 1) load_item(nxt, R > 1 ? u0 : u0 + 1, R > 1 ? 1 : 0);
+        }
+    }
     for (int it = 0; it < items; ++it) {
         if (r == 0) {
             // new unit: the wavefront's earlier LDS reads are done (same wavefront, in order)
-            stage_x<M, FMT>(a, lds_x, u, lane);
+            xs.store(lds_x, lane);
             __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
             __builtin_amdgcn_wave_barrier();
             __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
         }
-        int un = u, rn = r + 1;
-        if (rn == R) {
-            rn = 0;
-            un = u + 1;
-        }
-        if (it + 1 < items) load_item(nxt, un, rn);
 
         const int nt = min(TILES, a.KT - TILES * u);
         float accr[4] = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -249,12 +272,20 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
 #pragma unroll
                 for (int i = 0; i < MI; ++i) acc[rr][i] += FMT == kW4G32 ? accr[i] : accw[i];
             }
-        if (it + 1 < items) {
-#pragma unroll
-            for (int v = 0; v < NV; ++v) cur[v] = nxt[v];
+        if (++r == R) {
+            r = 0;
+            ++u;
         }
-        u = un;
-        r = rn;
+        if (it + 1 < items) {
+            if (r == 0) xs.load(a, u, lane);
+            if constexpr (DB) {
+#pragma unroll
+                for (int v = 0; v < NV; ++v) cur[v] = nxt[v];
+                if (it + 2 < items) load_item(nxt, r + 1 == R ? u + 1 : u, r + 1 == R ? 0 : r + 1);
+            } else {
+                load_item(cur, u, r);
+            }
+        }
     }
 
     // meet in LDS: red[wave][r][m][16 rows]; lane (c, q) holds token rows 4q .. 4q+3 of row c
@@ -288,10 +319,21 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t
     size_t lds = (size_t)waves * oct * M * 16;
     const size_t red = (size_t)waves * 4 * M * 16 * sizeof(float);
     if (red > lds) lds = red;
+    // long-lived wavefronts (>= 3 items each) get the double-buffered variant
+    const int items = ((g.KU + waves - 1) / waves) * a.row_tiles;
+    if constexpr (M <= 2) {
+        if (items >= 3) {
+            if (g.fmt == kW8C)
+                gemv_kernel<M, kW8C, true><<<grid, block, lds, st>>>(a);
+            else
+                gemv_kernel<M, kW4G32, true><<<grid, block, lds, st>>>(a);
+            return hipGetLastError();
+        }
+    }
     if (g.fmt == kW8C)
-        gemv_kernel<M, kW8C><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW8C, false><<<grid, block, lds, st>>>(a);
     else
-        gemv_kernel<M, kW4G32><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW4G32, false><<<grid, block, lds, st>>>(a);
     return hipGetLastError();
 }
 

@@ -95,8 +95,8 @@ struct GemvPlan {
 
 // Tunables (set through qfc_tune, used by the planners).
 struct Tuning {
-    int gemv_target_waves = 4096;
-    int gemv_max_row_tiles = 4;
+    int gemv_target_waves = 8192;
+    int gemv_max_row_tiles = 2;
     int gemm_variant = 0;
 };
 Tuning &tuning();
