@@ -1,0 +1,213 @@
+#!/usr/bin/env python3
+"""Benchmark of the quantized fully-connected hot path on one MI355X.
+
+A step is one pass of the decode hot path over the workload the headline metric
+is quoted on: every linear layer of a Llama-3.1-8B-shaped decode step at M = 1
+(32 layers x [QKV, O, gate+up, down] with int4 group-32 weights plus the int8
+per-channel LM head: 129 qfc_forward calls, 4.456 GB of packed weights streamed
+once).  Inputs are seeded synthetic tensors, resident in HBM before the timed
+region.  The same run also times the prefill kernels (int8 MFMA product with
+activation quantization and epilogue at M = 1024; fp16 MFMA product with in-LDS
+dequantization at M = 2048), the M = 4 decode step, and the CPU oracle on a
+bounded sample of the workload.
+
+Prints ONE JSON line.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0       # MI355X HBM3E
+MFMA_I8_PEAK_TOPS = 5000.0  # dense int8
+MFMA_F16_PEAK_TFLOPS = 2500.0
+
+
+def parse():
+    p = argparse.ArgumentParser()
+    p.add_argument("--gpus", type=int, default=1)
+    p.add_argument("--steps", type=int, default=20)
+    p.add_argument("--warmup", type=int, default=3)
+    p.add_argument("--layers", type=int, default=32, help="decoder layers of the decode step (32 = the full model)")
+    p.add_argument("--skip-prefill", action="store_true")
+    p.add_argument("--skip-cpu", action="store_true")
+    return p.parse_args()
+
+
+def main():
+    args = parse()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (no collectives or sharding); use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+    import numpy as np
+    import torch
+
+    from paper_2505_00232_amd import binding, synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(1)
+    binding.lib()  # fail loudly if the HIP library is missing
+    dev = "cuda"
+    SEED = 1003
+
+    def event_ms(fn, reps):
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        torch.cuda.synchronize()
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    # ------------------------------------------------------------ decode step (config 3)
+    t_setup = time.time()
+    fcs = []
+    for layer in range(args.layers):
+        for i, fc in enumerate(synth.LLAMA_FCS_W4):
+            fcs.append((layer, i, fc))
+    fcs.append((args.layers, 4, synth.LLAMA_LM_HEAD))
+    workspace = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
+    layers, x1, x4 = [], [], []
+    for layer, i, fc in fcs:
+        wq, s = synth.weights(SEED, layer, i, fc)
+        layers.append(binding.QuantLinear(wq, s, fc.fmt, max_m=8, workspace=workspace if fc.fmt == "w4g32" else None))
+        x1.append(torch.from_numpy(synth.activations(SEED, layer, i, 1, fc.K)).to(dev))
+        x4.append(torch.from_numpy(synth.activations(SEED, layer, i + 8, 4, fc.K)).to(dev))
+        del wq, s
+    setup_s = time.time() - t_setup
+
+    def step_runner(xs, M, subset=None):
+        idx = range(len(layers)) if subset is None else subset
+        ys = [torch.empty((M, layers[j].N), dtype=torch.float16, device=dev) for j in idx]
+        fb = binding.ForwardBatch([layers[j].handle for j in idx], [xs[j] for j in idx], ys, M)
+        return fb, ys
+
+    bytes_m1 = sum(synth.algorithmic_bytes(fc, 1) for _, _, fc in fcs)
+    bytes_m4 = sum(synth.algorithmic_bytes(fc, 4) for _, _, fc in fcs)
+    fb1, _ = step_runner(x1, 1)
+    for _ in range(args.warmup):
+        fb1.run()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        fb1.run()
+    torch.cuda.synchronize()
+    wall_s = time.perf_counter() - t0
+    ms_per_step = wall_s / args.steps * 1e3
+    value = bytes_m1 / (ms_per_step * 1e-3) / 1e9
+
+    # dominant kernel: the int4 group-32 decode kernel (128 of the 129 launches of a step)
+    w4_idx = [j for j, (_, _, fc) in enumerate(fcs) if fc.fmt == "w4g32"]
+    fb_w4, _ = step_runner(x1, 1, w4_idx)
+    fb_w4.run()
+    ms_w4 = event_ms(fb_w4.run, args.steps)
+    bytes_w4 = sum(synth.algorithmic_bytes(fcs[j][2], 1) for j in w4_idx)
+    launch_us = ms_w4 * 1e3 / len(w4_idx)
+    achieved = bytes_w4 / (ms_w4 * 1e-3) / 1e9
+    traffic = None
+    tpath = os.path.join(ROOT, "profiles", "traffic.json")
+    if os.path.exists(tpath):
+        traffic = json.load(open(tpath)).get("gemv_w4g32_m1_bytes_per_launch")
+    roofline = {"bound": "hbm", "kernel": "gemv_kernel<M=1, W4G32> (decode, int4 group-32)",
+                "achieved": round(achieved, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                "frac": round(achieved / HBM_PEAK_GBS, 4), "traffic": traffic,
+                "launches_per_step": len(w4_idx), "avg_launch_us": round(launch_us, 3),
+                "algorithmic_bytes_per_launch": bytes_w4 // len(w4_idx)}
+
+    # LM head (int8 per-channel decode kernel), and the M = 4 step
+    lm_idx = [len(fcs) - 1]
+    fb_lm, _ = step_runner(x1, 1, lm_idx)
+    fb_lm.run()
+    ms_lm = event_ms(fb_lm.run, args.steps)
+    lm_gbs = synth.algorithmic_bytes(synth.LLAMA_LM_HEAD, 1) / (ms_lm * 1e-3) / 1e9
+    fb4, _ = step_runner(x4, 4)
+    fb4.run()
+    ms_m4 = event_ms(fb4.run, max(3, args.steps // 2))
+    extra = {
+        "lm_head_w8c_m1": {"us": round(ms_lm * 1e3, 2), "GB/s": round(lm_gbs, 1), "frac_hbm_peak": round(lm_gbs / HBM_PEAK_GBS, 4)},
+        "decode_m4": {"ms_per_step": round(ms_m4, 4), "GB/s": round(bytes_m4 / (ms_m4 * 1e-3) / 1e9, 1),
+                      "tokens_per_s": round(4 / (ms_m4 * 1e-3), 1)},
+        "decode_m1_tokens_per_s": round(1 / (ms_per_step * 1e-3), 1),
+        "setup_s": round(setup_s, 1),
+    }
+
+    # ------------------------------------------------------------ CPU oracle on a bounded sample
+    cpu_baseline = None
+    if not args.skip_cpu:
+        import oracle
+        cores = oracle.threads()
+        n_layers = 4
+        sample = [(l, i, fc) for (l, i, fc) in fcs if l < n_layers and fc.fmt == "w4g32"]
+        tot_b, tot_t = 0, 0.0
+        for layer, i, fc in sample:
+            wq, s = synth.weights(SEED, layer, i, fc)
+            x = synth.activations(SEED, layer, i, 1, fc.K)
+            t0 = time.perf_counter()
+            oracle.fc_weight_only(x, wq, s, 32)
+            tot_t += time.perf_counter() - t0
+            tot_b += synth.algorithmic_bytes(fc, 1)
+            del wq, s
+        cpu_baseline = {"value": round(tot_b / tot_t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
+                        "sample": f"first {n_layers} decoder layers ({len(sample)} FCs, {tot_b / 1e6:.0f} MB of packed weights) "
+                                  f"of the same decode step at M=1, {tot_t:.1f} s"}
+
+    for l in layers:
+        l.close()
+    del layers, fb1, fb4, fb_w4, fb_lm
+    torch.cuda.empty_cache()
+
+    # ------------------------------------------------------------ prefill (configs 4 and 5)
+    if not args.skip_prefill:
+        def prefill(fc_list, M, seed, reps=10):
+            out, tot_ops, tot_ms = {}, 0, 0.0
+            for i, fc in enumerate(fc_list):
+                wq, s = synth.weights(seed, 0, i, fc)
+                lay = binding.QuantLinear(wq, s, fc.fmt, max_m=M)
+                x = torch.from_numpy(synth.activations(seed, 0, i, M, fc.K)).to(dev)
+                y = torch.empty((M, fc.N), dtype=torch.float16, device=dev)
+                run = lambda: binding.qfc_forward(lay.handle, x, y)
+                run()
+                ms = event_ms(run, reps)
+                ops = synth.algorithmic_ops(fc, M)
+                out[fc.name] = {"us": round(ms * 1e3, 1), "Tops": round(ops / (ms * 1e-3) / 1e12, 1)}
+                tot_ops += ops
+                tot_ms += ms
+                lay.close()
+                del wq, s, lay
+            out["total"] = {"us": round(tot_ms * 1e3, 1), "Tops": round(tot_ops / (tot_ms * 1e-3) / 1e12, 1)}
+            return out
+
+        p8 = prefill(synth.LLAMA_FCS_W8, 1024, 1004)
+        p8["roofline"] = {"bound": "mfma", "achieved": p8["total"]["Tops"], "peak": MFMA_I8_PEAK_TOPS, "unit": "TOP/s",
+                          "frac": round(p8["total"]["Tops"] / MFMA_I8_PEAK_TOPS, 4),
+                          "note": "activation quantization + int8 MFMA product + epilogue, Llama-3.1-8B layer, M=1024"}
+        p16 = prefill(synth.GEMMA_FCS_W4, 2048, 1005)
+        p16["roofline"] = {"bound": "mfma", "achieved": p16["total"]["Tops"], "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
+                           "frac": round(p16["total"]["Tops"] / MFMA_F16_PEAK_TFLOPS, 4),
+                           "note": "int4 group-32 weights dequantized into LDS, fp16 MFMA, Gemma2-2B layer, M=2048"}
+        extra["prefill_int8_m1024"] = p8
+        extra["prefill_fp16_m2048"] = p16
+
+    line = {
+        "metric": "decode quantized-FC HBM GB/s", "value": round(value, 1), "unit": "GB/s", "n_gpus": 1,
+        "steps": args.steps, "warmup": args.warmup, "ms_per_step": round(ms_per_step, 4),
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "f16", "data": "synthetic",
+        "config": {"workload": f"llama-3.1-8b decode step, all linear layers, M=1: {args.layers} x (qkv, o, gate_up, down) "
+                               "int4 group-32 fp16-scale + lm_head int8 per-channel",
+                   "launches_per_step": len(fcs), "algorithmic_bytes_per_step": bytes_m1},
+        "frac_of_hbm_peak": round(value / HBM_PEAK_GBS, 4),
+        "roofline": roofline, "cpu_baseline": cpu_baseline, "extra": extra,
+    }
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -5,16 +5,21 @@
 //   y[m,n]   = fp16(float(acc) * sx[m] * sw[n])
 //
 // Both operands arrive tiled the same way (KiB tiles of 16 rows x 64 k, lane
-// (c, q) = 16 codes of row c at k = 16q), so a stage of the K loop is a
-// verbatim, fully coalesced copy of KiB tiles into LDS, and an MFMA operand
-// fragment (32 rows x 32 k, lane = row + 32 * (k / 16)) is made of runs of 256
-// contiguous LDS bytes: bank-conflict free without padding or swizzling.
+// (c, q) = 16 codes of row c at k = 16q).  A stage of the K loop (128 k) is a
+// verbatim copy of KiB tiles into LDS, done by global_load_lds_dwordx4 (one
+// wavefront instruction moves one tile from memory straight into LDS, no
+// staging registers), in a ring of LDS stages that keeps several stages in
+// flight, with one workgroup barrier per stage.
+// An MFMA operand fragment (32 rows x 32 k, lane = row + 32 * (k / 16)) is made
+// of runs of 256 contiguous LDS bytes: conflict free without padding.
 //
-// Workgroup: 256 threads = 4 wavefronts in a 2 x 2 grid over a BN x BM tile
-// (weights rows x token rows); each wavefront owns (BN/2) x (BM/2) outputs as
-// 32x32 MFMA tiles (v_mfma_i32_32x32x32_i8).  The weights are the row operand
-// of the MFMA so that a lane ends up with 4 consecutive n of one token row:
-// 8-byte binary16 stores along the contiguous axis of y.
+// Workgroup: 4 wavefronts in a 2 x 2 grid over a BN x BM tile (weight rows x
+// token rows); each wavefront owns (BN/2) x (BM/2) outputs as 32x32 tiles of
+// v_mfma_i32_32x32x32_i8.  The weights are the row operand of the MFMA so that
+// a lane ends up with 4 consecutive n of one token row (8-byte fp16 stores
+// along the contiguous axis of y).  Tile ids are dealt so that every XCD works
+// on a contiguous range of (weight tile, token tile) pairs and the token tiles
+// that share a weight tile hit the same L2.
 #include "qfc_internal.h"
 
 namespace qfc {
@@ -22,60 +27,70 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef __attribute__((address_space(1))) const void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
 
-constexpr int BK = 128;            // k per stage
-constexpr int KCH = BK / 16;       // 16-byte chunks per row per stage
+// Wait until at most N vector-memory operations are outstanding and all LDS
+// operations are done (gfx9 s_waitcnt encoding: vmcnt in bits 3:0 and 15:14,
+// lgkmcnt in bits 11:8, expcnt left at its maximum).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+}
+
+__host__ __device__ inline int stages_total(int Kp, int bk) { return Kp / bk; }
 
 struct GemmI8Args {
-    const uint4 *w;      // packed weights, tiles [row tile][Kp/64][64]
-    const uint4 *x;      // tiled activations, tiles [row tile][Kp/64][64]
-    const float *sw;     // [Np]
-    const float *sx;     // [Mp] (null for raw accumulators)
+    const uint4 *w;   // packed weights, tiles [row tile][Kp/64][64]
+    const uint4 *x;   // tiled activations, tiles [row tile][Kp/64][64]
+    const float *sw;  // [Np]
+    const float *sx;  // [Mp] (null for raw accumulators)
     void *out;
     int M, N, Kp, n_tiles, m_tiles;
 };
 
-template <int BN, int BM, int OUT_MODE>
+// KTS = KiB k tiles (64 k each) per stage, NS = LDS stages (prefetch distance NS - 1)
+template <int BN, int BM, int KTS, int NS, int OUT_MODE>
 __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
-    constexpr int WN = BN / 2, WM = BM / 2;      // per-wavefront tile
-    constexpr int TN = WN / 32, TM = WM / 32;    // 32x32 MFMA tiles per wavefront
-    constexpr int W_VECS = BN * KCH, X_VECS = BM * KCH;  // 16-byte vectors per stage
-    constexpr int W_LD = W_VECS / 256, X_LD = X_VECS / 256;
-    __shared__ uint4 lds_w[W_VECS];
-    __shared__ uint4 lds_x[X_VECS];
+    constexpr int BK = KTS * 64;
+    constexpr int WN = BN / 2, WM = BM / 2;    // per-wavefront tile
+    constexpr int TN = WN / 32, TM = WM / 32;  // 32x32 MFMA tiles per wavefront
+    constexpr int W_TILES = BN / 16 * KTS, X_TILES = BM / 16 * KTS;  // KiB tiles per stage
+    constexpr int STAGE_VECS = (W_TILES + X_TILES) * 64;
+    extern __shared__ uint4 lds[];  // NS stages: [stage][W tiles | X tiles][64]
 
     const int tid = threadIdx.x;
     const int lane = tid & 63;
-    const int wave = tid >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wn = wave & 1, wm = wave >> 1;
 
-    // XCD-aware tile order: workgroups are dealt round-robin to the 8 XCDs, so
-    // give each XCD a contiguous range of logical tiles; the token tiles that
-    // share one weight tile are neighbours and hit the same L2.
     const int total = a.n_tiles * a.m_tiles;
     int logical = blockIdx.x;
     if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
     const int nt = logical / a.m_tiles;
     const int mt = logical % a.m_tiles;
-    const int KT = a.Kp / 64;  // k tiles per row tile
-    constexpr int KTS = BK / 64;  // k tiles per stage
+    const int KT = a.Kp / 64;
 
-    // global source of this thread's vectors for stage 0 (LDS vector v = tile * 64 + lane,
-    // tile = row tile of the block * KTS + k tile of the stage)
-    const uint4 *wsrc[W_LD];
-    const uint4 *xsrc[X_LD];
+    // One wavefront instruction copies one KiB tile: tile t of the stage, t = wave,
+    // wave + 4, ...  The tiles of one row tile are contiguous along K, so the source
+    // of a tile advances by a constant per stage; the stage-0 pointers are
+    // computed once.
+    constexpr int NLOAD = (W_TILES + X_TILES) / 4;
+    const uint4 *src0[NLOAD];
 #pragma unroll
-    for (int i = 0; i < W_LD; ++i) {
-        const int v = tid + 256 * i;
-        const int rtl = v / (KTS * 64), ktl = (v / 64) % KTS, ln = v % 64;
-        wsrc[i] = a.w + ((size_t)(nt * (BN / 16) + rtl) * KT + ktl) * 64 + ln;
+    for (int i = 0; i < NLOAD; ++i) {
+        const int t = wave + 4 * i;
+        if (t < W_TILES)
+            src0[i] = a.w + ((size_t)(nt * (BN / 16) + t / KTS) * KT + t % KTS) * 64 + lane;
+        else
+            src0[i] = a.x + ((size_t)(mt * (BM / 16) + (t - W_TILES) / KTS) * KT + (t - W_TILES) % KTS) * 64 + lane;
     }
+    auto issue_stage = [&](int kt, int buf) {
+        uint4 *dst = lds + buf * STAGE_VECS + wave * 64;
 #pragma unroll
-    for (int i = 0; i < X_LD; ++i) {
-        const int v = tid + 256 * i;
-        const int rtl = v / (KTS * 64), ktl = (v / 64) % KTS, ln = v % 64;
-        xsrc[i] = a.x + ((size_t)(mt * (BM / 16) + rtl) * KT + ktl) * 64 + ln;
-    }
+        for (int i = 0; i < NLOAD; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src0[i] + (size_t)kt * (KTS * 64)), (lptr_t)(dst + i * 256), 16, 0, 0);
+    };
 
     v16i acc[TN][TM];
 #pragma unroll
@@ -85,52 +100,119 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
-    uint4 wreg[W_LD], xreg[X_LD];
+    // Software pipeline over k steps of 32.  While the MFMAs of step s run, the
+    // fragments of step s + 1 are already being read from LDS (double-buffered in
+    // registers; scheduling barriers keep the reads ahead of the MFMA block), and
+    // NS - 1 stages of global -> LDS copies are in flight.  When step s + 1 is the
+    // first of the next stage, the wait for that stage and the workgroup barrier
+    // come before its reads, i.e. before the MFMAs of the last step of the current
+    // stage.  The barrier is a bare s_barrier: __syncthreads() would drain every
+    // outstanding copy and cancel the prefetch distance.  The copy issued after the
+    // barrier overwrites the buffer of the stage that is ending: every wavefront
+    // waited for its own last LDS reads of that stage before the barrier.
+    constexpr int KS = BK / 32;
+    auto load_frags = [&](v4i(&fa)[TN], v4i(&fb)[TM], int buf, int ks) {
+        const uint4 *lw = lds + buf * STAGE_VECS;
+        const uint4 *lx = lw + W_TILES * 64;
+        const int kc = 2 * ks + (lane >> 5);              // 16-code chunk inside the stage
+        const int koff = (kc >> 2) * 64 + (kc & 3) * 16;  // k tile and quarter
 #pragma unroll
-    for (int i = 0; i < W_LD; ++i) wreg[i] = wsrc[i][0];
-#pragma unroll
-    for (int i = 0; i < X_LD; ++i) xreg[i] = xsrc[i][0];
-
-    const int stages = a.Kp / BK;
-    for (int kt = 0; kt < stages; ++kt) {
-        __syncthreads();  // previous stage fully consumed
-#pragma unroll
-        for (int i = 0; i < W_LD; ++i) lds_w[tid + 256 * i] = wreg[i];
-#pragma unroll
-        for (int i = 0; i < X_LD; ++i) lds_x[tid + 256 * i] = xreg[i];
-        __syncthreads();
-        if (kt + 1 < stages) {
-            const size_t adv = (size_t)(kt + 1) * KTS * 64;
-#pragma unroll
-            for (int i = 0; i < W_LD; ++i) wreg[i] = wsrc[i][adv];
-#pragma unroll
-            for (int i = 0; i < X_LD; ++i) xreg[i] = xsrc[i][adv];
+        for (int i = 0; i < TN; ++i) {
+            const int row = wn * WN + i * 32 + (lane & 31);
+            fa[i] = __builtin_bit_cast(v4i, lw[(row >> 4) * (KTS * 64) + koff + (row & 15)]);
         }
 #pragma unroll
-        for (int ks = 0; ks < BK / 32; ++ks) {
-            const int kc = 2 * ks + (lane >> 5);           // 16-code chunk inside the stage
-            const int koff = (kc >> 2) * 64 + (kc & 3) * 16;  // k tile and quarter
-            v4i fa[TN], fb[TM];
+        for (int j = 0; j < TM; ++j) {
+            const int row = wm * WM + j * 32 + (lane & 31);
+            fb[j] = __builtin_bit_cast(v4i, lx[(row >> 4) * (KTS * 64) + koff + (row & 15)]);
+        }
+    };
+    auto stage_ready = [&](int kt) {  // stage kt has landed for the whole workgroup
+        if (kt + NS - 2 < stages_total(a.Kp, BK))
+            wait_vmcnt<(NS - 2) * NLOAD>();
+        else
+            wait_vmcnt<0>();
+        asm volatile("s_barrier" ::: "memory");
+    };
+    const int stages = stages_total(a.Kp, BK);
 #pragma unroll
-            for (int i = 0; i < TN; ++i) {
-                const int row = wn * WN + i * 32 + (lane & 31);
-                fa[i] = __builtin_bit_cast(v4i, lds_w[(row >> 4) * (KTS * 64) + koff + (row & 15)]);
-            }
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < stages) issue_stage(p, p);
+    v4i fa[2][TN], fb[2][TM];
+    stage_ready(0);
+    if (NS - 1 < stages) issue_stage(NS - 1, NS - 1);
+    load_frags(fa[0], fb[0], 0, 0);
+    for (int kt = 0; kt < stages; ++kt) {
 #pragma unroll
-            for (int j = 0; j < TM; ++j) {
-                const int row = wm * WM + j * 32 + (lane & 31);
-                fb[j] = __builtin_bit_cast(v4i, lds_x[(row >> 4) * (KTS * 64) + koff + (row & 15)]);
+        for (int ks = 0; ks < KS; ++ks) {
+            constexpr int kKsLast = KS - 1;
+            if (ks < kKsLast) {
+                load_frags(fa[(ks + 1) & 1], fb[(ks + 1) & 1], kt % NS, ks + 1);
+            } else if (kt + 1 < stages) {
+                stage_ready(kt + 1);
+                if (kt + NS < stages) issue_stage(kt + NS, (kt + NS) % NS);
+                load_frags(fa[(ks + 1) & 1], fb[(ks + 1) & 1], (kt + 1) % NS, 0);
             }
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of this step's MFMAs
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int j = 0; j < TM; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
 
-    // epilogue: lane holds token m = .. + lane % 32 and, per group of four
-    // accumulator registers, four consecutive n.
+    // Epilogue.  After the MFMAs a lane holds one token row m (lane % 32) and, per
+    // group of four accumulator registers, four consecutive n: stored as they are,
+    // every store instruction would touch 32 different rows of y with 8 bytes
+    // each.  The scaled binary16 values therefore take a detour through LDS (one
+    // block of 32 token rows x WN channels per wavefront at a time) and leave as
+    // 16-byte stores that cover whole rows segments of 2 * WN contiguous bytes.
+    asm volatile("s_barrier" ::: "memory");  // all wavefronts are done with the stage buffers
+    if (OUT_MODE == 0 && (a.N % 8) == 0) {
+        constexpr int PITCH = (WN + 8) * 2;  // bytes per staged row
+        char *region = reinterpret_cast<char *>(lds) + wave * (32 * PITCH);
+        const int n0 = nt * BN + wn * WN;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int mrow0 = mt * BM + wm * WM + j * 32;
+            const int m = mrow0 + (lane & 31);
+            const float sxm = m < a.M ? a.sx[m] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int nl = i * 32 + 8 * q + 4 * (lane >> 5);
+                    const float4 sc = *reinterpret_cast<const float4 *>(a.sw + n0 + nl);
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    const h4 hv = {(_Float16)((float)acc[i][j][4 * q + 0] * sxm * sc.x),
+                                   (_Float16)((float)acc[i][j][4 * q + 1] * sxm * sc.y),
+                                   (_Float16)((float)acc[i][j][4 * q + 2] * sxm * sc.z),
+                                   (_Float16)((float)acc[i][j][4 * q + 3] * sxm * sc.w)};
+                    *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + nl * 2) = hv;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            constexpr int CH = WN / 8;  // 16-byte chunks per staged row
+#pragma unroll
+            for (int it = 0; it < 32 * CH / 64; ++it) {
+                const int idx = it * 64 + lane;
+                const int row = idx / CH, ch = idx % CH;
+                const uint4 v = *reinterpret_cast<const uint4 *>(region + row * PITCH + ch * 16);
+                const int mm = mrow0 + row, nn = n0 + ch * 8;
+                if (mm < a.M && nn < a.N)
+                    *reinterpret_cast<uint4 *>(static_cast<_Float16 *>(a.out) + (size_t)mm * a.N + nn) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
+    // generic path (raw accumulators, or N not a multiple of 8): direct stores
     const bool vec_ok = (a.N % 4) == 0;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
@@ -175,17 +257,37 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
     }
 }
 
-template <int BN, int BM>
-hipError_t launch_tile(const GemmI8Args &args, int out_mode, hipStream_t st) {
-    GemmI8Args a = args;
+template <int BN, int BM, int KTS, int NS, int OUT_MODE>
+hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
+    constexpr size_t lds_bytes = (size_t)NS * ((BN + BM) / 16 * KTS) * 1024;
+    static_assert(lds_bytes <= 160 * 1024, "LDS budget");
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e =
+            hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_i8_kernel<BN, BM, KTS, NS, OUT_MODE>),
+                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     a.n_tiles = (a.N + BN - 1) / BN;
     a.m_tiles = (a.M + BM - 1) / BM;
-    const dim3 grid((unsigned)(a.n_tiles * a.m_tiles));
-    if (out_mode == 0)
-        gemm_i8_kernel<BN, BM, 0><<<grid, 256, 0, st>>>(a);
-    else
-        gemm_i8_kernel<BN, BM, 1><<<grid, 256, 0, st>>>(a);
+    gemm_i8_kernel<BN, BM, KTS, NS, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
     return hipGetLastError();
+}
+
+template <int OUT_MODE>
+hipError_t launch_mode(const GemmI8Args &a, hipStream_t st) {
+    // Tile shapes measured on MI355X at M = 1024 .. 2048: the 128 x 128 tile with a
+    // four-stage ring of 64-k stages is the fastest or within a few percent of it
+    // on every layer shape tried; the others stay selectable for experiments.
+    int variant = tuning().gemm_variant;
+    if (variant == 0) variant = 3;
+    switch (variant) {
+        case 1: return launch_variant<256, 256, 1, 4, OUT_MODE>(a, st);
+        case 2: return launch_variant<256, 128, 1, 4, OUT_MODE>(a, st);
+        case 4: return launch_variant<128, 128, 2, 3, OUT_MODE>(a, st);
+        default: return launch_variant<128, 128, 1, 4, OUT_MODE>(a, st);
+    }
 }
 
 }  // namespace
@@ -203,7 +305,7 @@ hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *x
     a.N = g.N;
     a.Kp = g.Kp;
     a.n_tiles = a.m_tiles = 0;
-    return launch_tile<128, 128>(a, out_mode, st);
+    return out_mode == 0 ? launch_mode<0>(a, st) : launch_mode<1>(a, st);
 }
 
 }  // namespace qfc
