@@ -37,6 +37,9 @@ def parse():
     p.add_argument("--layers", type=int, default=32, help="decoder layers of the decode step (32 = the full model)")
     p.add_argument("--skip-prefill", action="store_true")
     p.add_argument("--skip-cpu", action="store_true")
+    p.add_argument("--traffic-probe", action="store_true",
+                   help="for rocprofv3 --pmc runs: a few plain copies of a 1 GiB buffer (calibration of "
+                        "FETCH_SIZE / WRITE_SIZE) followed by a few decode steps, then exit")
     return p.parse_args()
 
 
@@ -90,6 +93,17 @@ def main():
         fb = binding.ForwardBatch([layers[j].handle for j in idx], [xs[j] for j in idx], ys, M)
         return fb, ys
 
+    if args.traffic_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        fbp, _ = step_runner(x1, 1)
+        for _ in range(3):
+            fbp.run()
+        torch.cuda.synchronize()
+        print(json.dumps({"traffic_probe": "3 copies of 1 GiB, then 3 decode steps", "layers": args.layers}))
+        return
     bytes_m1 = sum(synth.algorithmic_bytes(fc, 1) for _, _, fc in fcs)
     bytes_m4 = sum(synth.algorithmic_bytes(fc, 4) for _, _, fc in fcs)
     fb1, _ = step_runner(x1, 1)
@@ -144,7 +158,7 @@ def main():
     if not args.skip_cpu:
         import oracle
         cores = oracle.threads()
-        n_layers = 4
+        n_layers = min(args.layers, 32)
         sample = [(l, i, fc) for (l, i, fc) in fcs if l < n_layers and fc.fmt == "w4g32"]
         tot_b, tot_t = 0, 0.0
         for layer, i, fc in sample:
@@ -156,8 +170,8 @@ def main():
             tot_b += synth.algorithmic_bytes(fc, 1)
             del wq, s
         cpu_baseline = {"value": round(tot_b / tot_t / 1e9, 4), "unit": "GB/s", "cores": cores, "kind": "oracle",
-                        "sample": f"first {n_layers} decoder layers ({len(sample)} FCs, {tot_b / 1e6:.0f} MB of packed weights) "
-                                  f"of the same decode step at M=1, {tot_t:.1f} s"}
+                        "sample": f"{n_layers} decoder layers ({len(sample)} int4 FCs, {tot_b / 1e6:.0f} MB of packed weights) "
+                                  f"of the same decode step at M=1, LM head left out; {tot_t:.1f} s of oracle time"}
 
     for l in layers:
         l.close()

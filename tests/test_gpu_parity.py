@@ -234,6 +234,38 @@ def test_int8_prefill_config4_shapes_sampled():
         del wq
 
 
+def test_int8_prefill_config5_lm_head_sampled():
+    """Gemma2-2B LM head (2304 -> 256000, int8 per-channel) at M = 2048: quantized
+    activations bit for bit, sampled accumulators against the exact contraction,
+    sampled outputs within tolerance."""
+    print("config 5 lm head", flush=True)
+    rng = np.random.default_rng(55)
+    M, fc = 2048, synth.GEMMA_LM_HEAD
+    wq, sw = synth.weights(1005, 0, 4, fc)
+    x = synth.activations(1005, 0, 4, M, fc.K)
+    layer = _layer(wq, sw, "w8c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    xd = torch.from_numpy(x).to(DEV)
+    xq = torch.empty((M, fc.K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    binding.qfc_quantize_activations(xd, xq, sx)
+    acc = torch.empty((M, fc.N), dtype=torch.int32, device=DEV)
+    binding.qfc_forward_acc_i32(layer.handle, xq, acc)
+    y = layer.forward(xd)
+    torch.cuda.synchronize()
+    xq_ref, sx_ref = oracle.quantize_activations(x)
+    assert np.array_equal(xq.cpu().numpy(), xq_ref)
+    assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+    rows = np.sort(rng.choice(M, size=32, replace=False))
+    cols = np.sort(rng.choice(fc.N, size=512, replace=False))
+    rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, fc.N - 1
+    ri, ci = torch.from_numpy(rows).to(DEV), torch.from_numpy(cols).to(DEV)
+    acc_ref = oracle.int_contract(xq_ref[rows], wq[cols])
+    assert np.array_equal(acc[ri][:, ci].cpu().numpy().astype(np.int64), acc_ref)
+    y_ref = oracle.rescale(acc_ref, sx_ref[rows], sw[cols])
+    assert oracle.floored_rel_error(y[ri][:, ci].cpu().numpy(), y_ref) <= TOL
+    layer.close()
+
+
 # ------------------------------------------------------------------ A6 fp16 MFMA prefill with in-LDS dequantization
 @pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (130, 1000, 2304)])
 def test_fp16_prefill_matches_oracle(M, N, K):
