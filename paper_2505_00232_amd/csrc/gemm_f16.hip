@@ -142,6 +142,46 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
         }
     }
 
+    // Epilogue.  A lane holds one token row (lane % 32) and groups of four
+    // consecutive n; stored directly, every store instruction would touch 32 rows
+    // of y with 8 bytes each.  The binary16 values go through LDS (32 token rows x
+    // 64 channels per wavefront at a time) and leave as 16-byte stores along n.
+    __syncthreads();  // all wavefronts are done with the tiles in LDS
+    if ((a.N % 8) == 0) {
+        constexpr int PITCH = (64 + 8) * 2;  // bytes per staged row
+        char *region = reinterpret_cast<char *>(lds) + wave * (32 * PITCH);
+        const int n0 = nt * BN + wn * 64;
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int mrow0 = mt * BM + wm * 64 + j * 32;
+#pragma unroll
+            for (int i = 0; i < 2; ++i) {
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const int nl = i * 32 + 8 * qq + 4 * (lane >> 5);
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    const h4 hv = {(_Float16)acc[i][j][4 * qq + 0], (_Float16)acc[i][j][4 * qq + 1],
+                                   (_Float16)acc[i][j][4 * qq + 2], (_Float16)acc[i][j][4 * qq + 3]};
+                    *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + nl * 2) = hv;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {  // 32 rows x 8 chunks of 16 bytes
+                const int idx = it * 64 + lane;
+                const int row = idx >> 3, ch = idx & 7;
+                const uint4 v = *reinterpret_cast<const uint4 *>(region + row * PITCH + ch * 16);
+                const int mm = mrow0 + row, nn = n0 + ch * 8;
+                if (mm < a.M && nn < a.N) *reinterpret_cast<uint4 *>(a.y + (size_t)mm * a.N + nn) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
     const bool vec_ok = (a.N % 4) == 0;
 #pragma unroll
     for (int j = 0; j < 2; ++j) {

@@ -49,6 +49,105 @@ struct GemmI8Args {
     int M, N, Kp, n_tiles, m_tiles;
 };
 
+// Epilogue shared by the product kernels.
+template <int BN, int BM, int OUT_MODE, int TN, int TM>
+__device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM], uint4 *lds, int nt, int mt, int wn,
+                                         int wm, int wave, int lane) {
+    constexpr int WN = BN / 2, WM = BM / 2;
+    // Epilogue.  After the MFMAs a lane holds one token row m (lane % 32) and, per
+    // group of four accumulator registers, four consecutive n: stored as they are,
+    // every store instruction would touch 32 different rows of y with 8 bytes
+    // each.  The scaled binary16 values therefore take a detour through LDS (one
+    // block of 32 token rows x WN channels per wavefront at a time) and leave as
+    // 16-byte stores that cover whole rows segments of 2 * WN contiguous bytes.
+    asm volatile("s_barrier" ::: "memory");  // all wavefronts are done with the stage buffers
+    if (OUT_MODE == 0 && (a.N % 8) == 0) {
+        constexpr int PITCH = (WN + 8) * 2;  // bytes per staged row
+        char *region = reinterpret_cast<char *>(lds) + wave * (32 * PITCH);
+        const int n0 = nt * BN + wn * WN;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int mrow0 = mt * BM + wm * WM + j * 32;
+            const int m = mrow0 + (lane & 31);
+            const float sxm = m < a.M ? a.sx[m] : 0.0f;
+#pragma unroll
+            for (int i = 0; i < TN; ++i) {
+#pragma unroll
+                for (int q = 0; q < 4; ++q) {
+                    const int nl = i * 32 + 8 * q + 4 * (lane >> 5);
+                    const float4 sc = *reinterpret_cast<const float4 *>(a.sw + n0 + nl);
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    const h4 hv = {(_Float16)((float)acc[i][j][4 * q + 0] * sxm * sc.x),
+                                   (_Float16)((float)acc[i][j][4 * q + 1] * sxm * sc.y),
+                                   (_Float16)((float)acc[i][j][4 * q + 2] * sxm * sc.z),
+                                   (_Float16)((float)acc[i][j][4 * q + 3] * sxm * sc.w)};
+                    *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + nl * 2) = hv;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+            constexpr int CH = WN / 8;  // 16-byte chunks per staged row
+#pragma unroll
+            for (int it = 0; it < 32 * CH / 64; ++it) {
+                const int idx = it * 64 + lane;
+                const int row = idx / CH, ch = idx % CH;
+                const uint4 v = *reinterpret_cast<const uint4 *>(region + row * PITCH + ch * 16);
+                const int mm = mrow0 + row, nn = n0 + ch * 8;
+                if (mm < a.M && nn < a.N)
+                    *reinterpret_cast<uint4 *>(static_cast<_Float16 *>(a.out) + (size_t)mm * a.N + nn) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
+    // generic path (raw accumulators, or N not a multiple of 8): direct stores
+    const bool vec_ok = (a.N % 4) == 0;
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int m = mt * BM + wm * WM + j * 32 + (lane & 31);
+        if (m >= a.M) continue;
+        float sxm = 1.0f;
+        if (OUT_MODE == 0) sxm = a.sx[m];
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                const int n = nt * BN + wn * WN + i * 32 + 8 * q + 4 * (lane >> 5);
+                if (n >= a.N) continue;
+                if (OUT_MODE == 0) {
+                    _Float16 *y = static_cast<_Float16 *>(a.out) + (size_t)m * a.N + n;
+                    const float4 s = *reinterpret_cast<const float4 *>(a.sw + n);
+                    const float sv[4] = {s.x, s.y, s.z, s.w};
+                    _Float16 h[4];
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) h[e] = (_Float16)((float)acc[i][j][4 * q + e] * sxm * sv[e]);
+                    if (vec_ok) {
+                        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                        *reinterpret_cast<h4 *>(y) = h4{h[0], h[1], h[2], h[3]};
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < a.N) y[e] = h[e];
+                    }
+                } else {
+                    int32_t *o = static_cast<int32_t *>(a.out) + (size_t)m * a.N + n;
+                    if (vec_ok) {
+                        *reinterpret_cast<int4 *>(o) = make_int4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
+                                                                 acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                    } else {
+#pragma unroll
+                        for (int e = 0; e < 4; ++e)
+                            if (n + e < a.N) o[e] = acc[i][j][4 * q + e];
+                    }
+                }
+            }
+        }
+    }
+}
+
 // KTS = KiB k tiles (64 k each) per stage, NS = LDS stages (prefetch distance NS - 1)
 template <int BN, int BM, int KTS, int NS, int OUT_MODE>
 __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
@@ -163,98 +262,7 @@ __global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
         }
     }
 
-    // Epilogue.  After the MFMAs a lane holds one token row m (lane % 32) and, per
-    // group of four accumulator registers, four consecutive n: stored as they are,
-    // every store instruction would touch 32 different rows of y with 8 bytes
-    // each.  The scaled binary16 values therefore take a detour through LDS (one
-    // block of 32 token rows x WN channels per wavefront at a time) and leave as
-    // 16-byte stores that cover whole rows segments of 2 * WN contiguous bytes.
-    asm volatile("s_barrier" ::: "memory");  // all wavefronts are done with the stage buffers
-    if (OUT_MODE == 0 && (a.N % 8) == 0) {
-        constexpr int PITCH = (WN + 8) * 2;  // bytes per staged row
-        char *region = reinterpret_cast<char *>(lds) + wave * (32 * PITCH);
-        const int n0 = nt * BN + wn * WN;
-#pragma unroll
-        for (int j = 0; j < TM; ++j) {
-            const int mrow0 = mt * BM + wm * WM + j * 32;
-            const int m = mrow0 + (lane & 31);
-            const float sxm = m < a.M ? a.sx[m] : 0.0f;
-#pragma unroll
-            for (int i = 0; i < TN; ++i) {
-#pragma unroll
-                for (int q = 0; q < 4; ++q) {
-                    const int nl = i * 32 + 8 * q + 4 * (lane >> 5);
-                    const float4 sc = *reinterpret_cast<const float4 *>(a.sw + n0 + nl);
-                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                    const h4 hv = {(_Float16)((float)acc[i][j][4 * q + 0] * sxm * sc.x),
-                                   (_Float16)((float)acc[i][j][4 * q + 1] * sxm * sc.y),
-                                   (_Float16)((float)acc[i][j][4 * q + 2] * sxm * sc.z),
-                                   (_Float16)((float)acc[i][j][4 * q + 3] * sxm * sc.w)};
-                    *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + nl * 2) = hv;
-                }
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-            constexpr int CH = WN / 8;  // 16-byte chunks per staged row
-#pragma unroll
-            for (int it = 0; it < 32 * CH / 64; ++it) {
-                const int idx = it * 64 + lane;
-                const int row = idx / CH, ch = idx % CH;
-                const uint4 v = *reinterpret_cast<const uint4 *>(region + row * PITCH + ch * 16);
-                const int mm = mrow0 + row, nn = n0 + ch * 8;
-                if (mm < a.M && nn < a.N)
-                    *reinterpret_cast<uint4 *>(static_cast<_Float16 *>(a.out) + (size_t)mm * a.N + nn) = v;
-            }
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
-        return;
-    }
-    // generic path (raw accumulators, or N not a multiple of 8): direct stores
-    const bool vec_ok = (a.N % 4) == 0;
-#pragma unroll
-    for (int j = 0; j < TM; ++j) {
-        const int m = mt * BM + wm * WM + j * 32 + (lane & 31);
-        if (m >= a.M) continue;
-        float sxm = 1.0f;
-        if (OUT_MODE == 0) sxm = a.sx[m];
-#pragma unroll
-        for (int i = 0; i < TN; ++i) {
-#pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const int n = nt * BN + wn * WN + i * 32 + 8 * q + 4 * (lane >> 5);
-                if (n >= a.N) continue;
-                if (OUT_MODE == 0) {
-                    _Float16 *y = static_cast<_Float16 *>(a.out) + (size_t)m * a.N + n;
-                    const float4 s = *reinterpret_cast<const float4 *>(a.sw + n);
-                    const float sv[4] = {s.x, s.y, s.z, s.w};
-                    _Float16 h[4];
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) h[e] = (_Float16)((float)acc[i][j][4 * q + e] * sxm * sv[e]);
-                    if (vec_ok) {
-                        typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                        *reinterpret_cast<h4 *>(y) = h4{h[0], h[1], h[2], h[3]};
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n + e < a.N) y[e] = h[e];
-                    }
-                } else {
-                    int32_t *o = static_cast<int32_t *>(a.out) + (size_t)m * a.N + n;
-                    if (vec_ok) {
-                        *reinterpret_cast<int4 *>(o) = make_int4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
-                                                                 acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
-                    } else {
-#pragma unroll
-                        for (int e = 0; e < 4; ++e)
-                            if (n + e < a.N) o[e] = acc[i][j][4 * q + e];
-                    }
-                }
-            }
-        }
-    }
+    epilogue<BN, BM, OUT_MODE, TN, TM>(a, acc, lds, nt, mt, wn, wm, wave, lane);
 }
 
 template <int BN, int BM, int KTS, int NS, int OUT_MODE>

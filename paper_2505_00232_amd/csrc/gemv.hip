@@ -21,6 +21,8 @@
 // activations) and splits K over its wavefronts; their partial sums meet in
 // LDS in fixed order, so results are deterministic.  There is no reduction
 // across workgroups and no atomics.
+#include <type_traits>
+
 #include "qfc_internal.h"
 
 namespace qfc {
@@ -158,20 +160,25 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[r][i] = 0.0f;
 
-    // item = (unit, row tile); its vectors: weight tiles 0..nt-1, then (W4G32) 4 scale vectors
-    auto load_item = [&](u32x4(&buf)[NV], int u, int r) {
-        const int nt = min(TILES, a.KT - TILES * u);
+    // item = (unit, row tile); its vectors: (W4G32) 4 scale vectors, then weight tiles 0..nt-1.
+    // `full` = all 8 tiles present: unconditional loads, so that the compiler can
+    // count them and wait tile by tile instead of for everything.
+    auto load_item = [&](u32x4(&buf)[NV], int u, int r, auto full) {
+        const int nt = full ? TILES : min(TILES, a.KT - TILES * u);
         const int pos = FMT == kW4G32 ? 9 * u : TILES * u;
         const u32x4 *base = a.packed + ((size_t)(rt0 + r) * a.rt_stride + pos) * 64;
-#pragma unroll
-        for (int t = 0; t < TILES; ++t)
-            if (t < nt) buf[t] = __builtin_nontemporal_load(base + t * 64 + lane);
+        // scales first: loads return in order, and the first tile's results need them
         if (FMT == kW4G32) {
 #pragma unroll
             for (int p = 0; p < 4; ++p)
                 buf[TILES + p] = __builtin_nontemporal_load(base + nt * 64 + p * 16 + c);
         }
+#pragma unroll
+        for (int t = 0; t < TILES; ++t)
+            if (full || t < nt) buf[t] = __builtin_nontemporal_load(base + t * 64 + lane);
     };
+    constexpr std::false_type kMaybePartial{};
+    constexpr std::true_type kFull{};
 
     // Two variants.  DB = false: latency is hidden by occupancy, a wavefront
     // requests the activations and all weight vectors of an item at once, waits,
@@ -185,22 +192,21 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     u32x4 nxt[DB ? NV : 1];
     const int items = (u1 - u0) * R;
     int u = u0, r = 0;
-    if (items > 0) {
-        xs.load(a, u0, lane);
-        load_item(cur, u0, 0);
-        if constexpr (DB) {
-            if (items > 1) load_item(nxt, R > 1 ? u0 : u0 + 1, R > 1 ? 1 : 0);
+    if constexpr (DB) {
+        if (items > 0) {
+            xs.load(a, u0, lane);
+            load_item(cur, u0, 0, kMaybePartial);
+            if (items > 1) load_item(nxt, R > 1 ? u0 : u0 + 1, R > 1 ? 1 : 0, kMaybePartial);
         }
     }
+    auto stage = [&]() {
+        // the wavefront's earlier LDS reads are done (same wavefront, in order)
+        xs.store(lds_x, lane);
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    };
     for (int it = 0; it < items; ++it) {
-        if (r == 0) {
-            // new unit: the wavefront's earlier LDS reads are done (same wavefront, in order)
-            xs.store(lds_x, lane);
-            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
-            __builtin_amdgcn_wave_barrier();
-            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
-        }
-
         const int nt = min(TILES, a.KT - TILES * u);
         float accr[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         v4f accw = {0.0f, 0.0f, 0.0f, 0.0f};
@@ -240,7 +246,7 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
                 accw = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], dequant_i8x8(cur[t].z, cur[t].w), accw, 0, 0, 0);
             }
         };
-        if (nt == TILES) {
+        auto compute_full = [&]() {
             // full unit: straight-line code, A operands fetched one tile ahead
             v8h xa[XA], xn[XA];
             load_xa(xa, 0);
@@ -251,7 +257,8 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
 #pragma unroll
                 for (int j = 0; j < XA; ++j) xa[j] = xn[j];
             }
-        } else {
+        };
+        auto compute_tail = [&]() {
 #pragma unroll
             for (int t = 0; t < TILES; ++t) {
                 if (t < nt) {
@@ -259,6 +266,25 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
                     load_xa(xa, t);
                     tile_math(xa, t);
                 }
+            }
+        };
+        if constexpr (DB) {
+            if (r == 0) stage();
+            if (nt == TILES)
+                compute_full();
+            else
+                compute_tail();
+        } else {
+            // single buffer: request, stage and compute inside one branch
+            if (r == 0) xs.load(a, u, lane);
+            if (nt == TILES) {
+                load_item(cur, u, r, kFull);
+                if (r == 0) stage();
+                compute_full();
+            } else {
+                load_item(cur, u, r, kMaybePartial);
+                if (r == 0) stage();
+                compute_tail();
             }
         }
         if (FMT == kW4G32) {
@@ -276,14 +302,12 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
             r = 0;
             ++u;
         }
-        if (it + 1 < items) {
-            if (r == 0) xs.load(a, u, lane);
-            if constexpr (DB) {
+        if constexpr (DB) {
+            if (it + 1 < items) {
+                if (r == 0) xs.load(a, u, lane);
 #pragma unroll
                 for (int v = 0; v < NV; ++v) cur[v] = nxt[v];
-                if (it + 2 < items) load_item(nxt, r + 1 == R ? u + 1 : u, r + 1 == R ? 0 : r + 1);
-            } else {
-                load_item(cur, u, r);
+                if (it + 2 < items) load_item(nxt, r + 1 == R ? u + 1 : u, r + 1 == R ? 0 : r + 1, kMaybePartial);
             }
         }
     }
