@@ -151,7 +151,7 @@ qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (M > kMaxDecodeM && h->desc.compute_mode == QFC_COMPUTE_FP16_DEQUANT) {
         if (h->geo.fmt != kW4G32) return QFC_ERR_UNSUPPORTED;
-        return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, st));
+        return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
     }
     if (M <= kMaxDecodeM)
         return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));

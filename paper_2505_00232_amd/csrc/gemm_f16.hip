@@ -3,6 +3,19 @@
 // FP16 activations with quantized weights (section 4.2 of the paper), computed
 // on matrix units as the compute-bound prefill stage wants (section 3.7).
 //
+// Two kernels.  The main one (K a multiple of 128) never puts weights into LDS:
+// a packed weight tile is, lane for lane, a sequence of four 16x16x32 MFMA
+// operands (16 output rows x the 32 k of one quantization group), so every
+// wavefront loads the tiles of its own 64 output rows straight from memory into
+// registers, converts them there (exact int -> binary16, one binary16 multiply
+// by the group scale) and feeds the matrix core; only the activations, which
+// all wavefronts of the workgroup share, go through LDS, copied there as they
+// are by direct global -> LDS loads in a four-stage ring.  Int4 weights are a
+// quarter of the activation bytes, so the register path costs little memory
+// traffic, and LDS carries half the bytes per MFMA of a kernel that stages both
+// operands.  The second kernel is the general fallback (any K that is a
+// multiple of 32):
+//
 // Per K stage of 128 (one packed weight tile per 16 rows): every thread loads
 // 16-byte vectors of packed codes (four octets, one per quantization group of
 // the tile) plus the four group scales of its row, dequantizes in registers
@@ -210,18 +223,361 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
     }
 }
 
-}  // namespace
 
-hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                           hipStream_t st) {
-    if (g.fmt != kW4G32) return hipErrorNotSupported;
+// ---------------------------------------------------------------------------
+// Main kernel: weights never dequantized into LDS, activations through an LDS ring.
+//
+// Workgroup = 8 wavefronts over 256 output channels x 128 token rows: four
+// groups of 64 channels (four packed row tiles each), times two halves of K.
+// Both wavefronts of a channel group own the same 64 x 128 outputs as 2 x 4
+// tiles of v_mfma_f32_32x32x16_f16; in every 128-k tile one takes quantization
+// groups 0, 1 and the other groups 2, 3, and their accumulators are added through
+// LDS at the end.  The two share a SIMD, so that the integer -> binary16
+// conversion of one (about 60 vector instructions per group, each done by exactly
+// one wavefront of the chip) runs while the matrix core works for the other:
+// from a single wavefront the conversion and the MFMAs mostly add up instead of
+// overlapping.  (Measured on MI355X: this MFMA shape runs at the full matrix rate
+// from one wavefront per SIMD; the 16x16x32 shape reaches less than half of it.)
+// Weights are the row operand, so a lane ends up with groups of four consecutive
+// n of one token row.
+//
+// Everything arrives by direct global -> LDS copies (16 bytes per lane, one KiB
+// per wavefront instruction).  Per 128-k tile every wavefront issues one batch of
+// 7 copies: 2 of the 16 packed KiB tiles of codes (tile j + 3), the scales of its
+// channel group for tile j + 3 (lane = one of the 64 rows, 16 bytes = 8 groups;
+// both wavefronts of the group write the same bytes), and 4 KiB of the 32 KiB
+// activation stage j + 2 (128 rows x 128 k, stored as two halves of 64 k).
+// Three-slot rings; nothing else touches vector memory inside the loop, so the
+// copies complete in issue order and "the batch issued two tiles ago has landed"
+// is "at most one batch is outstanding".  One workgroup barrier per tile.
+//
+// Inside a wavefront the loop is software pipelined by one quantization group:
+// while the 16 MFMAs of a group run, the activations of the next group are read
+// from LDS and its codes are converted (exact int -> binary16, one binary16
+// multiply by the group scale); the codes and scales of a tile are read into
+// registers at the end of the tile before.
+//
+// An MFMA operand is 32 rows x 16 k, lane = (row r, k octet kh).  For the
+// weights, lane (r, kh) of row pair ip, k step s owns the 16-byte vector of row
+// tile 2 ip + r / 16, lane (2 s + kh) * 16 + r % 16 of a packed tile: dword g of
+// it is the lane's operand for group g.
+// A half of an activation stage is 128 rows x 64 k, row-major with 128-byte
+// rows; the 16-byte octet o of row r sits at octet position o ^ ((r >> 1) & 7),
+// which makes the operand reads conflict free while a wavefront copy instruction
+// still reads whole 128-byte rows from memory.
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+constexpr int DBN = 256, DBM = 128;
+constexpr int DRING = 3;
+constexpr int DX_BYTES = DBM * 128 * 2;           // activation stage: 128 rows x 128 k
+constexpr int DW_BYTES = 16 * 1024;               // codes of one tile: 16 row tiles
+constexpr int DS_BYTES = 4 * 1024;                // scales for one tile: 4 channel groups x 64 rows x 16 B
+constexpr int DW_OFF = DRING * DX_BYTES;
+constexpr int DS_OFF = DW_OFF + DRING * DW_BYTES;
+constexpr int kDirectLdsBytes = DS_OFF + DRING * DS_BYTES;
+constexpr int DBATCH = 2 + 1 + 4;                 // copies per wavefront per tile
+constexpr int DRED_BYTES = 4 * 128 * 64 * 4;      // accumulators of the four upper-half wavefronts
+constexpr int DEPI_PITCH = (64 + 8) * 2;
+static_assert(DRED_BYTES + 4 * 32 * DEPI_PITCH <= kDirectLdsBytes, "epilogue staging fits behind the reduction buffer");
+
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {  // vmcnt <= N, LDS operations done
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+}
+
+// Direct global -> LDS copy of one wavefront: lane l moves 16 bytes from
+// base + offset(l) to LDS byte address lds_base + 16 l.  Written as assembly
+// because the compiler, when it knows about such a copy, makes every later LDS
+// read wait for ALL outstanding copies (it cannot tell ring slots apart), which
+// would serialize the prefetch ring; the waits are explicit here instead.  M0
+// carries the LDS base (nothing else in this kernel uses M0).
+__device__ __forceinline__ void copy16_to_lds(const void *base, uint32_t lane_offset, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(base), "s"(lds_base)
+                 : "memory");
+}
+
+// eight biased codes -> eight scaled binary16 values (k ascending) as an MFMA operand
+__device__ __forceinline__ v8h dequant_frag(uint32_t w, h2 s) {
+    const h2 c1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
+    const h2 c72 = {(_Float16)72.0f, (_Float16)72.0f};
+    const h2 c16th = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const uint32_t lo = w & 0x0F0F0F0Fu, hi = w & 0xF0F0F0F0u;
+    const h2 p0 = (as_h2(__builtin_amdgcn_perm(0x64646464u, lo, 0x04010400u)) - c1032) * s;
+    const h2 p1 = (as_h2(__builtin_amdgcn_perm(0x64646464u, lo, 0x04030402u)) - c1032) * s;
+    const h2 p2 = (as_h2(__builtin_amdgcn_perm(0x64646464u, hi, 0x04010400u)) * c16th - c72) * s;
+    const h2 p3 = (as_h2(__builtin_amdgcn_perm(0x64646464u, hi, 0x04030402u)) * c16th - c72) * s;
+    return v8h{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+}
+
+// One MFMA followed by a few vector instructions, 16 times: the order the
+// instructions of a "multiply one group, convert the next" block are issued in.
+// The first MFMAs go alone so that the LDS reads issued just before have time to
+// land before the first conversion instruction needs them.
+__device__ __forceinline__ void interleave_mfma_valu() {
+#pragma unroll
+    for (int i = 0; i < 3; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+#pragma unroll
+    for (int i = 0; i < 13; ++i) {
+        __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+    }
+}
+
+__global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) {
+    extern __shared__ uint4 lds[];
+    char *lds_b = reinterpret_cast<char *>(lds);
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int ng = wave & 3;   // channel group: output channels 64 ng .. 64 ng + 63 of the tile
+    const int ks = wave >> 2;  // K half: quantization groups 2 ks, 2 ks + 1 of every 128-k tile
+    const int c = lane & 15, q = lane >> 4;
+    const int r = lane & 31, kh = lane >> 5;
+
+    const int total = a.n_tiles * a.m_tiles;
+    int logical = blockIdx.x;
+    if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
+    const int nt = logical / a.m_tiles;
+    const int mt = logical % a.m_tiles;
+
+    const int KT = a.KT;  // packed weight tiles (128 k) per row tile; K is a multiple of 128 here
+
+    // Sources of the copies: a wavefront-uniform base that advances along K, plus
+    // a per-lane byte offset that never changes.
+    // activations: block b = wave + 8 i (i < 4) = rows 8 (b % 16) .. + 7 of half b / 16 = i / 2
+    const char *xbase = reinterpret_cast<const char *>(a.x) + (size_t)mt * DBM * a.K * 2;
+    uint32_t xlane[2];
+#pragma unroll
+    for (int i = 0; i < 2; ++i) {
+        const int rl = 8 * (wave + 8 * i) + (lane >> 3);
+        const int oct = (lane & 7) ^ ((rl >> 1) & 7);
+        const int row = min(mt * DBM + rl, a.M - 1) - mt * DBM;  // rows past M: any finite data, never stored
+        xlane[i] = (uint32_t)row * (uint32_t)a.K * 2u + oct * 16;
+    }
+    // codes: row tiles 2 ks, 2 ks + 1 of the channel group; lane l takes vector l of a packed tile
+    const char *wbase = reinterpret_cast<const char *>(a.w) + (size_t)(nt * (DBN / 16) + ng * 4 + ks * 2) * a.rt_stride * 1024;
+    const uint32_t wlane = lane * 16;
+    // scales: lane l = (row tile l / 16, row l % 16) takes the 16-byte vector of its row
+    const char *sbase = reinterpret_cast<const char *>(a.w) + (size_t)(nt * (DBN / 16) + ng * 4) * a.rt_stride * 1024;
+    const uint32_t slane = (uint32_t)q * a.rt_stride * 1024u + c * 16;
+    const size_t rt_bytes = (size_t)a.rt_stride * 1024;
+
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;  // LDS byte address of the rings
+    auto issue_ws = [&](int t) {  // codes and scales of tile t (clamped: past the end the last tile again)
+        const int tc = min(t, KT - 1), u = tc >> 3;
+        const size_t wpos = (size_t)(tc + u) * 1024;
+        const uint32_t wdst = lds0 + DW_OFF + (t % DRING) * DW_BYTES + (ng * 4 + ks * 2) * 1024;
+        copy16_to_lds(wbase + wpos, wlane, wdst);
+        copy16_to_lds(wbase + rt_bytes + wpos, wlane, wdst + 1024);
+        // vector (t % 8) / 2 * 16 + row of the unit's scale tile holds the scales of 8 groups = 2 tiles
+        const size_t spos = (size_t)(min(8 * u + 8, KT) + u) * 1024 + (size_t)((tc & 7) >> 1) * 256;
+        copy16_to_lds(sbase + spos, slane, lds0 + DS_OFF + (t % DRING) * DS_BYTES + ng * 1024);
+    };
+    auto issue_x = [&](int t) {  // activation stage t
+        const int tc = min(t, KT - 1);
+        const uint32_t xdst = lds0 + (t % DRING) * DX_BYTES + wave * 1024;
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            copy16_to_lds(xbase + (size_t)tc * 256 + (i >> 1) * 128, xlane[i & 1], xdst + (i >> 1) * (DX_BYTES / 2) + (i & 1) * 8192);
+    };
+
+    v16f acc[2][4];
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 4; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
+
+    // operand read addresses of this lane
+    int xoff[2][2];  // [group of the half][k step s]: row r, octet (4 g + 2 s + kh) ^ ((r >> 1) & 7)
+#pragma unroll
+    for (int g = 0; g < 2; ++g)
+#pragma unroll
+        for (int s = 0; s < 2; ++s) xoff[g][s] = ks * (DX_BYTES / 2) + r * 128 + (((4 * g + 2 * s + kh) ^ ((r >> 1) & 7)) << 4);
+    const char *wring = lds_b + DW_OFF + ng * 4096 + ((r >> 4) * 64 + kh * 16 + (r & 15)) * 16 + ks * 8;
+    const char *sring = lds_b + DS_OFF + ng * 1024 + r * 16 + ks * 4;
+
+    uint4 x0[4][2], x1[4][2];  // activations of a group: [token row block jp][k step s]
+    uint2 wv[2][2];            // codes of the current tile: [row pair ip][k step s], .x / .y = this wavefront's two groups
+    uint32_t sv[2];            // their scales: [row pair ip], two binary16
+    v8h fa0[2][2], fa1[2][2];  // converted weights of a group
+
+    auto read_x = [&](uint4 (&x)[4][2], int g, int t) {
+        const char *lx = lds_b + (t % DRING) * DX_BYTES;
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp)
+#pragma unroll
+            for (int s = 0; s < 2; ++s) x[jp][s] = *reinterpret_cast<const uint4 *>(lx + xoff[g][s] + jp * 4096);
+    };
+    auto read_ws = [&](int t) {
+#pragma unroll
+        for (int ip = 0; ip < 2; ++ip) {
+#pragma unroll
+            for (int s = 0; s < 2; ++s)
+                wv[ip][s] = *reinterpret_cast<const uint2 *>(wring + (t % DRING) * DW_BYTES + ip * 2048 + s * 512);
+            sv[ip] = *reinterpret_cast<const uint32_t *>(sring + (t % DRING) * DS_BYTES + ip * 512 + (t & 1) * 8);
+        }
+    };
+    auto convert = [&](v8h (&fa)[2][2], int g) {  // g = 0, 1: group of this wavefront's half of the tile
+#pragma unroll
+        for (int ip = 0; ip < 2; ++ip) {
+            const h2 s2 = as_h2(__builtin_amdgcn_perm(0u, sv[ip], g ? 0x03020302u : 0x01000100u));
+#pragma unroll
+            for (int s = 0; s < 2; ++s) fa[ip][s] = dequant_frag(g ? wv[ip][s].y : wv[ip][s].x, s2);
+        }
+    };
+    auto multiply = [&](const v8h (&fa)[2][2], const uint4 (&x)[4][2]) {
+#pragma unroll
+        for (int s = 0; s < 2; ++s)
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp)
+#pragma unroll
+                for (int ip = 0; ip < 2; ++ip)
+                    acc[ip][jp] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ip][s], __builtin_bit_cast(v8h, x[jp][s]),
+                                                                         acc[ip][jp], 0, 0, 0);
+    };
+
+    // Copies in issue order: codes/scales 0, codes/scales 1, stage 0 | codes/scales 2,
+    // stage 1 | then at the top of tile t: codes/scales t + 3, stage t + 2.  Past the
+    // end of K the last tile is copied again (into slots nobody reads any more) so
+    // that the count holds on every iteration.
+    issue_ws(0);
+    issue_ws(1);
+    issue_x(0);
+    issue_ws(2);
+    issue_x(1);
+#pragma unroll
+    for (int i = 0; i < 2; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) fa1[i][j] = v8h{0, 0, 0, 0, 0, 0, 0, 0};
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+#pragma unroll
+        for (int j = 0; j < 2; ++j) x1[i][j] = make_uint4(0, 0, 0, 0);
+    wait_vmcnt<DBATCH>();
+    asm volatile("s_barrier" ::: "memory");
+    read_ws(0);
+    for (int t = 0; t < KT; ++t) {
+        // What was issued two tiles ago has landed once only the newest batch is
+        // outstanding: stage t, codes and scales of tile t + 1.  The barrier makes
+        // the other wavefronts' copies visible and says that every wavefront is done
+        // with stage t - 1 and has the codes of tile t in registers: their slots are
+        // overwritten next.
+        wait_vmcnt<DBATCH>();
+        asm volatile("s_barrier" ::: "memory");
+        issue_ws(t + 3);
+        issue_x(t + 2);
+        read_x(x0, 0, t);
+        __builtin_amdgcn_sched_barrier(0);  // the reads are in flight before the MFMAs start
+        multiply(fa1, x1);
+        convert(fa0, 0);
+        interleave_mfma_valu();
+        __builtin_amdgcn_sched_barrier(0);
+        read_x(x1, 1, t);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(fa0, x0);
+        convert(fa1, 1);
+        interleave_mfma_valu();
+        __builtin_amdgcn_sched_barrier(0);
+        read_ws(t + 1);
+    }
+    multiply(fa1, x1);
+    wait_vmcnt<0>();
+
+    // The upper-half wavefronts hand their accumulators over through LDS
+    // ([channel group][register][lane], 128 KiB over the dead rings).
+    asm volatile("s_barrier" ::: "memory");  // every wavefront is done with the rings
+    float *red = reinterpret_cast<float *>(lds_b) + ng * (128 * 64) + lane;
+    if (ks == 1) {
+#pragma unroll
+        for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+            for (int jp = 0; jp < 4; ++jp)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) red[((ip * 4 + jp) * 16 + e) * 64] = acc[ip][jp][e];
+    }
+    __syncthreads();
+    if (ks == 1) return;
+#pragma unroll
+    for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[ip][jp][e] += red[((ip * 4 + jp) * 16 + e) * 64];
+
+    // Epilogue: a lane holds one token row (lane % 32) and groups of four
+    // consecutive n.  The binary16 values go through a per-wavefront LDS block
+    // (32 token rows x 64 channels, behind the reduction buffer) and leave as
+    // 16-byte stores along n.
+    const int n0 = nt * DBN + ng * 64;
+    if ((a.N % 8) == 0) {
+        char *region = lds_b + DRED_BYTES + ng * (32 * DEPI_PITCH);
+#pragma unroll
+        for (int jp = 0; jp < 4; ++jp) {
+            const int mrow0 = mt * DBM + jp * 32;
+#pragma unroll
+            for (int ip = 0; ip < 2; ++ip) {
+#pragma unroll
+                for (int qq = 0; qq < 4; ++qq) {
+                    const int nl = ip * 32 + 8 * qq + 4 * kh;
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    const h4 hv = {(_Float16)acc[ip][jp][4 * qq + 0], (_Float16)acc[ip][jp][4 * qq + 1],
+                                   (_Float16)acc[ip][jp][4 * qq + 2], (_Float16)acc[ip][jp][4 * qq + 3]};
+                    *reinterpret_cast<h4 *>(region + r * DEPI_PITCH + nl * 2) = hv;
+                }
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int it = 0; it < 4; ++it) {  // 32 rows x 8 chunks of 16 bytes
+                const int idx = it * 64 + lane;
+                const int row = idx >> 3, ch = idx & 7;
+                const uint4 v = *reinterpret_cast<const uint4 *>(region + row * DEPI_PITCH + ch * 16);
+                const int mm = mrow0 + row, nn = n0 + ch * 8;
+                if (mm < a.M && nn < a.N) *reinterpret_cast<uint4 *>(a.y + (size_t)mm * a.N + nn) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
+#pragma unroll
+    for (int jp = 0; jp < 4; ++jp) {
+        const int m = mt * DBM + jp * 32 + r;
+        if (m >= a.M) continue;
+#pragma unroll
+        for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int n = n0 + ip * 32 + 8 * (e >> 2) + 4 * kh + (e & 3);
+                if (n < a.N) a.y[(size_t)m * a.N + n] = (_Float16)acc[ip][jp][e];
+            }
+    }
+}
+
+hipError_t launch_direct(GemmF16Args a, int M, hipStream_t st) {
     static bool attr_set = false;
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_direct_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kDirectLdsBytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
+    a.n_tiles = (a.N + DBN - 1) / DBN;
+    a.m_tiles = (M + DBM - 1) / DBM;
+    gemm_f16_w4_direct_kernel<<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 512, kDirectLdsBytes, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
+                           int num_cus, hipStream_t st) {
+    if (g.fmt != kW4G32) return hipErrorNotSupported;
     GemmF16Args a;
     a.w = static_cast<const uint4 *>(packed);
     a.x = static_cast<const uint4 *>(x);
@@ -231,6 +587,15 @@ hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x,
     a.K = g.K;
     a.KT = g.KT;
     a.rt_stride = g.rt_stride;
+    (void)num_cus;
+    if ((g.K % 128) == 0 && tuning().gemm_variant != 9) return launch_direct(a, M, st);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_kernel),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     a.n_tiles = (g.N + BN - 1) / BN;
     a.m_tiles = (M + BM - 1) / BM;
     gemm_f16_w4_kernel<<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, kLdsBytes, st>>>(a);

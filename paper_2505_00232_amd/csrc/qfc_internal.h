@@ -120,6 +120,6 @@ hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *x
                           const float *sx, int M, int Mp, void *out, int out_mode,
                           hipStream_t st);
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                           hipStream_t st);
+                           int num_cus, hipStream_t st);
 
 }  // namespace qfc

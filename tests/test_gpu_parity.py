@@ -267,7 +267,8 @@ def test_int8_prefill_config5_lm_head_sampled():
 
 
 # ------------------------------------------------------------------ A6 fp16 MFMA prefill with in-LDS dequantization
-@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (130, 1000, 2304)])
+@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (130, 1000, 2304),
+                                   (300, 264, 128), (129, 520, 1152), (16, 256, 2176)])
 def test_fp16_prefill_matches_oracle(M, N, K):
     print(f"fp16 prefill M={M} N={N} K={K}", flush=True)
     fc = synth.FC("t", K, N, "w4g32")
