@@ -231,8 +231,8 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
 // groups of 64 channels (four packed row tiles each), times two halves of K.
 // Both wavefronts of a channel group own the same 64 x 128 outputs as 2 x 4
 // tiles of v_mfma_f32_32x32x16_f16; in every 128-k tile one takes quantization
-// groups 0, 1 and the other groups 2, 3, and their accumulators are added through
-// LDS at the end.  The two share a SIMD, so that the integer -> binary16
+// groups 0, 1 and the other groups 2, 3; at the end they swap halves of their
+// accumulators through LDS and each stores half of the outputs.  The two share a SIMD, so that the integer -> binary16
 // conversion of one (about 60 vector instructions per group, each done by exactly
 // one wavefront of the chip) runs while the matrix core works for the other:
 // from a single wavefront the conversion and the MFMAs mostly add up instead of
@@ -276,9 +276,9 @@ constexpr int DW_OFF = DRING * DX_BYTES;
 constexpr int DS_OFF = DW_OFF + DRING * DW_BYTES;
 constexpr int kDirectLdsBytes = DS_OFF + DRING * DS_BYTES;
 constexpr int DBATCH = 2 + 1 + 4;                 // copies per wavefront per tile
-constexpr int DRED_BYTES = 4 * 128 * 64 * 4;      // accumulators of the four upper-half wavefronts
+constexpr int DEX_BYTES = 64 * 64 * 4;            // half of a wavefront's accumulators (exchange buffer)
 constexpr int DEPI_PITCH = (64 + 8) * 2;
-static_assert(DRED_BYTES + 4 * 32 * DEPI_PITCH <= kDirectLdsBytes, "epilogue staging fits behind the reduction buffer");
+static_assert(8 * DEX_BYTES <= kDirectLdsBytes && 32 * DEPI_PITCH <= DEX_BYTES, "exchange and store staging fit in the rings");
 
 template <int N>
 __device__ __forceinline__ void wait_vmcnt() {  // vmcnt <= N, LDS operations done
@@ -309,17 +309,14 @@ __device__ __forceinline__ v8h dequant_frag(uint32_t w, h2 s) {
     return v8h{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
 }
 
-// One MFMA followed by a few vector instructions, 16 times: the order the
-// instructions of a "multiply one group, convert the next" block are issued in.
-// The first MFMAs go alone so that the LDS reads issued just before have time to
-// land before the first conversion instruction needs them.
+// One MFMA followed by a few vector instructions, four times: the order the
+// instructions of a quarter of a "multiply one group, convert the next" block
+// (4 MFMAs, the conversion of one operand) are issued in.
 __device__ __forceinline__ void interleave_mfma_valu() {
 #pragma unroll
-    for (int i = 0; i < 3; ++i) __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-#pragma unroll
-    for (int i = 0; i < 13; ++i) {
+    for (int i = 0; i < 4; ++i) {
         __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-        __builtin_amdgcn_sched_group_barrier(0x002, 5, 0);
+        __builtin_amdgcn_sched_group_barrier(0x002, 4, 0);
     }
 }
 
@@ -335,11 +332,23 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     const int c = lane & 15, q = lane >> 4;
     const int r = lane & 31, kh = lane >> 5;
 
+    // Workgroups are dealt to the 8 XCDs round robin; each XCD has its own L2.  Where
+    // the tile grid allows, an XCD gets a rectangle of (n_tiles / 2) x (m_tiles / 4)
+    // tiles and walks it channel tile by channel tile, so that the workgroups in
+    // flight on it (about 32) share 4 activation tiles and 8 weight tiles.
     const int total = a.n_tiles * a.m_tiles;
-    int logical = blockIdx.x;
-    if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
-    const int nt = logical / a.m_tiles;
-    const int mt = logical % a.m_tiles;
+    int nt, mt;
+    if (a.m_tiles % 4 == 0 && a.n_tiles % 2 == 0) {
+        const int xcd = blockIdx.x % 8, j = blockIdx.x / 8;
+        const int cm = a.m_tiles / 4, cn = a.n_tiles / 2;
+        nt = (xcd & 1) * cn + j / cm;
+        mt = (xcd >> 1) * cm + j % cm;
+    } else {
+        int logical = blockIdx.x;
+        if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
+        nt = logical / a.m_tiles;
+        mt = logical % a.m_tiles;
+    }
 
     const int KT = a.KT;  // packed weight tiles (128 k) per row tile; K is a multiple of 128 here
 
@@ -364,22 +373,31 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     const size_t rt_bytes = (size_t)a.rt_stride * 1024;
 
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;  // LDS byte address of the rings
-    auto issue_ws = [&](int t) {  // codes and scales of tile t (clamped: past the end the last tile again)
+    // The 7 copies of a batch, one at a time (they are spread over the MFMA blocks of
+    // a tile: issued together by all eight wavefronts right after the barrier they
+    // would queue up behind each other in the memory pipeline while the matrix
+    // cores idle).  Index t is clamped: past the end of K the last tile is copied
+    // again, into slots nobody reads any more, so that the count of outstanding
+    // copies is the same on every iteration.
+    auto issue_w = [&](int t, int i) {  // codes of tile t, row tile 2 ks + i of the channel group
+        const int tc = min(t, KT - 1);
+        const size_t wpos = (size_t)(tc + (tc >> 3)) * 1024;
+        copy16_to_lds(wbase + i * rt_bytes + wpos, wlane, lds0 + DW_OFF + (t % DRING) * DW_BYTES + (ng * 4 + ks * 2 + i) * 1024);
+    };
+    auto issue_s = [&](int t) {  // scales of tile t: vector (t % 8) / 2 * 16 + row of the unit's scale tile (8 groups = 2 tiles)
         const int tc = min(t, KT - 1), u = tc >> 3;
-        const size_t wpos = (size_t)(tc + u) * 1024;
-        const uint32_t wdst = lds0 + DW_OFF + (t % DRING) * DW_BYTES + (ng * 4 + ks * 2) * 1024;
-        copy16_to_lds(wbase + wpos, wlane, wdst);
-        copy16_to_lds(wbase + rt_bytes + wpos, wlane, wdst + 1024);
-        // vector (t % 8) / 2 * 16 + row of the unit's scale tile holds the scales of 8 groups = 2 tiles
         const size_t spos = (size_t)(min(8 * u + 8, KT) + u) * 1024 + (size_t)((tc & 7) >> 1) * 256;
         copy16_to_lds(sbase + spos, slane, lds0 + DS_OFF + (t % DRING) * DS_BYTES + ng * 1024);
     };
-    auto issue_x = [&](int t) {  // activation stage t
+    auto issue_x = [&](int t, int i) {  // activation stage t, block wave + 8 (i % 2) of half i / 2
         const int tc = min(t, KT - 1);
-        const uint32_t xdst = lds0 + (t % DRING) * DX_BYTES + wave * 1024;
+        copy16_to_lds(xbase + (size_t)tc * 256 + (i >> 1) * 128, xlane[i & 1],
+                      lds0 + (t % DRING) * DX_BYTES + wave * 1024 + (i >> 1) * (DX_BYTES / 2) + (i & 1) * 8192);
+    };
+    auto issue_batch = [&](int tw, int tx) {
+        issue_w(tw, 0); issue_w(tw, 1); issue_s(tw);
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            copy16_to_lds(xbase + (size_t)tc * 256 + (i >> 1) * 128, xlane[i & 1], xdst + (i >> 1) * (DX_BYTES / 2) + (i & 1) * 8192);
+        for (int i = 0; i < 4; ++i) issue_x(tx, i);
     };
 
     v16f acc[2][4];
@@ -420,34 +438,32 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
             sv[ip] = *reinterpret_cast<const uint32_t *>(sring + (t % DRING) * DS_BYTES + ip * 512 + (t & 1) * 8);
         }
     };
-    auto convert = [&](v8h (&fa)[2][2], int g) {  // g = 0, 1: group of this wavefront's half of the tile
-#pragma unroll
-        for (int ip = 0; ip < 2; ++ip) {
-            const h2 s2 = as_h2(__builtin_amdgcn_perm(0u, sv[ip], g ? 0x03020302u : 0x01000100u));
-#pragma unroll
-            for (int s = 0; s < 2; ++s) fa[ip][s] = dequant_frag(g ? wv[ip][s].y : wv[ip][s].x, s2);
-        }
+    // quarter qb of the conversion of a group: operand (ip, s) = (qb / 2, qb % 2)
+    auto convert = [&](v8h (&fa)[2][2], int g, int qb) {  // g = 0, 1: group of this wavefront's half of the tile
+        const int ip = qb >> 1, sx = qb & 1;
+        const h2 s2 = as_h2(__builtin_amdgcn_perm(0u, sv[ip], g ? 0x03020302u : 0x01000100u));
+        fa[ip][sx] = dequant_frag(g ? wv[ip][sx].y : wv[ip][sx].x, s2);
     };
-    auto multiply = [&](const v8h (&fa)[2][2], const uint4 (&x)[4][2]) {
+    // quarter qb of the product of a group: k step qb / 2, token row blocks 2 (qb % 2), + 1
+    auto multiply = [&](const v8h (&fa)[2][2], const uint4 (&x)[4][2], int qb) {
+        const int sx = qb >> 1;
 #pragma unroll
-        for (int s = 0; s < 2; ++s)
+        for (int jj = 0; jj < 2; ++jj) {
+            const int jp = 2 * (qb & 1) + jj;
 #pragma unroll
-            for (int jp = 0; jp < 4; ++jp)
-#pragma unroll
-                for (int ip = 0; ip < 2; ++ip)
-                    acc[ip][jp] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ip][s], __builtin_bit_cast(v8h, x[jp][s]),
-                                                                         acc[ip][jp], 0, 0, 0);
+            for (int ip = 0; ip < 2; ++ip)
+                acc[ip][jp] = __builtin_amdgcn_mfma_f32_32x32x16_f16(fa[ip][sx], __builtin_bit_cast(v8h, x[jp][sx]),
+                                                                     acc[ip][jp], 0, 0, 0);
+        }
     };
 
     // Copies in issue order: codes/scales 0, codes/scales 1, stage 0 | codes/scales 2,
-    // stage 1 | then at the top of tile t: codes/scales t + 3, stage t + 2.  Past the
-    // end of K the last tile is copied again (into slots nobody reads any more) so
-    // that the count holds on every iteration.
-    issue_ws(0);
-    issue_ws(1);
-    issue_x(0);
-    issue_ws(2);
-    issue_x(1);
+    // stage 1 | then during tile t: codes/scales t + 3, stage t + 2.
+    issue_w(0, 0); issue_w(0, 1); issue_s(0);
+    issue_w(1, 0); issue_w(1, 1); issue_s(1);
+#pragma unroll
+    for (int i = 0; i < 4; ++i) issue_x(0, i);
+    issue_batch(2, 1);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
 #pragma unroll
@@ -464,67 +480,92 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
         // outstanding: stage t, codes and scales of tile t + 1.  The barrier makes
         // the other wavefronts' copies visible and says that every wavefront is done
         // with stage t - 1 and has the codes of tile t in registers: their slots are
-        // overwritten next.
+        // overwritten by the copies issued during this tile.
         wait_vmcnt<DBATCH>();
         asm volatile("s_barrier" ::: "memory");
-        issue_ws(t + 3);
-        issue_x(t + 2);
         read_x(x0, 0, t);
         __builtin_amdgcn_sched_barrier(0);  // the reads are in flight before the MFMAs start
-        multiply(fa1, x1);
-        convert(fa0, 0);
-        interleave_mfma_valu();
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) {  // group before x converted group 0; activation copies in between
+            multiply(fa1, x1, qb);
+            convert(fa0, 0, qb);
+            interleave_mfma_valu();
+            __builtin_amdgcn_sched_barrier(0);
+            issue_x(t + 2, qb);
+        }
         read_x(x1, 1, t);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(fa0, x0);
-        convert(fa1, 1);
-        interleave_mfma_valu();
-        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+        for (int qb = 0; qb < 4; ++qb) {
+            multiply(fa0, x0, qb);
+            convert(fa1, 1, qb);
+            interleave_mfma_valu();
+            __builtin_amdgcn_sched_barrier(0);
+            if (qb == 0) issue_w(t + 3, 0);
+            if (qb == 1) issue_w(t + 3, 1);
+            if (qb == 2) issue_s(t + 3);
+        }
         read_ws(t + 1);
     }
-    multiply(fa1, x1);
+#pragma unroll
+    for (int qb = 0; qb < 4; ++qb) multiply(fa1, x1, qb);
     wait_vmcnt<0>();
 
-    // The upper-half wavefronts hand their accumulators over through LDS
-    // ([channel group][register][lane], 128 KiB over the dead rings).
+    // The two wavefronts of a channel group hold partial sums of the same outputs.
+    // Each keeps two of the four 32-row blocks and hands the other two to its
+    // partner through LDS ([wavefront][16-byte vector][lane], 16 KiB per wavefront
+    // over the dead rings), adds what it receives, and stores its half.
     asm volatile("s_barrier" ::: "memory");  // every wavefront is done with the rings
-    float *red = reinterpret_cast<float *>(lds_b) + ng * (128 * 64) + lane;
-    if (ks == 1) {
+    const int keep = 2 * ks;                  // token row blocks keep, keep + 1 stay here
+    {
+        float4 *mine = reinterpret_cast<float4 *>(lds_b + wave * DEX_BYTES) + lane;
 #pragma unroll
         for (int ip = 0; ip < 2; ++ip)
 #pragma unroll
-            for (int jp = 0; jp < 4; ++jp)
+            for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-                for (int e = 0; e < 16; ++e) red[((ip * 4 + jp) * 16 + e) * 64] = acc[ip][jp][e];
+                for (int qq = 0; qq < 4; ++qq) {
+                    const v16f &v = ks ? acc[ip][jj] : acc[ip][2 + jj];
+                    mine[((ip * 2 + jj) * 4 + qq) * 64] = make_float4(v[4 * qq], v[4 * qq + 1], v[4 * qq + 2], v[4 * qq + 3]);
+                }
     }
     __syncthreads();
-    if (ks == 1) return;
+    v16f out[2][2];  // [ip][jj]: block keep + jj
+    {
+        const float4 *theirs = reinterpret_cast<const float4 *>(lds_b + (wave ^ 4) * DEX_BYTES) + lane;
 #pragma unroll
-    for (int ip = 0; ip < 2; ++ip)
+        for (int ip = 0; ip < 2; ++ip)
 #pragma unroll
-        for (int jp = 0; jp < 4; ++jp)
+            for (int jj = 0; jj < 2; ++jj)
 #pragma unroll
-            for (int e = 0; e < 16; ++e) acc[ip][jp][e] += red[((ip * 4 + jp) * 16 + e) * 64];
+                for (int qq = 0; qq < 4; ++qq) {
+                    const float4 p = theirs[((ip * 2 + jj) * 4 + qq) * 64];
+                    const v16f &v = ks ? acc[ip][2 + jj] : acc[ip][jj];
+                    out[ip][jj][4 * qq + 0] = v[4 * qq + 0] + p.x;
+                    out[ip][jj][4 * qq + 1] = v[4 * qq + 1] + p.y;
+                    out[ip][jj][4 * qq + 2] = v[4 * qq + 2] + p.z;
+                    out[ip][jj][4 * qq + 3] = v[4 * qq + 3] + p.w;
+                }
+    }
+    __syncthreads();  // the exchange buffers are free: each wavefront stages its stores in its own
 
     // Epilogue: a lane holds one token row (lane % 32) and groups of four
     // consecutive n.  The binary16 values go through a per-wavefront LDS block
-    // (32 token rows x 64 channels, behind the reduction buffer) and leave as
-    // 16-byte stores along n.
+    // (32 token rows x 64 channels) and leave as 16-byte stores along n.
     const int n0 = nt * DBN + ng * 64;
     if ((a.N % 8) == 0) {
-        char *region = lds_b + DRED_BYTES + ng * (32 * DEPI_PITCH);
+        char *region = lds_b + wave * DEX_BYTES;
 #pragma unroll
-        for (int jp = 0; jp < 4; ++jp) {
-            const int mrow0 = mt * DBM + jp * 32;
+        for (int jj = 0; jj < 2; ++jj) {
+            const int mrow0 = mt * DBM + (keep + jj) * 32;
 #pragma unroll
             for (int ip = 0; ip < 2; ++ip) {
 #pragma unroll
                 for (int qq = 0; qq < 4; ++qq) {
                     const int nl = ip * 32 + 8 * qq + 4 * kh;
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                    const h4 hv = {(_Float16)acc[ip][jp][4 * qq + 0], (_Float16)acc[ip][jp][4 * qq + 1],
-                                   (_Float16)acc[ip][jp][4 * qq + 2], (_Float16)acc[ip][jp][4 * qq + 3]};
+                    const h4 hv = {(_Float16)out[ip][jj][4 * qq + 0], (_Float16)out[ip][jj][4 * qq + 1],
+                                   (_Float16)out[ip][jj][4 * qq + 2], (_Float16)out[ip][jj][4 * qq + 3]};
                     *reinterpret_cast<h4 *>(region + r * DEPI_PITCH + nl * 2) = hv;
                 }
             }
@@ -546,15 +587,15 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
         return;
     }
 #pragma unroll
-    for (int jp = 0; jp < 4; ++jp) {
-        const int m = mt * DBM + jp * 32 + r;
+    for (int jj = 0; jj < 2; ++jj) {
+        const int m = mt * DBM + (keep + jj) * 32 + r;
         if (m >= a.M) continue;
 #pragma unroll
         for (int ip = 0; ip < 2; ++ip)
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int n = n0 + ip * 32 + 8 * (e >> 2) + 4 * kh + (e & 3);
-                if (n < a.N) a.y[(size_t)m * a.N + n] = (_Float16)acc[ip][jp][e];
+                if (n < a.N) a.y[(size_t)m * a.N + n] = (_Float16)out[ip][jj][e];
             }
     }
 }
