@@ -7,8 +7,8 @@ is quoted on: every linear layer of a Llama-3.1-8B-shaped decode step at M = 1
 per-channel LM head: 129 qfc_forward calls, 4.456 GB of packed weights streamed
 once).  Inputs are seeded synthetic tensors, resident in HBM before the timed
 region.  The same run also times the prefill kernels (int8 MFMA product with
-activation quantization and epilogue at M = 1024; fp16 MFMA product with in-LDS
-dequantization at M = 2048), the M = 4 decode step, and the CPU oracle on a
+activation quantization and epilogue at M = 1024; fp16 MFMA product with int4
+weights converted on the way to the matrix core at M = 2048), the M = 4 decode step, and the CPU oracle on a
 bounded sample of the workload.
 
 Prints ONE JSON line.
@@ -206,7 +206,7 @@ def main():
         p16 = prefill(synth.GEMMA_FCS_W4, 2048, 1005)
         p16["roofline"] = {"bound": "mfma", "achieved": p16["total"]["Tops"], "peak": MFMA_F16_PEAK_TFLOPS, "unit": "TFLOP/s",
                            "frac": round(p16["total"]["Tops"] / MFMA_F16_PEAK_TFLOPS, 4),
-                           "note": "int4 group-32 weights dequantized into LDS, fp16 MFMA, Gemma2-2B layer, M=2048"}
+                           "note": "int4 group-32 weights converted in registers on the way to the MFMA operand, fp16 MFMA, Gemma2-2B layer, M=2048"}
         extra["prefill_int8_m1024"] = p8
         extra["prefill_fp16_m2048"] = p16
 
