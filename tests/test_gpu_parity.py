@@ -299,6 +299,67 @@ def test_fp16_prefill_config5_shapes_sampled():
         layer.close()
 
 
+# ------------------------------------------------------------------ A7 dispatch, batches, streams
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+def test_dispatch_boundary_m8_m9(fmt):
+    """M = 8 takes the decode kernel, M = 9 the prefill path: both within tolerance of the
+    oracle, and the first eight rows of the M = 9 result agree with the M = 8 result to
+    within twice the tolerance (different kernels, same definition)."""
+    print(f"dispatch boundary {fmt}", flush=True)
+    fc = synth.FC("t", 1024, 520, fmt)
+    wq, s = synth.weights(7000, 0, 0, fc)
+    x = synth.activations(7000, 0, 0, 9, fc.K)
+    layer = _layer(wq, s, fmt, max_m=9)
+    y8 = _forward(layer, x[:8])
+    y9 = _forward(layer, x)
+    if fmt == "w8c":
+        _, _, _, ref9 = oracle.fc_int8_act(x, wq, s)
+    else:
+        ref9 = oracle.fc_weight_only(x, wq, s, 32)
+    ref8 = oracle.fc_weight_only(x[:8], wq, s, _group(fmt))
+    assert oracle.floored_rel_error(y8, ref8) <= TOL
+    assert oracle.floored_rel_error(y9, ref9) <= TOL
+    if fmt == "w4g32":
+        assert oracle.floored_rel_error(y9[:8], ref8) <= TOL
+    layer.close()
+
+
+def test_forward_batch_equals_single_calls_on_a_side_stream():
+    print("forward batch", flush=True)
+    fcs = [synth.FC("a", 512, 300, "w4g32"), synth.FC("b", 2304, 264, "w4g32"), synth.FC("c", 256, 1000, "w8c")]
+    layers, xs, singles = [], [], []
+    for i, fc in enumerate(fcs):
+        wq, s = synth.weights(7001, 0, i, fc)
+        layers.append(_layer(wq, s, fc.fmt))
+        xs.append(torch.from_numpy(synth.activations(7001, 0, i, 3, fc.K)).to(DEV))
+        singles.append(layers[-1].forward(xs[-1]))
+    torch.cuda.synchronize()
+    side = torch.cuda.Stream()
+    ys = [torch.full((3, l.N), 7.0, dtype=torch.float16, device=DEV) for l in layers]
+    torch.cuda.synchronize()
+    with torch.cuda.stream(side):
+        fb = binding.ForwardBatch([l.handle for l in layers], xs, ys, 3)
+        fb.run()
+    side.synchronize()
+    for y, y1 in zip(ys, singles):
+        assert torch.equal(y.view(torch.int16), y1.view(torch.int16))
+    for l in layers:
+        l.close()
+
+
+@pytest.mark.parametrize("fmt,M", [("w8c", 200), ("w4g32", 300)])
+def test_prefill_is_deterministic(fmt, M):
+    print(f"prefill determinism {fmt}", flush=True)
+    fc = synth.FC("t", 1152, 520, fmt)
+    wq, s = synth.weights(7002, 0, 0, fc)
+    x = synth.activations(7002, 0, 0, M, fc.K)
+    layer = _layer(wq, s, fmt, max_m=M)
+    y1 = _forward(layer, x)
+    y2 = _forward(layer, x)
+    assert np.array_equal(y1.view(np.uint16), y2.view(np.uint16))
+    layer.close()
+
+
 def test_error_paths_on_device():
     print("error paths", flush=True)
     fc = synth.FC("t", 64, 64, "w4g32")
