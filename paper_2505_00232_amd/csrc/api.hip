@@ -162,7 +162,7 @@ qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f
     int8_t *tiled = reinterpret_cast<int8_t *>(body);
     float *sx = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
     if (launch_act_quant(x_f16, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, st) != hipSuccess) return QFC_ERR_HIP;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, h->num_cus, st));
 }
 
 qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M, void *y_f16,
@@ -174,7 +174,7 @@ qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
     if (s != QFC_OK) return s;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, prefill_rows(M), y_f16, 0, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, prefill_rows(M), y_f16, 0, h->num_cus, st));
 }
 
 qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc, void *stream) {
@@ -185,7 +185,7 @@ qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, in
     hipStream_t st = static_cast<hipStream_t>(stream);
     const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
     if (s != QFC_OK) return s;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, h->num_cus, st));
 }
 
 qfc_status_t qfc_forward_batch(const qfc_handle_t *handles, const void *const *xs, int32_t M,

@@ -150,7 +150,7 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
 
 // KTS = KiB k tiles (64 k each) per stage, NS = LDS stages (prefetch distance NS - 1)
 template <int BN, int BM, int KTS, int NS, int OUT_MODE>
-__global__ __launch_bounds__(256) void gemm_i8_kernel(GemmI8Args a) {
+__global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_kernel(GemmI8Args a) {
     constexpr int BK = KTS * 64;
     constexpr int WN = BN / 2, WM = BM / 2;    // per-wavefront tile
     constexpr int TN = WN / 32, TM = WM / 32;  // 32x32 MFMA tiles per wavefront
@@ -284,16 +284,26 @@ hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
 }
 
 template <int OUT_MODE>
-hipError_t launch_mode(const GemmI8Args &a, hipStream_t st) {
-    // Tile shapes measured on MI355X at M = 1024 .. 2048: the 128 x 128 tile with a
-    // four-stage ring of 64-k stages is the fastest or within a few percent of it
-    // on every layer shape tried; the others stay selectable for experiments.
+hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
+    // Tile shapes measured on MI355X.  128 x 128 (two workgroups per compute unit,
+    // four-stage ring of 64-k stages) is the fastest or within a few percent of it
+    // on every layer shape at M = 1024.  The 256 x 128 tile (128 x 64 per wavefront:
+    // 25 % fewer LDS bytes per MFMA, still two wavefronts per SIMD) is 10-30 %
+    // faster once there are enough tiles to fill the chip for at least two full
+    // rounds (LM head at M = 2048: 1.37 ms against 1.81 ms), and slower below that.
+    // The others stay selectable for experiments.
     int variant = tuning().gemm_variant;
-    if (variant == 0) variant = 3;
+    if (variant == 0) {
+        const long slots = 2L * num_cus;
+        const long big_tiles = (long)((a.N + 255) / 256) * ((a.M + 127) / 128);
+        variant = (big_tiles >= 2 * slots || (big_tiles >= slots && big_tiles % slots == 0)) ? 6 : 3;
+    }
     switch (variant) {
         case 1: return launch_variant<256, 256, 1, 4, OUT_MODE>(a, st);
         case 2: return launch_variant<256, 128, 1, 4, OUT_MODE>(a, st);
         case 4: return launch_variant<128, 128, 2, 3, OUT_MODE>(a, st);
+        case 5: return launch_variant<128, 256, 1, 3, OUT_MODE>(a, st);
+        case 6: return launch_variant<256, 128, 1, 3, OUT_MODE>(a, st);
         default: return launch_variant<128, 128, 1, 4, OUT_MODE>(a, st);
     }
 }
@@ -301,7 +311,8 @@ hipError_t launch_mode(const GemmI8Args &a, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *xq_tiled,
-                          const float *sx, int M, int Mp, void *out, int out_mode, hipStream_t st) {
+                          const float *sx, int M, int Mp, void *out, int out_mode, int num_cus,
+                          hipStream_t st) {
     (void)Mp;
     GemmI8Args a;
     a.w = static_cast<const uint4 *>(packed);
@@ -313,7 +324,7 @@ hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *x
     a.N = g.N;
     a.Kp = g.Kp;
     a.n_tiles = a.m_tiles = 0;
-    return out_mode == 0 ? launch_mode<0>(a, st) : launch_mode<1>(a, st);
+    return out_mode == 0 ? launch_mode<0>(a, num_cus, st) : launch_mode<1>(a, num_cus, st);
 }
 
 }  // namespace qfc

@@ -117,7 +117,7 @@ hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int M
                             hipStream_t st);
 // out_mode 0: binary16 y with scales; 1: raw int32 accumulators.
 hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *xq_tiled,
-                          const float *sx, int M, int Mp, void *out, int out_mode,
+                          const float *sx, int M, int Mp, void *out, int out_mode, int num_cus,
                           hipStream_t st);
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
                            int num_cus, hipStream_t st);

@@ -201,6 +201,29 @@ def test_int8_prefill_matches_oracle(M, N, K):
     layer.close()
 
 
+@pytest.mark.parametrize("variant", [1, 4, 5, 6])
+def test_int8_prefill_other_tile_shapes_bit_exact(variant):
+    """The tile shapes the dispatcher picks for larger problems (and the selectable ones),
+    forced on a ragged shape."""
+    print(f"int8 prefill tile variant {variant}", flush=True)
+    M, N, K = 300, 520, 1152
+    fc = synth.FC("t", K, N, "w8c")
+    wq, sw = synth.weights(4100, M, N, fc)
+    x = synth.activations(4100, M, N, M, K)
+    xq_ref, sx_ref, acc_ref, y_ref = oracle.fc_int8_act(x, wq, sw)
+    layer = _layer(wq, sw, "w8c", max_m=M)
+    binding.qfc_tune(2, variant)
+    try:
+        acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+        binding.qfc_forward_acc_i32(layer.handle, torch.from_numpy(xq_ref).to(DEV), acc)
+        y = _forward(layer, x)
+    finally:
+        binding.qfc_tune(2, 0)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref)
+    assert oracle.floored_rel_error(y, y_ref) <= TOL
+    layer.close()
+
+
 def test_int8_prefill_config4_shapes_sampled():
     """Llama layer at M = 1024, int8 per-channel weights: accumulators of a
     sample of (token, channel) pairs against the exact integer contraction."""
