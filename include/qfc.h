@@ -58,7 +58,9 @@ enum { QFC_COMPUTE_FP16_DEQUANT = 0, QFC_COMPUTE_INT8_ACT = 1 };
  * sub-channel quantization the paper names as its next step):
  *   wbits 8, group_size 0,  scale_dtype F32: int8 codes, one fp32 scale per output channel;
  *   wbits 4, group_size 32, scale_dtype F16: int4 codes in [-8,7], one binary16 scale per
- *                                            32 consecutive k of a row, scales [N, K/32].
+ *                                            32 consecutive k of a row, scales [N, K/32];
+ *   wbits 4, group_size 0,  scale_dtype F32: int4 codes in [-8,7], one fp32 scale per output
+ *                                            channel (the paper's per-channel 4-bit scheme).
  * Any other combination returns QFC_ERR_UNSUPPORTED.
  * compute_mode selects the M > 8 path: QFC_COMPUTE_INT8_ACT (needs 8-bit per-channel weights)
  * or QFC_COMPUTE_FP16_DEQUANT.  It has no effect for M <= 8. */

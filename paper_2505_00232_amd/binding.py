@@ -90,6 +90,9 @@ def make_desc(N: int, K: int, fmt: str, compute_mode: int | None = None) -> Desc
     if fmt == "w4g32":
         mode = QFC_COMPUTE_FP16_DEQUANT if compute_mode is None else compute_mode
         return Desc(N, K, 4, 32, QFC_SCALE_F16, mode)
+    if fmt == "w4c":
+        mode = QFC_COMPUTE_FP16_DEQUANT if compute_mode is None else compute_mode
+        return Desc(N, K, 4, 0, QFC_SCALE_F32, mode)
     raise ValueError(fmt)
 
 

@@ -36,6 +36,9 @@ qfc_status_t check_desc(const qfc_desc_t *d, int *fmt) {
     } else if (d->wbits == 4 && d->group_size == 32 && d->scale_dtype == QFC_SCALE_F16) {
         *fmt = kW4G32;
         if (d->compute_mode == QFC_COMPUTE_INT8_ACT) return QFC_ERR_UNSUPPORTED;
+    } else if (d->wbits == 4 && d->group_size == 0 && d->scale_dtype == QFC_SCALE_F32) {
+        *fmt = kW4C;
+        if (d->compute_mode == QFC_COMPUTE_INT8_ACT) return QFC_ERR_UNSUPPORTED;
     } else {
         return QFC_ERR_UNSUPPORTED;
     }
@@ -150,7 +153,7 @@ qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f
     if (!aligned16(x_f16) || !aligned16(y_f16)) return QFC_ERR_ALIGNMENT;
     hipStream_t st = static_cast<hipStream_t>(stream);
     if (M > kMaxDecodeM && h->desc.compute_mode == QFC_COMPUTE_FP16_DEQUANT) {
-        if (h->geo.fmt != kW4G32) return QFC_ERR_UNSUPPORTED;
+        if (h->geo.fmt != kW4G32 && h->geo.fmt != kW4C) return QFC_ERR_UNSUPPORTED;
         return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
     }
     if (M <= kMaxDecodeM)

@@ -41,9 +41,10 @@ constexpr int LDX = BM + 1;      // vectors per octet, activations (padded)
 constexpr size_t kLdsBytes = (size_t)OCT * (LDW + LDX) * 16;
 
 struct GemmF16Args {
-    const uint4 *w;   // packed W4G32 row tiles
+    const uint4 *w;   // packed int4 row tiles (W4G32 or W4C)
     const uint4 *x;   // binary16 [M, K] viewed as 16-byte vectors
     _Float16 *y;
+    const float *sw;  // W4C: fp32 scale per output channel [Np]
     int M, N, K, KT, rt_stride, n_tiles, m_tiles;
 };
 
@@ -65,6 +66,8 @@ __device__ __forceinline__ uint4 dequant8_scaled(uint32_t w, uint32_t scale_bits
     return make_uint4(as_u32(p0), as_u32(p1), as_u32(p2), as_u32(p3));
 }
 
+// PC = per-channel scales (W4C): unscaled integer weights in the MFMA, fp32 scale in the epilogue
+template <bool PC>
 __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
     extern __shared__ uint4 lds[];
     uint4 *lds_w = lds;
@@ -101,13 +104,14 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
     uint2 sreg[2];
     auto load_stage = [&](int kt) {
         const int u = kt >> 3;
-        const int wpos = kt + u;                               // weight tile kt of the row tile
+        const int wpos = PC ? kt : kt + u;                     // weight tile kt of the row tile
         const int spos = min(8 * u + 8, a.KT) + u;             // scale tile of its unit
         const int soff = (((kt & 7) >> 1) * 16 + c) * 2 + (kt & 1);  // 8-byte index inside it
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             wreg[i] = w_rt[i][(size_t)wpos * 64 + lane];
-            sreg[i] = reinterpret_cast<const uint2 *>(w_rt[i] + (size_t)spos * 64)[soff];
+            sreg[i] = PC ? make_uint2(0x3C003C00u, 0x3C003C00u)  // 1.0: the multiply is exact
+                         : reinterpret_cast<const uint2 *>(w_rt[i] + (size_t)spos * 64)[soff];
         }
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
@@ -173,8 +177,10 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
                 for (int qq = 0; qq < 4; ++qq) {
                     const int nl = i * 32 + 8 * qq + 4 * (lane >> 5);
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                    const h4 hv = {(_Float16)acc[i][j][4 * qq + 0], (_Float16)acc[i][j][4 * qq + 1],
-                                   (_Float16)acc[i][j][4 * qq + 2], (_Float16)acc[i][j][4 * qq + 3]};
+                    float4 sc = make_float4(1.0f, 1.0f, 1.0f, 1.0f);
+                    if (PC) sc = *reinterpret_cast<const float4 *>(a.sw + n0 + nl);
+                    const h4 hv = {(_Float16)(acc[i][j][4 * qq + 0] * sc.x), (_Float16)(acc[i][j][4 * qq + 1] * sc.y),
+                                   (_Float16)(acc[i][j][4 * qq + 2] * sc.z), (_Float16)(acc[i][j][4 * qq + 3] * sc.w)};
                     *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + nl * 2) = hv;
                 }
             }
@@ -209,7 +215,7 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
                 _Float16 *y = a.y + (size_t)m * a.N + n;
                 _Float16 h[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = (_Float16)acc[i][j][4 * qq + e];
+                for (int e = 0; e < 4; ++e) h[e] = (_Float16)(PC ? acc[i][j][4 * qq + e] * a.sw[n + e] : acc[i][j][4 * qq + e]);
                 if (vec_ok) {
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
                     *reinterpret_cast<h4 *>(y) = h4{h[0], h[1], h[2], h[3]};
@@ -275,7 +281,7 @@ constexpr int DS_BYTES = 4 * 1024;                // scales for one tile: 4 chan
 constexpr int DW_OFF = DRING * DX_BYTES;
 constexpr int DS_OFF = DW_OFF + DRING * DW_BYTES;
 constexpr int kDirectLdsBytes = DS_OFF + DRING * DS_BYTES;
-constexpr int DBATCH = 2 + 1 + 4;                 // copies per wavefront per tile
+constexpr int DBATCH = 2 + 1 + 4;                 // copies per wavefront per tile (one fewer without group scales)
 constexpr int DEX_BYTES = 64 * 64 * 4;            // half of a wavefront's accumulators (exchange buffer)
 constexpr int DEPI_PITCH = (64 + 8) * 2;
 static_assert(8 * DEX_BYTES <= kDirectLdsBytes && 32 * DEPI_PITCH <= DEX_BYTES, "exchange and store staging fit in the rings");
@@ -309,6 +315,19 @@ __device__ __forceinline__ v8h dequant_frag(uint32_t w, h2 s) {
     return v8h{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
 }
 
+// the same without a scale: the integer values themselves (W4C; the scale is applied to the output)
+__device__ __forceinline__ v8h dequant_frag_unscaled(uint32_t w) {
+    const h2 c1032 = {(_Float16)1032.0f, (_Float16)1032.0f};
+    const h2 c72 = {(_Float16)72.0f, (_Float16)72.0f};
+    const h2 c16th = {(_Float16)0.0625f, (_Float16)0.0625f};
+    const uint32_t lo = w & 0x0F0F0F0Fu, hi = w & 0xF0F0F0F0u;
+    const h2 p0 = as_h2(__builtin_amdgcn_perm(0x64646464u, lo, 0x04010400u)) - c1032;
+    const h2 p1 = as_h2(__builtin_amdgcn_perm(0x64646464u, lo, 0x04030402u)) - c1032;
+    const h2 p2 = as_h2(__builtin_amdgcn_perm(0x64646464u, hi, 0x04010400u)) * c16th - c72;
+    const h2 p3 = as_h2(__builtin_amdgcn_perm(0x64646464u, hi, 0x04030402u)) * c16th - c72;
+    return v8h{p0[0], p0[1], p1[0], p1[1], p2[0], p2[1], p3[0], p3[1]};
+}
+
 // One MFMA followed by a few vector instructions, four times: the order the
 // instructions of a quarter of a "multiply one group, convert the next" block
 // (4 MFMAs, the conversion of one operand) are issued in.
@@ -320,7 +339,9 @@ __device__ __forceinline__ void interleave_mfma_valu() {
     }
 }
 
+template <bool PC>
 __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) {
+    constexpr int BATCH = PC ? DBATCH - 1 : DBATCH;
     extern __shared__ uint4 lds[];
     char *lds_b = reinterpret_cast<char *>(lds);
 
@@ -381,7 +402,7 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     // copies is the same on every iteration.
     auto issue_w = [&](int t, int i) {  // codes of tile t, row tile 2 ks + i of the channel group
         const int tc = min(t, KT - 1);
-        const size_t wpos = (size_t)(tc + (tc >> 3)) * 1024;
+        const size_t wpos = (size_t)(PC ? tc : tc + (tc >> 3)) * 1024;
         copy16_to_lds(wbase + i * rt_bytes + wpos, wlane, lds0 + DW_OFF + (t % DRING) * DW_BYTES + (ng * 4 + ks * 2 + i) * 1024);
     };
     auto issue_s = [&](int t) {  // scales of tile t: vector (t % 8) / 2 * 16 + row of the unit's scale tile (8 groups = 2 tiles)
@@ -395,7 +416,8 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
                       lds0 + (t % DRING) * DX_BYTES + wave * 1024 + (i >> 1) * (DX_BYTES / 2) + (i & 1) * 8192);
     };
     auto issue_batch = [&](int tw, int tx) {
-        issue_w(tw, 0); issue_w(tw, 1); issue_s(tw);
+        issue_w(tw, 0); issue_w(tw, 1);
+        if (!PC) issue_s(tw);
 #pragma unroll
         for (int i = 0; i < 4; ++i) issue_x(tx, i);
     };
@@ -435,14 +457,18 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
 #pragma unroll
             for (int s = 0; s < 2; ++s)
                 wv[ip][s] = *reinterpret_cast<const uint2 *>(wring + (t % DRING) * DW_BYTES + ip * 2048 + s * 512);
-            sv[ip] = *reinterpret_cast<const uint32_t *>(sring + (t % DRING) * DS_BYTES + ip * 512 + (t & 1) * 8);
+            if (!PC) sv[ip] = *reinterpret_cast<const uint32_t *>(sring + (t % DRING) * DS_BYTES + ip * 512 + (t & 1) * 8);
         }
     };
     // quarter qb of the conversion of a group: operand (ip, s) = (qb / 2, qb % 2)
     auto convert = [&](v8h (&fa)[2][2], int g, int qb) {  // g = 0, 1: group of this wavefront's half of the tile
         const int ip = qb >> 1, sx = qb & 1;
-        const h2 s2 = as_h2(__builtin_amdgcn_perm(0u, sv[ip], g ? 0x03020302u : 0x01000100u));
-        fa[ip][sx] = dequant_frag(g ? wv[ip][sx].y : wv[ip][sx].x, s2);
+        if (PC) {
+            fa[ip][sx] = dequant_frag_unscaled(g ? wv[ip][sx].y : wv[ip][sx].x);
+        } else {
+            const h2 s2 = as_h2(__builtin_amdgcn_perm(0u, sv[ip], g ? 0x03020302u : 0x01000100u));
+            fa[ip][sx] = dequant_frag(g ? wv[ip][sx].y : wv[ip][sx].x, s2);
+        }
     };
     // quarter qb of the product of a group: k step qb / 2, token row blocks 2 (qb % 2), + 1
     auto multiply = [&](const v8h (&fa)[2][2], const uint4 (&x)[4][2], int qb) {
@@ -459,8 +485,10 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
 
     // Copies in issue order: codes/scales 0, codes/scales 1, stage 0 | codes/scales 2,
     // stage 1 | then during tile t: codes/scales t + 3, stage t + 2.
-    issue_w(0, 0); issue_w(0, 1); issue_s(0);
-    issue_w(1, 0); issue_w(1, 1); issue_s(1);
+    issue_w(0, 0); issue_w(0, 1);
+    if (!PC) issue_s(0);
+    issue_w(1, 0); issue_w(1, 1);
+    if (!PC) issue_s(1);
 #pragma unroll
     for (int i = 0; i < 4; ++i) issue_x(0, i);
     issue_batch(2, 1);
@@ -472,7 +500,7 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     for (int i = 0; i < 4; ++i)
 #pragma unroll
         for (int j = 0; j < 2; ++j) x1[i][j] = make_uint4(0, 0, 0, 0);
-    wait_vmcnt<DBATCH>();
+    wait_vmcnt<BATCH>();
     asm volatile("s_barrier" ::: "memory");
     read_ws(0);
     for (int t = 0; t < KT; ++t) {
@@ -481,7 +509,7 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
         // the other wavefronts' copies visible and says that every wavefront is done
         // with stage t - 1 and has the codes of tile t in registers: their slots are
         // overwritten by the copies issued during this tile.
-        wait_vmcnt<DBATCH>();
+        wait_vmcnt<BATCH>();
         asm volatile("s_barrier" ::: "memory");
         read_x(x0, 0, t);
         __builtin_amdgcn_sched_barrier(0);  // the reads are in flight before the MFMAs start
@@ -503,7 +531,7 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
             __builtin_amdgcn_sched_barrier(0);
             if (qb == 0) issue_w(t + 3, 0);
             if (qb == 1) issue_w(t + 3, 1);
-            if (qb == 2) issue_s(t + 3);
+            if (qb == 2 && !PC) issue_s(t + 3);
         }
         read_ws(t + 1);
     }
@@ -548,6 +576,21 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
                 }
     }
     __syncthreads();  // the exchange buffers are free: each wavefront stages its stores in its own
+    if (PC) {  // per-channel scale of the lane's output channels
+#pragma unroll
+        for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+            for (int qq = 0; qq < 4; ++qq) {
+                const float4 sc = *reinterpret_cast<const float4 *>(a.sw + nt * DBN + ng * 64 + ip * 32 + 8 * qq + 4 * kh);
+#pragma unroll
+                for (int jj = 0; jj < 2; ++jj) {
+                    out[ip][jj][4 * qq + 0] *= sc.x;
+                    out[ip][jj][4 * qq + 1] *= sc.y;
+                    out[ip][jj][4 * qq + 2] *= sc.z;
+                    out[ip][jj][4 * qq + 3] *= sc.w;
+                }
+            }
+    }
 
     // Epilogue: a lane holds one token row (lane % 32) and groups of four
     // consecutive n.  The binary16 values go through a per-wavefront LDS block
@@ -600,17 +643,33 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     }
 }
 
+template <bool PC>
 hipError_t launch_direct(GemmF16Args a, int M, hipStream_t st) {
     static bool attr_set = false;
     if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_direct_kernel),
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_direct_kernel<PC>),
                                                  hipFuncAttributeMaxDynamicSharedMemorySize, kDirectLdsBytes);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
     a.n_tiles = (a.N + DBN - 1) / DBN;
     a.m_tiles = (M + DBM - 1) / DBM;
-    gemm_f16_w4_direct_kernel<<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 512, kDirectLdsBytes, st>>>(a);
+    gemm_f16_w4_direct_kernel<PC><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 512, kDirectLdsBytes, st>>>(a);
+    return hipGetLastError();
+}
+
+template <bool PC>
+hipError_t launch_fallback(GemmF16Args a, int M, hipStream_t st) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_kernel<PC>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    a.n_tiles = (a.N + BN - 1) / BN;
+    a.m_tiles = (M + BM - 1) / BM;
+    gemm_f16_w4_kernel<PC><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, kLdsBytes, st>>>(a);
     return hipGetLastError();
 }
 
@@ -618,29 +677,22 @@ hipError_t launch_direct(GemmF16Args a, int M, hipStream_t st) {
 
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
                            int num_cus, hipStream_t st) {
-    if (g.fmt != kW4G32) return hipErrorNotSupported;
+    if (g.fmt != kW4G32 && g.fmt != kW4C) return hipErrorNotSupported;
+    (void)num_cus;
     GemmF16Args a;
     a.w = static_cast<const uint4 *>(packed);
     a.x = static_cast<const uint4 *>(x);
     a.y = static_cast<_Float16 *>(y);
+    a.sw = reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off);
     a.M = M;
     a.N = g.N;
     a.K = g.K;
     a.KT = g.KT;
     a.rt_stride = g.rt_stride;
-    (void)num_cus;
-    if ((g.K % 128) == 0 && tuning().gemm_variant != 9) return launch_direct(a, M, st);
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_kernel),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
-    a.n_tiles = (g.N + BN - 1) / BN;
-    a.m_tiles = (M + BM - 1) / BM;
-    gemm_f16_w4_kernel<<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, kLdsBytes, st>>>(a);
-    return hipGetLastError();
+    a.n_tiles = a.m_tiles = 0;
+    const bool pc = g.fmt == kW4C;
+    if ((g.K % 128) == 0 && tuning().gemm_variant != 9) return pc ? launch_direct<true>(a, M, st) : launch_direct<false>(a, M, st);
+    return pc ? launch_fallback<true>(a, M, st) : launch_fallback<false>(a, M, st);
 }
 
 }  // namespace qfc

@@ -12,8 +12,8 @@
 // cost does not depend on M, and the matrix pipe is idle in a bandwidth-bound
 // kernel anyway.  For int4 group-quantized weights every MFMA covers exactly
 // one quantization group, and its fp32 result is scaled and accumulated with
-// one FMA per token row; int8 per-channel weights accumulate inside the MFMA
-// and are scaled once at the end.
+// one FMA per token row; per-channel weights (int8 or int4) accumulate inside
+// the MFMA and are scaled once at the end.
 //
 // Activations of the k range a wavefront is working on are staged in a private
 // LDS region in A-operand order (no workgroup barrier in the streaming loop).
@@ -96,18 +96,18 @@ struct GemvArgs {
     const u32x4 *packed;
     const u32x4 *x;     // binary16 [M, K] as 16-byte vectors (8 values)
     _Float16 *y;        // [M, N]
-    const float *sw;    // W8C scales [Np]
+    const float *sw;    // per-channel scales [Np] (W8C, W4C)
     int N, K, RT, KT, KU, rt_stride;
     int row_tiles;           // R: row tiles per workgroup
     int units_q, units_rem;  // KU = units_q * waves + units_rem
 };
 
 // LDS view of one wavefront's staged activations: vector (slot * M + m).
-// W4G32 unit: 1024 k = 128 octets, slot = octet index (4 * group + q).
-// W8C unit:    512 k =  64 octets, slot = tile * 8 + j * 4 + q for octet 2q + j of the tile.
+// int4 unit: 1024 k = 128 octets, slot = octet index (4 * group + q).
+// W8C unit:   512 k =  64 octets, slot = tile * 8 + j * 4 + q for octet 2q + j of the tile.
 template <int M, int FMT>
 struct XStage {
-    static constexpr int OCT = FMT == kW4G32 ? 128 : 64;  // octets per unit
+    static constexpr int OCT = FMT == kW8C ? 64 : 128;  // octets per unit
     static constexpr int XV = M * OCT / 64;               // 16-byte vectors per lane per unit
     u32x4 v[XV];
 
@@ -140,7 +140,7 @@ template <int M, int FMT, bool DB>
 __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     constexpr int TILES = 8;                    // weight tiles per unit
     constexpr int NV = FMT == kW4G32 ? 12 : 8;  // 16-byte vectors per lane per (unit, row tile)
-    constexpr int OCT = FMT == kW4G32 ? 128 : 64;
+    constexpr int OCT = FMT == kW8C ? 64 : 128;
     constexpr int MI = M < 4 ? M : 4;           // accumulator rows that matter on a lane
     extern __shared__ u32x4 lds_all[];
 
@@ -210,15 +210,16 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
         const int nt = min(TILES, a.KT - TILES * u);
         float accr[4] = {0.0f, 0.0f, 0.0f, 0.0f};
         v4f accw = {0.0f, 0.0f, 0.0f, 0.0f};
+        v4f accw2 = {0.0f, 0.0f, 0.0f, 0.0f};  // second chain (W4C), so that MFMAs do not wait on each other
         // A operands (token rows) of one tile; lanes whose row index is >= M read
         // row c % M instead: an A row only feeds the D row of the same index, and
         // D rows >= M are never used, so no masking or zeroing is needed.
-        constexpr int XA = FMT == kW4G32 ? 4 : 2;
+        constexpr int XA = FMT == kW8C ? 2 : 4;
         const u32x4 *xrow = lds_x + q * M + (c % M);
         auto load_xa = [&](v8h(&xa)[XA], int t) {
 #pragma unroll
             for (int j = 0; j < XA; ++j)
-                xa[j] = __builtin_bit_cast(v8h, xrow[(FMT == kW4G32 ? (4 * t + j) * 4 : t * 8 + j * 4) * M]);
+                xa[j] = __builtin_bit_cast(v8h, xrow[(FMT == kW8C ? t * 8 + j * 4 : (4 * t + j) * 4) * M]);
         };
         // The scaled accumulation of an MFMA result is issued one step late, after the
         // next MFMA has been started, so that its latency is covered by the next
@@ -241,6 +242,11 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
                     s_prev = __builtin_bit_cast(_Float16, (uint16_t)(sd >> (16 * (gl & 1))));
                     d_prev = d;
                 }
+            } else if (FMT == kW4C) {
+                accw = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[0], dequant8(cur[t].x), accw, 0, 0, 0);
+                accw2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], dequant8(cur[t].y), accw2, 0, 0, 0);
+                accw = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[2], dequant8(cur[t].z), accw, 0, 0, 0);
+                accw2 = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[3], dequant8(cur[t].w), accw2, 0, 0, 0);
             } else {
                 accw = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[0], dequant_i8x8(cur[t].x, cur[t].y), accw, 0, 0, 0);
                 accw = __builtin_amdgcn_mfma_f32_16x16x32_f16(xa[1], dequant_i8x8(cur[t].z, cur[t].w), accw, 0, 0, 0);
@@ -296,7 +302,7 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
         for (int rr = 0; rr < 4; ++rr)
             if (rr == r) {
 #pragma unroll
-                for (int i = 0; i < MI; ++i) acc[rr][i] += FMT == kW4G32 ? accr[i] : accw[i];
+                for (int i = 0; i < MI; ++i) acc[rr][i] += FMT == kW4G32 ? accr[i] : FMT == kW4C ? accw[i] + accw2[i] : accw[i];
             }
         if (++r == R) {
             r = 0;
@@ -329,7 +335,7 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
         for (int w = 0; w < nwaves; ++w) s += red[((w * 4 + rr) * M + m) * 16 + cc];
         const int n = (rt0 + rr) * 16 + cc;
         if (n < a.N) {
-            if (FMT == kW8C) s *= a.sw[n];
+            if (FMT != kW4G32) s *= a.sw[n];
             a.y[(size_t)m * a.N + n] = (_Float16)s;
         }
     }
@@ -339,7 +345,7 @@ template <int M>
 hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t st) {
     const dim3 grid((unsigned)((g.RT + a.row_tiles - 1) / a.row_tiles));
     const dim3 block((unsigned)(waves * 64));
-    const int oct = g.fmt == kW4G32 ? 128 : 64;
+    const int oct = g.fmt == kW8C ? 64 : 128;
     size_t lds = (size_t)waves * oct * M * 16;
     const size_t red = (size_t)waves * 4 * M * 16 * sizeof(float);
     if (red > lds) lds = red;
@@ -349,6 +355,8 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t
         if (items >= 3) {
             if (g.fmt == kW8C)
                 gemv_kernel<M, kW8C, true><<<grid, block, lds, st>>>(a);
+            else if (g.fmt == kW4C)
+                gemv_kernel<M, kW4C, true><<<grid, block, lds, st>>>(a);
             else
                 gemv_kernel<M, kW4G32, true><<<grid, block, lds, st>>>(a);
             return hipGetLastError();
@@ -356,6 +364,8 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t
     }
     if (g.fmt == kW8C)
         gemv_kernel<M, kW8C, false><<<grid, block, lds, st>>>(a);
+    else if (g.fmt == kW4C)
+        gemv_kernel<M, kW4C, false><<<grid, block, lds, st>>>(a);
     else
         gemv_kernel<M, kW4G32, false><<<grid, block, lds, st>>>(a);
     return hipGetLastError();

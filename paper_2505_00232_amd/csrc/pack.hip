@@ -160,6 +160,67 @@ __global__ __launch_bounds__(256) void unpack_w4g32_kernel(const uint4 *__restri
     }
 }
 
+// ---------------------------------------------------------------- W4C
+// The weight tiles of W4G32 without scale tiles; fp32 scales per row like W8C.
+__global__ __launch_bounds__(256) void pack_w4c_kernel(const int8_t *__restrict__ wq,
+                                                       const float *__restrict__ scales,
+                                                       uint4 *__restrict__ packed, float *__restrict__ ps,
+                                                       int N, int K, int Np, int KT) {
+    const int Kg = K / 32;
+    const size_t total = (size_t)(Np / 16) * KT * 64;
+    const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < (size_t)Np) ps[v] = v < (size_t)N ? scales[v] : 0.0f;
+    if (v >= total) return;
+    const int lane = (int)(v % 64);
+    const size_t tile = v / 64;
+    const int kt = (int)(tile % KT);
+    const int rt = (int)(tile / KT);
+    const int n = rt * 16 + (lane & 15);
+    const int q = lane >> 4;
+    uint32_t d[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int g = 4 * kt + j;
+        if (n < N && g < Kg) {
+            alignas(8) int8_t c[8];
+            *reinterpret_cast<uint2 *>(c) = *reinterpret_cast<const uint2 *>(wq + (size_t)n * K + (size_t)g * 32 + 8 * q);
+            d[j] = pack8(c);
+        } else {
+            d[j] = 0x88888888u;
+        }
+    }
+    packed[v] = make_uint4(d[0], d[1], d[2], d[3]);
+}
+
+__global__ __launch_bounds__(256) void unpack_w4c_kernel(const uint4 *__restrict__ packed,
+                                                         const float *__restrict__ ps,
+                                                         int8_t *__restrict__ wq, float *__restrict__ scales,
+                                                         int N, int K, int Np, int KT) {
+    const int Kg = K / 32;
+    const size_t total = (size_t)(Np / 16) * KT * 64;
+    const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+    if (v < (size_t)N) scales[v] = ps[v];
+    if (v >= total) return;
+    const int lane = (int)(v % 64);
+    const size_t tile = v / 64;
+    const int kt = (int)(tile % KT);
+    const int rt = (int)(tile / KT);
+    const int n = rt * 16 + (lane & 15);
+    if (n >= N) return;
+    const int q = lane >> 4;
+    const uint4 in = packed[v];
+    const uint32_t w[4] = {in.x, in.y, in.z, in.w};
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int g = 4 * kt + j;
+        if (g < Kg) {
+            alignas(8) int8_t c[8];
+            unpack8(w[j], c);
+            *reinterpret_cast<uint2 *>(wq + (size_t)n * K + (size_t)g * 32 + 8 * q) = *reinterpret_cast<uint2 *>(c);
+        }
+    }
+}
+
 inline unsigned blocks_for(size_t threads) { return (unsigned)((threads + 255) / 256); }
 
 }  // namespace
@@ -169,6 +230,11 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
     if (g.fmt == kW8C) {
         const size_t total = (size_t)g.RTp * g.KT * 64;
         pack_w8c_kernel<<<blocks_for(total), 256, 0, st>>>(
+            wq, static_cast<const float *>(scales), static_cast<uint4 *>(packed),
+            reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.KT);
+    } else if (g.fmt == kW4C) {
+        const size_t total = (size_t)g.RTp * g.KT * 64;
+        pack_w4c_kernel<<<blocks_for(total > (size_t)g.Np ? total : (size_t)g.Np), 256, 0, st>>>(
             wq, static_cast<const float *>(scales), static_cast<uint4 *>(packed),
             reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.KT);
     } else {
@@ -185,6 +251,12 @@ hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void
     if (g.fmt == kW8C) {
         const size_t total = (size_t)g.RTp * g.KT * 64;
         unpack_w8c_kernel<<<blocks_for(total), 256, 0, st>>>(
+            static_cast<const uint4 *>(packed),
+            reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off), wq,
+            static_cast<float *>(scales), g.N, g.K, g.Np, g.KT);
+    } else if (g.fmt == kW4C) {
+        const size_t total = (size_t)g.RTp * g.KT * 64;
+        unpack_w4c_kernel<<<blocks_for(total > (size_t)g.Np ? total : (size_t)g.Np), 256, 0, st>>>(
             static_cast<const uint4 *>(packed),
             reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off), wq,
             static_cast<float *>(scales), g.N, g.K, g.Np, g.KT);

@@ -31,6 +31,11 @@
 //   of row c for groups 8p .. 8p+7 of the unit.  A row tile is the sequence
 //   [8 tiles][scales][8 tiles][scales]...[last <= 8 tiles][scales].
 //   K is padded to a multiple of 128 (codes 8 = zero, scales 0), N to 256.
+//
+// W4C (int4 codes, one fp32 scale per output channel: the per-channel 4-bit
+//   scheme of section 4.2 of the paper)
+//   the same 16 rows x 128 k weight tiles as W4G32, stored [row tile][k tile]
+//   with no scale tiles in between; the fp32 scales [Np] follow, as for W8C.
 #pragma once
 
 #include <hip/hip_runtime.h>
@@ -44,19 +49,19 @@ constexpr int kTileRows = 16;
 constexpr int kPadN = 256;
 constexpr int kMaxDecodeM = 8;
 
-enum Format { kW8C = 0, kW4G32 = 1 };
+enum Format { kW8C = 0, kW4G32 = 1, kW4C = 2 };
 
 struct Geometry {
     int N, K;    // logical
     int Np, Kp;  // padded
     int RT;      // row tiles holding real rows: ceil(N / 16)
     int RTp;     // Np / 16
-    int KT;      // k tiles per row tile (64 k for W8C, 128 k for W4G32)
-    int KU;      // units per row tile (W4G32: ceil(KT / 8); W8C: ceil(KT / 8))
-    int rt_stride;       // KiB tiles per row tile (W4G32: KT + KU, W8C: KT)
+    int KT;      // k tiles per row tile (64 k for W8C, 128 k for the int4 formats)
+    int KU;      // units of 8 tiles per row tile: ceil(KT / 8)
+    int rt_stride;       // KiB tiles per row tile (W4G32: KT + KU, else KT)
     int fmt;
     size_t code_bytes;   // bytes of the code (+ group scale) region
-    size_t scale_off;    // W8C: byte offset of the fp32 scales
+    size_t scale_off;    // W8C, W4C: byte offset of the fp32 scales
     size_t total_bytes;
 };
 
@@ -76,7 +81,7 @@ inline Geometry make_geometry(int N, int K, int fmt) {
         g.code_bytes = (size_t)g.Np * g.Kp;
         g.scale_off = g.code_bytes;
         g.total_bytes = g.code_bytes + (size_t)g.Np * 4;
-    } else {
+    } else if (fmt == kW4G32) {
         g.Kp = round_up(K, 128);
         g.KT = g.Kp / 128;
         g.KU = (g.KT + 7) / 8;
@@ -84,6 +89,14 @@ inline Geometry make_geometry(int N, int K, int fmt) {
         g.code_bytes = (size_t)g.RTp * g.rt_stride * 1024;
         g.scale_off = 0;
         g.total_bytes = g.code_bytes;
+    } else {
+        g.Kp = round_up(K, 128);
+        g.KT = g.Kp / 128;
+        g.KU = (g.KT + 7) / 8;
+        g.rt_stride = g.KT;
+        g.code_bytes = (size_t)g.RTp * g.KT * 1024;
+        g.scale_off = g.code_bytes;
+        g.total_bytes = g.code_bytes + (size_t)g.Np * 4;
     }
     return g;
 }

@@ -8,7 +8,9 @@ the one module both the CPU oracle's tests and the GPU path's tests consume.
 
 Formats: "w8c" = int8 weights with one fp32 scale per output channel;
 "w4g32" = int4 weights (one value per int8, range [-8, 7]) with one binary16
-scale per 32 consecutive k of a row, scales [N, K/32].
+scale per 32 consecutive k of a row, scales [N, K/32];
+"w4c" = int4 weights with one fp32 scale per output channel (the paper's
+per-channel 4-bit scheme).
 """
 from __future__ import annotations
 
@@ -24,18 +26,20 @@ class FC:
     name: str
     K: int
     N: int
-    fmt: str  # "w8c" | "w4g32"
+    fmt: str  # "w8c" | "w4g32" | "w4c"
 
 
 # Llama-3.1-8B: hidden 4096, 32 q heads + 2 x 8 kv heads of 128, FFN 14336.
 LLAMA_FCS_W4 = (FC("qkv", 4096, 6144, "w4g32"), FC("o", 4096, 4096, "w4g32"),
                 FC("gate_up", 4096, 28672, "w4g32"), FC("down", 14336, 4096, "w4g32"))
 LLAMA_FCS_W8 = tuple(FC(f.name, f.K, f.N, "w8c") for f in LLAMA_FCS_W4)
+LLAMA_FCS_W4C = tuple(FC(f.name, f.K, f.N, "w4c") for f in LLAMA_FCS_W4)
 LLAMA_LM_HEAD = FC("lm_head", 4096, 128256, "w8c")
 LLAMA_LAYERS = 32
 # Gemma2-2B: hidden 2304, 8 q heads + 2 x 4 kv heads of 256, FFN 9216.
 GEMMA_FCS_W4 = (FC("qkv", 2304, 4096, "w4g32"), FC("o", 2048, 2304, "w4g32"),
                 FC("gate_up", 2304, 18432, "w4g32"), FC("down", 9216, 2304, "w4g32"))
+GEMMA_FCS_W4C = tuple(FC(f.name, f.K, f.N, "w4c") for f in GEMMA_FCS_W4)
 GEMMA_LM_HEAD = FC("lm_head", 2304, 256000, "w8c")
 CFG1_FC = FC("fc", 512, 1024, "w8c")
 
@@ -54,6 +58,7 @@ def weights(cfg_seed: int, layer: int, fc_id: int, fc: FC):
 
     w8c: Wq uniform in [-127, 127], scales fp32 log-uniform in [1e-3, 1e-1].
     w4g32: Wq uniform in [-8, 7], scales binary16 log-uniform in [2e-3, 2e-2].
+    w4c: Wq uniform in [-8, 7], scales fp32 log-uniform in [2e-3, 2e-2].
     """
     rw = _rng(cfg_seed, layer, fc_id, KIND_W)
     rs = _rng(cfg_seed, layer, fc_id, KIND_S)
@@ -63,6 +68,9 @@ def weights(cfg_seed: int, layer: int, fc_id: int, fc: FC):
     elif fc.fmt == "w4g32":
         wq = rw.integers(-8, 8, size=(fc.N, fc.K), dtype=np.int8)
         s = np.exp(rs.uniform(np.log(2e-3), np.log(2e-2), size=(fc.N, fc.K // 32))).astype(np.float16)
+    elif fc.fmt == "w4c":
+        wq = rw.integers(-8, 8, size=(fc.N, fc.K), dtype=np.int8)
+        s = np.exp(rs.uniform(np.log(2e-3), np.log(2e-2), size=fc.N)).astype(np.float32)
     else:
         raise ValueError(fc.fmt)
     return wq, s
@@ -72,6 +80,8 @@ def algorithmic_bytes(fc: FC, M: int) -> int:
     """Bytes one decode FC must move: packed weights once, scales, x and y."""
     if fc.fmt == "w8c":
         w = fc.N * fc.K + 4 * fc.N
+    elif fc.fmt == "w4c":
+        w = fc.N * fc.K // 2 + 4 * fc.N
     else:
         w = fc.N * fc.K // 2 + 2 * fc.N * (fc.K // 32)
     return w + 2 * M * fc.K + 2 * M * fc.N

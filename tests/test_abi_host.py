@@ -42,13 +42,16 @@ def test_packed_size_and_descriptor_checks(L):
     assert binding.qfc_packed_size(d) == (4096 // 16) * (18 + 3) * 1024
     d = binding.make_desc(1, 32, "w4g32")
     assert binding.qfc_packed_size(d) == 16 * 2 * 1024  # padded to 256 rows x 128 k, one scale tile each
+    d = binding.make_desc(4096, 2304, "w4c")
+    # per 16 rows: 18 KiB tiles of 128 k, no scale tiles; 4096 fp32 scales follow
+    assert binding.qfc_packed_size(d) == (4096 // 16) * 18 * 1024 + 4 * 4096
     out = ctypes.c_size_t(0)
     bad = [binding.Desc(0, 512, 8, 0, 0, 1), binding.Desc(8, 48, 8, 0, 0, 1), binding.Desc(8, 64, 3, 0, 0, 1),
            binding.Desc(8, 64, 8, -1, 0, 1), binding.Desc(8, 64, 8, 0, 7, 1), binding.Desc(8, 64, 8, 0, 0, 5)]
     for d in bad:
         assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 1
     unsupported = [binding.Desc(8, 64, 8, 32, 0, 1), binding.Desc(8, 64, 4, 32, 1, 1),
-                   binding.Desc(8, 64, 4, 0, 0, 0), binding.Desc(8, 64, 8, 0, 1, 1)]
+                   binding.Desc(8, 64, 4, 0, 0, 1), binding.Desc(8, 64, 4, 0, 1, 0), binding.Desc(8, 64, 8, 0, 1, 1)]
     for d in unsupported:
         assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 2
     assert L.qfc_packed_size(None, ctypes.byref(out)) == 1

@@ -20,7 +20,7 @@ def _layer(wq, s, fmt, max_m=8, mode=None):
 
 
 def _group(fmt):
-    return 0 if fmt == "w8c" else 32
+    return 32 if fmt == "w4g32" else 0
 
 
 def _forward(layer, x):
@@ -31,7 +31,7 @@ def _forward(layer, x):
 
 
 # ------------------------------------------------------------------ A1 pack / unpack
-@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
 @pytest.mark.parametrize("N,K", [(1, 32), (17, 96), (64, 256), (300, 512), (1000, 2304)])
 def test_pack_unpack_round_trip_bit_exact(fmt, N, K):
     print(f"pack/unpack {fmt} N={N} K={K}", flush=True)
@@ -43,16 +43,20 @@ def test_pack_unpack_round_trip_bit_exact(fmt, N, K):
     else:
         wq = rng.integers(-8, 8, size=(N, K), dtype=np.int8)
         wq.flat[:16] = np.arange(-8, 8, dtype=np.int8)
-        s = rng.integers(0, 2**16, size=(N, K // 32), dtype=np.uint16).view(np.float16)
+        if fmt == "w4c":
+            s = rng.integers(0, 2**32, size=N, dtype=np.uint32).view(np.float32)
+        else:
+            s = rng.integers(0, 2**16, size=(N, K // 32), dtype=np.uint16).view(np.float16)
+    per_channel = fmt != "w4g32"
     layer = _layer(wq, s, fmt)
     wq_back = torch.full((N, K), 99, dtype=torch.int8, device=DEV)
-    s_back = torch.zeros(s.shape, dtype=torch.float32 if fmt == "w8c" else torch.float16, device=DEV)
+    s_back = torch.zeros(s.shape, dtype=torch.float32 if per_channel else torch.float16, device=DEV)
     binding.qfc_unpack_weights(layer.handle, wq_back, s_back)
     torch.cuda.synchronize()
     assert np.array_equal(wq_back.cpu().numpy(), wq)
     sb = s_back.cpu().numpy()
-    assert np.array_equal(sb.view(np.uint32 if fmt == "w8c" else np.uint16),
-                          s.view(np.uint32 if fmt == "w8c" else np.uint16))
+    assert np.array_equal(sb.view(np.uint32 if per_channel else np.uint16),
+                          s.view(np.uint32 if per_channel else np.uint16))
     layer.close()
 
 
@@ -60,7 +64,7 @@ def test_pack_unpack_round_trip_bit_exact(fmt, N, K):
 DECODE_SHAPES = [(1, 32), (17, 96), (130, 256), (1000, 2304), (96, 14336), (1024, 512)]
 
 
-@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
 @pytest.mark.parametrize("N,K", DECODE_SHAPES)
 def test_decode_matches_oracle(fmt, N, K):
     fc = synth.FC("t", K, N, fmt)
@@ -79,13 +83,13 @@ def test_decode_matches_oracle(fmt, N, K):
     layer.close()
 
 
-@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
 def test_decode_config1_and_structure_cases(fmt):
     print(f"decode structure cases {fmt}", flush=True)
     # identity weights with unit scales return x bit for bit (one non-zero term per output)
     K = 512
     eye = np.eye(K, dtype=np.int8)
-    ones = np.ones(K, np.float32) if fmt == "w8c" else np.ones((K, K // 32), np.float16)
+    ones = np.ones(K, np.float32) if fmt != "w4g32" else np.ones((K, K // 32), np.float16)
     layer = _layer(eye, ones, fmt)
     x = synth.activations(2001, 0, 0, 4, K)
     y = _forward(layer, x)
@@ -98,7 +102,7 @@ def test_decode_config1_and_structure_cases(fmt):
     q = rng.integers(1, 8, size=N) * rng.choice([-1, 1], size=N)
     wq = np.zeros((N, K), np.int8)
     wq[np.arange(N), perm] = q
-    if fmt == "w8c":
+    if fmt != "w4g32":
         s = (2.0 ** rng.integers(-6, 3, size=N)).astype(np.float32)
         sn = s.astype(np.float64)
     else:
@@ -290,17 +294,18 @@ def test_int8_prefill_config5_lm_head_sampled():
 
 
 # ------------------------------------------------------------------ A6 fp16 MFMA prefill with in-LDS dequantization
+@pytest.mark.parametrize("fmt", ["w4g32", "w4c"])
 @pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (130, 1000, 2304),
                                    (300, 264, 128), (129, 520, 1152), (16, 256, 2176)])
-def test_fp16_prefill_matches_oracle(M, N, K):
-    print(f"fp16 prefill M={M} N={N} K={K}", flush=True)
-    fc = synth.FC("t", K, N, "w4g32")
+def test_fp16_prefill_matches_oracle(fmt, M, N, K):
+    print(f"fp16 prefill {fmt} M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, fmt)
     wq, s = synth.weights(5000, M, N, fc)
     wq.flat[0] = -8
     x = synth.activations(5000, M, N, M, K)
-    layer = _layer(wq, s, "w4g32", max_m=M)
+    layer = _layer(wq, s, fmt, max_m=M)
     y = _forward(layer, x)
-    ref = oracle.fc_weight_only(x, wq, s, 32)
+    ref = oracle.fc_weight_only(x, wq, s, _group(fmt))
     assert oracle.floored_rel_error(y, ref) <= TOL
     layer.close()
 
@@ -323,7 +328,7 @@ def test_fp16_prefill_config5_shapes_sampled():
 
 
 # ------------------------------------------------------------------ A7 dispatch, batches, streams
-@pytest.mark.parametrize("fmt", ["w8c", "w4g32"])
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
 def test_dispatch_boundary_m8_m9(fmt):
     """M = 8 takes the decode kernel, M = 9 the prefill path: both within tolerance of the
     oracle, and the first eight rows of the M = 9 result agree with the M = 8 result to
@@ -338,11 +343,11 @@ def test_dispatch_boundary_m8_m9(fmt):
     if fmt == "w8c":
         _, _, _, ref9 = oracle.fc_int8_act(x, wq, s)
     else:
-        ref9 = oracle.fc_weight_only(x, wq, s, 32)
+        ref9 = oracle.fc_weight_only(x, wq, s, _group(fmt))
     ref8 = oracle.fc_weight_only(x[:8], wq, s, _group(fmt))
     assert oracle.floored_rel_error(y8, ref8) <= TOL
     assert oracle.floored_rel_error(y9, ref9) <= TOL
-    if fmt == "w4g32":
+    if fmt != "w8c":
         assert oracle.floored_rel_error(y9[:8], ref8) <= TOL
     layer.close()
 
@@ -370,7 +375,7 @@ def test_forward_batch_equals_single_calls_on_a_side_stream():
         l.close()
 
 
-@pytest.mark.parametrize("fmt,M", [("w8c", 200), ("w4g32", 300)])
+@pytest.mark.parametrize("fmt,M", [("w8c", 200), ("w4g32", 300), ("w4c", 300)])
 def test_prefill_is_deterministic(fmt, M):
     print(f"prefill determinism {fmt}", flush=True)
     fc = synth.FC("t", 1152, 520, fmt)
