@@ -1,20 +1,16 @@
-// Prefill product for group-quantized int4 weights on the fp16 matrix cores:
-//   y[m,n] = sum_k x[m,k] * (s[n, k/32] * Wq[n,k]),  fp32 accumulation.
+// Prefill product for int4 weights on the fp16 matrix cores:
+//   y[m,n] = sum_k x[m,k] * (s * Wq[n,k]),  fp32 accumulation,
+// with s = s[n, k/32] (group scales) or s[n] (per-channel scales).
 // FP16 activations with quantized weights (section 4.2 of the paper), computed
 // on matrix units as the compute-bound prefill stage wants (section 3.7).
 //
-// Two kernels.  The main one (K a multiple of 128) never puts weights into LDS:
-// a packed weight tile is, lane for lane, a sequence of four 16x16x32 MFMA
-// operands (16 output rows x the 32 k of one quantization group), so every
-// wavefront loads the tiles of its own 64 output rows straight from memory into
-// registers, converts them there (exact int -> binary16, one binary16 multiply
-// by the group scale) and feeds the matrix core; only the activations, which
-// all wavefronts of the workgroup share, go through LDS, copied there as they
-// are by direct global -> LDS loads in a four-stage ring.  Int4 weights are a
-// quarter of the activation bytes, so the register path costs little memory
-// traffic, and LDS carries half the bytes per MFMA of a kernel that stages both
-// operands.  The second kernel is the general fallback (any K that is a
-// multiple of 32):
+// Two kernels.  The main one (K a multiple of 128; described in front of it)
+// never writes dequantized weights anywhere: packed tiles are copied verbatim
+// into LDS, a lane reads the dword that is its MFMA operand, converts it in
+// registers and feeds the matrix core.  Int4 weights are a quarter of the
+// activation bytes, so LDS carries far fewer bytes per MFMA than with a
+// dequantized weight tile.  The second kernel is the general fallback (any K
+// that is a multiple of 32):
 //
 // Per K stage of 128 (one packed weight tile per 16 rows): every thread loads
 // 16-byte vectors of packed codes (four octets, one per quantization group of
