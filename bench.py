@@ -219,7 +219,25 @@ def main():
                                            "algorithmic_bytes_per_step": bytes_pc}
     for l in ls_pc:
         l.close()
-    del ls_pc, xs_pc, ys_pc, fb_pc
+    del ls_pc, ys_pc, fb_pc
+    torch.cuda.empty_cache()
+    # ... and with the paper's decode design: activations quantized to int8 inside the kernel,
+    # integer accumulation (section 3.7)
+    ls_q = []
+    for layer, i, fc in fcs_pc:
+        wq, s = synth.weights(SEED + 100, layer, i, fc)
+        ls_q.append(binding.QuantLinear(wq, s, fc.fmt, compute_mode=binding.QFC_COMPUTE_INT8_ACT_DECODE, max_m=8))
+        del wq, s
+    ys_q = [torch.empty((1, l.N), dtype=torch.float16, device=dev) for l in ls_q]
+    fb_q = binding.ForwardBatch([l.handle for l in ls_q], xs_pc, ys_q, 1)
+    fb_q.run()
+    ms_q = event_ms(fb_q.run, args.steps)
+    extra["decode_m1_int4_per_channel_int8_activations"] = {
+        "ms_per_step": round(ms_q, 4), "GB/s": round(bytes_pc / (ms_q * 1e-3) / 1e9, 1),
+        "frac_hbm_peak": round(bytes_pc / (ms_q * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "tokens_per_s": round(1 / (ms_q * 1e-3), 1)}
+    for l in ls_q:
+        l.close()
+    del ls_q, xs_pc, ys_q, fb_q
     torch.cuda.empty_cache()
 
     ms_c1, b_c1 = rotating([synth.CFG1_FC], 1001, 512)

@@ -51,7 +51,7 @@ typedef enum {
 } qfc_status_t;
 
 enum { QFC_SCALE_F32 = 0, QFC_SCALE_F16 = 1 };
-enum { QFC_COMPUTE_FP16_DEQUANT = 0, QFC_COMPUTE_INT8_ACT = 1 };
+enum { QFC_COMPUTE_FP16_DEQUANT = 0, QFC_COMPUTE_INT8_ACT = 1, QFC_COMPUTE_INT8_ACT_DECODE = 2 };
 
 /* Description of one quantized linear layer, y[M,N] = x[M,K] . W[N,K]^T.
  * Supported formats (section 4.2 per-channel schemes; group scales are the
@@ -63,7 +63,11 @@ enum { QFC_COMPUTE_FP16_DEQUANT = 0, QFC_COMPUTE_INT8_ACT = 1 };
  *                                            channel (the paper's per-channel 4-bit scheme).
  * Any other combination returns QFC_ERR_UNSUPPORTED.
  * compute_mode selects the M > 8 path: QFC_COMPUTE_INT8_ACT (needs 8-bit per-channel weights)
- * or QFC_COMPUTE_FP16_DEQUANT.  It has no effect for M <= 8. */
+ * or QFC_COMPUTE_FP16_DEQUANT; neither changes M <= 8, which keeps binary16 activations.
+ * QFC_COMPUTE_INT8_ACT_DECODE (per-channel formats only) is the decode design of section 3.7
+ * of the paper: for M <= 8 the kernel quantizes the activations itself (one scale per token
+ * row, as qfc_quantize_activations does) and accumulates integers; for M > 8 it behaves like
+ * QFC_COMPUTE_INT8_ACT with 8-bit weights and like QFC_COMPUTE_FP16_DEQUANT with 4-bit ones. */
 typedef struct {
     int32_t N;
     int32_t K;

@@ -14,7 +14,7 @@ LIB_PATH = os.path.join(_HERE, "libqfc.so")
 
 QFC_OK = 0
 QFC_SCALE_F32, QFC_SCALE_F16 = 0, 1
-QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT = 0, 1
+QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT, QFC_COMPUTE_INT8_ACT_DECODE = 0, 1, 2
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
            "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_q8",

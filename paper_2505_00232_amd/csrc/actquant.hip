@@ -16,70 +16,122 @@ namespace {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int off = 32; off > 0; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
-    return v;
-}
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
-__device__ __forceinline__ uint32_t quant4(const float *v, float inv) {
-    uint32_t d = 0;
+// Four binary16 values -> four int8 codes in one dword.  The product is rounded to fp32 first and
+// then to the nearest integer (ties to even) by adding 1.5 * 2^23, which leaves the two's complement
+// code in the low mantissa byte: the same two roundings as rintf(x * inv).  |x * inv| cannot exceed
+// 127 by more than two units in the last place, so the clamp to +-127 of the definition never acts.
+__device__ __forceinline__ uint32_t quant4(const _Float16 *h, float inv) {
+    uint32_t b[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-        float r = rintf(v[i] * inv);
-        r = fminf(fmaxf(r, -127.0f), 127.0f);
-        d |= ((uint32_t)(int)r & 0xFFu) << (8 * i);
+#pragma clang fp contract(off)  // a fused multiply-add would round once, not twice
+        const float v = (float)h[i] * inv;
+        b[i] = __float_as_uint(v + 12582912.0f);
     }
-    return d;
+    const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+    return lo | (hi << 16);
 }
 
-template <bool kTiled>
-__global__ __launch_bounds__(256) void act_quant_kernel(const uint4 *__restrict__ x, int M, int K,
-                                                        uint4 *__restrict__ xq, float *__restrict__ sx,
-                                                        int Kp) {
-    __shared__ float wmax[4];
-    const int m = blockIdx.x;
-    const int tid = threadIdx.x;
+// Running maximum of |x| over pairs of binary16 values, on the bit patterns with the sign cleared:
+// for finite values the order of the magnitudes is the order of these 15-bit integers.
+__device__ __forceinline__ us2 fold_abs(us2 acc, uint32_t d) {
+    return __builtin_elementwise_max(acc, __builtin_bit_cast(us2, d & 0x7FFF7FFFu));
+}
+
+// A workgroup of NW = 2 ROWS wavefronts takes ROWS token rows (8, 4 or 2).  With T = 16 / ROWS, lane
+// (c, q, t) of wavefront w handles, in step i, the 16 values k = 64 kt + 16 q .. + 15 of row c,
+// kt = T (NW i + w) + t: a wavefront instruction reads 256 T contiguous bytes of each of its rows
+// and, in the tiled layout, writes 16 ROWS contiguous bytes per tile quarter.  The values of the
+// first KEEP steps stay in registers between the maximum pass and the quantization pass (rows up
+// to K = 14336 are read once); longer rows are read a second time.  Few rows per workgroup spread
+// a small M over the whole chip (a compute unit streams only about 30 GB/s on its own); many rows
+// per workgroup write whole 128-byte lines.
+template <bool kTiled, int ROWS>
+__global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__restrict__ x, int M, int K,
+                                                         uint4 *__restrict__ xq, float *__restrict__ sx,
+                                                         int Kp) {
+    constexpr int T = 16 / ROWS;           // tiles per wavefront instruction
+    constexpr int NW = 2 * ROWS;           // wavefronts; NW * T = 32 tiles per step
+    constexpr int KEEP = 7;
+    __shared__ float wmax[NW][ROWS];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int c = lane % ROWS, q = (lane / ROWS) & 3, t = lane / (4 * ROWS);
+    // Tiled output: the workgroups that share the lines of a tile run on one XCD (workgroup b runs
+    // on XCD b % 8), so the pieces of a line meet in that XCD's L2.  The grid is a multiple of 8 then.
+    const int wg = kTiled ? (int)((blockIdx.x & 7) * (gridDim.x >> 3) + (blockIdx.x >> 3)) : (int)blockIdx.x;
+    const int m = wg * ROWS + c;
     const bool real = m < M;
-    float a = 0.0f;
-    if (real) {
-        const uint4 *row = x + (size_t)m * (K / 8);
-        for (int v = tid; v < K / 8; v += 256) {
-            const h8 h = __builtin_bit_cast(h8, row[v]);
+    const int tiles = (kTiled ? Kp : K + 63) / 64;
+    const int steps = (tiles + 31) / 32;
+    const uint4 *row = x + (size_t)(real ? m : 0) * (K / 8);
+
+    uint4 keep[KEEP][2];
+    us2 amax = {0, 0};
+    auto load = [&](int i, uint4 &v0, uint4 &v1) {
+        const int k0 = (T * (NW * i + wave) + t) * 64 + q * 16;
+        const bool in = real && k0 < K;
+        const uint4 *src = row + (in ? k0 / 8 : 0);
+        v0 = src[0];
+        v1 = src[1];
+        if (!in) v0 = v1 = make_uint4(0, 0, 0, 0);
+    };
+    auto fold = [&](const uint4 &v0, const uint4 &v1) {
+        amax = fold_abs(fold_abs(fold_abs(fold_abs(amax, v0.x), v0.y), v0.z), v0.w);
+        amax = fold_abs(fold_abs(fold_abs(fold_abs(amax, v1.x), v1.y), v1.z), v1.w);
+    };
 #pragma unroll
-            for (int i = 0; i < 8; ++i) a = fmaxf(a, fabsf((float)h[i]));
+    for (int i = 0; i < KEEP; ++i) {
+        if (i < steps) {
+            load(i, keep[i][0], keep[i][1]);
+            fold(keep[i][0], keep[i][1]);
         }
     }
-    a = wave_max(a);
-    if ((tid & 63) == 0) wmax[tid >> 6] = a;
+    for (int i = KEEP; i < steps; ++i) {
+        uint4 v0, v1;
+        load(i, v0, v1);
+        fold(v0, v1);
+    }
+    const unsigned short top = amax.x > amax.y ? amax.x : amax.y;
+    float a = (float)__builtin_bit_cast(_Float16, top);
+#pragma unroll
+    for (int off = ROWS; off < 64; off <<= 1) a = fmaxf(a, __shfl_xor(a, off, 64));
+    if (lane < ROWS) wmax[wave][lane] = a;
     __syncthreads();
-    a = fmaxf(fmaxf(wmax[0], wmax[1]), fmaxf(wmax[2], wmax[3]));
+#pragma unroll
+    for (int w = 0; w < NW; ++w) a = fmaxf(a, wmax[w][c]);
     float scale = 0.0f, inv = 0.0f;
     if (a != 0.0f) {
         scale = a / 127.0f;
         inv = 127.0f / a;
     }
-    if (tid == 0) sx[m] = scale;
+    if (wave == 0 && lane < ROWS && (kTiled || real)) sx[m] = scale;
 
-    const int chunks = (kTiled ? Kp : K) / 16;
-    for (int c = tid; c < chunks; c += 256) {
-        uint4 out = make_uint4(0, 0, 0, 0);
-        if (real && c * 16 < K) {
-            const uint4 *src = x + (size_t)m * (K / 8) + c * 2;
-            const h8 h0 = __builtin_bit_cast(h8, src[0]);
-            const h8 h1 = __builtin_bit_cast(h8, src[1]);
-            float v[16];
+    auto emit = [&](int i, const uint4 &v0, const uint4 &v1) {
+        const int kt = T * (NW * i + wave) + t;
+        if (kt >= tiles) return;
+        const h8 h0 = __builtin_bit_cast(h8, v0), h1 = __builtin_bit_cast(h8, v1);
+        _Float16 v[16];
 #pragma unroll
-            for (int i = 0; i < 8; ++i) {
-                v[i] = (float)h0[i];
-                v[8 + i] = (float)h1[i];
-            }
-            out = make_uint4(quant4(v, inv), quant4(v + 4, inv), quant4(v + 8, inv), quant4(v + 12, inv));
+        for (int e = 0; e < 8; ++e) {
+            v[e] = h0[e];
+            v[8 + e] = h1[e];
         }
+        const uint4 out = make_uint4(quant4(v, inv), quant4(v + 4, inv), quant4(v + 8, inv), quant4(v + 12, inv));
         if (kTiled)
-            xq[((size_t)(m >> 4) * (Kp / 64) + (c >> 2)) * 64 + (c & 3) * 16 + (m & 15)] = out;
-        else
-            xq[(size_t)m * (K / 16) + c] = out;
+            xq[((size_t)(m >> 4) * (Kp / 64) + kt) * 64 + q * 16 + (m & 15)] = out;
+        else if (real && kt * 64 + q * 16 < K)
+            xq[(size_t)m * (K / 16) + kt * 4 + q] = out;
+    };
+#pragma unroll
+    for (int i = 0; i < KEEP; ++i)
+        if (i < steps) emit(i, keep[i][0], keep[i][1]);
+    for (int i = KEEP; i < steps; ++i) {
+        uint4 v0, v1;
+        load(i, v0, v1);
+        emit(i, v0, v1);
     }
 }
 
@@ -98,16 +150,33 @@ __global__ __launch_bounds__(256) void retile_xq_kernel(const uint4 *__restrict_
     tiled[v] = out;
 }
 
+
+template <int ROWS>
+void launch_rows(const void *x, int M, int K, int8_t *xq, float *sx, int tiled, int Mp, int Kp, hipStream_t st) {
+    const uint4 *xv = static_cast<const uint4 *>(x);
+    uint4 *qv = reinterpret_cast<uint4 *>(xq);
+    if (tiled)
+        act_quant_kernel<true, ROWS><<<Mp / ROWS, 128 * ROWS, 0, st>>>(xv, M, K, qv, sx, Kp);
+    else
+        act_quant_kernel<false, ROWS><<<(M + ROWS - 1) / ROWS, 128 * ROWS, 0, st>>>(xv, M, K, qv, sx, K);
+}
+
 }  // namespace
 
+// Mp (tiled output) must be a multiple of 16.  The most rows per workgroup that still give two
+// workgroups per compute unit, else two.
 hipError_t launch_act_quant(const void *x, int M, int K, int8_t *xq, float *sx, int tiled, int Mp,
-                            int Kp, hipStream_t st) {
-    if (tiled)
-        act_quant_kernel<true><<<Mp, 256, 0, st>>>(static_cast<const uint4 *>(x), M, K,
-                                                   reinterpret_cast<uint4 *>(xq), sx, Kp);
+                            int Kp, int num_cus, hipStream_t st) {
+    const int rows_total = tiled ? Mp : M;
+    int rows = rows_total >= 16 * num_cus ? 8 : rows_total >= 8 * num_cus ? 4 : 2;
+    const int forced = tuning().act_quant_rows;
+    if (forced == 2 || forced == 4 || forced == 8) rows = forced;
+    if (rows == 8)
+        launch_rows<8>(x, M, K, xq, sx, tiled, Mp, Kp, st);
+    else if (rows == 4)
+        launch_rows<4>(x, M, K, xq, sx, tiled, Mp, Kp, st);
     else
-        act_quant_kernel<false><<<M, 256, 0, st>>>(static_cast<const uint4 *>(x), M, K,
-                                                   reinterpret_cast<uint4 *>(xq), sx, K);
+        launch_rows<2>(x, M, K, xq, sx, tiled, Mp, Kp, st);
     return hipGetLastError();
 }
 

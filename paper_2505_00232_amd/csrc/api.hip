@@ -29,13 +29,14 @@ qfc_status_t check_desc(const qfc_desc_t *d, int *fmt) {
     if (d->wbits != 8 && d->wbits != 4) return QFC_ERR_INVALID_ARG;
     if (d->group_size < 0) return QFC_ERR_INVALID_ARG;
     if (d->scale_dtype != QFC_SCALE_F32 && d->scale_dtype != QFC_SCALE_F16) return QFC_ERR_INVALID_ARG;
-    if (d->compute_mode != QFC_COMPUTE_FP16_DEQUANT && d->compute_mode != QFC_COMPUTE_INT8_ACT)
+    if (d->compute_mode != QFC_COMPUTE_FP16_DEQUANT && d->compute_mode != QFC_COMPUTE_INT8_ACT &&
+        d->compute_mode != QFC_COMPUTE_INT8_ACT_DECODE)
         return QFC_ERR_INVALID_ARG;
     if (d->wbits == 8 && d->group_size == 0 && d->scale_dtype == QFC_SCALE_F32) {
         *fmt = kW8C;
     } else if (d->wbits == 4 && d->group_size == 32 && d->scale_dtype == QFC_SCALE_F16) {
         *fmt = kW4G32;
-        if (d->compute_mode == QFC_COMPUTE_INT8_ACT) return QFC_ERR_UNSUPPORTED;
+        if (d->compute_mode != QFC_COMPUTE_FP16_DEQUANT) return QFC_ERR_UNSUPPORTED;
     } else if (d->wbits == 4 && d->group_size == 0 && d->scale_dtype == QFC_SCALE_F32) {
         *fmt = kW4C;
         if (d->compute_mode == QFC_COMPUTE_INT8_ACT) return QFC_ERR_UNSUPPORTED;
@@ -145,26 +146,32 @@ qfc_status_t qfc_quantize_activations(const void *x_f16, int32_t M, int32_t K, i
                                       void *stream) {
     if (!x_f16 || !xq || !sx || M < 1 || K < 1 || K % 32 != 0) return QFC_ERR_INVALID_ARG;
     if (!aligned16(x_f16) || !aligned16(xq) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return QFC_ERR_ALIGNMENT;
-    return hip_status(launch_act_quant(x_f16, M, K, xq, sx, 0, M, K, static_cast<hipStream_t>(stream)));
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return QFC_ERR_HIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return QFC_ERR_HIP;
+    return hip_status(launch_act_quant(x_f16, M, K, xq, sx, 0, M, K, cus, static_cast<hipStream_t>(stream)));
 }
 
 qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream) {
     if (!valid(h) || !x_f16 || !y_f16 || M < 1) return QFC_ERR_INVALID_ARG;
     if (!aligned16(x_f16) || !aligned16(y_f16)) return QFC_ERR_ALIGNMENT;
     hipStream_t st = static_cast<hipStream_t>(stream);
-    if (M > kMaxDecodeM && h->desc.compute_mode == QFC_COMPUTE_FP16_DEQUANT) {
+    if (M <= kMaxDecodeM) {
+        if (h->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE)
+            return hip_status(launch_gemv_q8(h->geo, h->packed, x_f16, nullptr, 0, M, y_f16, 0, h->num_cus, st));
+        return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
+    }
+    if (h->desc.compute_mode == QFC_COMPUTE_FP16_DEQUANT || h->geo.fmt == kW4C) {
         if (h->geo.fmt != kW4G32 && h->geo.fmt != kW4C) return QFC_ERR_UNSUPPORTED;
         return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
     }
-    if (M <= kMaxDecodeM)
-        return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
     if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     // int8 activations: quantize into the workspace (tiled), multiply, rescale
     const int Mp = prefill_rows(M);
     char *body = static_cast<char *>(h->workspace);
     int8_t *tiled = reinterpret_cast<int8_t *>(body);
     float *sx = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
-    if (launch_act_quant(x_f16, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, st) != hipSuccess) return QFC_ERR_HIP;
+    if (launch_act_quant(x_f16, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, h->num_cus, st) != hipSuccess) return QFC_ERR_HIP;
     return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, h->num_cus, st));
 }
 
@@ -172,6 +179,11 @@ qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, i
                             void *stream) {
     if (!sx || !y_f16) return QFC_ERR_INVALID_ARG;
     if (!aligned16(y_f16) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return QFC_ERR_ALIGNMENT;
+    if (valid(h) && xq && M >= 1 && M <= kMaxDecodeM && (h->geo.fmt == kW8C || h->geo.fmt == kW4C)) {
+        if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
+        return hip_status(launch_gemv_q8(h->geo, h->packed, xq, sx, 1, M, y_f16, 0, h->num_cus,
+                                         static_cast<hipStream_t>(stream)));
+    }
     int8_t *tiled = nullptr;
     float *sx_ws = nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -183,6 +195,11 @@ qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, i
 qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc, void *stream) {
     if (!acc) return QFC_ERR_INVALID_ARG;
     if (!aligned16(acc)) return QFC_ERR_ALIGNMENT;
+    if (valid(h) && xq && M >= 1 && M <= kMaxDecodeM && (h->geo.fmt == kW8C || h->geo.fmt == kW4C)) {
+        if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
+        return hip_status(launch_gemv_q8(h->geo, h->packed, xq, nullptr, 1, M, acc, 1, h->num_cus,
+                                         static_cast<hipStream_t>(stream)));
+    }
     int8_t *tiled = nullptr;
     float *sx_ws = nullptr;
     hipStream_t st = static_cast<hipStream_t>(stream);
@@ -222,12 +239,14 @@ const char *qfc_status_string(qfc_status_t s) {
 
 // Tuning knob for experiments (not part of the documented interface):
 // key 0 = target wavefronts of a decode launch, 1 = max row tiles per
-// decode workgroup, 2 = prefill kernel variant.
+// decode workgroup, 2 = prefill kernel variant, 3 = token rows per workgroup of the
+// activation quantization kernel (2, 4, 8; 0 = automatic).
 void qfc_tune(int32_t key, int32_t value) {
     Tuning &t = tuning();
     if (key == 0) t.gemv_target_waves = value;
     if (key == 1) t.gemv_max_row_tiles = value;
     if (key == 2) t.gemm_variant = value;
+    if (key == 3) t.act_quant_rows = value;
 }
 
 }  // extern "C"

@@ -111,6 +111,7 @@ struct Tuning {
     int gemv_target_waves = 8192;
     int gemv_max_row_tiles = 2;
     int gemm_variant = 0;
+    int act_quant_rows = 0;  // 0: automatic
 };
 Tuning &tuning();
 
@@ -124,8 +125,12 @@ hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void
                          hipStream_t st);
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
                        int num_cus, hipStream_t st);
+// Decode with 8-bit activations (per-channel weight formats).  src 0: x is binary16 and is
+// quantized in the kernel; 1: x is int8 with scales sx.  out_mode 0: binary16 y; 1: int32 sums.
+hipError_t launch_gemv_q8(const Geometry &g, const void *packed, const void *x, const float *sx, int src,
+                          int M, void *out, int out_mode, int num_cus, hipStream_t st);
 hipError_t launch_act_quant(const void *x, int M, int K, int8_t *xq, float *sx, int tiled,
-                            int Mp, int Kp, hipStream_t st);
+                            int Mp, int Kp, int num_cus, hipStream_t st);
 hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp,
                             hipStream_t st);
 // out_mode 0: binary16 y with scales; 1: raw int32 accumulators.

@@ -48,10 +48,12 @@ def test_packed_size_and_descriptor_checks(L):
     out = ctypes.c_size_t(0)
     bad = [binding.Desc(0, 512, 8, 0, 0, 1), binding.Desc(8, 48, 8, 0, 0, 1), binding.Desc(8, 64, 3, 0, 0, 1),
            binding.Desc(8, 64, 8, -1, 0, 1), binding.Desc(8, 64, 8, 0, 7, 1), binding.Desc(8, 64, 8, 0, 0, 5)]
+    assert binding.qfc_packed_size(binding.Desc(8, 64, 4, 0, 0, 2)) > 0  # int8-activation decode, per-channel int4
     for d in bad:
         assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 1
     unsupported = [binding.Desc(8, 64, 8, 32, 0, 1), binding.Desc(8, 64, 4, 32, 1, 1),
-                   binding.Desc(8, 64, 4, 0, 0, 1), binding.Desc(8, 64, 4, 0, 1, 0), binding.Desc(8, 64, 8, 0, 1, 1)]
+                   binding.Desc(8, 64, 4, 0, 0, 1), binding.Desc(8, 64, 4, 0, 1, 0), binding.Desc(8, 64, 8, 0, 1, 1),
+                   binding.Desc(8, 64, 4, 32, 1, 2)]
     for d in unsupported:
         assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 2
     assert L.qfc_packed_size(None, ctypes.byref(out)) == 1

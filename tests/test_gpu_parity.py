@@ -327,6 +327,50 @@ def test_fp16_prefill_config5_shapes_sampled():
         layer.close()
 
 
+# ------------------------------------------------------------------ decode with 8-bit activations (the paper's decode design)
+@pytest.mark.parametrize("fmt", ["w8c", "w4c"])
+@pytest.mark.parametrize("N,K", DECODE_SHAPES)
+def test_decode_int8_activations(fmt, N, K):
+    """Activations quantized inside the decode kernel: integer sums bit for bit (through the
+    entry points that take quantized activations), y within tolerance of the step-by-step
+    oracle, and the fused kernel equal to the pre-quantized one bit for bit."""
+    fc = synth.FC("t", K, N, fmt)
+    wq, sw = synth.weights(2100, N, K, fc)
+    wq.flat[0] = -128 if fmt == "w8c" else -8
+    layer = _layer(wq, sw, fmt, mode=binding.QFC_COMPUTE_INT8_ACT_DECODE)
+    for M in range(1, 9):
+        print(f"decode int8 activations {fmt} N={N} K={K} M={M}", flush=True)
+        x = synth.activations(2100, N, K + M, M, K)
+        if M == 3:
+            x[1] = 0  # an all-zero token row: scale 0, codes 0, output 0
+        xq_ref, sx_ref, acc_ref, y_ref = oracle.fc_int8_act(x, wq, sw)
+        xq_d = torch.from_numpy(xq_ref).to(DEV)
+        acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+        binding.qfc_forward_acc_i32(layer.handle, xq_d, acc)
+        y_q8 = torch.empty((M, N), dtype=torch.float16, device=DEV)
+        binding.qfc_forward_q8(layer.handle, xq_d, torch.from_numpy(sx_ref).to(DEV), y_q8)
+        y = _forward(layer, x)
+        assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), M
+        assert oracle.floored_rel_error(y, y_ref) <= TOL, M
+        assert np.array_equal(y.view(np.uint16), y_q8.cpu().numpy().view(np.uint16)), M
+    layer.close()
+
+
+def test_decode_int8_activations_llama_shapes_sampled():
+    rng = np.random.default_rng(31)
+    for i, fc in enumerate(synth.LLAMA_FCS_W4C):
+        print(f"int8-activation decode {fc.name} {fc.K}->{fc.N}", flush=True)
+        wq, sw = synth.weights(1103, 0, i, fc)
+        x = synth.activations(1103, 0, i, 4, fc.K)
+        layer = _layer(wq, sw, fc.fmt, mode=binding.QFC_COMPUTE_INT8_ACT_DECODE)
+        y = _forward(layer, x)
+        cols = np.sort(rng.choice(fc.N, size=512, replace=False))
+        cols[0], cols[-1] = 0, fc.N - 1
+        _, _, _, y_ref = oracle.fc_int8_act(x, wq[cols], sw[cols])
+        assert oracle.floored_rel_error(y[:, cols], y_ref) <= TOL
+        layer.close()
+
+
 # ------------------------------------------------------------------ A7 dispatch, batches, streams
 @pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
 def test_dispatch_boundary_m8_m9(fmt):
