@@ -2,8 +2,9 @@
 
 TEST INFRASTRUCTURE ONLY.  Only tests, the smoke check and the CPU-baseline leg
 of the benchmark may import this package; the product path never does.  The
-arithmetic lives in ``qfc_oracle.c`` (plain C, fp64 / fp32 as stated there);
-this file only marshals numpy arrays.  It imports nothing from the GPU package.
+arithmetic of the layer lives in ``qfc_oracle.c`` (plain C, fp64 / fp32 as stated
+there) and this file only marshals numpy arrays; the element-wise operators fused
+with the layer are plain numpy in ``elementwise.py``.  It imports nothing from the GPU package.
 
 Passages followed (section 3.7 for the two stages, section 4.2 for the weight
 formats and FP16 activations) are cited function by function in the C file.
@@ -15,6 +16,8 @@ import os
 import subprocess
 
 import numpy as np
+
+from .elementwise import GELU_TANH, SILU, add_residual, gated_input, gelu_tanh, silu  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qfc_oracle.c")

@@ -1,0 +1,53 @@
+"""CPU oracle, element-wise operators fused with the fully connected operator.
+
+TEST INFRASTRUCTURE ONLY (same rule as the package: tests, the smoke check and
+the CPU-baseline leg of the benchmark may import it; the product path never
+does).  Plain numpy in fp64, one function per operator, nothing blocked or
+reordered.  It imports nothing from the GPU package.
+
+The paper (operator fusion, section 3.6 and its figure) merges element-wise
+operators of two branches into a fully connected operator and residual
+connections into the neighbouring operator; it prints no formulas for them.
+The two branches in the models it evaluates are the gated feed-forward network:
+Llama multiplies SiLU(gate) with the other branch, Gemma the tanh form of GELU.
+"""
+from __future__ import annotations
+
+import numpy as np
+
+SILU = 0
+GELU_TANH = 1
+
+
+def silu(g) -> np.ndarray:
+    """g * sigmoid(g) = g / (1 + exp(-g)), fp64."""
+    g = np.asarray(g, dtype=np.float64)
+    return g / (1.0 + np.exp(-g))
+
+
+def gelu_tanh(g) -> np.ndarray:
+    """0.5 g (1 + tanh(sqrt(2/pi) (g + 0.044715 g^3))), fp64."""
+    g = np.asarray(g, dtype=np.float64)
+    return 0.5 * g * (1.0 + np.tanh(np.sqrt(2.0 / np.pi) * (g + 0.044715 * g * g * g)))
+
+
+def gated_input(gate_f16, up_f16, activation: int) -> np.ndarray:
+    """The FC input of the fused operator: act(gate) * up, rounded once to binary16.
+
+    That is the tensor an unfused element-wise operator would have written with
+    FP16 activations (section 4.2).  Returns float16 [M, K].
+    """
+    g = np.asarray(gate_f16, dtype=np.float16).astype(np.float64)
+    u = np.asarray(up_f16, dtype=np.float16).astype(np.float64)
+    if activation == SILU:
+        a = silu(g)
+    elif activation == GELU_TANH:
+        a = gelu_tanh(g)
+    else:
+        raise ValueError("unknown activation")
+    return (a * u).astype(np.float16)  # fp64 -> binary16, round to nearest even
+
+
+def add_residual(y, residual_f16) -> np.ndarray:
+    """y + residual in fp64 (the caller's comparison applies the final binary16 rounding)."""
+    return np.asarray(y, dtype=np.float64) + np.asarray(residual_f16, dtype=np.float16).astype(np.float64)

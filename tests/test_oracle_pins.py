@@ -273,3 +273,60 @@ def test_error_metric():
     assert oracle.floored_rel_error(y, y) == 0.0
     rho = np.sqrt(np.mean(y * y))
     assert abs(oracle.floored_rel_error(y + np.array([[0, 0, 1e-3, 0]]), y) - 1e-3 / rho) < 1e-15
+
+
+# ---------------------------------------------------------------- fused element-wise operators
+def test_gate_activations_hand_values_and_identities():
+    c = _golden()["gated_activations"]
+    g = np.array([float(v) for v in c["g"]])
+    assert np.allclose(oracle.silu(g), [float(v) for v in c["silu"]], rtol=0, atol=5e-10)
+    assert np.allclose(oracle.gelu_tanh(g), [float(v) for v in c["gelu_tanh"]], rtol=0, atol=5e-10)
+    # library routines: the logistic function, and the exact (erf) GELU the tanh form approximates
+    from scipy.special import erf, expit
+    t = np.linspace(-12.0, 12.0, 4801)
+    assert np.allclose(oracle.silu(t), t * expit(t), rtol=1e-14, atol=1e-300)
+    exact = 0.5 * t * (1.0 + erf(t / np.sqrt(2.0)))
+    assert np.max(np.abs(oracle.gelu_tanh(t) - exact)) < 1e-3
+    # both are x times a function s with s(x) + s(-x) = 1: the odd part is x / 2 ... i.e. f(x) - f(-x) = x
+    assert np.allclose(oracle.silu(t) - oracle.silu(-t), t, rtol=0, atol=1e-14)
+    assert np.allclose(oracle.gelu_tanh(t) - oracle.gelu_tanh(-t), t, rtol=0, atol=1e-14)
+    # limits: identity for large positive inputs, zero for large negative ones
+    assert abs(oracle.silu(40.0) - 40.0) < 1e-12 and abs(oracle.silu(-40.0)) < 1e-12
+    assert abs(oracle.gelu_tanh(10.0) - 10.0) < 1e-12 and abs(oracle.gelu_tanh(-10.0)) < 1e-12
+
+
+def test_gated_fc_hand_worked_case():
+    c = _golden()["gated_fc"]
+    gate = np.array([[float(v) for v in c["gate"]]], dtype=np.float16)
+    up = np.array([[float(v) for v in c["up"]]], dtype=np.float16)
+    res = np.array([[float(v) for v in c["residual"]]], dtype=np.float16)
+    x_in = oracle.gated_input(gate, up, oracle.SILU)
+    assert x_in.dtype == np.float16
+    assert np.array_equal(x_in.astype(np.float64)[0], [float(v) for v in c["in_f16"]])
+    # the activation goes on the gate branch, not on the other one
+    assert not np.array_equal(oracle.gated_input(up, gate, oracle.SILU), x_in)
+    wq = np.eye(3, dtype=np.int8)
+    y = oracle.add_residual(oracle.fc_weight_only(x_in, wq, np.ones(3, dtype=np.float32)), res)
+    assert np.array_equal(y[0], [float(v) for v in c["y"]])
+
+
+def test_gated_input_special_cases():
+    rng = np.random.default_rng(77)
+    g = rng.standard_normal((3, 64)).astype(np.float16)
+    u = rng.standard_normal((3, 64)).astype(np.float16)
+    zero = np.zeros_like(g)
+    for act in (oracle.SILU, oracle.GELU_TANH):
+        assert not oracle.gated_input(zero, u, act).any()      # act(0) = 0
+        assert not oracle.gated_input(g, zero, act).any()
+        # linear in the other branch up to the one binary16 rounding
+        a = oracle.gated_input(g, u, act).astype(np.float64)
+        b = oracle.gated_input(g, (2 * u.astype(np.float32)).astype(np.float16), act).astype(np.float64)
+        assert np.array_equal(b, 2 * a)
+        # within half a binary16 ulp of the unrounded product
+        f = oracle.silu if act == oracle.SILU else oracle.gelu_tanh
+        exact = f(g.astype(np.float64)) * u.astype(np.float64)
+        assert np.all(np.abs(a - exact) <= np.maximum(np.abs(exact) * 2.0 ** -11, 2.0 ** -25))
+    # a large gate passes the other branch through: act(g) = g exactly in fp64 for g = 40 (silu within 1e-16)
+    big = np.full((1, 4), 16.0, dtype=np.float16)
+    ones = np.array([[1.0, -2.0, 0.5, 3.0]], dtype=np.float16)
+    assert np.array_equal(oracle.gated_input(big, ones, oracle.GELU_TANH).astype(np.float64), 16.0 * ones.astype(np.float64))
