@@ -132,6 +132,40 @@ qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, i
 qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc,
                                  void *stream);
 
+/* Element-wise operators fused with the fully connected operator (operator
+ * fusion, section 3.6 and its figure: element-wise operators of two branches
+ * merged into a fully connected operator; residual connections merged into the
+ * neighbouring operator).  Both parts are optional (null pointer = absent):
+ *   gate      binary16 [M, K]: the FC input is in = fp16(act(gate) * x), computed
+ *             in fp32 and rounded once to binary16 (what an unfused element-wise
+ *             operator would have stored); x is the other branch ("up").
+ *             act: QFC_ACT_SILU  g / (1 + exp(-g))
+ *                  QFC_ACT_GELU_TANH  0.5 g (1 + tanh(sqrt(2/pi) (g + 0.044715 g^3)))
+ *   residual  binary16 [M, N]: added to the fp32 result before the one rounding
+ *             to binary16: y = fp16(fc(in)[m,n] + residual[m,n]).  May alias y.
+ *   gated_output  nonzero: the layer produces both branches, output channels
+ *             [0, N/2) the gate and [N/2, N) the other one (N a multiple of 32), and
+ *             y is binary16 [M, N/2]: y[m,n] = fp16(act(fc[m,n]) * fc[m,n + N/2]) with
+ *             both fp32 results taken before any rounding.  Excludes the other two.
+ * Supported: the decode kernels of QFC_COMPUTE_FP16_DEQUANT / QFC_COMPUTE_INT8_ACT
+ * handles (M <= 8; all parts), the int8 prefill path (gate and residual: the gate is
+ * applied by the activation quantization kernel) and the fp16 prefill path
+ * (residual only: its activations go from memory to LDS without passing through
+ * registers); anything else returns QFC_ERR_UNSUPPORTED. */
+#define QFC_ACT_SILU 0
+#define QFC_ACT_GELU_TANH 1
+typedef struct qfc_fusion {
+    const void *gate;      /* device, binary16 [M, K], or null */
+    int32_t activation;    /* QFC_ACT_*; read when gate or gated_output is given */
+    const void *residual;  /* device, binary16 [M, N], or null */
+    int32_t gated_output;  /* 0 or 1 */
+} qfc_fusion_t;
+
+/* qfc_forward with the fused element-wise parts `f` names (host pointer, read
+ * during the call; null or all parts absent = qfc_forward). */
+qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16,
+                               const qfc_fusion_t *f, void *stream);
+
 /* `count` forward calls issued in order on one stream: handles, xs and ys are
  * host arrays of `count` entries; every call uses the same M.  Stops at the
  * first error and returns it. */

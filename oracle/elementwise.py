@@ -51,3 +51,15 @@ def gated_input(gate_f16, up_f16, activation: int) -> np.ndarray:
 def add_residual(y, residual_f16) -> np.ndarray:
     """y + residual in fp64 (the caller's comparison applies the final binary16 rounding)."""
     return np.asarray(y, dtype=np.float64) + np.asarray(residual_f16, dtype=np.float16).astype(np.float64)
+
+
+def gated_output(y, activation: int) -> np.ndarray:
+    """A layer that produces both branches: act(y[:, :N/2]) * y[:, N/2:] in fp64 on the unrounded
+    outputs (the fused operator keeps them in registers; nothing is rounded in between)."""
+    y = np.asarray(y, dtype=np.float64)
+    half = y.shape[1] // 2
+    assert y.shape[1] == 2 * half
+    f = silu if activation == SILU else gelu_tanh if activation == GELU_TANH else None
+    if f is None:
+        raise ValueError("unknown activation")
+    return f(y[:, :half]) * y[:, half:]

@@ -13,11 +13,13 @@ _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libqfc.so")
 
 QFC_OK = 0
+QFC_ERR_INVALID_ARG, QFC_ERR_UNSUPPORTED, QFC_ERR_BUFFER_TOO_SMALL, QFC_ERR_ALIGNMENT, QFC_ERR_HIP = 1, 2, 3, 4, 5
 QFC_SCALE_F32, QFC_SCALE_F16 = 0, 1
 QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT, QFC_COMPUTE_INT8_ACT_DECODE = 0, 1, 2
+QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
-           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_q8",
+           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_forward_q8",
            "qfc_forward_acc_i32", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
 
 
@@ -25,6 +27,12 @@ class Desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int32), ("K", ctypes.c_int32), ("wbits", ctypes.c_int32),
                 ("group_size", ctypes.c_int32), ("scale_dtype", ctypes.c_int32),
                 ("compute_mode", ctypes.c_int32)]
+
+
+class Fusion(ctypes.Structure):
+    """qfc_fusion_t: element-wise parts fused with the layer (null = absent)."""
+    _fields_ = [("gate", ctypes.c_void_p), ("activation", ctypes.c_int32), ("residual", ctypes.c_void_p),
+                ("gated_output", ctypes.c_int32)]
 
 
 class QfcError(RuntimeError):
@@ -51,6 +59,7 @@ def lib() -> ctypes.CDLL:
         L.qfc_bind_workspace.argtypes = [vp, vp, sz, vp]
         L.qfc_quantize_activations.argtypes = [vp, i32, i32, vp, vp, vp]
         L.qfc_forward.argtypes = [vp, vp, i32, vp, vp]
+        L.qfc_forward_fused.argtypes = [vp, vp, i32, vp, ctypes.POINTER(Fusion), vp]
         L.qfc_forward_q8.argtypes = [vp, vp, vp, i32, vp, vp]
         L.qfc_forward_acc_i32.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_batch.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, vp]
@@ -131,6 +140,14 @@ def qfc_quantize_activations(x: torch.Tensor, xq: torch.Tensor, sx: torch.Tensor
 
 def qfc_forward(h, x: torch.Tensor, y: torch.Tensor):
     _check(lib().qfc_forward(h, _ptr(x), x.shape[0], _ptr(y), _stream()), "qfc_forward")
+
+
+def qfc_forward_fused(h, x: torch.Tensor, y: torch.Tensor, gate: torch.Tensor | None = None,
+                      activation: int = QFC_ACT_SILU, residual: torch.Tensor | None = None,
+                      gated_output: bool = False):
+    f = Fusion(gate.data_ptr() if gate is not None else None, activation,
+               residual.data_ptr() if residual is not None else None, 1 if gated_output else 0)
+    _check(lib().qfc_forward_fused(h, _ptr(x), x.shape[0], _ptr(y), ctypes.byref(f), _stream()), "qfc_forward_fused")
 
 
 def qfc_forward_q8(h, xq: torch.Tensor, sx: torch.Tensor, y: torch.Tensor):

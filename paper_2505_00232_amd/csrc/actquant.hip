@@ -49,10 +49,13 @@ __device__ __forceinline__ us2 fold_abs(us2 acc, uint32_t d) {
 // to K = 14336 are read once); longer rows are read a second time.  Few rows per workgroup spread
 // a small M over the whole chip (a compute unit streams only about 30 GB/s on its own); many rows
 // per workgroup write whole 128-byte lines.
-template <bool kTiled, int ROWS>
-__global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__restrict__ x, int M, int K,
-                                                         uint4 *__restrict__ xq, float *__restrict__ sx,
-                                                         int Kp) {
+// `gate` (or null): the row that is quantized is fp16(act(gate) * x), the input of a layer whose
+// two input branches are merged into it (operator fusion, section 3.6 of the paper).
+template <bool kTiled, int ROWS, bool GLU>
+__global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__restrict__ x,
+                                                               const uint4 *__restrict__ gate, int act, int M,
+                                                               int K, uint4 *__restrict__ xq,
+                                                               float *__restrict__ sx, int Kp) {
     constexpr int T = 16 / ROWS;           // tiles per wavefront instruction
     constexpr int NW = 2 * ROWS;           // wavefronts; NW * T = 32 tiles per step
     constexpr int KEEP = 7;
@@ -73,9 +76,14 @@ __global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__re
     auto load = [&](int i, uint4 &v0, uint4 &v1) {
         const int k0 = (T * (NW * i + wave) + t) * 64 + q * 16;
         const bool in = real && k0 < K;
-        const uint4 *src = row + (in ? k0 / 8 : 0);
-        v0 = src[0];
-        v1 = src[1];
+        const size_t off = in ? k0 / 8 : 0;
+        v0 = row[off];
+        v1 = row[off + 1];
+        if (GLU) {
+            const uint4 *grow = gate + (size_t)(real ? m : 0) * (K / 8);
+            v0 = gated_input8_u4(grow[off], v0, act);
+            v1 = gated_input8_u4(grow[off + 1], v1, act);
+        }
         if (!in) v0 = v1 = make_uint4(0, 0, 0, 0);
     };
     auto fold = [&](const uint4 &v0, const uint4 &v1) {
@@ -152,31 +160,41 @@ __global__ __launch_bounds__(256) void retile_xq_kernel(const uint4 *__restrict_
 
 
 template <int ROWS>
-void launch_rows(const void *x, int M, int K, int8_t *xq, float *sx, int tiled, int Mp, int Kp, hipStream_t st) {
+void launch_rows(const void *x, const void *gate, int act, int M, int K, int8_t *xq, float *sx, int tiled, int Mp,
+                 int Kp, hipStream_t st) {
     const uint4 *xv = static_cast<const uint4 *>(x);
+    const uint4 *gv = static_cast<const uint4 *>(gate);
     uint4 *qv = reinterpret_cast<uint4 *>(xq);
-    if (tiled)
-        act_quant_kernel<true, ROWS><<<Mp / ROWS, 128 * ROWS, 0, st>>>(xv, M, K, qv, sx, Kp);
-    else
-        act_quant_kernel<false, ROWS><<<(M + ROWS - 1) / ROWS, 128 * ROWS, 0, st>>>(xv, M, K, qv, sx, K);
+    const dim3 grid((unsigned)(tiled ? Mp / ROWS : (M + ROWS - 1) / ROWS)), block(128 * ROWS);
+    if (tiled) {
+        if (gate)
+            act_quant_kernel<true, ROWS, true><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
+        else
+            act_quant_kernel<true, ROWS, false><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
+    } else {
+        if (gate)
+            act_quant_kernel<false, ROWS, true><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, K);
+        else
+            act_quant_kernel<false, ROWS, false><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, K);
+    }
 }
 
 }  // namespace
 
 // Mp (tiled output) must be a multiple of 16.  The most rows per workgroup that still give two
 // workgroups per compute unit, else two.
-hipError_t launch_act_quant(const void *x, int M, int K, int8_t *xq, float *sx, int tiled, int Mp,
-                            int Kp, int num_cus, hipStream_t st) {
+hipError_t launch_act_quant(const void *x, const void *gate, int act, int M, int K, int8_t *xq, float *sx,
+                            int tiled, int Mp, int Kp, int num_cus, hipStream_t st) {
     const int rows_total = tiled ? Mp : M;
     int rows = rows_total >= 16 * num_cus ? 8 : rows_total >= 8 * num_cus ? 4 : 2;
     const int forced = tuning().act_quant_rows;
     if (forced == 2 || forced == 4 || forced == 8) rows = forced;
     if (rows == 8)
-        launch_rows<8>(x, M, K, xq, sx, tiled, Mp, Kp, st);
+        launch_rows<8>(x, gate, act, M, K, xq, sx, tiled, Mp, Kp, st);
     else if (rows == 4)
-        launch_rows<4>(x, M, K, xq, sx, tiled, Mp, Kp, st);
+        launch_rows<4>(x, gate, act, M, K, xq, sx, tiled, Mp, Kp, st);
     else
-        launch_rows<2>(x, M, K, xq, sx, tiled, Mp, Kp, st);
+        launch_rows<2>(x, gate, act, M, K, xq, sx, tiled, Mp, Kp, st);
     return hipGetLastError();
 }
 

@@ -149,30 +149,59 @@ qfc_status_t qfc_quantize_activations(const void *x_f16, int32_t M, int32_t K, i
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return QFC_ERR_HIP;
     if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return QFC_ERR_HIP;
-    return hip_status(launch_act_quant(x_f16, M, K, xq, sx, 0, M, K, cus, static_cast<hipStream_t>(stream)));
+    return hip_status(launch_act_quant(x_f16, nullptr, 0, M, K, xq, sx, 0, M, K, cus, static_cast<hipStream_t>(stream)));
 }
 
-qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream) {
+// Shared body of qfc_forward and qfc_forward_fused.
+static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, const Fusion &f,
+                                 hipStream_t st) {
     if (!valid(h) || !x_f16 || !y_f16 || M < 1) return QFC_ERR_INVALID_ARG;
     if (!aligned16(x_f16) || !aligned16(y_f16)) return QFC_ERR_ALIGNMENT;
-    hipStream_t st = static_cast<hipStream_t>(stream);
+    if ((f.gate && !aligned16(f.gate)) || (f.residual && !aligned16(f.residual))) return QFC_ERR_ALIGNMENT;
+    if ((f.gate || f.gated_output) && f.activation != QFC_ACT_SILU && f.activation != QFC_ACT_GELU_TANH)
+        return QFC_ERR_INVALID_ARG;
+    if (f.gated_output && (f.gate || f.residual || h->geo.N % 32 != 0)) return QFC_ERR_INVALID_ARG;
+    const bool fused = f.gate || f.residual || f.gated_output;
     if (M <= kMaxDecodeM) {
-        if (h->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE)
+        if (h->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE) {
+            if (fused) return QFC_ERR_UNSUPPORTED;
             return hip_status(launch_gemv_q8(h->geo, h->packed, x_f16, nullptr, 0, M, y_f16, 0, h->num_cus, st));
-        return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
+        }
+        return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, f, h->num_cus, st));
     }
     if (h->desc.compute_mode == QFC_COMPUTE_FP16_DEQUANT || h->geo.fmt == kW4C) {
         if (h->geo.fmt != kW4G32 && h->geo.fmt != kW4C) return QFC_ERR_UNSUPPORTED;
-        return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, h->num_cus, st));
+        // activations go from memory to LDS without passing registers; a tile holds one branch
+        if (f.gate || f.gated_output) return QFC_ERR_UNSUPPORTED;
+        return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, f.residual, h->num_cus, st));
     }
+    if (f.gated_output) return QFC_ERR_UNSUPPORTED;
     if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     // int8 activations: quantize into the workspace (tiled), multiply, rescale
     const int Mp = prefill_rows(M);
     char *body = static_cast<char *>(h->workspace);
     int8_t *tiled = reinterpret_cast<int8_t *>(body);
     float *sx = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
-    if (launch_act_quant(x_f16, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, h->num_cus, st) != hipSuccess) return QFC_ERR_HIP;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, h->num_cus, st));
+    if (launch_act_quant(x_f16, f.gate, f.activation, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, h->num_cus, st) !=
+        hipSuccess)
+        return QFC_ERR_HIP;
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, f.residual, h->num_cus, st));
+}
+
+qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream) {
+    return forward_impl(h, x_f16, M, y_f16, Fusion(), static_cast<hipStream_t>(stream));
+}
+
+qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16,
+                               const qfc_fusion_t *fusion, void *stream) {
+    Fusion f;
+    if (fusion) {
+        f.gate = fusion->gate;
+        f.activation = fusion->activation;
+        f.residual = fusion->residual;
+        f.gated_output = fusion->gated_output != 0;
+    }
+    return forward_impl(h, x_f16, M, y_f16, f, static_cast<hipStream_t>(stream));
 }
 
 qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M, void *y_f16,
@@ -189,7 +218,7 @@ qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
     if (s != QFC_OK) return s;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, prefill_rows(M), y_f16, 0, h->num_cus, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, prefill_rows(M), y_f16, 0, nullptr, h->num_cus, st));
 }
 
 qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc, void *stream) {
@@ -205,7 +234,7 @@ qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, in
     hipStream_t st = static_cast<hipStream_t>(stream);
     const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
     if (s != QFC_OK) return s;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, h->num_cus, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, nullptr, h->num_cus, st));
 }
 
 qfc_status_t qfc_forward_batch(const qfc_handle_t *handles, const void *const *xs, int32_t M,

@@ -40,6 +40,7 @@ struct GemmF16Args {
     const uint4 *w;   // packed int4 row tiles (W4G32 or W4C)
     const uint4 *x;   // binary16 [M, K] viewed as 16-byte vectors
     _Float16 *y;
+    const _Float16 *res;  // [M, N] residual added before the rounding, or null
     const float *sw;  // W4C: fp32 scale per output channel [Np]
     int M, N, K, KT, rt_stride, n_tiles, m_tiles;
 };
@@ -167,6 +168,8 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
 #pragma unroll
         for (int j = 0; j < 2; ++j) {
             const int mrow0 = mt * BM + wm * 64 + j * 32;
+            const bool has_res = a.res != nullptr;
+            if (has_res) stage_residual_block<8, PITCH>(region, a.res, mrow0, n0, a.M, a.N, lane);
 #pragma unroll
             for (int i = 0; i < 2; ++i) {
 #pragma unroll
@@ -175,8 +178,15 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
                     float4 sc = make_float4(1.0f, 1.0f, 1.0f, 1.0f);
                     if (PC) sc = *reinterpret_cast<const float4 *>(a.sw + n0 + nl);
-                    const h4 hv = {(_Float16)(acc[i][j][4 * qq + 0] * sc.x), (_Float16)(acc[i][j][4 * qq + 1] * sc.y),
-                                   (_Float16)(acc[i][j][4 * qq + 2] * sc.z), (_Float16)(acc[i][j][4 * qq + 3] * sc.w)};
+                    float v[4] = {acc[i][j][4 * qq + 0] * sc.x, acc[i][j][4 * qq + 1] * sc.y,
+                                  acc[i][j][4 * qq + 2] * sc.z, acc[i][j][4 * qq + 3] * sc.w};
+                    if (has_res) {
+                        float rv[4];
+                        staged_residual4(region, (lane & 31) * PITCH + nl * 2, rv);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += rv[e];
+                    }
+                    const h4 hv = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
                     *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + nl * 2) = hv;
                 }
             }
@@ -211,7 +221,11 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
                 _Float16 *y = a.y + (size_t)m * a.N + n;
                 _Float16 h[4];
 #pragma unroll
-                for (int e = 0; e < 4; ++e) h[e] = (_Float16)(PC ? acc[i][j][4 * qq + e] * a.sw[n + e] : acc[i][j][4 * qq + e]);
+                for (int e = 0; e < 4; ++e) {
+                    float v = PC ? acc[i][j][4 * qq + e] * a.sw[n + e] : acc[i][j][4 * qq + e];
+                    if (a.res && n + e < a.N) v += (float)a.res[(size_t)m * a.N + n + e];
+                    h[e] = (_Float16)v;
+                }
                 if (vec_ok) {
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
                     *reinterpret_cast<h4 *>(y) = h4{h[0], h[1], h[2], h[3]};
@@ -597,14 +611,23 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
 #pragma unroll
         for (int jj = 0; jj < 2; ++jj) {
             const int mrow0 = mt * DBM + (keep + jj) * 32;
+            const bool has_res = a.res != nullptr;
+            if (has_res) stage_residual_block<8, DEPI_PITCH>(region, a.res, mrow0, n0, a.M, a.N, lane);
 #pragma unroll
             for (int ip = 0; ip < 2; ++ip) {
 #pragma unroll
                 for (int qq = 0; qq < 4; ++qq) {
                     const int nl = ip * 32 + 8 * qq + 4 * kh;
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                    const h4 hv = {(_Float16)out[ip][jj][4 * qq + 0], (_Float16)out[ip][jj][4 * qq + 1],
-                                   (_Float16)out[ip][jj][4 * qq + 2], (_Float16)out[ip][jj][4 * qq + 3]};
+                    float v[4] = {out[ip][jj][4 * qq + 0], out[ip][jj][4 * qq + 1], out[ip][jj][4 * qq + 2],
+                                  out[ip][jj][4 * qq + 3]};
+                    if (has_res) {
+                        float rv[4];
+                        staged_residual4(region, r * DEPI_PITCH + nl * 2, rv);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += rv[e];
+                    }
+                    const h4 hv = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
                     *reinterpret_cast<h4 *>(region + r * DEPI_PITCH + nl * 2) = hv;
                 }
             }
@@ -634,7 +657,11 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int n = n0 + ip * 32 + 8 * (e >> 2) + 4 * kh + (e & 3);
-                if (n < a.N) a.y[(size_t)m * a.N + n] = (_Float16)out[ip][jj][e];
+                if (n < a.N) {
+                    float v = out[ip][jj][e];
+                    if (a.res) v += (float)a.res[(size_t)m * a.N + n];
+                    a.y[(size_t)m * a.N + n] = (_Float16)v;
+                }
             }
     }
 }
@@ -672,13 +699,14 @@ hipError_t launch_fallback(GemmF16Args a, int M, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                           int num_cus, hipStream_t st) {
+                           const void *residual, int num_cus, hipStream_t st) {
     if (g.fmt != kW4G32 && g.fmt != kW4C) return hipErrorNotSupported;
     (void)num_cus;
     GemmF16Args a;
     a.w = static_cast<const uint4 *>(packed);
     a.x = static_cast<const uint4 *>(x);
     a.y = static_cast<_Float16 *>(y);
+    a.res = static_cast<const _Float16 *>(residual);
     a.sw = reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off);
     a.M = M;
     a.N = g.N;

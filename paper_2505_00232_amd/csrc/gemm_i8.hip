@@ -45,6 +45,7 @@ struct GemmI8Args {
     const uint4 *x;   // tiled activations, tiles [row tile][Kp/64][64]
     const float *sw;  // [Np]
     const float *sx;  // [Mp] (null for raw accumulators)
+    const _Float16 *res;  // [M, N] residual added before the rounding, or null
     void *out;
     int M, N, Kp, n_tiles, m_tiles;
 };
@@ -70,6 +71,8 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
             const int mrow0 = mt * BM + wm * WM + j * 32;
             const int m = mrow0 + (lane & 31);
             const float sxm = m < a.M ? a.sx[m] : 0.0f;
+            const bool has_res = a.res != nullptr;
+            if (has_res) stage_residual_block<WN / 8, PITCH>(region, a.res, mrow0, n0, a.M, a.N, lane);
 #pragma unroll
             for (int i = 0; i < TN; ++i) {
 #pragma unroll
@@ -77,10 +80,15 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
                     const int nl = i * 32 + 8 * q + 4 * (lane >> 5);
                     const float4 sc = *reinterpret_cast<const float4 *>(a.sw + n0 + nl);
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
-                    const h4 hv = {(_Float16)((float)acc[i][j][4 * q + 0] * sxm * sc.x),
-                                   (_Float16)((float)acc[i][j][4 * q + 1] * sxm * sc.y),
-                                   (_Float16)((float)acc[i][j][4 * q + 2] * sxm * sc.z),
-                                   (_Float16)((float)acc[i][j][4 * q + 3] * sxm * sc.w)};
+                    float v[4] = {(float)acc[i][j][4 * q + 0] * sxm * sc.x, (float)acc[i][j][4 * q + 1] * sxm * sc.y,
+                                  (float)acc[i][j][4 * q + 2] * sxm * sc.z, (float)acc[i][j][4 * q + 3] * sxm * sc.w};
+                    if (has_res) {
+                        float rv[4];
+                        staged_residual4(region, (lane & 31) * PITCH + nl * 2, rv);
+#pragma unroll
+                        for (int e = 0; e < 4; ++e) v[e] += rv[e];
+                    }
+                    const h4 hv = {(_Float16)v[0], (_Float16)v[1], (_Float16)v[2], (_Float16)v[3]};
                     *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + nl * 2) = hv;
                 }
             }
@@ -123,7 +131,11 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
                     const float sv[4] = {s.x, s.y, s.z, s.w};
                     _Float16 h[4];
 #pragma unroll
-                    for (int e = 0; e < 4; ++e) h[e] = (_Float16)((float)acc[i][j][4 * q + e] * sxm * sv[e]);
+                    for (int e = 0; e < 4; ++e) {
+                        float v = (float)acc[i][j][4 * q + e] * sxm * sv[e];
+                        if (a.res && n + e < a.N) v += (float)a.res[(size_t)m * a.N + n + e];
+                        h[e] = (_Float16)v;
+                    }
                     if (vec_ok) {
                         typedef _Float16 h4 __attribute__((ext_vector_type(4)));
                         *reinterpret_cast<h4 *>(y) = h4{h[0], h[1], h[2], h[3]};
@@ -311,14 +323,15 @@ hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *xq_tiled,
-                          const float *sx, int M, int Mp, void *out, int out_mode, int num_cus,
-                          hipStream_t st) {
+                          const float *sx, int M, int Mp, void *out, int out_mode, const void *residual,
+                          int num_cus, hipStream_t st) {
     (void)Mp;
     GemmI8Args a;
     a.w = static_cast<const uint4 *>(packed);
     a.x = reinterpret_cast<const uint4 *>(xq_tiled);
     a.sw = reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off);
     a.sx = sx;
+    a.res = out_mode == 0 ? static_cast<const _Float16 *>(residual) : nullptr;
     a.out = out;
     a.M = M;
     a.N = g.N;

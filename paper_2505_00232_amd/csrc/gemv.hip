@@ -92,24 +92,37 @@ __device__ __forceinline__ v8h dequant_i8x8(uint32_t lo, uint32_t hi) {
     return __builtin_bit_cast(v8h, r);
 }
 
+__device__ __forceinline__ u32x4 gated_input8(const u32x4 &gate, const u32x4 &x, int act) {
+    return __builtin_bit_cast(u32x4, gated_input8_u4(__builtin_bit_cast(uint4, gate), __builtin_bit_cast(uint4, x), act));
+}
+
 struct GemvArgs {
     const u32x4 *packed;
     const u32x4 *x;     // binary16 [M, K] as 16-byte vectors (8 values)
+    const u32x4 *gate;  // GLU kernels: binary16 [M, K]; the layer's input is fp16(act(gate) * x)
+    const _Float16 *res;  // binary16 [M, N] added before the final rounding, or null
+    int act;            // QFC_ACT_* of the gate
     _Float16 *y;        // [M, N]
     const float *sw;    // per-channel scales [Np] (W8C, W4C)
     int N, K, RT, KT, KU, rt_stride;
     int row_tiles;           // R: row tiles per workgroup
+    int rt_step;             // distance between a workgroup's row tiles (1; RT / 2 for a gated output)
+    int gated_out;           // 1: rows [0, N/2) are the gate, rows [N/2, N) the other branch; y is [M, N/2]
     int units_q, units_rem;  // KU = units_q * waves + units_rem
 };
 
 // LDS view of one wavefront's staged activations: vector (slot * M + m).
 // int4 unit: 1024 k = 128 octets, slot = octet index (4 * group + q).
 // W8C unit:   512 k =  64 octets, slot = tile * 8 + j * 4 + q for octet 2q + j of the tile.
-template <int M, int FMT>
+// GLU: the gate branch travels with x and the two are merged on the way into LDS (operator
+// fusion, section 3.6 of the paper: element-wise operators of two branches merged into the
+// fully connected operator).
+template <int M, int FMT, bool GLU>
 struct XStage {
     static constexpr int OCT = FMT == kW8C ? 64 : 128;  // octets per unit
     static constexpr int XV = M * OCT / 64;               // 16-byte vectors per lane per unit
     u32x4 v[XV];
+    u32x4 g[GLU ? XV : 1];
 
     // global -> registers (zeros beyond K)
     __device__ __forceinline__ void load(const GemvArgs &a, int unit, int lane) {
@@ -121,23 +134,24 @@ struct XStage {
             const int m = p / OCT, o = p % OCT;
             const u32x4 zero = {0, 0, 0, 0};
             v[i] = o_base + o < K8 ? a.x[(size_t)m * K8 + o_base + o] : zero;
+            if (GLU) g[i] = o_base + o < K8 ? a.gate[(size_t)m * K8 + o_base + o] : zero;
         }
     }
     // registers -> this wavefront's LDS region, A-operand order
-    __device__ __forceinline__ void store(u32x4 *lds, int lane) const {
+    __device__ __forceinline__ void store(u32x4 *lds, int lane, int act) const {
 #pragma unroll
         for (int i = 0; i < XV; ++i) {
             const int p = i * 64 + lane;
             const int m = p / OCT, o = p % OCT;
             int slot = o;
             if (FMT == kW8C) slot = (o & ~7) | ((o & 1) << 2) | ((o >> 1) & 3);
-            lds[slot * M + m] = v[i];
+            lds[slot * M + m] = GLU ? gated_input8(g[i], v[i], act) : v[i];
         }
     }
 };
 
-template <int M, int FMT, bool DB>
-__global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
+template <int M, int FMT, bool DB, bool GLU>
+__global__ __launch_bounds__(GLU && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs a) {
     constexpr int TILES = 8;                    // weight tiles per unit
     constexpr int NV = FMT == kW4G32 ? 12 : 8;  // 16-byte vectors per lane per (unit, row tile)
     constexpr int OCT = FMT == kW8C ? 64 : 128;
@@ -148,8 +162,10 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int nwaves = blockDim.x >> 6;
     const int c = lane & 15, q = lane >> 4;
-    const int rt0 = blockIdx.x * a.row_tiles;
-    const int R = min(a.row_tiles, a.RT - rt0);
+    // Gated output: a workgroup owns the two row tiles (t, t + RT / 2) that hold the gate and the
+    // other branch of the same 16 output channels.
+    const int rt0 = a.gated_out ? blockIdx.x : blockIdx.x * a.row_tiles;
+    const int R = a.gated_out ? 2 : min(a.row_tiles, a.RT - rt0);
     const int u0 = wave * a.units_q + min(wave, a.units_rem);
     const int u1 = u0 + a.units_q + (wave < a.units_rem ? 1 : 0);
     u32x4 *lds_x = lds_all + wave * (OCT * M);
@@ -166,7 +182,7 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     auto load_item = [&](u32x4(&buf)[NV], int u, int r, auto full) {
         const int nt = full ? TILES : min(TILES, a.KT - TILES * u);
         const int pos = FMT == kW4G32 ? 9 * u : TILES * u;
-        const u32x4 *base = a.packed + ((size_t)(rt0 + r) * a.rt_stride + pos) * 64;
+        const u32x4 *base = a.packed + ((size_t)(rt0 + r * a.rt_step) * a.rt_stride + pos) * 64;
         // scales first: loads return in order, and the first tile's results need them
         if (FMT == kW4G32) {
 #pragma unroll
@@ -187,7 +203,7 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     // one or two items.  DB = true: the next item's vectors are requested before
     // the current item is computed, for long-lived wavefronts.  Vector loads
     // return in order, so the (small) activation loads are issued first.
-    XStage<M, FMT> xs;
+    XStage<M, FMT, GLU> xs;
     u32x4 cur[NV];
     u32x4 nxt[DB ? NV : 1];
     const int items = (u1 - u0) * R;
@@ -201,7 +217,7 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
     }
     auto stage = [&]() {
         // the wavefront's earlier LDS reads are done (same wavefront, in order)
-        xs.store(lds_x, lane);
+        xs.store(lds_x, lane, a.act);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -329,6 +345,30 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
             if (rr < R && m < M) red[((wave * 4 + rr) * M + m) * 16 + c] = acc[rr][i];
         }
     __syncthreads();
+    if (a.gated_out) {
+        // y[m, n] = fp16(act(gate) * other), both fp32 sums of this workgroup (operator fusion,
+        // section 3.6 of the paper: the element-wise operators of the two branches are merged
+        // into the fully connected operator that produces them)
+        const GateCoeffs gc = gate_coeffs(a.act);
+        const int half = a.N / 2;
+        for (int e = threadIdx.x; e < M * 16; e += blockDim.x) {
+            const int cc = e & 15, m = e >> 4;
+            float sg = 0.0f, su = 0.0f;
+            for (int w = 0; w < nwaves; ++w) {
+                sg += red[((w * 4 + 0) * M + m) * 16 + cc];
+                su += red[((w * 4 + 1) * M + m) * 16 + cc];
+            }
+            const int n = rt0 * 16 + cc;
+            if (n < half) {
+                if (FMT != kW4G32) {
+                    sg *= a.sw[n];
+                    su *= a.sw[n + half];
+                }
+                a.y[(size_t)m * half + n] = (_Float16)(gate_activation(sg, gc) * su);
+            }
+        }
+        return;
+    }
     for (int e = threadIdx.x; e < R * M * 16; e += blockDim.x) {
         const int cc = e & 15, m = (e >> 4) % M, rr = (e >> 4) / M;
         float s = 0.0f;
@@ -336,49 +376,68 @@ __global__ __launch_bounds__(512) void gemv_kernel(GemvArgs a) {
         const int n = (rt0 + rr) * 16 + cc;
         if (n < a.N) {
             if (FMT != kW4G32) s *= a.sw[n];
+            if (a.res) s += (float)a.res[(size_t)m * a.N + n];
             a.y[(size_t)m * a.N + n] = (_Float16)s;
         }
     }
 }
 
-template <int M>
+template <int M, bool GLU>
 hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t st) {
-    const dim3 grid((unsigned)((g.RT + a.row_tiles - 1) / a.row_tiles));
+    const dim3 grid((unsigned)(a.gated_out ? g.RT / 2 : (g.RT + a.row_tiles - 1) / a.row_tiles));
     const dim3 block((unsigned)(waves * 64));
     const int oct = g.fmt == kW8C ? 64 : 128;
     size_t lds = (size_t)waves * oct * M * 16;
     const size_t red = (size_t)waves * 4 * M * 16 * sizeof(float);
     if (red > lds) lds = red;
     // long-lived wavefronts (>= 3 items each) get the double-buffered variant
-    const int items = ((g.KU + waves - 1) / waves) * a.row_tiles;
+    const int items = ((g.KU + waves - 1) / waves) * (a.gated_out ? 2 : a.row_tiles);
     if constexpr (M <= 2) {
         if (items >= 3) {
             if (g.fmt == kW8C)
-                gemv_kernel<M, kW8C, true><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW8C, true, GLU><<<grid, block, lds, st>>>(a);
             else if (g.fmt == kW4C)
-                gemv_kernel<M, kW4C, true><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW4C, true, GLU><<<grid, block, lds, st>>>(a);
             else
-                gemv_kernel<M, kW4G32, true><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW4G32, true, GLU><<<grid, block, lds, st>>>(a);
             return hipGetLastError();
         }
     }
     if (g.fmt == kW8C)
-        gemv_kernel<M, kW8C, false><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW8C, false, GLU><<<grid, block, lds, st>>>(a);
     else if (g.fmt == kW4C)
-        gemv_kernel<M, kW4C, false><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW4C, false, GLU><<<grid, block, lds, st>>>(a);
     else
-        gemv_kernel<M, kW4G32, false><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW4G32, false, GLU><<<grid, block, lds, st>>>(a);
     return hipGetLastError();
+}
+
+template <bool GLU>
+hipError_t launch_any_m(const Geometry &g, const GemvArgs &a, int M, int waves, hipStream_t st) {
+    switch (M) {
+        case 1: return launch_m<1, GLU>(g, a, waves, st);
+        case 2: return launch_m<2, GLU>(g, a, waves, st);
+        case 3: return launch_m<3, GLU>(g, a, waves, st);
+        case 4: return launch_m<4, GLU>(g, a, waves, st);
+        case 5: return launch_m<5, GLU>(g, a, waves, st);
+        case 6: return launch_m<6, GLU>(g, a, waves, st);
+        case 7: return launch_m<7, GLU>(g, a, waves, st);
+        case 8: return launch_m<8, GLU>(g, a, waves, st);
+        default: return hipErrorInvalidValue;
+    }
 }
 
 }  // namespace
 
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                       int num_cus, hipStream_t st) {
+                       const Fusion &f, int num_cus, hipStream_t st) {
     const GemvPlan p = plan_gemv(g, M, num_cus);
     GemvArgs a;
     a.packed = static_cast<const u32x4 *>(packed);
     a.x = static_cast<const u32x4 *>(x);
+    a.gate = static_cast<const u32x4 *>(f.gate);
+    a.res = static_cast<const _Float16 *>(f.residual);
+    a.act = f.activation;
     a.y = static_cast<_Float16 *>(y);
     a.sw = reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off);
     a.N = g.N;
@@ -388,19 +447,11 @@ hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int
     a.KU = g.KU;
     a.rt_stride = g.rt_stride;
     a.row_tiles = p.row_tiles;
+    a.rt_step = f.gated_output ? g.RT / 2 : 1;
+    a.gated_out = f.gated_output ? 1 : 0;
     a.units_q = g.KU / p.waves;
     a.units_rem = g.KU % p.waves;
-    switch (M) {
-        case 1: return launch_m<1>(g, a, p.waves, st);
-        case 2: return launch_m<2>(g, a, p.waves, st);
-        case 3: return launch_m<3>(g, a, p.waves, st);
-        case 4: return launch_m<4>(g, a, p.waves, st);
-        case 5: return launch_m<5>(g, a, p.waves, st);
-        case 6: return launch_m<6>(g, a, p.waves, st);
-        case 7: return launch_m<7>(g, a, p.waves, st);
-        case 8: return launch_m<8>(g, a, p.waves, st);
-        default: return hipErrorInvalidValue;
-    }
+    return f.gate ? launch_any_m<true>(g, a, M, p.waves, st) : launch_any_m<false>(g, a, M, p.waves, st);
 }
 
 }  // namespace qfc

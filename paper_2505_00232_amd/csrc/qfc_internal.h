@@ -123,21 +123,91 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
                        hipStream_t st);
 hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void *scales,
                          hipStream_t st);
+// Gate activations of the fused input act(gate) * x.  Both are g * sigmoid(t): t = g for SiLU,
+// t = 2 sqrt(2/pi) (g + 0.044715 g^3) for the tanh form of GELU (0.5 (1 + tanh z) = sigmoid(2 z)).
+// Written as t = g (c1 + c3 g^2) with the pair (c1, c3) chosen once per kernel, and with the
+// hardware reciprocal (1 ulp) in place of an IEEE division: the result is rounded to binary16.
+struct GateCoeffs {
+    float c1, c3;
+};
+__device__ __forceinline__ GateCoeffs gate_coeffs(int act) {
+    GateCoeffs c;
+    c.c1 = act == QFC_ACT_GELU_TANH ? 1.5957691216f : 1.0f;
+    c.c3 = act == QFC_ACT_GELU_TANH ? 1.5957691216f * 0.044715f : 0.0f;
+    return c;
+}
+__device__ __forceinline__ float gate_activation(float g, const GateCoeffs &c) {
+    const float t = g * fmaf(c.c3, g * g, c.c1);
+    return g * __builtin_amdgcn_rcpf(1.0f + __expf(-t));
+}
+
+// Eight binary16 pairs (gate, x) -> eight binary16 values fp16(act(gate) * x): fp32 arithmetic,
+// one rounding to binary16.
+__device__ __forceinline__ uint4 gated_input8_u4(const uint4 &gate, const uint4 &x, int act) {
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const half8 g = __builtin_bit_cast(half8, gate), u = __builtin_bit_cast(half8, x);
+    const GateCoeffs c = gate_coeffs(act);
+    half8 r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (_Float16)(gate_activation((float)g[e], c) * (float)u[e]);
+    return __builtin_bit_cast(uint4, r);
+}
+
+// Residual connection merged into the store phase of the prefill kernels (operator fusion,
+// section 3.6 of the paper).  Those kernels stage a block of 32 token rows x 8 CH channels of
+// binary16 outputs per wavefront in LDS and store it with 16 bytes per lane along n.  The
+// residual's block is copied into the same LDS positions with the same access pattern first;
+// each lane then adds the four values under its own outputs in fp32, before the one rounding.
+template <int CH, int PITCH>
+__device__ __forceinline__ void stage_residual_block(char *region, const _Float16 *res, int mrow0, int n0, int M,
+                                                     int N, int lane) {
+#pragma unroll
+    for (int it = 0; it < 32 * CH / 64; ++it) {
+        const int idx = it * 64 + lane;
+        const int row = idx / CH, ch = idx % CH;
+        const int mm = mrow0 + row, nn = n0 + ch * 8;
+        uint4 v = make_uint4(0, 0, 0, 0);
+        if (mm < M && nn < N) v = *reinterpret_cast<const uint4 *>(res + (size_t)mm * N + nn);
+        *reinterpret_cast<uint4 *>(region + row * PITCH + ch * 16) = v;
+    }
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+    __builtin_amdgcn_wave_barrier();
+    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+}
+
+// the four residual values staged at byte offset `off` of the region, as fp32
+__device__ __forceinline__ void staged_residual4(const char *region, int off, float (&r)[4]) {
+    typedef _Float16 half4 __attribute__((ext_vector_type(4)));
+    const half4 v = *reinterpret_cast<const half4 *>(region + off);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) r[e] = (float)v[e];
+}
+
+// Element-wise parts fused with the layer (null pointer = absent), see qfc_fusion_t.
+struct Fusion {
+    const void *gate = nullptr;      // binary16 [M, K]
+    int activation = 0;              // QFC_ACT_*
+    const void *residual = nullptr;  // binary16 [M, N]
+    bool gated_output = false;       // y [M, N/2] = fp16(act(rows [0, N/2)) * rows [N/2, N))
+};
+
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                       int num_cus, hipStream_t st);
+                       const Fusion &f, int num_cus, hipStream_t st);
 // Decode with 8-bit activations (per-channel weight formats).  src 0: x is binary16 and is
 // quantized in the kernel; 1: x is int8 with scales sx.  out_mode 0: binary16 y; 1: int32 sums.
 hipError_t launch_gemv_q8(const Geometry &g, const void *packed, const void *x, const float *sx, int src,
                           int M, void *out, int out_mode, int num_cus, hipStream_t st);
-hipError_t launch_act_quant(const void *x, int M, int K, int8_t *xq, float *sx, int tiled,
-                            int Mp, int Kp, int num_cus, hipStream_t st);
+// `gate` (binary16 [M, K] or null): the rows quantized are fp16(act(gate) * x).
+hipError_t launch_act_quant(const void *x, const void *gate, int act, int M, int K, int8_t *xq, float *sx,
+                            int tiled, int Mp, int Kp, int num_cus, hipStream_t st);
 hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp,
                             hipStream_t st);
 // out_mode 0: binary16 y with scales; 1: raw int32 accumulators.
+// `residual` (binary16 [M, N] or null) is added before the final rounding (out_mode 0 only).
 hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *xq_tiled,
-                          const float *sx, int M, int Mp, void *out, int out_mode, int num_cus,
-                          hipStream_t st);
+                          const float *sx, int M, int Mp, void *out, int out_mode, const void *residual,
+                          int num_cus, hipStream_t st);
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                           int num_cus, hipStream_t st);
+                           const void *residual, int num_cus, hipStream_t st);
 
 }  // namespace qfc

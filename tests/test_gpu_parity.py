@@ -455,3 +455,163 @@ def test_error_paths_on_device():
     layer.close()
     layer2.close()
     del x
+
+
+# ------------------------------------------------------------------ element-wise operators fused with the layer
+def _fused(layer, x, gate=None, act=binding.QFC_ACT_SILU, residual=None, alias=False):
+    xd = torch.from_numpy(x).to(DEV)
+    gd = torch.from_numpy(gate).to(DEV) if gate is not None else None
+    rd = torch.from_numpy(residual).to(DEV) if residual is not None else None
+    y = rd if alias else torch.empty((x.shape[0], layer.N), dtype=torch.float16, device=DEV)
+    binding.qfc_forward_fused(layer.handle, xd, y, gate=gd, activation=act, residual=rd)
+    torch.cuda.synchronize()
+    return y.cpu().numpy()
+
+
+def _fused_ref(x, wq, s, fmt, gate, act, residual, int8_act=False):
+    x_in = oracle.gated_input(gate, x, act) if gate is not None else x
+    ref = oracle.fc_int8_act(x_in, wq, s)[3] if int8_act else oracle.fc_weight_only(x_in, wq, s, _group(fmt))
+    return oracle.add_residual(ref, residual) if residual is not None else ref
+
+
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
+@pytest.mark.parametrize("N,K", [(17, 96), (130, 256), (1000, 2304), (96, 14336)])
+def test_decode_fused_gate_and_residual(fmt, N, K):
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(3100, N, K, fc)
+    layer = _layer(wq, s, fmt)
+    for M in (1, 2, 3, 5, 8):
+        print(f"decode fused {fmt} N={N} K={K} M={M}", flush=True)
+        up = synth.activations(3100, N, K + M, M, K)
+        gate = synth.activations(3101, N, K + M, M, K)
+        res = synth.activations(3102, N, K + M, M, N)
+        if M == 3:
+            gate[1] = 0  # act(0) = 0: the row's input is zero, the output is the residual
+        act = binding.QFC_ACT_SILU if M % 2 else binding.QFC_ACT_GELU_TANH
+        oact = oracle.SILU if M % 2 else oracle.GELU_TANH
+        y = _fused(layer, up, gate, act, res)
+        assert oracle.floored_rel_error(y, _fused_ref(up, wq, s, fmt, gate, oact, res)) <= TOL, M
+        if M == 3:
+            assert np.array_equal(y[1], res[1])
+        # each part alone, and the output written over the residual
+        y = _fused(layer, up, gate, act, None)
+        assert oracle.floored_rel_error(y, _fused_ref(up, wq, s, fmt, gate, oact, None)) <= TOL, M
+        y = _fused(layer, up, None, act, res, alias=True)
+        assert oracle.floored_rel_error(y, _fused_ref(up, wq, s, fmt, None, oact, res)) <= TOL, M
+        # no parts: the plain call, bit for bit
+        assert np.array_equal(_fused(layer, up), _forward(layer, up))
+    layer.close()
+
+
+def test_decode_fused_gate_is_the_unfused_pipeline_bit_for_bit():
+    """fp16(act(gate) * up) computed on the host in fp32 and fed to the plain call gives the same
+    bits as the fused call whenever the two fp32 evaluations round to the same binary16 value;
+    with the oracle's binary16 input instead, the outputs agree within the tolerance."""
+    fc = synth.FC("t", 2048, 512, "w4g32")
+    wq, s = synth.weights(3200, 0, 0, fc)
+    layer = _layer(wq, s, "w4g32")
+    up = synth.activations(3200, 0, 1, 4, fc.K)
+    gate = synth.activations(3200, 0, 2, 4, fc.K)
+    x_in = oracle.gated_input(gate, up, oracle.SILU)
+    y_fused = _fused(layer, up, gate, binding.QFC_ACT_SILU)
+    y_plain = _forward(layer, x_in)
+    assert oracle.floored_rel_error(y_fused, y_plain.astype(np.float64)) <= 1e-3
+    layer.close()
+
+
+@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (300, 1000, 2304)])
+def test_int8_prefill_fused_gate_and_residual(M, N, K):
+    print(f"int8 prefill fused M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, "w8c")
+    wq, sw = synth.weights(3300, M, N, fc)
+    up = synth.activations(3300, M, N, M, K)
+    gate = synth.activations(3301, M, N, M, K)
+    res = synth.activations(3302, M, N, M, N)
+    gate[M // 2] = 0
+    layer = _layer(wq, sw, "w8c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    for act, oact in ((binding.QFC_ACT_SILU, oracle.SILU), (binding.QFC_ACT_GELU_TANH, oracle.GELU_TANH)):
+        y = _fused(layer, up, gate, act, res)
+        ref = _fused_ref(up, wq, sw, "w8c", gate, oact, res, int8_act=True)
+        # the gate activation is evaluated in fp32 on the GPU: where that flips the binary16 rounding
+        # of an input element, its int8 code can move by one, i.e. by sx * |w| in the output
+        assert oracle.floored_rel_error(y, ref) <= 2 * TOL
+        assert np.array_equal(y[M // 2], res[M // 2])
+    y = _fused(layer, up, None, 0, res)
+    assert oracle.floored_rel_error(y, _fused_ref(up, wq, sw, "w8c", None, 0, res, int8_act=True)) <= TOL
+    assert np.array_equal(_fused(layer, up), _forward(layer, up))
+    layer.close()
+
+
+@pytest.mark.parametrize("fmt", ["w4g32", "w4c"])
+@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (130, 1000, 2304), (300, 264, 128), (129, 520, 1152)])
+def test_fp16_prefill_fused_residual(fmt, M, N, K):
+    print(f"fp16 prefill residual {fmt} M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(3400, M, N, fc)
+    x = synth.activations(3400, M, N, M, K)
+    res = synth.activations(3401, M, N, M, N)
+    layer = _layer(wq, s, fmt, max_m=M)
+    y = _fused(layer, x, None, 0, res)
+    assert oracle.floored_rel_error(y, _fused_ref(x, wq, s, fmt, None, 0, res)) <= TOL
+    assert np.array_equal(_fused(layer, x), _forward(layer, x))
+    with pytest.raises(binding.QfcError) as e:  # no place for the gate on this path
+        _fused(layer, x, x, binding.QFC_ACT_SILU, None)
+    assert e.value.code == binding.QFC_ERR_UNSUPPORTED
+    layer.close()
+
+
+def test_fused_mlp_llama_shapes_sampled():
+    """down(silu(gate) * up) + residual at the full Llama-3.1-8B shape (K = 14336 -> N = 4096)."""
+    fc = synth.LLAMA_FCS_W4[3]
+    wq, s = synth.weights(1003, 0, 3, fc)
+    layer = _layer(wq, s, fc.fmt)
+    rng = np.random.default_rng(31)
+    for M in (1, 4):
+        up = synth.activations(1003, 0, 30, M, fc.K)
+        gate = synth.activations(1003, 0, 31, M, fc.K)
+        res = synth.activations(1003, 0, 32, M, fc.N)
+        y = _fused(layer, up, gate, binding.QFC_ACT_SILU, res)
+        cols = np.sort(rng.choice(fc.N, size=256, replace=False))
+        cols[0], cols[-1] = 0, fc.N - 1
+        ref = _fused_ref(up, wq[cols], s[cols], fc.fmt, gate, oracle.SILU, res[:, cols])
+        assert oracle.floored_rel_error(y[:, cols], ref) <= TOL
+    layer.close()
+
+
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
+@pytest.mark.parametrize("N,K", [(32, 96), (160, 256), (2048, 2304), (64, 14336)])
+def test_decode_gated_output(fmt, N, K):
+    """The layer produces [gate; other]; y [M, N/2] = fp16(act(gate) * other) from the unrounded sums."""
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(3500, N, K, fc)
+    layer = _layer(wq, s, fmt)
+    for M in (1, 2, 3, 4, 7, 8):
+        print(f"decode gated output {fmt} N={N} K={K} M={M}", flush=True)
+        # small activations: the product of two outputs must stay inside the binary16 range
+        x = (synth.activations(3500, N, K + M, M, K) * np.float16(0.0625)).astype(np.float16)
+        act, oact = (binding.QFC_ACT_SILU, oracle.SILU) if M % 2 else (binding.QFC_ACT_GELU_TANH, oracle.GELU_TANH)
+        xd = torch.from_numpy(x).to(DEV)
+        y = torch.full((M, N // 2), 77.0, dtype=torch.float16, device=DEV)
+        binding.qfc_forward_fused(layer.handle, xd, y, activation=act, gated_output=True)
+        torch.cuda.synchronize()
+        ref = oracle.gated_output(oracle.fc_weight_only(x, wq, s, _group(fmt)), oact)
+        assert oracle.floored_rel_error(y.cpu().numpy(), ref) <= TOL, M
+    # combinations the interface excludes
+    xd = torch.from_numpy(synth.activations(3500, N, K, 1, K)).to(DEV)
+    y = torch.empty((1, N // 2), dtype=torch.float16, device=DEV)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_forward_fused(layer.handle, xd, y, residual=y, gated_output=True)
+    assert e.value.code == binding.QFC_ERR_INVALID_ARG
+    layer.close()
+
+
+def test_gated_output_needs_even_halves_of_whole_tiles():
+    fc = synth.FC("t", 64, 48, "w8c")  # N / 2 = 24 is not a whole number of 16-row tiles
+    wq, s = synth.weights(3501, 0, 0, fc)
+    layer = _layer(wq, s, "w8c")
+    xd = torch.from_numpy(synth.activations(3501, 0, 0, 1, 64)).to(DEV)
+    y = torch.empty((1, 24), dtype=torch.float16, device=DEV)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_forward_fused(layer.handle, xd, y, gated_output=True)
+    assert e.value.code == binding.QFC_ERR_INVALID_ARG
+    layer.close()

@@ -330,3 +330,18 @@ def test_gated_input_special_cases():
     big = np.full((1, 4), 16.0, dtype=np.float16)
     ones = np.array([[1.0, -2.0, 0.5, 3.0]], dtype=np.float16)
     assert np.array_equal(oracle.gated_input(big, ones, oracle.GELU_TANH).astype(np.float64), 16.0 * ones.astype(np.float64))
+
+
+def test_gated_output_hand_worked_case():
+    # the same numbers as the gated_fc case, now as the two halves of one layer's output:
+    # identity 6x6 weights, x = (gate | other)
+    c = _golden()["gated_fc"]
+    x = np.array([[float(v) for v in c["gate"]] + [float(v) for v in c["up"]]], dtype=np.float16)
+    y = oracle.fc_weight_only(x, np.eye(6, dtype=np.int8), np.ones(6, dtype=np.float32))
+    out = oracle.gated_output(y, oracle.SILU)
+    assert out.shape == (1, 3)
+    # unrounded values of the products; in_f16 of the golden case is their binary16 rounding
+    assert np.allclose(out[0], [1.462117157, 0.0, -1.761594156], rtol=0, atol=5e-10)
+    assert np.array_equal(out.astype(np.float16).astype(np.float64)[0], [float(v) for v in c["in_f16"]])
+    # halves are not interchangeable
+    assert not np.allclose(oracle.gated_output(y[:, ::-1].copy(), oracle.SILU), out)
