@@ -63,3 +63,19 @@ def gated_output(y, activation: int) -> np.ndarray:
     if f is None:
         raise ValueError("unknown activation")
     return f(y[:, :half]) * y[:, half:]
+
+
+def rmsnorm(x_f16, gamma_f16, eps: float, gamma_offset: float = 0.0, residual_f16=None):
+    """Root-mean-square normalization with the residual connection merged in (section 3.6, figure).
+
+    h = x + residual, rounded once to binary16 (the residual stream as it is stored with FP16
+    activations; h = x when there is no residual); per token row
+    y[k] = h[k] / sqrt(mean_k(h^2) + eps) * (gamma_offset + gamma[k]) in fp64 on the stored h.
+    gamma_offset is 0 for Llama and 1 for Gemma.  Returns (h float16 [M, K], y float64 [M, K]).
+    """
+    x = np.asarray(x_f16, dtype=np.float16)
+    h = x if residual_f16 is None else (x.astype(np.float64) + np.asarray(residual_f16, dtype=np.float16).astype(np.float64)).astype(np.float16)
+    hd = h.astype(np.float64)
+    ms = np.mean(hd * hd, axis=1, keepdims=True)
+    w = gamma_offset + np.asarray(gamma_f16, dtype=np.float16).astype(np.float64)
+    return h, hd / np.sqrt(ms + eps) * w[None, :]

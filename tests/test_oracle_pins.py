@@ -345,3 +345,35 @@ def test_gated_output_hand_worked_case():
     assert np.array_equal(out.astype(np.float16).astype(np.float64)[0], [float(v) for v in c["in_f16"]])
     # halves are not interchangeable
     assert not np.allclose(oracle.gated_output(y[:, ::-1].copy(), oracle.SILU), out)
+
+
+def test_rmsnorm_hand_values_library_routine_and_invariants():
+    c = _golden()["rmsnorm"]
+    x = np.array([[float(v) for v in c["x"]]], dtype=np.float16)
+    ones = np.ones(2, dtype=np.float16)
+    h, y = oracle.rmsnorm(x, ones, 0.0)
+    assert np.array_equal(h, x)
+    assert np.allclose(y[0], [float(v) for v in c["y_unit"]], rtol=0, atol=5e-10)
+    g = np.array([float(v) for v in c["gamma"]], dtype=np.float16)
+    _, y = oracle.rmsnorm(x, g, 0.0, gamma_offset=1.0)
+    assert np.allclose(y[0], [float(v) for v in c["y_offset1"]], rtol=0, atol=5e-10)
+    h, y2 = oracle.rmsnorm(np.array([[1, 1]], dtype=np.float16), g, 0.0, 1.0, residual_f16=np.array([[2, 3]], dtype=np.float16))
+    assert np.array_equal(h, x) and np.array_equal(y2, y)
+    # library routine on random rows (fp64), with eps and a weight
+    import torch
+    rng = np.random.default_rng(5)
+    xr = rng.standard_normal((5, 96)).astype(np.float16)
+    gr = rng.standard_normal(96).astype(np.float16)
+    _, yr = oracle.rmsnorm(xr, gr, 1e-5)
+    ref = torch.nn.functional.rms_norm(torch.from_numpy(xr.astype(np.float64)), (96,), torch.from_numpy(gr.astype(np.float64)), 1e-5)
+    assert np.allclose(yr, ref.numpy(), rtol=1e-13, atol=0)
+    # unit weight, eps = 0: the output has unit mean square; scaling the input by 4 changes nothing
+    _, yu = oracle.rmsnorm(xr, np.ones(96, dtype=np.float16), 0.0)
+    assert np.allclose(np.mean(yu * yu, axis=1), 1.0, rtol=1e-13)
+    _, y4 = oracle.rmsnorm((4 * xr.astype(np.float32)).astype(np.float16), np.ones(96, dtype=np.float16), 0.0)
+    assert np.allclose(y4, yu, rtol=1e-13)
+    # the residual stream is rounded once to binary16 before it is normalized
+    a = np.array([[1.0, 2.0 ** -11]], dtype=np.float16)
+    b = np.array([[2.0 ** -11, 1.0]], dtype=np.float16)
+    h, _ = oracle.rmsnorm(a, ones, 0.0, residual_f16=b)
+    assert np.array_equal(h.astype(np.float64), [[1.0, 1.0]])  # 1 + 2^-11 ties to even = 1
