@@ -322,6 +322,30 @@ def main():
     extra["decode_m1_mlp_block_fused"] = mlp_block()
     torch.cuda.empty_cache()
 
+    # RMS normalization with the residual connection and the next layer's activation quantization merged
+    # in (the producer of the int8 prefill layers' input): M = 1024 token rows of a Llama-3.1-8B layer,
+    # rotating buffers (8 x 25 MB in flight per call sequence)
+    def rmsnorm_line(M=1024, K=4096, copies=12):
+        xs = [torch.from_numpy(synth.activations(SEED + 300, cpy, 0, M, K)).to(dev) for cpy in range(copies)]
+        rs = [torch.from_numpy(synth.activations(SEED + 300, cpy, 1, M, K)).to(dev) for cpy in range(copies)]
+        gamma = torch.from_numpy(synth.activations(SEED + 300, 0, 2, 1, K)[0]).to(dev)
+        xq = torch.empty((M, K), dtype=torch.int8, device=dev)
+        sx = torch.empty((M,), dtype=torch.float32, device=dev)
+
+        def run():
+            for x, r in zip(xs, rs):
+                binding.qfc_rmsnorm(x, gamma, 1e-5, 0.0, residual=r, h_out=r, xq=xq, sx=sx)
+
+        run()
+        ms = event_ms(run, max(3, args.steps // 2)) / copies
+        nbytes = M * K * 7 + 2 * K + 4 * M  # x, residual in; residual stream and int8 codes out
+        return {"us": round(ms * 1e3, 2), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "note": "h = x + residual, y = rmsnorm(h) * gamma, (xq, sx) = per-token int8 of y; one kernel, 7 B per element"}
+
+    extra["rmsnorm_residual_quantize_m1024_k4096"] = rmsnorm_line()
+    torch.cuda.empty_cache()
+
     # ------------------------------------------------------------ prefill (configs 4 and 5)
     if not args.skip_prefill:
         def prefill(fc_list, M, seed, reps=10):

@@ -166,6 +166,30 @@ typedef struct qfc_fusion {
 qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16,
                                const qfc_fusion_t *f, void *stream);
 
+/* RMS normalization with the residual connection and the quantization of the
+ * next layer's input merged into one kernel (operator fusion, section 3.6 and
+ * the right half of its figure).  Per token row, in fp32:
+ *   h    = fp16(x + residual)          (h = x when residual is null)
+ *   y[k] = fp16(h[k] * rs * (gamma_offset + gamma[k])),  rs = 1 / sqrt(mean_k h[k]^2 + eps)
+ *   (xq, sx) = qfc_quantize_activations applied to y.
+ * x, residual, h_out, y: binary16 [M, K]; gamma: binary16 [K]; xq int8 [M, K]; sx fp32 [M].
+ * Each of h_out, y, (xq and sx together) is written when given; at least one must be.
+ * h_out may be x or residual itself; y may be x when h_out is not x.  gamma_offset is 0
+ * for a plain weight and 1 for models that store weight - 1.  K: a multiple of 32, at
+ * most 14336 (a row is held in registers), else QFC_ERR_UNSUPPORTED. */
+typedef struct qfc_rmsnorm {
+    const void *x;        /* device */
+    const void *residual; /* device or null */
+    const void *gamma;    /* device */
+    float eps;
+    float gamma_offset;
+    void *h_out;          /* device or null */
+    void *y;              /* device or null */
+    int8_t *xq;           /* device or null */
+    float *sx;            /* device or null (with xq) */
+} qfc_rmsnorm_t;
+qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *args, int32_t M, int32_t K, void *stream);
+
 /* `count` forward calls issued in order on one stream: handles, xs and ys are
  * host arrays of `count` entries; every call uses the same M.  Stops at the
  * first error and returns it. */

@@ -19,7 +19,7 @@ QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT, QFC_COMPUTE_INT8_ACT_DECODE = 0,
 QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
-           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_forward_q8",
+           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_rmsnorm", "qfc_forward_q8",
            "qfc_forward_acc_i32", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
 
 
@@ -33,6 +33,13 @@ class Fusion(ctypes.Structure):
     """qfc_fusion_t: element-wise parts fused with the layer (null = absent)."""
     _fields_ = [("gate", ctypes.c_void_p), ("activation", ctypes.c_int32), ("residual", ctypes.c_void_p),
                 ("gated_output", ctypes.c_int32)]
+
+
+class RmsNorm(ctypes.Structure):
+    """qfc_rmsnorm_t."""
+    _fields_ = [("x", ctypes.c_void_p), ("residual", ctypes.c_void_p), ("gamma", ctypes.c_void_p),
+                ("eps", ctypes.c_float), ("gamma_offset", ctypes.c_float), ("h_out", ctypes.c_void_p),
+                ("y", ctypes.c_void_p), ("xq", ctypes.c_void_p), ("sx", ctypes.c_void_p)]
 
 
 class QfcError(RuntimeError):
@@ -60,6 +67,7 @@ def lib() -> ctypes.CDLL:
         L.qfc_quantize_activations.argtypes = [vp, i32, i32, vp, vp, vp]
         L.qfc_forward.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_fused.argtypes = [vp, vp, i32, vp, ctypes.POINTER(Fusion), vp]
+        L.qfc_rmsnorm.argtypes = [ctypes.POINTER(RmsNorm), i32, i32, vp]
         L.qfc_forward_q8.argtypes = [vp, vp, vp, i32, vp, vp]
         L.qfc_forward_acc_i32.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_batch.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, vp]
@@ -148,6 +156,15 @@ def qfc_forward_fused(h, x: torch.Tensor, y: torch.Tensor, gate: torch.Tensor | 
     f = Fusion(gate.data_ptr() if gate is not None else None, activation,
                residual.data_ptr() if residual is not None else None, 1 if gated_output else 0)
     _check(lib().qfc_forward_fused(h, _ptr(x), x.shape[0], _ptr(y), ctypes.byref(f), _stream()), "qfc_forward_fused")
+
+
+def qfc_rmsnorm(x: torch.Tensor, gamma: torch.Tensor, eps: float, gamma_offset: float = 0.0, residual=None,
+                h_out=None, y=None, xq=None, sx=None):
+    def p(t):
+        return t.data_ptr() if t is not None else None
+    M, K = x.shape
+    a = RmsNorm(p(x), p(residual), p(gamma), eps, gamma_offset, p(h_out), p(y), p(xq), p(sx))
+    _check(lib().qfc_rmsnorm(ctypes.byref(a), M, K, _stream()), "qfc_rmsnorm")
 
 
 def qfc_forward_q8(h, xq: torch.Tensor, sx: torch.Tensor, y: torch.Tensor):

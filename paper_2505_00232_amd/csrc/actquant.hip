@@ -16,31 +16,6 @@ namespace {
 
 typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 
-typedef unsigned short us2 __attribute__((ext_vector_type(2)));
-
-// Four binary16 values -> four int8 codes in one dword.  The product is rounded to fp32 first and
-// then to the nearest integer (ties to even) by adding 1.5 * 2^23, which leaves the two's complement
-// code in the low mantissa byte: the same two roundings as rintf(x * inv).  |x * inv| cannot exceed
-// 127 by more than two units in the last place, so the clamp to +-127 of the definition never acts.
-__device__ __forceinline__ uint32_t quant4(const _Float16 *h, float inv) {
-    uint32_t b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma clang fp contract(off)  // a fused multiply-add would round once, not twice
-        const float v = (float)h[i] * inv;
-        b[i] = __float_as_uint(v + 12582912.0f);
-    }
-    const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
-    const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
-    return lo | (hi << 16);
-}
-
-// Running maximum of |x| over pairs of binary16 values, on the bit patterns with the sign cleared:
-// for finite values the order of the magnitudes is the order of these 15-bit integers.
-__device__ __forceinline__ us2 fold_abs(us2 acc, uint32_t d) {
-    return __builtin_elementwise_max(acc, __builtin_bit_cast(us2, d & 0x7FFF7FFFu));
-}
-
 // A workgroup of NW = 2 ROWS wavefronts takes ROWS token rows (8, 4 or 2).  With T = 16 / ROWS, lane
 // (c, q, t) of wavefront w handles, in step i, the 16 values k = 64 kt + 16 q .. + 15 of row c,
 // kt = T (NW i + w) + t: a wavefront instruction reads 256 T contiguous bytes of each of its rows

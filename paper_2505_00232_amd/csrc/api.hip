@@ -204,6 +204,32 @@ qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, voi
     return forward_impl(h, x_f16, M, y_f16, f, static_cast<hipStream_t>(stream));
 }
 
+qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *r, int32_t M, int32_t K, void *stream) {
+    if (!r || !r->x || !r->gamma || M < 1 || K < 32 || K % 32 != 0) return QFC_ERR_INVALID_ARG;
+    if (!r->h_out && !r->y && !r->xq) return QFC_ERR_INVALID_ARG;
+    if ((r->xq == nullptr) != (r->sx == nullptr)) return QFC_ERR_INVALID_ARG;
+    if (!(r->eps >= 0.0f)) return QFC_ERR_INVALID_ARG;
+    if (K > 14336) return QFC_ERR_UNSUPPORTED;
+    if (!aligned16(r->x) || !aligned16(r->gamma) || (r->residual && !aligned16(r->residual)) ||
+        (r->h_out && !aligned16(r->h_out)) || (r->y && !aligned16(r->y)) || (r->xq && !aligned16(r->xq)) ||
+        (reinterpret_cast<uintptr_t>(r->sx) & 3u))
+        return QFC_ERR_ALIGNMENT;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return QFC_ERR_HIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return QFC_ERR_HIP;
+    RmsNormArgs a;
+    a.x = r->x;
+    a.residual = r->residual;
+    a.gamma = r->gamma;
+    a.h_out = r->h_out;
+    a.y = r->y;
+    a.xq = r->xq;
+    a.sx = r->sx;
+    a.eps = r->eps;
+    a.gamma_offset = r->gamma_offset;
+    return hip_status(launch_rmsnorm(a, M, K, cus, static_cast<hipStream_t>(stream)));
+}
+
 qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M, void *y_f16,
                             void *stream) {
     if (!sx || !y_f16) return QFC_ERR_INVALID_ARG;

@@ -53,23 +53,6 @@ __device__ __forceinline__ int wave_sum(int v) {
     return v;
 }
 
-// Four binary16 values -> four int8 codes in one dword.  The product is rounded to fp32 first and
-// then to the nearest integer (ties to even) by adding 1.5 * 2^23, which leaves the two's complement
-// code in the low mantissa byte: the same two roundings as rintf(x * inv).  |x * inv| cannot exceed
-// 127 by more than two units in the last place, so the clamp to +-127 of the definition never acts.
-__device__ __forceinline__ uint32_t quant4(const _Float16 *h, float inv) {
-    uint32_t b[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-#pragma clang fp contract(off)  // a fused multiply-add would round once, not twice
-        const float v = (float)h[i] * inv;
-        b[i] = __float_as_uint(v + 12582912.0f);
-    }
-    const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
-    const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
-    return lo | (hi << 16);
-}
-
 // sum of the four signed bytes of a dword, added to acc
 __device__ __forceinline__ int bytes_sum(uint32_t d, int acc) {
     return __builtin_amdgcn_sdot4((int)d, 0x01010101, acc, false);

@@ -123,6 +123,32 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
                        hipStream_t st);
 hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void *scales,
                          hipStream_t st);
+// ---- per-token int8 quantization steps shared by the kernels that produce quantized activations
+typedef unsigned short us2 __attribute__((ext_vector_type(2)));
+
+// Four binary16 values -> four int8 codes in one dword.  The product is rounded to fp32 first and
+// then to the nearest integer (ties to even) by adding 1.5 * 2^23, which leaves the two's complement
+// code in the low mantissa byte: the same two roundings as rintf(x * inv).  |x * inv| cannot exceed
+// 127 by more than two units in the last place, so the clamp to +-127 of the definition never acts.
+__device__ __forceinline__ uint32_t quant4(const _Float16 *h, float inv) {
+    uint32_t b[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+#pragma clang fp contract(off)  // a fused multiply-add would round once, not twice
+        const float v = (float)h[i] * inv;
+        b[i] = __float_as_uint(v + 12582912.0f);
+    }
+    const uint32_t lo = __builtin_amdgcn_perm(b[1], b[0], 0x0c0c0400u);
+    const uint32_t hi = __builtin_amdgcn_perm(b[3], b[2], 0x0c0c0400u);
+    return lo | (hi << 16);
+}
+
+// Running maximum of |x| over pairs of binary16 values, on the bit patterns with the sign cleared:
+// for finite values the order of the magnitudes is the order of these 15-bit integers.
+__device__ __forceinline__ us2 fold_abs(us2 acc, uint32_t d) {
+    return __builtin_elementwise_max(acc, __builtin_bit_cast(us2, d & 0x7FFF7FFFu));
+}
+
 // Gate activations of the fused input act(gate) * x.  Both are g * sigmoid(t): t = g for SiLU,
 // t = 2 sqrt(2/pi) (g + 0.044715 g^3) for the tanh form of GELU (0.5 (1 + tanh z) = sigmoid(2 z)).
 // Written as t = g (c1 + c3 g^2) with the pair (c1, c3) chosen once per kernel, and with the
@@ -200,6 +226,15 @@ hipError_t launch_gemv_q8(const Geometry &g, const void *packed, const void *x, 
 // `gate` (binary16 [M, K] or null): the rows quantized are fp16(act(gate) * x).
 hipError_t launch_act_quant(const void *x, const void *gate, int act, int M, int K, int8_t *xq, float *sx,
                             int tiled, int Mp, int Kp, int num_cus, hipStream_t st);
+// RMS normalization with the residual connection merged in; see qfc_rmsnorm_t.
+struct RmsNormArgs {
+    const void *x, *residual, *gamma;
+    void *h_out, *y;
+    int8_t *xq;
+    float *sx;
+    float eps, gamma_offset;
+};
+hipError_t launch_rmsnorm(const RmsNormArgs &a, int M, int K, int num_cus, hipStream_t st);
 hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp,
                             hipStream_t st);
 // out_mode 0: binary16 y with scales; 1: raw int32 accumulators.

@@ -82,3 +82,15 @@ def test_argument_errors_before_any_launch(L):
     assert L.qfc_quantize_activations(odd, 4, 64, a, a, s) == 4
     assert L.qfc_quantize_activations(None, 4, 64, a, a, s) == 1
     assert L.qfc_forward_batch(None, None, 1, None, 0, s) == 1
+    assert L.qfc_forward_fused(None, a, 1, a, None, s) == 1
+    # RMS normalization: argument checks come before any launch
+    R = binding.RmsNorm
+    A, ODD = 0x1000, 0x1008
+    assert L.qfc_rmsnorm(None, 1, 64, s) == 1
+    assert L.qfc_rmsnorm(ctypes.byref(R(A, None, A, 1e-5, 0.0, None, None, None, None)), 1, 64, s) == 1   # no output
+    assert L.qfc_rmsnorm(ctypes.byref(R(A, None, A, 1e-5, 0.0, None, A, A, None)), 1, 64, s) == 1        # xq without sx
+    assert L.qfc_rmsnorm(ctypes.byref(R(A, None, A, 1e-5, 0.0, None, A, None, None)), 1, 40, s) == 1      # K % 32
+    assert L.qfc_rmsnorm(ctypes.byref(R(A, None, A, -1.0, 0.0, None, A, None, None)), 1, 64, s) == 1      # eps < 0
+    assert L.qfc_rmsnorm(ctypes.byref(R(A, None, A, 1e-5, 0.0, None, A, None, None)), 1, 14368, s) == 2   # row too long
+    assert L.qfc_rmsnorm(ctypes.byref(R(A, ODD, A, 1e-5, 0.0, None, A, None, None)), 1, 64, s) == 4
+    assert L.qfc_rmsnorm(ctypes.byref(R(None, None, A, 1e-5, 0.0, None, A, None, None)), 1, 64, s) == 1

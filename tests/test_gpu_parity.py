@@ -615,3 +615,72 @@ def test_gated_output_needs_even_halves_of_whole_tiles():
         binding.qfc_forward_fused(layer.handle, xd, y, gated_output=True)
     assert e.value.code == binding.QFC_ERR_INVALID_ARG
     layer.close()
+
+
+# ------------------------------------------------------------------ RMS normalization with merged residual and quantization
+@pytest.mark.parametrize("M,K", [(1, 32), (3, 96), (5, 2304), (8, 4096), (70, 4096), (33, 14336), (600, 256)])
+def test_rmsnorm_residual_quantize(M, K):
+    print(f"rmsnorm M={M} K={K}", flush=True)
+    x = synth.activations(3600, M, K, M, K)
+    r = synth.activations(3601, M, K, M, K)
+    gamma = (synth.activations(3602, M, K, 1, K)[0] * np.float16(0.25)).astype(np.float16)
+    if M > 2:
+        x[1] = 0
+        r[1] = 0  # an all-zero row: h = 0, y = 0 (eps > 0), codes 0, scale 0
+    xd, rd, gd = (torch.from_numpy(t).to(DEV) for t in (x, r, gamma))
+    for goff, eps in ((0.0, 1e-5), (1.0, 1e-6)):
+        h_out = torch.empty((M, K), dtype=torch.float16, device=DEV)
+        y = torch.empty((M, K), dtype=torch.float16, device=DEV)
+        xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+        sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+        binding.qfc_rmsnorm(xd, gd, eps, goff, residual=rd, h_out=h_out, y=y, xq=xq, sx=sx)
+        torch.cuda.synchronize()
+        h_ref, y_ref = oracle.rmsnorm(x, gamma, eps, goff, residual_f16=r)
+        # the residual stream: one correctly rounded binary16 addition, bit for bit
+        assert np.array_equal(h_out.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
+        y_gpu = y.cpu().numpy()
+        assert oracle.floored_rel_error(y_gpu, y_ref) <= TOL
+        # the quantization is the activation quantization of the stored y, bit for bit
+        xq_ref, sx_ref = oracle.quantize_activations(y_gpu)
+        assert np.array_equal(xq.cpu().numpy(), xq_ref)
+        assert np.array_equal(sx.cpu().numpy().view(np.uint32), sx_ref.view(np.uint32))
+        if M > 2:
+            assert not y_gpu[1].any() and not xq_ref[1].any() and sx_ref[1] == 0
+    # without a residual, and with only some outputs; in place on the residual stream
+    y2 = torch.empty((M, K), dtype=torch.float16, device=DEV)
+    binding.qfc_rmsnorm(xd, gd, 1e-5, 0.0, y=y2)
+    torch.cuda.synchronize()
+    h_ref, y_ref = oracle.rmsnorm(x, gamma, 1e-5, 0.0)
+    assert oracle.floored_rel_error(y2.cpu().numpy(), y_ref) <= TOL
+    stream_buf = xd.clone()
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    binding.qfc_rmsnorm(stream_buf, gd, 1e-5, 0.0, residual=rd, h_out=stream_buf, xq=xq, sx=sx)
+    torch.cuda.synchronize()
+    h_ref, y_ref = oracle.rmsnorm(x, gamma, 1e-5, 0.0, residual_f16=r)
+    assert np.array_equal(stream_buf.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
+    # codes of the oracle's y agree except where the fp32 evaluation rounds y to the neighbouring binary16 value
+    xq_o, sx_o = oracle.quantize_activations(y_ref.astype(np.float16))
+    assert np.max(np.abs(xq.cpu().numpy().astype(np.int32) - xq_o.astype(np.int32))) <= 1
+    assert np.allclose(sx.cpu().numpy(), sx_o, rtol=2e-3, atol=0)
+
+
+def test_rmsnorm_feeds_the_int8_layer():
+    """norm -> quantized activations -> qfc_forward_q8 equals norm -> y -> int8 prefill layer, bit for bit."""
+    M, K, N = 40, 512, 300
+    fc = synth.FC("t", K, N, "w8c")
+    wq, sw = synth.weights(3700, M, N, fc)
+    layer = _layer(wq, sw, "w8c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    x = torch.from_numpy(synth.activations(3700, M, N, M, K)).to(DEV)
+    gamma = torch.from_numpy(synth.activations(3701, M, N, 1, K)[0]).to(DEV)
+    y = torch.empty((M, K), dtype=torch.float16, device=DEV)
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    binding.qfc_rmsnorm(x, gamma, 1e-5, 0.0, y=y, xq=xq, sx=sx)
+    out_a = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    out_b = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    binding.qfc_forward_q8(layer.handle, xq, sx, out_a)
+    binding.qfc_forward(layer.handle, y, out_b)
+    torch.cuda.synchronize()
+    assert np.array_equal(out_a.cpu().numpy().view(np.uint16), out_b.cpu().numpy().view(np.uint16))
+    layer.close()
