@@ -18,6 +18,7 @@ import subprocess
 import numpy as np
 
 from .elementwise import GELU_TANH, SILU, add_residual, gated_input, gated_output, gelu_tanh, rmsnorm, silu  # noqa: F401
+from .attention import attention, rope, rope_qkv_layout  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qfc_oracle.c")

@@ -377,3 +377,75 @@ def test_rmsnorm_hand_values_library_routine_and_invariants():
     b = np.array([[2.0 ** -11, 1.0]], dtype=np.float16)
     h, _ = oracle.rmsnorm(a, ones, 0.0, residual_f16=b)
     assert np.array_equal(h.astype(np.float64), [[1.0, 1.0]])  # 1 + 2^-11 ties to even = 1
+
+
+# ---------------------------------------------------------------- attention-side operators
+def test_rope_hand_values_and_invariants():
+    c = _golden()["rope"]
+    c1, s1 = float(c["cos1"][0]), float(c["sin1"][0])
+    assert np.allclose(oracle.rope([1.0, 0.0], 1, 10000.0), [c1, s1], rtol=0, atol=5e-10)
+    assert np.allclose(oracle.rope([0.0, 2.0], 1, 10000.0), [-2 * s1, 2 * c1], rtol=0, atol=1e-9)
+    assert np.allclose(oracle.rope([1.0, 1.0, 0.0, 0.0], 2, 100.0), [float(v) for v in c["d4_pos2"]], rtol=0, atol=5e-10)
+    rng = np.random.default_rng(9)
+    q, k = rng.standard_normal(64), rng.standard_normal(64)
+    assert np.array_equal(oracle.rope(q, 0, 10000.0), q)                      # position 0: identity
+    r = oracle.rope(q, 77, 10000.0)
+    assert np.allclose(r[:32] ** 2 + r[32:] ** 2, q[:32] ** 2 + q[32:] ** 2, rtol=1e-12)  # rotations of the pairs
+    # the product of two rotated vectors depends on the distance of their positions only
+    a = oracle.rope(q, 1000, 10000.0) @ oracle.rope(k, 990, 10000.0)
+    b = oracle.rope(q, 15, 10000.0) @ oracle.rope(k, 5, 10000.0)
+    assert abs(a - b) < 1e-9
+    # rotating twice adds the positions
+    assert np.allclose(oracle.rope(oracle.rope(q, 3, 500.0), 4, 500.0), oracle.rope(q, 7, 500.0), rtol=1e-12, atol=1e-13)
+
+
+def test_rope_qkv_layout_places_heads():
+    B, S, h_q, h_kv, d = 2, 3, 4, 2, 8
+    W = (h_q + 2 * h_kv) * d
+    # the value of an element encodes where it came from; position 0 for all tokens would need pos0 = 0 and S = 1,
+    # so the check is done on v (not rotated) and on the norms of the rotated pairs of q and k
+    x = np.arange(B * S * W, dtype=np.float64).reshape(B, S, W) / 64.0
+    xf = x.astype(np.float16)
+    q, k, v = oracle.rope_qkv_layout(xf, 5, h_q, h_kv, d, 10000.0)
+    assert q.shape == (B * h_kv, S * (h_q // h_kv), d) and k.shape == (B * h_kv, S, d) and v.shape == k.shape
+    xr = xf.astype(np.float64)
+    for b in range(B):
+        for kv in range(h_kv):
+            for s in range(S):
+                src_v = xr[b, s, (h_q + h_kv + kv) * d: (h_q + h_kv + kv + 1) * d]
+                assert np.array_equal(v[b * h_kv + kv, s].astype(np.float64), src_v)
+                src_k = xr[b, s, (h_q + kv) * d: (h_q + kv + 1) * d]
+                assert np.allclose(k[b * h_kv + kv, s].astype(np.float64), oracle.rope(src_k, 5 + s, 10000.0), rtol=2e-3)
+                for j in range(h_q // h_kv):
+                    head = kv * (h_q // h_kv) + j
+                    src_q = xr[b, s, head * d: (head + 1) * d]
+                    got = q[b * h_kv + kv, s * (h_q // h_kv) + j].astype(np.float64)
+                    assert np.allclose(got, oracle.rope(src_q, 5 + s, 10000.0), rtol=2e-3, atol=1e-3)
+
+
+def test_attention_hand_case_library_routine_and_special_cases():
+    c = _golden()["attention"]
+    q = np.array([[[2.0, 0.0]]], dtype=np.float16)
+    K = np.array([[[1, 0], [0, 1], [-1, 0], [9, 9]]], dtype=np.float16)          # 4th position is not valid yet
+    V = np.array([[[10, 20, 30, 99], [1, 0, -1, 99]]], dtype=np.float16)         # [d, cache]
+    out = oracle.attention(q, K, V, 3, 1)
+    assert np.allclose(out[0, 0], [float(v) for v in c["out"]], rtol=0, atol=5e-9)
+    # a single valid position returns its value column; equal keys return the mean of the values
+    assert np.array_equal(oracle.attention(q, K, V, 1, 1)[0, 0], [10.0, 1.0])
+    K2 = np.ones((1, 3, 2), dtype=np.float16)
+    assert np.allclose(oracle.attention(q, K2, V[:, :, :3], 3, 1)[0, 0], [20.0, 0.0], rtol=1e-14, atol=1e-14)
+    # torch's scaled_dot_product_attention in fp64, grouped queries and causal mask (S = 3 tokens, g = 2 heads per KV head)
+    import torch
+    rng = np.random.default_rng(4)
+    G, S, g, d, C, n = 3, 3, 2, 16, 40, 29
+    qr = rng.standard_normal((G, S * g, d)).astype(np.float16)
+    Kr = rng.standard_normal((G, C, d)).astype(np.float16)
+    Vr = rng.standard_normal((G, d, C)).astype(np.float16)
+    got = oracle.attention(qr, Kr, Vr, n, S)
+    for j in range(g):
+        qj = torch.from_numpy(qr[:, j::g].astype(np.float64))                     # [G, S, d]: head j of every token
+        kj = torch.from_numpy(Kr[:, :n].astype(np.float64))
+        vj = torch.from_numpy(Vr[:, :, :n].astype(np.float64)).transpose(1, 2)
+        mask = torch.ones(S, n, dtype=torch.bool).tril(diagonal=n - S)
+        ref = torch.nn.functional.scaled_dot_product_attention(qj, kj, vj, attn_mask=mask)
+        assert np.allclose(got[:, j::g], ref.numpy(), rtol=1e-12, atol=1e-13)
