@@ -190,6 +190,44 @@ typedef struct qfc_rmsnorm {
 } qfc_rmsnorm_t;
 qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *args, int32_t M, int32_t K, void *stream);
 
+/* Attention-side operators of the decode stage.
+ *
+ * Shapes: `batch` sequences, `h_q` query heads and `h_kv` key/value heads of
+ * `d_head` values (h_q a multiple of h_kv, g = h_q / h_kv; d_head 64, 128 or
+ * 256), a KV cache of `cache_size` positions (a multiple of 64).  G = batch * h_kv.
+ * Layouts (sections 3.6 and 3.8), all binary16:
+ *   queries  q      [G, S * g, d_head]   row s * g + j = query head kv * g + j of token s
+ *   K cache  kcache [G, cache_size, d_head]   (the transposed operand of Q K^T, stored as weights)
+ *   V cache  vcache [G, d_head, cache_size]
+ *   output   out    [G, S * g, d_head]   (for S = 1 this is [batch, h_q * d_head], the next layer's input)
+ */
+typedef struct qfc_attn_shape {
+    int32_t batch, h_q, h_kv, d_head, cache_size;
+} qfc_attn_shape_t;
+
+/* Rotary embedding fused with the layout transformation of the query, key and
+ * value projections (section 3.6): qkv_f16 is the QKV layer's output
+ * [batch, S, (h_q + 2 h_kv) * d_head] (query heads, key heads, value heads) for
+ * the tokens at positions pos0 .. pos0 + S - 1.  Queries and keys are rotated
+ * (pairs (i, i + d_head / 2) by the angle pos * rope_base^(-2 i / d_head)); the
+ * queries go to q_out, the keys are written into kcache as rows pos0 + s and
+ * the values into vcache as columns pos0 + s.  pos0 + S <= cache_size. */
+qfc_status_t qfc_rope_qkv(const void *qkv_f16, int32_t S, int32_t pos0, const qfc_attn_shape_t *shape,
+                          float rope_base, void *q_out, void *kcache, void *vcache, void *stream);
+
+/* Bytes of scratch qfc_attention needs for this shape and S (host pointer). */
+qfc_status_t qfc_attention_workspace_size(const qfc_attn_shape_t *shape, int32_t S, size_t *bytes);
+
+/* Attention with the KV cache in the role of weights (section 3.8):
+ * out = softmax(q K^T / sqrt(d_head)) V per group, over the first n_ctx cache
+ * positions; the S query tokens are the last S of them (token s sees positions
+ * 0 .. n_ctx - S + s).  S * g <= 16 (decode: S = 1).  Positions >= n_ctx of the
+ * caches are never used, whatever they hold.  The scores are not materialized.
+ * workspace: device scratch of at least qfc_attention_workspace_size bytes, 16-byte aligned. */
+qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache, int32_t S, int32_t n_ctx,
+                           const qfc_attn_shape_t *shape, void *workspace, size_t workspace_bytes,
+                           void *out_f16, void *stream);
+
 /* `count` forward calls issued in order on one stream: handles, xs and ys are
  * host arrays of `count` entries; every call uses the same M.  Stops at the
  * first error and returns it. */

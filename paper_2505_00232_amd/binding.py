@@ -19,7 +19,7 @@ QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT, QFC_COMPUTE_INT8_ACT_DECODE = 0,
 QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
-           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_rmsnorm", "qfc_forward_q8",
+           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
            "qfc_forward_acc_i32", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
 
 
@@ -40,6 +40,12 @@ class RmsNorm(ctypes.Structure):
     _fields_ = [("x", ctypes.c_void_p), ("residual", ctypes.c_void_p), ("gamma", ctypes.c_void_p),
                 ("eps", ctypes.c_float), ("gamma_offset", ctypes.c_float), ("h_out", ctypes.c_void_p),
                 ("y", ctypes.c_void_p), ("xq", ctypes.c_void_p), ("sx", ctypes.c_void_p)]
+
+
+class AttnShape(ctypes.Structure):
+    """qfc_attn_shape_t."""
+    _fields_ = [("batch", ctypes.c_int32), ("h_q", ctypes.c_int32), ("h_kv", ctypes.c_int32),
+                ("d_head", ctypes.c_int32), ("cache_size", ctypes.c_int32)]
 
 
 class QfcError(RuntimeError):
@@ -68,6 +74,9 @@ def lib() -> ctypes.CDLL:
         L.qfc_forward.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_fused.argtypes = [vp, vp, i32, vp, ctypes.POINTER(Fusion), vp]
         L.qfc_rmsnorm.argtypes = [ctypes.POINTER(RmsNorm), i32, i32, vp]
+        L.qfc_rope_qkv.argtypes = [vp, i32, i32, ctypes.POINTER(AttnShape), ctypes.c_float, vp, vp, vp, vp]
+        L.qfc_attention_workspace_size.argtypes = [ctypes.POINTER(AttnShape), i32, ctypes.POINTER(sz)]
+        L.qfc_attention.argtypes = [vp, vp, vp, i32, i32, ctypes.POINTER(AttnShape), vp, sz, vp, vp]
         L.qfc_forward_q8.argtypes = [vp, vp, vp, i32, vp, vp]
         L.qfc_forward_acc_i32.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_batch.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, vp]
@@ -165,6 +174,25 @@ def qfc_rmsnorm(x: torch.Tensor, gamma: torch.Tensor, eps: float, gamma_offset: 
     M, K = x.shape
     a = RmsNorm(p(x), p(residual), p(gamma), eps, gamma_offset, p(h_out), p(y), p(xq), p(sx))
     _check(lib().qfc_rmsnorm(ctypes.byref(a), M, K, _stream()), "qfc_rmsnorm")
+
+
+def qfc_rope_qkv(qkv: torch.Tensor, pos0: int, shape: AttnShape, rope_base: float, q_out: torch.Tensor,
+                 kcache: torch.Tensor, vcache: torch.Tensor):
+    S = qkv.shape[1]
+    _check(lib().qfc_rope_qkv(_ptr(qkv), S, pos0, ctypes.byref(shape), rope_base, _ptr(q_out), _ptr(kcache),
+                              _ptr(vcache), _stream()), "qfc_rope_qkv")
+
+
+def qfc_attention_workspace_size(shape: AttnShape, S: int) -> int:
+    out = ctypes.c_size_t(0)
+    _check(lib().qfc_attention_workspace_size(ctypes.byref(shape), S, ctypes.byref(out)), "qfc_attention_workspace_size")
+    return out.value
+
+
+def qfc_attention(q: torch.Tensor, kcache: torch.Tensor, vcache: torch.Tensor, S: int, n_ctx: int, shape: AttnShape,
+                  workspace: torch.Tensor, out: torch.Tensor):
+    _check(lib().qfc_attention(_ptr(q), _ptr(kcache), _ptr(vcache), S, n_ctx, ctypes.byref(shape), _ptr(workspace),
+                               workspace.numel() * workspace.element_size(), _ptr(out), _stream()), "qfc_attention")
 
 
 def qfc_forward_q8(h, xq: torch.Tensor, sx: torch.Tensor, y: torch.Tensor):

@@ -230,6 +230,58 @@ qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *r, int32_t M, int32_t K, void *str
     return hip_status(launch_rmsnorm(a, M, K, cus, static_cast<hipStream_t>(stream)));
 }
 
+static qfc_status_t check_attn_shape(const qfc_attn_shape_t *a, int32_t S) {
+    if (!a || a->batch < 1 || a->h_q < 1 || a->h_kv < 1 || a->h_q % a->h_kv != 0 || S < 1 || a->cache_size < 64 ||
+        a->cache_size % 64 != 0)
+        return QFC_ERR_INVALID_ARG;
+    if (a->d_head != 64 && a->d_head != 128 && a->d_head != 256) return QFC_ERR_UNSUPPORTED;
+    return QFC_OK;
+}
+
+qfc_status_t qfc_rope_qkv(const void *qkv_f16, int32_t S, int32_t pos0, const qfc_attn_shape_t *a, float rope_base,
+                          void *q_out, void *kcache, void *vcache, void *stream) {
+    const qfc_status_t s = check_attn_shape(a, S);
+    if (s != QFC_OK) return s;
+    if (!qkv_f16 || !q_out || !kcache || !vcache || pos0 < 0 || !(rope_base > 1.0f)) return QFC_ERR_INVALID_ARG;
+    if ((long)pos0 + S > a->cache_size) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(qkv_f16) || !aligned16(q_out) || !aligned16(kcache) || !aligned16(vcache)) return QFC_ERR_ALIGNMENT;
+    return hip_status(launch_rope_qkv(qkv_f16, a->batch, S, a->h_q, a->h_kv, a->d_head, a->cache_size, pos0, rope_base,
+                                      q_out, kcache, vcache, static_cast<hipStream_t>(stream)));
+}
+
+static size_t attn_workspace(const qfc_attn_shape_t *a, int32_t S) {
+    const size_t rows = (size_t)a->batch * a->h_kv * kAttnMaxSplits * (size_t)(S * (a->h_q / a->h_kv));
+    return rows * (a->d_head + 2) * sizeof(float);
+}
+
+qfc_status_t qfc_attention_workspace_size(const qfc_attn_shape_t *a, int32_t S, size_t *bytes) {
+    if (!bytes) return QFC_ERR_INVALID_ARG;
+    const qfc_status_t s = check_attn_shape(a, S);
+    if (s != QFC_OK) return s;
+    if (S * (a->h_q / a->h_kv) > 16) return QFC_ERR_UNSUPPORTED;
+    *bytes = attn_workspace(a, S);
+    return QFC_OK;
+}
+
+qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache, int32_t S, int32_t n_ctx,
+                           const qfc_attn_shape_t *a, void *workspace, size_t workspace_bytes, void *out_f16,
+                           void *stream) {
+    const qfc_status_t s = check_attn_shape(a, S);
+    if (s != QFC_OK) return s;
+    if (!q || !kcache || !vcache || !workspace || !out_f16 || n_ctx < S || n_ctx > a->cache_size)
+        return QFC_ERR_INVALID_ARG;
+    const int g = a->h_q / a->h_kv;
+    if (S * g > 16) return QFC_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(kcache) || !aligned16(vcache) || !aligned16(workspace) || !aligned16(out_f16))
+        return QFC_ERR_ALIGNMENT;
+    if (workspace_bytes < attn_workspace(a, S)) return QFC_ERR_BUFFER_TOO_SMALL;
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return QFC_ERR_HIP;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return QFC_ERR_HIP;
+    return hip_status(launch_attention(q, kcache, vcache, a->batch * a->h_kv, S, g, a->d_head, a->cache_size, n_ctx,
+                                       workspace, out_f16, cus, static_cast<hipStream_t>(stream)));
+}
+
 qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M, void *y_f16,
                             void *stream) {
     if (!sx || !y_f16) return QFC_ERR_INVALID_ARG;

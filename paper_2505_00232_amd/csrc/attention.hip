@@ -1,0 +1,357 @@
+// Attention-side operators of the decode stage.
+//
+// 1. Rotary embedding fused with the layout transformation of the query, key and value
+//    projections (section 3.6 of the paper): the QKV layer's output [B, S, (h_q + 2 h_kv) d] goes
+//    to queries [B h_kv, S g, d] (g = h_q / h_kv query heads per KV head, row s g + j), the rotated
+//    keys are appended to the K cache [B h_kv, C, d] as rows pos0 + s and the values to the V cache
+//    [B h_kv, d, C] as columns pos0 + s.
+// 2. The two matrix products of attention with the KV cache in the role of weights (section 3.8):
+//    the K cache is stored (cache position, d), i.e. K^T of Q K^T, the V cache (d, cache position);
+//    both are row-major [N, K] operands exactly like a layer's logical weight matrix, and 16 bytes
+//    of a row are one lane's MFMA operand.  Here the two products and the softmax between them run
+//    in one pass over the cache (the scores never leave registers): per step of 64 positions a
+//    wavefront computes S^T = K Q^T with v_mfma_f32_16x16x32_f16 (keys as rows), updates the running
+//    maximum and sum of every query row, and accumulates O^T += V P^T, where the positions are
+//    taken in the order in which the score tiles leave them in the lanes (no cross-lane traffic:
+//    the rows of the score tiles are assigned to positions so that lane (m, r) ends up with 2 x 8
+//    contiguous positions for query row m, and reads the same positions of its V rows, 16 bytes each).  The context is split over workgroups and
+//    wavefronts; partial (maximum, sum, O) triples meet in LDS and then in a second small kernel.
+#include "qfc_internal.h"
+
+namespace qfc {
+namespace {
+
+typedef _Float16 h8 __attribute__((ext_vector_type(8)));
+typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+typedef float v4f __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+constexpr float kNegBig = -1.0e30f;
+static_assert(kAttnMaxSplits <= 64, "the combine kernel takes one split per lane");
+
+// ---------------------------------------------------------------- rotary embedding + layouts
+// One thread per (b, s, head, i), i < d / 2: the pair (i, i + d / 2) of one head of one token.
+__global__ __launch_bounds__(256) void rope_qkv_kernel(const _Float16 *__restrict__ qkv, int B, int S, int h_q,
+                                                       int h_kv, int d, int C, int pos0, double log_base,
+                                                       _Float16 *__restrict__ q_out, _Float16 *__restrict__ kc,
+                                                       _Float16 *__restrict__ vc) {
+    const int half = d / 2;
+    const int heads = h_q + 2 * h_kv;
+    const long total = (long)B * S * heads * half;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= total) return;
+    const int i = (int)(idx % half);
+    const int head = (int)((idx / half) % heads);
+    const int s = (int)((idx / ((long)half * heads)) % S);
+    const int b = (int)(idx / ((long)half * heads * S));
+    const _Float16 *src = qkv + ((size_t)(b * S + s) * heads + head) * d;
+    const double x0 = (double)(float)src[i], x1 = (double)(float)src[i + half];
+    const int g = h_q / h_kv;
+    if (head >= h_q + h_kv) {  // value head: no rotation, transposed into the cache
+        const int kv = head - h_q - h_kv;
+        _Float16 *dst = vc + (size_t)(b * h_kv + kv) * d * C + (pos0 + s);
+        dst[(size_t)i * C] = src[i];
+        dst[(size_t)(i + half) * C] = src[i + half];
+        return;
+    }
+    // angle = pos * base^(-2 i / d), in double so that long contexts keep the low bits of the angle
+    const double ang = (double)(pos0 + s) * exp(-2.0 * (double)i / (double)d * log_base);
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    const _Float16 y0 = (_Float16)(float)(x0 * cs - x1 * sn);
+    const _Float16 y1 = (_Float16)(float)(x1 * cs + x0 * sn);
+    _Float16 *dst;
+    if (head < h_q) {
+        const int kv = head / g, j = head % g;
+        dst = q_out + ((size_t)(b * h_kv + kv) * (S * g) + (s * g + j)) * d;
+    } else {
+        const int kv = head - h_q;
+        dst = kc + ((size_t)(b * h_kv + kv) * C + (pos0 + s)) * d;
+    }
+    dst[i] = y0;
+    dst[i + half] = y1;
+}
+
+// ---------------------------------------------------------------- attention over the cache
+struct AttnArgs {
+    const _Float16 *q;   // [G, M, D]
+    const _Float16 *kc;  // [G, C, D]
+    const _Float16 *vc;  // [G, D, C]
+    float *ws_o;         // [G, splits, M, D] partial outputs (unnormalized)
+    float *ws_ml;        // [G, splits, M, 2] partial (maximum, sum)
+    _Float16 *out;       // [G, M, D]
+    int M, g, S, C, n_ctx, splits;
+    float scale;
+};
+
+// Workgroup = 4 wavefronts.  grid = (splits, G).
+template <int D>
+__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
+    constexpr int DJ = D / 32;  // MFMA steps along d of the score product
+    constexpr int DT = D / 16;  // row tiles of O^T
+    constexpr int PITCH = D + 4;  // floats per staged query row: O^T column, maximum, sum (16-byte aligned rows)
+    extern __shared__ float lds[];  // [4][16][PITCH]
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    const int m = lane & 15, r = lane >> 4;
+    const int G = blockIdx.y;
+    const int part = blockIdx.x * 4 + wave, parts = a.splits * 4;
+    const int nb = (a.n_ctx + 63) / 64;  // steps of 64 positions
+    const int b0 = (int)((long)part * nb / parts), b1 = (int)((long)(part + 1) * nb / parts);
+
+    // Q^T operand: lane (m, r) holds Q[m][32 j + 8 r .. + 7]; rows >= M are zero
+    u32x4 qf[DJ];
+#pragma unroll
+    for (int j = 0; j < DJ; ++j) {
+        const u32x4 zero = {0, 0, 0, 0};
+        qf[j] = m < a.M ? *reinterpret_cast<const u32x4 *>(a.q + ((size_t)G * a.M + m) * D + 32 * j + 8 * r) : zero;
+    }
+    // positions a query row may see: those before the end of its own token
+    const int lim = m < a.M ? a.n_ctx - a.S + m / a.g + 1 : 0;
+
+    v4f acc[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t) acc[t] = v4f{0.0f, 0.0f, 0.0f, 0.0f};
+    float run_max = kNegBig, run_sum = 0.0f;  // run_sum: this lane's share (its 8 positions per block)
+
+    const _Float16 *kbase = a.kc + (size_t)G * a.C * D;
+    const _Float16 *vbase = a.vc + (size_t)G * D * a.C;
+    // One step = 64 positions: four score tiles of 16 positions, two MFMA steps of 32 positions for
+    // O^T.  All operands of a step are requested at once, so that each 128-byte line of a V row (64
+    // positions) is fetched by one burst of one wavefront.  The loop is software pipelined without a
+    // second set of registers: the next step's K operands are requested as soon as the score MFMAs
+    // have consumed the current ones (they fly during the softmax and the O^T MFMAs), the next step's
+    // V operands at the end of the step (they fly during the next score MFMAs and softmax).
+    // Which position a row of a score tile stands for is free; row w of tile t is position
+    //   k0 + 32 (t / 2) + 8 (w / 4) + 4 (t % 2) + w % 4,
+    // so that the eight values lane (m, r) holds of tiles (2 u, 2 u + 1) are the contiguous positions
+    // k0 + 32 u + 8 r .. + 7: its V operand of MFMA step u is one 16-byte load, and the four lanes r
+    // of a V row read 64 contiguous bytes.  K: lane (w = lane & 15, r) reads d = 32 j + 8 r .. + 7 of
+    // its position's row (a K row is contiguous whatever the order of the rows).
+    u32x4 kf[4][DJ];
+    u32x4 vf[DT][2];
+    auto load_k = [&](int blk) {
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            const int pos = blk * 64 + 32 * (t >> 1) + 8 * (m >> 2) + 4 * (t & 1) + (m & 3);
+            const _Float16 *krow = kbase + (size_t)pos * D + 8 * r;
+#pragma unroll
+            for (int j = 0; j < DJ; ++j) kf[t][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(krow + 32 * j));
+        }
+    };
+    auto load_v = [&](int blk) {
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            const _Float16 *vrow = vbase + (size_t)(16 * dt + m) * a.C + blk * 64 + 8 * r;
+#pragma unroll
+            for (int u = 0; u < 2; ++u)
+                vf[dt][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vrow + 32 * u));
+        }
+    };
+    if (b0 < b1) {
+        load_k(b0);
+        load_v(b0);
+    }
+    for (int blk = b0; blk < b1; ++blk) {
+        const int k0 = blk * 64;
+        // ---- S^T = K Q^T; lane (m, r) holds positions k0 + 32 (t / 2) + 8 r + 4 (t % 2) + i
+        v4f st[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            v4f acc_s = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int j = 0; j < DJ; ++j)
+                acc_s = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, kf[t][j]), __builtin_bit_cast(h8, qf[j]), acc_s, 0, 0, 0);
+            st[t] = acc_s;
+        }
+        if (blk + 1 < b1) load_k(blk + 1);
+        // ---- masked and scaled
+        float sc[16];
+        bool ok[16];
+        float bmax = kNegBig;
+#pragma unroll
+        for (int t = 0; t < 4; ++t)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int pos = k0 + 32 * (t >> 1) + 8 * r + 4 * (t & 1) + i;
+                ok[4 * t + i] = pos < lim;
+                sc[4 * t + i] = ok[4 * t + i] ? st[t][i] * a.scale : kNegBig;
+                bmax = fmaxf(bmax, sc[4 * t + i]);
+            }
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+        const float new_max = fmaxf(run_max, bmax);
+        const float corr = __expf(run_max - new_max);
+        run_max = new_max;
+        float psum = 0.0f;
+        h8 pv[2];  // P^T operands of the two MFMA steps: positions of tiles (0, 1) and (2, 3)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const float p = ok[e] ? __expf(sc[e] - new_max) : 0.0f;
+            psum += p;
+            pv[e >> 3][e & 7] = (_Float16)p;
+        }
+        run_sum = run_sum * corr + psum;
+        // positions at or past the end of the context may hold anything (0 * NaN would poison the sum)
+        if (k0 + 64 > a.n_ctx) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int u = 0; u < 2; ++u) {
+                    const int p0 = k0 + 32 * u + 8 * r;
+                    uint32_t w[4] = {vf[dt][u].x, vf[dt][u].y, vf[dt][u].z, vf[dt][u].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (p0 + 2 * e >= a.n_ctx) w[e] &= 0xFFFF0000u;
+                        if (p0 + 2 * e + 1 >= a.n_ctx) w[e] &= 0x0000FFFFu;
+                    }
+                    vf[dt][u] = u32x4{w[0], w[1], w[2], w[3]};
+                }
+        }
+        // ---- O^T = O^T corr + V P^T
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            v4f o = acc[dt];
+#pragma unroll
+            for (int i = 0; i < 4; ++i) o[i] *= corr;
+#pragma unroll
+            for (int u = 0; u < 2; ++u) {
+                o = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, vf[dt][u]), pv[u], o, 0, 0, 0);
+            }
+            acc[dt] = o;
+        }
+        if (blk + 1 < b1) load_v(blk + 1);
+    }
+    run_sum += __shfl_xor(run_sum, 16, 64);
+    run_sum += __shfl_xor(run_sum, 32, 64);
+
+    // ---- the four wavefronts meet in LDS: [wave][m][PITCH] = O^T column m, then (maximum, sum)
+    float *mine = lds + (size_t)wave * 16 * PITCH + (size_t)m * PITCH;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) *reinterpret_cast<v4f *>(mine + 16 * dt + 4 * r) = acc[dt];  // rows d = 16 dt + 4 r + i
+    if (r == 0) {
+        mine[D] = run_max;
+        mine[D + 1] = run_sum;
+    }
+    __syncthreads();
+    for (int e = threadIdx.x; e < a.M * D; e += 256) {
+        const int mm = e / D, dd = e % D;
+        float mx = kNegBig;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) mx = fmaxf(mx, lds[(size_t)w * 16 * PITCH + (size_t)mm * PITCH + D]);
+        float o = 0.0f, l = 0.0f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+            const float *src = lds + (size_t)w * 16 * PITCH + (size_t)mm * PITCH;
+            const float f = __expf(src[D] - mx);
+            o += f * src[dd];
+            l += f * src[D + 1];
+        }
+        if (a.splits == 1) {
+            a.out[((size_t)G * a.M + mm) * D + dd] = (_Float16)(o / l);
+        } else {
+            const size_t p = ((size_t)G * a.splits + blockIdx.x) * a.M + mm;
+            a.ws_o[p * D + dd] = o;
+            if (dd == 0) {
+                a.ws_ml[p * 2] = mx;
+                a.ws_ml[p * 2 + 1] = l;
+            }
+        }
+    }
+}
+
+// grid = (M, G), one workgroup of 64 lanes per query row: lane s first takes the (maximum, sum) pair
+// of split s (splits <= 64) and the factors exp(maximum_s - maximum) are shared by lane broadcast;
+// then lane l sums columns l, l + 64, .. of the partial outputs in split order.
+template <int D>
+__global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
+    const int G = blockIdx.y, mm = blockIdx.x, lane = threadIdx.x;
+    const size_t row0 = ((size_t)G * a.splits) * a.M + mm;  // partial row of split s: row0 + s * M
+    float mx = kNegBig, l = 0.0f;
+    if (lane < a.splits) {
+        mx = a.ws_ml[(row0 + (size_t)lane * a.M) * 2];
+        l = a.ws_ml[(row0 + (size_t)lane * a.M) * 2 + 1];
+    }
+    float top = mx;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) top = fmaxf(top, __shfl_xor(top, off, 64));
+    const float f = lane < a.splits ? __expf(mx - top) : 0.0f;
+    float lsum = f * l;
+#pragma unroll
+    for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off, 64);
+    float o[D / 64];
+#pragma unroll
+    for (int c = 0; c < D / 64; ++c) o[c] = 0.0f;
+    for (int s = 0; s < a.splits; ++s) {
+        const float fs = __shfl(f, s, 64);
+        const float *src = a.ws_o + (row0 + (size_t)s * a.M) * D;
+#pragma unroll
+        for (int c = 0; c < D / 64; ++c) o[c] = fmaf(fs, src[64 * c + lane], o[c]);
+    }
+#pragma unroll
+    for (int c = 0; c < D / 64; ++c) a.out[((size_t)G * a.M + mm) * D + 64 * c + lane] = (_Float16)(o[c] / lsum);
+}
+
+template <int D>
+hipError_t launch_attn(const AttnArgs &a, int G, hipStream_t st) {
+    const size_t lds = (size_t)4 * 16 * (D + 4) * sizeof(float);
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_partial_kernel<D>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    attn_partial_kernel<D><<<dim3((unsigned)a.splits, (unsigned)G), 256, lds, st>>>(a);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess || a.splits == 1) return e;
+    attn_combine_kernel<D><<<dim3((unsigned)a.M, (unsigned)G), 64, 0, st>>>(a);
+    return hipGetLastError();
+}
+
+}  // namespace
+
+// Workgroups per (batch, KV head) group: enough wavefronts to fill the chip, at least one block
+// of 32 positions per wavefront, at most kAttnMaxSplits.
+int attn_splits(int G, int n_ctx, int num_cus) {
+    const int nb = (n_ctx + 63) / 64;
+    int s = (8 * num_cus + 4 * G - 1) / (4 * G);
+    if (s > (nb + 3) / 4) s = (nb + 3) / 4;  // at least one step of 64 positions per wavefront
+    if (s > kAttnMaxSplits) s = kAttnMaxSplits;
+    if (s < 1) s = 1;
+    return s;
+}
+
+hipError_t launch_rope_qkv(const void *qkv, int B, int S, int h_q, int h_kv, int d, int C, int pos0, float base,
+                           void *q_out, void *kc, void *vc, hipStream_t st) {
+    const long total = (long)B * S * (h_q + 2 * h_kv) * (d / 2);
+    rope_qkv_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(
+        static_cast<const _Float16 *>(qkv), B, S, h_q, h_kv, d, C, pos0, log((double)base),
+        static_cast<_Float16 *>(q_out), static_cast<_Float16 *>(kc), static_cast<_Float16 *>(vc));
+    return hipGetLastError();
+}
+
+hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G, int S, int g, int d, int C,
+                            int n_ctx, void *workspace, void *out, int num_cus, hipStream_t st) {
+    AttnArgs a;
+    a.q = static_cast<const _Float16 *>(q);
+    a.kc = static_cast<const _Float16 *>(kc);
+    a.vc = static_cast<const _Float16 *>(vc);
+    a.M = S * g;
+    a.g = g;
+    a.S = S;
+    a.C = C;
+    a.n_ctx = n_ctx;
+    a.splits = attn_splits(G, n_ctx, num_cus);
+    a.scale = 1.0f / sqrtf((float)d);
+    a.ws_o = static_cast<float *>(workspace);
+    a.ws_ml = a.ws_o + (size_t)G * kAttnMaxSplits * a.M * d;
+    a.out = static_cast<_Float16 *>(out);
+    switch (d) {
+        case 64: return launch_attn<64>(a, G, st);
+        case 128: return launch_attn<128>(a, G, st);
+        case 256: return launch_attn<256>(a, G, st);
+        default: return hipErrorInvalidValue;
+    }
+}
+
+}  // namespace qfc

@@ -235,6 +235,13 @@ struct RmsNormArgs {
     float eps, gamma_offset;
 };
 hipError_t launch_rmsnorm(const RmsNormArgs &a, int M, int K, int num_cus, hipStream_t st);
+// Attention-side operators (see qfc_rope_qkv / qfc_attention).  G = batch * h_kv groups.
+constexpr int kAttnMaxSplits = 64;
+int attn_splits(int G, int n_ctx, int num_cus);
+hipError_t launch_rope_qkv(const void *qkv, int B, int S, int h_q, int h_kv, int d, int C, int pos0, float base,
+                           void *q_out, void *kc, void *vc, hipStream_t st);
+hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G, int S, int g, int d, int C,
+                            int n_ctx, void *workspace, void *out, int num_cus, hipStream_t st);
 hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp,
                             hipStream_t st);
 // out_mode 0: binary16 y with scales; 1: raw int32 accumulators.

@@ -94,3 +94,21 @@ def test_argument_errors_before_any_launch(L):
     assert L.qfc_rmsnorm(ctypes.byref(R(A, None, A, 1e-5, 0.0, None, A, None, None)), 1, 14368, s) == 2   # row too long
     assert L.qfc_rmsnorm(ctypes.byref(R(A, ODD, A, 1e-5, 0.0, None, A, None, None)), 1, 64, s) == 4
     assert L.qfc_rmsnorm(ctypes.byref(R(None, None, A, 1e-5, 0.0, None, A, None, None)), 1, 64, s) == 1
+    # attention-side operators
+    S8 = binding.AttnShape
+    A = ctypes.c_void_p(0x1000)
+    out = ctypes.c_size_t(0)
+    assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 128, 4096)), 1, ctypes.byref(out)) == 0
+    assert out.value == 8 * 64 * 4 * 130 * 4
+    assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 96, 4096)), 1, ctypes.byref(out)) == 2    # head size
+    assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 128, 4128)), 1, ctypes.byref(out)) == 1   # cache % 64
+    assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 6, 128, 4096)), 1, ctypes.byref(out)) == 1   # h_q % h_kv
+    assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 128, 4096)), 5, ctypes.byref(out)) == 2   # S * g > 16
+    sh = S8(1, 32, 8, 128, 4096)
+    assert L.qfc_attention(A, A, A, 1, 0, ctypes.byref(sh), A, 1 << 30, A, s) == 1        # n_ctx < S
+    assert L.qfc_attention(A, A, A, 1, 5000, ctypes.byref(sh), A, 1 << 30, A, s) == 1     # n_ctx > cache
+    assert L.qfc_attention(A, A, A, 1, 100, ctypes.byref(sh), A, 1024, A, s) == 3         # workspace too small
+    assert L.qfc_attention(A, A, ctypes.c_void_p(0x1008), 1, 100, ctypes.byref(sh), A, 1 << 30, A, s) == 4
+    assert L.qfc_rope_qkv(A, 1, 4096, ctypes.byref(sh), 10000.0, A, A, A, s) == 1           # position past the cache
+    assert L.qfc_rope_qkv(A, 1, 0, ctypes.byref(sh), 1.0, A, A, A, s) == 1                  # base must exceed 1
+    assert L.qfc_rope_qkv(None, 1, 0, ctypes.byref(sh), 10000.0, A, A, A, s) == 1

@@ -684,3 +684,95 @@ def test_rmsnorm_feeds_the_int8_layer():
     torch.cuda.synchronize()
     assert np.array_equal(out_a.cpu().numpy().view(np.uint16), out_b.cpu().numpy().view(np.uint16))
     layer.close()
+
+
+# ------------------------------------------------------------------ attention-side operators
+def _attn_shape(B, h_q, h_kv, d, C):
+    return binding.AttnShape(B, h_q, h_kv, d, C)
+
+
+@pytest.mark.parametrize("B,S,h_q,h_kv,d,C,pos0", [(1, 1, 4, 2, 64, 64, 0), (2, 3, 8, 2, 128, 128, 17),
+                                                   (1, 1, 32, 8, 128, 192, 131), (3, 2, 8, 4, 256, 64, 62),
+                                                   (1, 1, 2, 1, 128, 131072, 131071)])
+def test_rope_qkv_layout(B, S, h_q, h_kv, d, C, pos0):
+    print(f"rope B={B} S={S} h_q={h_q} h_kv={h_kv} d={d} C={C} pos0={pos0}", flush=True)
+    base = 500000.0 if d == 128 else 10000.0
+    W = (h_q + 2 * h_kv) * d
+    qkv = synth.activations(3800, B, S, B * S, W).reshape(B, S, W)
+    G, g = B * h_kv, h_q // h_kv
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+    q_out = torch.zeros((G, S * g, d), dtype=torch.float16, device=DEV)
+    # sentinels in the caches: nothing but the S new positions may change
+    kc = torch.full((G, C, d), 3.0, dtype=torch.float16, device=DEV)
+    vc = torch.full((G, d, C), 5.0, dtype=torch.float16, device=DEV)
+    binding.qfc_rope_qkv(torch.from_numpy(qkv).to(DEV), pos0, shape, base, q_out, kc, vc)
+    torch.cuda.synchronize()
+    q_ref, k_ref, v_ref = oracle.rope_qkv_layout(qkv, pos0, h_q, h_kv, d, base)
+    kc, vc = kc.cpu().numpy(), vc.cpu().numpy()
+
+    def close(a, b):  # one binary16 unit in the last place of the larger magnitude, or of 2^-10
+        a, b = a.astype(np.float64), b.astype(np.float64)
+        return np.all(np.abs(a - b) <= 2.0 ** -10 * np.maximum(np.maximum(np.abs(a), np.abs(b)), 2.0 ** -10))
+
+    assert close(q_out.cpu().numpy(), q_ref)
+    assert close(kc[:, pos0:pos0 + S], k_ref)
+    assert np.array_equal(vc[:, :, pos0:pos0 + S].view(np.uint16), v_ref.transpose(0, 2, 1).view(np.uint16))
+    kc[:, pos0:pos0 + S] = 3.0
+    vc[:, :, pos0:pos0 + S] = 5.0
+    assert np.all(kc == 3.0) and np.all(vc == 5.0)
+
+
+@pytest.mark.parametrize("B,S,h_q,h_kv,d,C,n_ctx", [(1, 1, 4, 4, 64, 64, 1), (1, 1, 4, 2, 64, 64, 33),
+                                                    (2, 1, 32, 8, 128, 1024, 1000), (1, 1, 8, 4, 256, 4096, 4096),
+                                                    (1, 4, 8, 2, 128, 512, 259), (3, 2, 16, 2, 128, 128, 65),
+                                                    (1, 1, 16, 1, 64, 8192, 8191), (1, 1, 32, 8, 128, 16384, 12345)])
+def test_attention_over_the_cache(B, S, h_q, h_kv, d, C, n_ctx):
+    print(f"attention B={B} S={S} h_q={h_q} h_kv={h_kv} d={d} C={C} n_ctx={n_ctx}", flush=True)
+    G, g = B * h_kv, h_q // h_kv
+    M = S * g
+    rng = np.random.default_rng(n_ctx * 31 + d)
+    q = rng.standard_normal((G, M, d)).astype(np.float16)
+    K = rng.standard_normal((G, C, d)).astype(np.float16)
+    V = rng.standard_normal((G, d, C)).astype(np.float16)
+    # a few dominant keys, so that the softmax is not flat; and poison past the end of the context
+    for gi in range(G):
+        K[gi, rng.integers(0, n_ctx)] = (q[gi, 0].astype(np.float32) * 2).astype(np.float16)
+    Kd, Vd = K.copy(), V.copy()
+    Kd[:, n_ctx:] = np.float16(np.nan)
+    Vd[:, :, n_ctx:] = np.float16(np.inf)
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+    ws = torch.empty(binding.qfc_attention_workspace_size(shape, S), dtype=torch.uint8, device=DEV)
+    out = torch.full((G, M, d), 9.0, dtype=torch.float16, device=DEV)
+    binding.qfc_attention(torch.from_numpy(q).to(DEV), torch.from_numpy(Kd).to(DEV), torch.from_numpy(Vd).to(DEV), S,
+                          n_ctx, shape, ws, out)
+    torch.cuda.synchronize()
+    ref = oracle.attention(q, K, V, n_ctx, S)
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    assert oracle.floored_rel_error(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
+
+
+def test_rope_then_attention_decode_step():
+    """One decode step end to end: the token's QKV row goes through the rotary kernel into the caches
+    and attention reads them; compared with the oracle's pipeline on the same binary16 caches."""
+    B, h_q, h_kv, d, C, pos0 = 2, 8, 2, 128, 256, 100
+    G, g = B * h_kv, h_q // h_kv
+    rng = np.random.default_rng(12)
+    K = rng.standard_normal((G, C, d)).astype(np.float16)
+    V = rng.standard_normal((G, d, C)).astype(np.float16)
+    qkv = synth.activations(3900, 0, 0, B, (h_q + 2 * h_kv) * d).reshape(B, 1, -1)
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+    q_out = torch.empty((G, g, d), dtype=torch.float16, device=DEV)
+    kc, vc = torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV)
+    ws = torch.empty(binding.qfc_attention_workspace_size(shape, 1), dtype=torch.uint8, device=DEV)
+    out = torch.empty((G, g, d), dtype=torch.float16, device=DEV)
+    binding.qfc_rope_qkv(torch.from_numpy(qkv).to(DEV), pos0, shape, 10000.0, q_out, kc, vc)
+    binding.qfc_attention(q_out, kc, vc, 1, pos0 + 1, shape, ws, out)
+    torch.cuda.synchronize()
+    q_ref, k_ref, v_ref = oracle.rope_qkv_layout(qkv, pos0, h_q, h_kv, d, 10000.0)
+    K[:, pos0] = k_ref[:, 0]
+    V[:, :, pos0] = v_ref[:, 0]
+    ref = oracle.attention(q_ref, K, V, pos0 + 1, 1)
+    assert oracle.floored_rel_error(out.cpu().numpy().reshape(G * g, d), ref.reshape(G * g, d)) <= TOL
+    # [G, g, d] is [B, h_q * d]: query head kv * g + j of batch b at row b, columns (kv * g + j) * d ..
+    assert out.reshape(B, h_q * d).shape == (B, h_q * d)
