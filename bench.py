@@ -346,6 +346,40 @@ def main():
     extra["rmsnorm_residual_quantize_m1024_k4096"] = rmsnorm_line()
     torch.cuda.empty_cache()
 
+    # ------------------------------------------------------------ attention-side operators (sections 3.6 and 3.8)
+    # One decode step of attention for Llama-3.1-8B (32 query heads, 8 KV heads of 128) per layer: rotary
+    # embedding + layout transformation + cache append, then attention over the cache (K^T and V in the
+    # role of weights).  Rotating caches so that every call reads HBM.
+    def attention_line(B, n_ctx, copies):
+        h_q, h_kv, d = 32, 8, 128
+        C = n_ctx
+        G, g = B * h_kv, h_q // h_kv
+        shape = binding.AttnShape(B, h_q, h_kv, d, C)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(SEED + 400)
+        kcs = [torch.randn((G, C, d), generator=gen, device=dev, dtype=torch.float32).half() for _ in range(copies)]
+        vcs = [torch.randn((G, C // 64, d, 64), generator=gen, device=dev, dtype=torch.float32).half() for _ in range(copies)]
+        qkv = torch.from_numpy(synth.activations(SEED + 400, 0, 0, B, (h_q + 2 * h_kv) * d)).to(dev).reshape(B, 1, -1)
+        q = torch.empty((G, g, d), dtype=torch.float16, device=dev)
+        out = torch.empty((G, g, d), dtype=torch.float16, device=dev)
+        ws = torch.empty(binding.qfc_attention_workspace_size(shape, 1), dtype=torch.uint8, device=dev)
+
+        def run():
+            for kc, vc in zip(kcs, vcs):
+                binding.qfc_rope_qkv(qkv, n_ctx - 1, shape, 500000.0, q, kc, vc)
+                binding.qfc_attention(q, kc, vc, 1, n_ctx, shape, ws, out)
+
+        run()
+        ms = event_ms(run, max(3, args.steps // 2)) / copies
+        nbytes = 2 * G * n_ctx * d * 2
+        return {"us": round(ms * 1e3, 2), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "kv_cache_MB": round(nbytes / 1e6, 1),
+                "launches": 3}
+
+    extra["decode_attention_llama8b_b1_ctx8192"] = attention_line(1, 8192, 12)
+    extra["decode_attention_llama8b_b8_ctx8192"] = attention_line(8, 8192, 3)
+    torch.cuda.empty_cache()
+
     # ------------------------------------------------------------ prefill (configs 4 and 5)
     if not args.skip_prefill:
         def prefill(fc_list, M, seed, reps=10):

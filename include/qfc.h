@@ -198,7 +198,8 @@ qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *args, int32_t M, int32_t K, void *
  * Layouts (sections 3.6 and 3.8), all binary16:
  *   queries  q      [G, S * g, d_head]   row s * g + j = query head kv * g + j of token s
  *   K cache  kcache [G, cache_size, d_head]   (the transposed operand of Q K^T, stored as weights)
- *   V cache  vcache [G, d_head, cache_size]
+ *   V cache  vcache [G, cache_size / 64, d_head, 64]   (d_head x cache position, cut into blocks of
+ *                   64 positions: element (d, p) of a group is at ((p / 64) * d_head + d) * 64 + p % 64)
  *   output   out    [G, S * g, d_head]   (for S = 1 this is [batch, h_q * d_head], the next layer's input)
  */
 typedef struct qfc_attn_shape {

@@ -183,6 +183,18 @@ def qfc_rope_qkv(qkv: torch.Tensor, pos0: int, shape: AttnShape, rope_base: floa
                               _ptr(vcache), _stream()), "qfc_rope_qkv")
 
 
+def vcache_physical(v_logical: torch.Tensor) -> torch.Tensor:
+    """[G, d_head, cache] -> the library's V cache layout [G, cache / 64, d_head, 64] (a copy)."""
+    G, d, C = v_logical.shape
+    return v_logical.reshape(G, d, C // 64, 64).permute(0, 2, 1, 3).contiguous()
+
+
+def vcache_logical(v_physical: torch.Tensor) -> torch.Tensor:
+    """Inverse of vcache_physical."""
+    G, nb, d, _ = v_physical.shape
+    return v_physical.permute(0, 2, 1, 3).reshape(G, d, nb * 64).contiguous()
+
+
 def qfc_attention_workspace_size(shape: AttnShape, S: int) -> int:
     out = ctypes.c_size_t(0)
     _check(lib().qfc_attention_workspace_size(ctypes.byref(shape), S, ctypes.byref(out)), "qfc_attention_workspace_size")

@@ -4,11 +4,13 @@
 //    projections (section 3.6 of the paper): the QKV layer's output [B, S, (h_q + 2 h_kv) d] goes
 //    to queries [B h_kv, S g, d] (g = h_q / h_kv query heads per KV head, row s g + j), the rotated
 //    keys are appended to the K cache [B h_kv, C, d] as rows pos0 + s and the values to the V cache
-//    [B h_kv, d, C] as columns pos0 + s.
+//    (d, cache position) as columns pos0 + s.
 // 2. The two matrix products of attention with the KV cache in the role of weights (section 3.8):
 //    the K cache is stored (cache position, d), i.e. K^T of Q K^T, the V cache (d, cache position);
-//    both are row-major [N, K] operands exactly like a layer's logical weight matrix, and 16 bytes
-//    of a row are one lane's MFMA operand.  Here the two products and the softmax between them run
+//    both are [N, K] operands exactly like a layer's logical weight matrix, and 16 bytes of a row
+//    are one lane's MFMA operand.  Physically the V cache is cut into blocks of 64 positions,
+//    [B h_kv, C / 64, d, 64]: a step of the kernel then reads 128 d contiguous bytes of V as it does
+//    of K, instead of d pieces of 128 bytes that lie a whole cache row apart.  Here the two products and the softmax between them run
 //    in one pass over the cache (the scores never leave registers): per step of 64 positions a
 //    wavefront computes S^T = K Q^T with v_mfma_f32_16x16x32_f16 (keys as rows), updates the running
 //    maximum and sum of every query row, and accumulates O^T += V P^T, where the positions are
@@ -49,9 +51,10 @@ __global__ __launch_bounds__(256) void rope_qkv_kernel(const _Float16 *__restric
     const int g = h_q / h_kv;
     if (head >= h_q + h_kv) {  // value head: no rotation, transposed into the cache
         const int kv = head - h_q - h_kv;
-        _Float16 *dst = vc + (size_t)(b * h_kv + kv) * d * C + (pos0 + s);
-        dst[(size_t)i * C] = src[i];
-        dst[(size_t)(i + half) * C] = src[i + half];
+        const int p = pos0 + s;
+        _Float16 *dst = vc + (((size_t)(b * h_kv + kv) * (C / 64) + p / 64) * d) * 64 + p % 64;
+        dst[(size_t)i * 64] = src[i];
+        dst[(size_t)(i + half) * 64] = src[i + half];
         return;
     }
     // angle = pos * base^(-2 i / d), in double so that long contexts keep the low bits of the angle
@@ -76,7 +79,7 @@ __global__ __launch_bounds__(256) void rope_qkv_kernel(const _Float16 *__restric
 struct AttnArgs {
     const _Float16 *q;   // [G, M, D]
     const _Float16 *kc;  // [G, C, D]
-    const _Float16 *vc;  // [G, D, C]
+    const _Float16 *vc;  // [G, C / 64, D, 64]
     float *ws_o;         // [G, splits, M, D] partial outputs (unnormalized)
     float *ws_ml;        // [G, splits, M, 2] partial (maximum, sum)
     _Float16 *out;       // [G, M, D]
@@ -106,7 +109,8 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         qf[j] = m < a.M ? *reinterpret_cast<const u32x4 *>(a.q + ((size_t)G * a.M + m) * D + 32 * j + 8 * r) : zero;
     }
     // positions a query row may see: those before the end of its own token
-    const int lim = m < a.M ? a.n_ctx - a.S + m / a.g + 1 : 0;
+    // (rows >= M are all-zero queries whose results are never stored: they see everything)
+    const int lim = m < a.M ? a.n_ctx - a.S + m / a.g + 1 : a.n_ctx;
 
     v4f acc[DT];
 #pragma unroll
@@ -141,7 +145,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     auto load_v = [&](int blk) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            const _Float16 *vrow = vbase + (size_t)(16 * dt + m) * a.C + blk * 64 + 8 * r;
+            const _Float16 *vrow = vbase + ((size_t)blk * D + 16 * dt + m) * 64 + 8 * r;
 #pragma unroll
             for (int u = 0; u < 2; ++u)
                 vf[dt][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vrow + 32 * u));
@@ -164,29 +168,40 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
             st[t] = acc_s;
         }
         if (blk + 1 < b1) load_k(blk + 1);
-        // ---- masked and scaled
+        // ---- scaled (in units of log 2, so that exponentials are bare v_exp_f32) and, in the steps that
+        // reach past the first query token's horizon, masked
         float sc[16];
-        bool ok[16];
         float bmax = kNegBig;
+        const bool edge = k0 + 64 > a.n_ctx - a.S + 1;  // same for the whole wavefront
+        if (!edge) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int pos = k0 + 32 * (t >> 1) + 8 * r + 4 * (t & 1) + i;
-                ok[4 * t + i] = pos < lim;
-                sc[4 * t + i] = ok[4 * t + i] ? st[t][i] * a.scale : kNegBig;
-                bmax = fmaxf(bmax, sc[4 * t + i]);
+            for (int e = 0; e < 16; ++e) {
+                sc[e] = st[e >> 2][e & 3] * a.scale;
+                bmax = fmaxf(bmax, sc[e]);
             }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t)
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const int pos = k0 + 32 * (t >> 1) + 8 * r + 4 * (t & 1) + i;
+                    sc[4 * t + i] = pos < lim ? st[t][i] * a.scale : kNegBig;
+                    bmax = fmaxf(bmax, sc[4 * t + i]);
+                }
+        }
         bmax = fmaxf(bmax, __shfl_xor(bmax, 16, 64));
         bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
         const float new_max = fmaxf(run_max, bmax);
-        const float corr = __expf(run_max - new_max);
+        const float corr = __builtin_amdgcn_exp2f(run_max - new_max);
         run_max = new_max;
         float psum = 0.0f;
         h8 pv[2];  // P^T operands of the two MFMA steps: positions of tiles (0, 1) and (2, 3)
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            const float p = ok[e] ? __expf(sc[e] - new_max) : 0.0f;
+            // a masked score is kNegBig: 2^(kNegBig - maximum) is 0 unless the row has seen no valid
+            // position yet (maximum = kNegBig), which the test on the score itself excludes
+            float p = __builtin_amdgcn_exp2f(sc[e] - new_max);
+            if (edge) p = sc[e] > 0.5f * kNegBig ? p : 0.0f;
             psum += p;
             pv[e >> 3][e & 7] = (_Float16)p;
         }
@@ -207,12 +222,15 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
                     vf[dt][u] = u32x4{w[0], w[1], w[2], w[3]};
                 }
         }
-        // ---- O^T = O^T corr + V P^T
+        // ---- O^T = O^T corr + V P^T (the running maxima settle early: most steps have corr = 1 in every lane)
+        const bool rescale = __any(corr != 1.0f);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             v4f o = acc[dt];
+            if (rescale) {
 #pragma unroll
-            for (int i = 0; i < 4; ++i) o[i] *= corr;
+                for (int i = 0; i < 4; ++i) o[i] *= corr;
+            }
 #pragma unroll
             for (int u = 0; u < 2; ++u) {
                 o = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, vf[dt][u]), pv[u], o, 0, 0, 0);
@@ -242,7 +260,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
 #pragma unroll
         for (int w = 0; w < 4; ++w) {
             const float *src = lds + (size_t)w * 16 * PITCH + (size_t)mm * PITCH;
-            const float f = __expf(src[D] - mx);
+            const float f = __builtin_amdgcn_exp2f(src[D] - mx);
             o += f * src[dd];
             l += f * src[D + 1];
         }
@@ -274,7 +292,7 @@ __global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
     float top = mx;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) top = fmaxf(top, __shfl_xor(top, off, 64));
-    const float f = lane < a.splits ? __expf(mx - top) : 0.0f;
+    const float f = lane < a.splits ? __builtin_amdgcn_exp2f(mx - top) : 0.0f;
     float lsum = f * l;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off, 64);
@@ -342,7 +360,7 @@ hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G
     a.C = C;
     a.n_ctx = n_ctx;
     a.splits = attn_splits(G, n_ctx, num_cus);
-    a.scale = 1.0f / sqrtf((float)d);
+    a.scale = 1.4426950408889634f / sqrtf((float)d);  // scores in units of log 2
     a.ws_o = static_cast<float *>(workspace);
     a.ws_ml = a.ws_o + (size_t)G * kAttnMaxSplits * a.M * d;
     a.out = static_cast<_Float16 *>(out);

@@ -704,9 +704,10 @@ def test_rope_qkv_layout(B, S, h_q, h_kv, d, C, pos0):
     q_out = torch.zeros((G, S * g, d), dtype=torch.float16, device=DEV)
     # sentinels in the caches: nothing but the S new positions may change
     kc = torch.full((G, C, d), 3.0, dtype=torch.float16, device=DEV)
-    vc = torch.full((G, d, C), 5.0, dtype=torch.float16, device=DEV)
+    vc = torch.full((G, C // 64, d, 64), 5.0, dtype=torch.float16, device=DEV)
     binding.qfc_rope_qkv(torch.from_numpy(qkv).to(DEV), pos0, shape, base, q_out, kc, vc)
     torch.cuda.synchronize()
+    vc = binding.vcache_logical(vc)
     q_ref, k_ref, v_ref = oracle.rope_qkv_layout(qkv, pos0, h_q, h_kv, d, base)
     kc, vc = kc.cpu().numpy(), vc.cpu().numpy()
 
@@ -743,7 +744,7 @@ def test_attention_over_the_cache(B, S, h_q, h_kv, d, C, n_ctx):
     shape = _attn_shape(B, h_q, h_kv, d, C)
     ws = torch.empty(binding.qfc_attention_workspace_size(shape, S), dtype=torch.uint8, device=DEV)
     out = torch.full((G, M, d), 9.0, dtype=torch.float16, device=DEV)
-    binding.qfc_attention(torch.from_numpy(q).to(DEV), torch.from_numpy(Kd).to(DEV), torch.from_numpy(Vd).to(DEV), S,
+    binding.qfc_attention(torch.from_numpy(q).to(DEV), torch.from_numpy(Kd).to(DEV), binding.vcache_physical(torch.from_numpy(Vd).to(DEV)), S,
                           n_ctx, shape, ws, out)
     torch.cuda.synchronize()
     ref = oracle.attention(q, K, V, n_ctx, S)
@@ -763,7 +764,7 @@ def test_rope_then_attention_decode_step():
     qkv = synth.activations(3900, 0, 0, B, (h_q + 2 * h_kv) * d).reshape(B, 1, -1)
     shape = _attn_shape(B, h_q, h_kv, d, C)
     q_out = torch.empty((G, g, d), dtype=torch.float16, device=DEV)
-    kc, vc = torch.from_numpy(K).to(DEV), torch.from_numpy(V).to(DEV)
+    kc, vc = torch.from_numpy(K).to(DEV), binding.vcache_physical(torch.from_numpy(V).to(DEV))
     ws = torch.empty(binding.qfc_attention_workspace_size(shape, 1), dtype=torch.uint8, device=DEV)
     out = torch.empty((G, g, d), dtype=torch.float16, device=DEV)
     binding.qfc_rope_qkv(torch.from_numpy(qkv).to(DEV), pos0, shape, 10000.0, q_out, kc, vc)
