@@ -277,12 +277,13 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     }
 }
 
-// grid = (M, G), one workgroup of 64 lanes per query row: lane s first takes the (maximum, sum) pair
-// of split s (splits <= 64) and the factors exp(maximum_s - maximum) are shared by lane broadcast;
-// then lane l sums columns l, l + 64, .. of the partial outputs in split order.
+// grid = (M, G, D / 64), one wavefront per query row and 64 columns: lane s first takes the (maximum,
+// sum) pair of split s (splits <= 64) and the factors 2^(maximum_s - maximum) are shared by lane
+// broadcast; then lane l sums column 64 z + l of the partial outputs in split order.
 template <int D>
 __global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
     const int G = blockIdx.y, mm = blockIdx.x, lane = threadIdx.x;
+    const int col = 64 * blockIdx.z + lane;
     const size_t row0 = ((size_t)G * a.splits) * a.M + mm;  // partial row of split s: row0 + s * M
     float mx = kNegBig, l = 0.0f;
     if (lane < a.splits) {
@@ -296,17 +297,19 @@ __global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
     float lsum = f * l;
 #pragma unroll
     for (int off = 32; off > 0; off >>= 1) lsum += __shfl_xor(lsum, off, 64);
-    float o[D / 64];
+    float o = 0.0f;
+    const float *src = a.ws_o + row0 * D + col;
+    const size_t step = (size_t)a.M * D;
+    int s = 0;
+    for (; s + 8 <= a.splits; s += 8) {  // eight loads in flight
+        float v[8];
 #pragma unroll
-    for (int c = 0; c < D / 64; ++c) o[c] = 0.0f;
-    for (int s = 0; s < a.splits; ++s) {
-        const float fs = __shfl(f, s, 64);
-        const float *src = a.ws_o + (row0 + (size_t)s * a.M) * D;
+        for (int u = 0; u < 8; ++u) v[u] = src[(size_t)(s + u) * step];
 #pragma unroll
-        for (int c = 0; c < D / 64; ++c) o[c] = fmaf(fs, src[64 * c + lane], o[c]);
+        for (int u = 0; u < 8; ++u) o = fmaf(__shfl(f, s + u, 64), v[u], o);
     }
-#pragma unroll
-    for (int c = 0; c < D / 64; ++c) a.out[((size_t)G * a.M + mm) * D + 64 * c + lane] = (_Float16)(o[c] / lsum);
+    for (; s < a.splits; ++s) o = fmaf(__shfl(f, s, 64), src[(size_t)s * step], o);
+    a.out[((size_t)G * a.M + mm) * D + col] = (_Float16)(o / lsum);
 }
 
 template <int D>
@@ -322,7 +325,7 @@ hipError_t launch_attn(const AttnArgs &a, int G, hipStream_t st) {
     attn_partial_kernel<D><<<dim3((unsigned)a.splits, (unsigned)G), 256, lds, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.splits == 1) return e;
-    attn_combine_kernel<D><<<dim3((unsigned)a.M, (unsigned)G), 64, 0, st>>>(a);
+    attn_combine_kernel<D><<<dim3((unsigned)a.M, (unsigned)G, D / 64), 64, 0, st>>>(a);
     return hipGetLastError();
 }
 
