@@ -87,9 +87,12 @@ struct AttnArgs {
     float scale;
 };
 
-// Workgroup = 4 wavefronts.  grid = (splits, G).
+// Workgroup = 4 wavefronts.  grid = (splits, G).  A step covers TP pairs of score tiles = 32 TP positions:
+// 64 for head sizes up to 128, 32 for 256 (whose operands of 64 positions would leave one wavefront per SIMD).
 template <int D>
 __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
+    constexpr int TP = D <= 128 ? 2 : 1;
+    constexpr int SP = 32 * TP;  // positions per step
     constexpr int DJ = D / 32;  // MFMA steps along d of the score product
     constexpr int DT = D / 16;  // row tiles of O^T
     constexpr int PITCH = D + 4;  // floats per staged query row: O^T column, maximum, sum (16-byte aligned rows)
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     const int m = lane & 15, r = lane >> 4;
     const int G = blockIdx.y;
     const int part = blockIdx.x * 4 + wave, parts = a.splits * 4;
-    const int nb = (a.n_ctx + 63) / 64;  // steps of 64 positions
+    const int nb = (a.n_ctx + SP - 1) / SP;  // steps
     const int b0 = (int)((long)part * nb / parts), b1 = (int)((long)(part + 1) * nb / parts);
 
     // Q^T operand: lane (m, r) holds Q[m][32 j + 8 r .. + 7]; rows >= M are zero
@@ -131,12 +134,12 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     // k0 + 32 u + 8 r .. + 7: its V operand of MFMA step u is one 16-byte load, and the four lanes r
     // of a V row read 64 contiguous bytes.  K: lane (w = lane & 15, r) reads d = 32 j + 8 r .. + 7 of
     // its position's row (a K row is contiguous whatever the order of the rows).
-    u32x4 kf[4][DJ];
-    u32x4 vf[DT][2];
+    u32x4 kf[2 * TP][DJ];
+    u32x4 vf[DT][TP];
     auto load_k = [&](int blk) {
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
-            const int pos = blk * 64 + 32 * (t >> 1) + 8 * (m >> 2) + 4 * (t & 1) + (m & 3);
+        for (int t = 0; t < 2 * TP; ++t) {
+            const int pos = blk * SP + 32 * (t >> 1) + 8 * (m >> 2) + 4 * (t & 1) + (m & 3);
             const _Float16 *krow = kbase + (size_t)pos * D + 8 * r;
 #pragma unroll
             for (int j = 0; j < DJ; ++j) kf[t][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(krow + 32 * j));
@@ -145,9 +148,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     auto load_v = [&](int blk) {
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
-            const _Float16 *vrow = vbase + ((size_t)blk * D + 16 * dt + m) * 64 + 8 * r;
+            const int p0 = blk * SP;  // first position of the step: block p0 / 64 of the cache, column p0 % 64
+            const _Float16 *vrow = vbase + ((size_t)(p0 / 64) * D + 16 * dt + m) * 64 + p0 % 64 + 8 * r;
 #pragma unroll
-            for (int u = 0; u < 2; ++u)
+            for (int u = 0; u < TP; ++u)
                 vf[dt][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vrow + 32 * u));
         }
     };
@@ -156,11 +160,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         load_v(b0);
     }
     for (int blk = b0; blk < b1; ++blk) {
-        const int k0 = blk * 64;
+        const int k0 = blk * SP;
         // ---- S^T = K Q^T; lane (m, r) holds positions k0 + 32 (t / 2) + 8 r + 4 (t % 2) + i
-        v4f st[4];
+        v4f st[2 * TP];
 #pragma unroll
-        for (int t = 0; t < 4; ++t) {
+        for (int t = 0; t < 2 * TP; ++t) {
             v4f acc_s = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
             for (int j = 0; j < DJ; ++j)
@@ -170,18 +174,18 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         if (blk + 1 < b1) load_k(blk + 1);
         // ---- scaled (in units of log 2, so that exponentials are bare v_exp_f32) and, in the steps that
         // reach past the first query token's horizon, masked
-        float sc[16];
+        float sc[8 * TP];
         float bmax = kNegBig;
-        const bool edge = k0 + 64 > a.n_ctx - a.S + 1;  // same for the whole wavefront
+        const bool edge = k0 + SP > a.n_ctx - a.S + 1;  // same for the whole wavefront
         if (!edge) {
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
+            for (int e = 0; e < 8 * TP; ++e) {
                 sc[e] = st[e >> 2][e & 3] * a.scale;
                 bmax = fmaxf(bmax, sc[e]);
             }
         } else {
 #pragma unroll
-            for (int t = 0; t < 4; ++t)
+            for (int t = 0; t < 2 * TP; ++t)
 #pragma unroll
                 for (int i = 0; i < 4; ++i) {
                     const int pos = k0 + 32 * (t >> 1) + 8 * r + 4 * (t & 1) + i;
@@ -195,9 +199,9 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         const float corr = __builtin_amdgcn_exp2f(run_max - new_max);
         run_max = new_max;
         float psum = 0.0f;
-        h8 pv[2];  // P^T operands of the two MFMA steps: positions of tiles (0, 1) and (2, 3)
+        h8 pv[TP];  // P^T operands of the MFMA steps: positions of tiles (0, 1), (2, 3)
 #pragma unroll
-        for (int e = 0; e < 16; ++e) {
+        for (int e = 0; e < 8 * TP; ++e) {
             // a masked score is kNegBig: 2^(kNegBig - maximum) is 0 unless the row has seen no valid
             // position yet (maximum = kNegBig), which the test on the score itself excludes
             float p = __builtin_amdgcn_exp2f(sc[e] - new_max);
@@ -207,11 +211,11 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
         }
         run_sum = run_sum * corr + psum;
         // positions at or past the end of the context may hold anything (0 * NaN would poison the sum)
-        if (k0 + 64 > a.n_ctx) {
+        if (k0 + SP > a.n_ctx) {
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-                for (int u = 0; u < 2; ++u) {
+                for (int u = 0; u < TP; ++u) {
                     const int p0 = k0 + 32 * u + 8 * r;
                     uint32_t w[4] = {vf[dt][u].x, vf[dt][u].y, vf[dt][u].z, vf[dt][u].w};
 #pragma unroll
@@ -232,7 +236,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
                 for (int i = 0; i < 4; ++i) o[i] *= corr;
             }
 #pragma unroll
-            for (int u = 0; u < 2; ++u) {
+            for (int u = 0; u < TP; ++u) {
                 o = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, vf[dt][u]), pv[u], o, 0, 0, 0);
             }
             acc[dt] = o;
