@@ -255,6 +255,21 @@ def main():
     # three PyTorch element-wise kernels between and after them.  8 independent blocks (0.79 GB of
     # weights) are walked so that every launch reads HBM; both sequences are replayed from a captured
     # graph so that the host does not limit either.
+    # Replays of a captured graph: the host does not limit sequences of many short launches.
+    def graph_ms(fn, reps):
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            fn()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            fn()
+        g.replay()
+        return event_ms(g.replay, reps)
+
+
     def mlp_block():
         fc_gu, fc_dn = synth.LLAMA_FCS_W4[2], synth.LLAMA_FCS_W4[3]
         blocks = []
@@ -293,23 +308,10 @@ def main():
                 binding.qfc_forward(dn.handle, act, y_dn)
                 torch.add(y_dn, h, out=out)
 
-        def graph_ms(fn, reps):
-            side = torch.cuda.Stream()
-            side.wait_stream(torch.cuda.current_stream())
-            with torch.cuda.stream(side):
-                fn()
-            torch.cuda.current_stream().wait_stream(side)
-            torch.cuda.synchronize()
-            g = torch.cuda.CUDAGraph()
-            with torch.cuda.graph(g):
-                fn()
-            g.replay()
-            return event_ms(g.replay, reps) / len(blocks)
-
         unfused()
-        ms_f = graph_ms(fused, args.steps)
+        ms_f = graph_ms(fused, args.steps) / len(blocks)
         out_f = out.clone()
-        ms_u = graph_ms(unfused_graphable, args.steps)
+        ms_u = graph_ms(unfused_graphable, args.steps) / len(blocks)
         agree = bool(torch.allclose(out_f.float(), out.float(), rtol=4e-3, atol=4e-3 * float(out.float().abs().max())))
         for gu, dn in blocks:
             gu.close()
@@ -376,6 +378,54 @@ def main():
                 "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "kv_cache_MB": round(nbytes / 1e6, 1),
                 "launches": 3}
 
+    # One whole decoder layer of Llama-3.1-8B at M = 1 with 8192 cached positions, every operator from this
+    # library: rmsnorm, QKV, rotary + append, attention (2 launches), O + residual, rmsnorm, gate+up with gated
+    # output, down + residual: 10 launches.  Four layers with their own weights and caches are walked.
+    def decoder_layer_line(n_ctx=8192, n_layers=4):
+        hidden, h_q, h_kv, d, ffn = 4096, 32, 8, 128, 14336
+        shape = binding.AttnShape(1, h_q, h_kv, d, n_ctx)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(SEED + 500)
+        Ls = []
+        for li in range(n_layers):
+            ws4 = []
+            for i, fc in enumerate(synth.LLAMA_FCS_W4):
+                wq, s = synth.weights(SEED + 500, li, i, fc)
+                ws4.append(binding.QuantLinear(wq, s, fc.fmt, max_m=8))
+                del wq, s
+            kc = torch.randn((h_kv, n_ctx, d), generator=gen, device=dev, dtype=torch.float32).half()
+            vc = torch.randn((h_kv, n_ctx // 64, d, 64), generator=gen, device=dev, dtype=torch.float32).half()
+            Ls.append((ws4, kc, vc))
+        E = lambda *sh: torch.empty(sh, dtype=torch.float16, device=dev)
+        h = torch.from_numpy(synth.activations(SEED + 500, 0, 0, 1, hidden)).to(dev)
+        gamma = torch.ones(hidden, dtype=torch.float16, device=dev)
+        x1, qkv, q, att, h1, x2, act, h2 = E(1, hidden), E(1, 1, (h_q + 2 * h_kv) * d), E(h_kv, h_q // h_kv, d), \
+            E(h_kv, h_q // h_kv, d), E(1, hidden), E(1, hidden), E(1, ffn), E(1, hidden)
+        wsp = torch.empty(binding.qfc_attention_workspace_size(shape, 1), dtype=torch.uint8, device=dev)
+
+        def run():
+            for (l_qkv, l_o, l_gu, l_dn), kc, vc in Ls:
+                binding.qfc_rmsnorm(h, gamma, 1e-5, 0.0, y=x1)
+                binding.qfc_forward(l_qkv.handle, x1, qkv.view(1, -1))
+                binding.qfc_rope_qkv(qkv, n_ctx - 1, shape, 500000.0, q, kc, vc)
+                binding.qfc_attention(q, kc, vc, 1, n_ctx, shape, wsp, att)
+                binding.qfc_forward_fused(l_o.handle, att.view(1, h_q * d), h1, residual=h)
+                binding.qfc_rmsnorm(h1, gamma, 1e-5, 0.0, y=x2)
+                binding.qfc_forward_fused(l_gu.handle, x2, act, activation=binding.QFC_ACT_SILU, gated_output=True)
+                binding.qfc_forward_fused(l_dn.handle, act, h2, residual=h1)
+
+        ms = graph_ms(run, args.steps) / n_layers
+        nbytes = sum(synth.algorithmic_bytes(fc, 1) for fc in synth.LLAMA_FCS_W4) + 2 * h_kv * n_ctx * d * 2
+        for ws4, _, _ in Ls:
+            for l in ws4:
+                l.close()
+        return {"us_per_layer": round(ms * 1e3, 2), "launches": 10, "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                "bytes_per_layer_MB": round(nbytes / 1e6, 1),
+                "note": "weights (int4 group-32) + KV cache (fp16) streamed once per layer; 32 such layers + LM head = one token"}
+
+    extra["decode_layer_llama8b_m1_ctx8192"] = decoder_layer_line()
+    torch.cuda.empty_cache()
     extra["decode_attention_llama8b_b1_ctx8192"] = attention_line(1, 8192, 12)
     extra["decode_attention_llama8b_b8_ctx8192"] = attention_line(8, 8192, 3)
     torch.cuda.empty_cache()

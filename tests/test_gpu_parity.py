@@ -777,3 +777,77 @@ def test_rope_then_attention_decode_step():
     assert oracle.floored_rel_error(out.cpu().numpy().reshape(G * g, d), ref.reshape(G * g, d)) <= TOL
     # [G, g, d] is [B, h_q * d]: query head kv * g + j of batch b at row b, columns (kv * g + j) * d ..
     assert out.reshape(B, h_q * d).shape == (B, h_q * d)
+
+
+# ------------------------------------------------------------------ one decoder layer, decode step, every operator chained
+def test_decoder_layer_decode_step_chain():
+    """rmsnorm -> QKV layer -> rotary + layouts + cache append -> attention -> O layer + residual ->
+    rmsnorm -> gate+up layer with gated output -> down layer + residual, M = B token rows.
+    Every stage is compared with the oracle applied to the tensors the previous GPU stage stored
+    (so each comparison carries one stage's error), and the layouts line up without any glue."""
+    B, hidden, h_q, h_kv, d, ffn, C, pos0 = 2, 512, 8, 2, 64, 1024, 128, 77
+    G, g = B * h_kv, h_q // h_kv
+    eps = 1e-5
+    rng = np.random.default_rng(41)
+
+    def mk(name, K, N, fmt, seed):
+        fc = synth.FC(name, K, N, fmt)
+        wq, s = synth.weights(4000, seed, 0, fc)
+        if fmt == "w4g32":
+            s = (s.astype(np.float32) * 0.25).astype(np.float16)  # keep the chain's magnitudes moderate
+        else:
+            s = (s * 0.05).astype(np.float32)
+        return wq, s, _layer(wq, s, fmt)
+
+    wq_qkv, s_qkv, l_qkv = mk("qkv", hidden, (h_q + 2 * h_kv) * d, "w4g32", 1)
+    wq_o, s_o, l_o = mk("o", h_q * d, hidden, "w4g32", 2)
+    wq_gu, s_gu, l_gu = mk("gate_up", hidden, 2 * ffn, "w4g32", 3)
+    wq_dn, s_dn, l_dn = mk("down", ffn, hidden, "w4g32", 4)
+    h0 = synth.activations(4000, 0, 9, B, hidden)
+    g1 = (1 + 0.1 * rng.standard_normal(hidden)).astype(np.float16)
+    g2 = (1 + 0.1 * rng.standard_normal(hidden)).astype(np.float16)
+    K0 = rng.standard_normal((G, C, d)).astype(np.float16)
+    V0 = rng.standard_normal((G, d, C)).astype(np.float16)
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+
+    T = lambda a: torch.from_numpy(a).to(DEV)
+    E = lambda *sh: torch.empty(sh, dtype=torch.float16, device=DEV)
+    h_d, g1_d, g2_d = T(h0), T(g1), T(g2)
+    kc, vc = T(K0), binding.vcache_physical(T(V0))
+    x1, qkv, q, att, h1, x2, a, h2 = E(B, hidden), E(B, 1, (h_q + 2 * h_kv) * d), E(G, g, d), E(G, g, d), E(B, hidden), E(B, hidden), E(B, ffn), E(B, hidden)
+    ws = torch.empty(binding.qfc_attention_workspace_size(shape, 1), dtype=torch.uint8, device=DEV)
+
+    binding.qfc_rmsnorm(h_d, g1_d, eps, 0.0, y=x1)
+    binding.qfc_forward(l_qkv.handle, x1, qkv.view(B, -1))
+    binding.qfc_rope_qkv(qkv, pos0, shape, 10000.0, q, kc, vc)
+    binding.qfc_attention(q, kc, vc, 1, pos0 + 1, shape, ws, att)
+    binding.qfc_forward_fused(l_o.handle, att.view(B, h_q * d), h1, residual=h_d)
+    binding.qfc_rmsnorm(h1, g2_d, eps, 0.0, y=x2)
+    binding.qfc_forward_fused(l_gu.handle, x2, a, activation=binding.QFC_ACT_SILU, gated_output=True)
+    binding.qfc_forward_fused(l_dn.handle, a, h2, residual=h1)
+    torch.cuda.synchronize()
+    N = lambda t: t.cpu().numpy()
+    err = oracle.floored_rel_error
+
+    _, x1_ref = oracle.rmsnorm(h0, g1, eps)
+    assert err(N(x1), x1_ref) <= TOL
+    assert err(N(qkv).reshape(B, -1), oracle.fc_weight_only(N(x1), wq_qkv, s_qkv, 32)) <= TOL
+    q_ref, k_ref, v_ref = oracle.rope_qkv_layout(N(qkv), pos0, h_q, h_kv, d, 10000.0)
+    assert err(N(q).reshape(G * g, d), q_ref.reshape(G * g, d).astype(np.float64)) <= TOL
+    K1, V1 = K0.copy(), V0.copy()
+    K1[:, pos0], V1[:, :, pos0] = N(kc)[:, pos0], N(binding.vcache_logical(vc))[:, :, pos0]
+    assert err(K1[:, pos0], k_ref[:, 0].astype(np.float64)) <= TOL and np.array_equal(V1[:, :, pos0], v_ref[:, 0])
+    att_ref = oracle.attention(N(q), K1, V1, pos0 + 1, 1)
+    assert err(N(att).reshape(G * g, d), att_ref.reshape(G * g, d)) <= TOL
+    # the attention output [G, g, d] is [B, h_q * d] as it stands: head kv * g + j of batch b
+    o_ref = oracle.add_residual(oracle.fc_weight_only(N(att).reshape(B, h_q * d), wq_o, s_o, 32), h0)
+    assert err(N(h1), o_ref) <= TOL
+    _, x2_ref = oracle.rmsnorm(N(h1), g2, eps)
+    assert err(N(x2), x2_ref) <= TOL
+    a_ref = oracle.gated_output(oracle.fc_weight_only(N(x2), wq_gu, s_gu, 32), oracle.SILU)
+    assert err(N(a), a_ref) <= TOL
+    h2_ref = oracle.add_residual(oracle.fc_weight_only(N(a), wq_dn, s_dn, 32), N(h1))
+    assert err(N(h2), h2_ref) <= TOL
+    assert np.all(np.isfinite(N(h2)))
+    for l in (l_qkv, l_o, l_gu, l_dn):
+        l.close()
