@@ -51,10 +51,12 @@ struct GemmI8Args {
 };
 
 // Epilogue shared by the product kernels.
-template <int BN, int BM, int OUT_MODE, int TN, int TM>
-__device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM], uint4 *lds, int nt, int mt, int wn,
-                                         int wm, int wave, int lane) {
-    constexpr int WN = BN / 2, WM = BM / 2;
+// A wavefront holds TN x TM tiles of 32 x 32 outputs whose first weight row is n_base and first
+// token row is m_base.
+template <int OUT_MODE, int TN, int TM>
+__device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM], uint4 *lds, int n_base, int m_base,
+                                         int wave, int lane) {
+    constexpr int WN = TN * 32;
     // Epilogue.  After the MFMAs a lane holds one token row m (lane % 32) and, per
     // group of four accumulator registers, four consecutive n: stored as they are,
     // every store instruction would touch 32 different rows of y with 8 bytes
@@ -65,10 +67,10 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
     if (OUT_MODE == 0 && (a.N % 8) == 0) {
         constexpr int PITCH = (WN + 8) * 2;  // bytes per staged row
         char *region = reinterpret_cast<char *>(lds) + wave * (32 * PITCH);
-        const int n0 = nt * BN + wn * WN;
+        const int n0 = n_base;
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
-            const int mrow0 = mt * BM + wm * WM + j * 32;
+            const int mrow0 = m_base + j * 32;
             const int m = mrow0 + (lane & 31);
             const float sxm = m < a.M ? a.sx[m] : 0.0f;
             const bool has_res = a.res != nullptr;
@@ -115,7 +117,7 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
     const bool vec_ok = (a.N % 4) == 0;
 #pragma unroll
     for (int j = 0; j < TM; ++j) {
-        const int m = mt * BM + wm * WM + j * 32 + (lane & 31);
+        const int m = m_base + j * 32 + (lane & 31);
         if (m >= a.M) continue;
         float sxm = 1.0f;
         if (OUT_MODE == 0) sxm = a.sx[m];
@@ -123,7 +125,7 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
         for (int i = 0; i < TN; ++i) {
 #pragma unroll
             for (int q = 0; q < 4; ++q) {
-                const int n = nt * BN + wn * WN + i * 32 + 8 * q + 4 * (lane >> 5);
+                const int n = n_base + i * 32 + 8 * q + 4 * (lane >> 5);
                 if (n >= a.N) continue;
                 if (OUT_MODE == 0) {
                     _Float16 *y = static_cast<_Float16 *>(a.out) + (size_t)m * a.N + n;
@@ -274,7 +276,135 @@ __global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_ke
         }
     }
 
-    epilogue<BN, BM, OUT_MODE, TN, TM>(a, acc, lds, nt, mt, wn, wm, wave, lane);
+    epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wn * WN, mt * BM + wm * WM, wave, lane);
+}
+
+// Direct global -> LDS copy of one wavefront: lane l moves 16 bytes from base + 16 l to LDS byte
+// address lds_base + 16 l.  Assembly, so that the compiler's own waits for the register loads of the
+// kernel below do not have to account for it; M0 carries the LDS base (nothing else there uses M0).
+__device__ __forceinline__ void copy_tile_to_lds(const void *base, uint32_t lane_offset, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(base), "s"(lds_base)
+                 : "memory");
+}
+
+// Variant with the weights going from memory straight into the MFMA operand registers.  The packed
+// layout already is operand order (a lane's 16 bytes of a KiB tile are 16 consecutive k of one row),
+// so only the activations, which all four wavefronts share, pass through LDS: 64 instead of 96-128
+// LDS bytes per clock at full MFMA rate.  Tile 256 (n) x 128 (m); wavefront w owns weight rows
+// 64 w .. 64 w + 63 and all 128 token rows (2 x 4 tiles of 32 x 32, 128 accumulator registers) and
+// loads only its own weights, PW stages of 64 k ahead, into a ring of registers (slot = stage % PW,
+// refilled right after the MFMAs that consumed it).  Activation stages: ring of NS LDS stages of
+// 8 KiB, two tile copies per wavefront and stage.  Copies and loads past the end of K repeat the
+// last stage, so that every iteration issues the same number of operations and the waits are
+// constants.  The number of stages must be a multiple of PW.
+template <int NS, int PW, int OUT_MODE>
+__global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
+    constexpr int BN = 256, BM = 128, TN = 2, TM = 4;
+    static_assert(NS >= 3 && NS <= 5, "wait table below");
+    extern __shared__ uint4 lds[];  // NS stages of 8 tiles x 64 vectors
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int total = a.n_tiles * a.m_tiles;
+    int logical = blockIdx.x;
+    if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
+    const int nt = logical / a.m_tiles, mt = logical % a.m_tiles;
+    const int KT = a.Kp / 64;  // stages
+
+    // weights: operand (i, ks) of a stage = rows 32 i + (lane & 31) of the wavefront's 64, k = 32 ks + 16 (lane >> 5) ..
+    const uint4 *wsrc[TN];
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+        const int row = 32 * i + (lane & 31);
+        wsrc[i] = a.w + ((size_t)(nt * (BN / 16) + 4 * wave + (row >> 4)) * KT) * 64 + (lane >> 5) * 16 + (row & 15);
+    }
+    v4i wreg[PW][TN][2];
+    auto load_w = [&](int slot, int kt) {
+        const int kc = min(kt, KT - 1);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+                wreg[slot][i][ks] =
+                    __builtin_nontemporal_load(reinterpret_cast<const v4i *>(wsrc[i] + (size_t)kc * 64 + ks * 32));
+    };
+    // activations: tiles wave and wave + 4 of the 8 token-row tiles of a stage
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
+    const uint4 *xsrc = a.x + ((size_t)(mt * (BM / 16)) * KT) * 64;
+    auto issue_x = [&](int kt) {
+        const int kc = min(kt, KT - 1);
+#pragma unroll
+        for (int h = 0; h < 2; ++h) {
+            const int t = wave + 4 * h;
+            copy_tile_to_lds(xsrc + ((size_t)t * KT + kc) * 64, lane * 16, lds0 + ((kt % NS) * 8 + t) * 1024);
+        }
+    };
+
+    v16i acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+    // prologue: PW weight stages, then NS - 1 activation stages
+#pragma unroll
+    for (int p = 0; p < PW; ++p) load_w(p, p);
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p) issue_x(p);
+
+    // A wavefront issues per iteration 2 copies (after the barrier) and 4 loads (at the end).  What it has
+    // issued after the copies of stage kt when it reaches the top of iteration kt: for the stages of the
+    // prologue (kt <= NS - 2) the 2 (NS - 2 - kt) later prologue copies and 6 per iteration since, i.e.
+    // 2 (NS - 2) + 4 kt; afterwards the 4 loads of the copies' own iteration and NS - 2 whole iterations.
+    for (int kt0 = 0; kt0 < KT; kt0 += PW) {
+#pragma unroll
+        for (int u = 0; u < PW; ++u) {
+            const int kt = kt0 + u;
+            if (kt == 0)
+                wait_vmcnt<2 * (NS - 2)>();
+            else if (kt == 1)
+                wait_vmcnt<2 * (NS - 2) + 4>();
+            else if (kt == 2 && NS > 3)
+                wait_vmcnt<2 * (NS - 2) + 8>();
+            else if (kt == 3 && NS > 4)
+                wait_vmcnt<2 * (NS - 2) + 12>();
+            else
+                wait_vmcnt<6 * (NS - 2) + 4>();
+            asm volatile("s_barrier" ::: "memory");
+            issue_x(kt + NS - 1);
+            const uint4 *lx = lds + (kt % NS) * 512;
+            v4i xf[2][TM];
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    const int row = 32 * j + (lane & 31);
+                    xf[ks][j] = __builtin_bit_cast(v4i, lx[(row >> 4) * 64 + (2 * ks + (lane >> 5)) * 16 + (row & 15)]);
+                }
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+                for (int i = 0; i < TN; ++i)
+#pragma unroll
+                    for (int j = 0; j < TM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[u][i][ks], xf[ks][j], acc[i][j], 0, 0, 0);
+            load_w(u, kt + PW);
+        }
+    }
+    wait_vmcnt<0>();
+    epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wave * 64, mt * BM, wave, lane);
+}
+
+template <int NS, int PW, int OUT_MODE>
+hipError_t launch_dw(GemmI8Args a, hipStream_t st) {
+    constexpr size_t lds_bytes = (size_t)NS * 8 * 1024;
+    static_assert(lds_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks in the same LDS");
+    if ((a.Kp / 64) % PW != 0) return hipErrorInvalidValue;
+    a.n_tiles = (a.N + 255) / 256;
+    a.m_tiles = (a.M + 127) / 128;
+    gemm_i8_dw_kernel<NS, PW, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
+    return hipGetLastError();
 }
 
 template <int BN, int BM, int KTS, int NS, int OUT_MODE>
@@ -297,18 +427,16 @@ hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
 
 template <int OUT_MODE>
 hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
-    // Tile shapes measured on MI355X.  128 x 128 (two workgroups per compute unit,
-    // four-stage ring of 64-k stages) is the fastest or within a few percent of it
-    // on every layer shape at M = 1024.  The 256 x 128 tile (128 x 64 per wavefront:
-    // 25 % fewer LDS bytes per MFMA, still two wavefronts per SIMD) is 10-30 %
-    // faster once there are enough tiles to fill the chip for at least two full
-    // rounds (LM head at M = 2048: 1.37 ms against 1.81 ms), and slower below that.
-    // The others stay selectable for experiments.
+    // Tile shapes measured on MI355X.  The direct-weights kernel (256 x 128 tile, weights from memory
+    // into operand registers, activations through LDS) is the fastest wherever its tiles cover at
+    // least three quarters of the compute units: 1.7 POP/s on the gate+up shape at M = 1024 against
+    // 1.56 (128 x 128) and 1.50 (256 x 128 through LDS), 1.9-1.95 POP/s at M = 2048 and 4096.  Below
+    // that (N = 4096 at M = 1024 gives 128 such tiles) the 128 x 128 tile with its 64 x 64 outputs per
+    // wavefront spreads the work over more SIMDs and wins.  The others stay selectable for experiments.
     int variant = tuning().gemm_variant;
     if (variant == 0) {
-        const long slots = 2L * num_cus;
         const long big_tiles = (long)((a.N + 255) / 256) * ((a.M + 127) / 128);
-        variant = (big_tiles >= 2 * slots || (big_tiles >= slots && big_tiles % slots == 0)) ? 6 : 3;
+        variant = 4 * big_tiles >= 3L * num_cus ? 10 : 3;
     }
     switch (variant) {
         case 1: return launch_variant<256, 256, 1, 4, OUT_MODE>(a, st);
@@ -316,6 +444,8 @@ hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
         case 4: return launch_variant<128, 128, 2, 3, OUT_MODE>(a, st);
         case 5: return launch_variant<128, 256, 1, 3, OUT_MODE>(a, st);
         case 6: return launch_variant<256, 128, 1, 3, OUT_MODE>(a, st);
+        case 10: return launch_dw<4, 4, OUT_MODE>(a, st);
+        case 11: return launch_dw<5, 4, OUT_MODE>(a, st);
         default: return launch_variant<128, 128, 1, 4, OUT_MODE>(a, st);
     }
 }
