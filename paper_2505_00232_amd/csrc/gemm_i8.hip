@@ -297,11 +297,15 @@ __device__ __forceinline__ void copy_tile_to_lds(const void *base, uint32_t lane
 // 8 KiB, two tile copies per wavefront and stage.  Copies and loads past the end of K repeat the
 // last stage, so that every iteration issues the same number of operations and the waits are
 // constants.  The number of stages must be a multiple of PW.
-template <int NS, int PW, int OUT_MODE>
+// TM = 4: 256 x 128 tile; TM = 2: 256 x 64 tile (twice the tiles for small outputs, twice the weight
+// loads per MFMA).
+template <int NS, int PW, int TM, int OUT_MODE>
 __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
-    constexpr int BN = 256, BM = 128, TN = 2, TM = 4;
-    static_assert(NS >= 3 && NS <= 5, "wait table below");
-    extern __shared__ uint4 lds[];  // NS stages of 8 tiles x 64 vectors
+    constexpr int BN = 256, BM = 32 * TM, TN = 2;
+    constexpr int XT = BM / 16;  // activation tiles (KiB) per stage
+    constexpr int CP = XT / 4;   // copies per wavefront and stage
+    static_assert(NS >= 3 && NS <= 5 && (TM == 2 || TM == 4), "wait table below");
+    extern __shared__ uint4 lds[];  // NS stages of XT tiles x 64 vectors
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int total = a.n_tiles * a.m_tiles;
@@ -327,15 +331,15 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
                 wreg[slot][i][ks] =
                     __builtin_nontemporal_load(reinterpret_cast<const v4i *>(wsrc[i] + (size_t)kc * 64 + ks * 32));
     };
-    // activations: tiles wave and wave + 4 of the 8 token-row tiles of a stage
+    // activations: tiles wave (and wave + 4) of the XT token-row tiles of a stage
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
     const uint4 *xsrc = a.x + ((size_t)(mt * (BM / 16)) * KT) * 64;
     auto issue_x = [&](int kt) {
         const int kc = min(kt, KT - 1);
 #pragma unroll
-        for (int h = 0; h < 2; ++h) {
+        for (int h = 0; h < CP; ++h) {
             const int t = wave + 4 * h;
-            copy_tile_to_lds(xsrc + ((size_t)t * KT + kc) * 64, lane * 16, lds0 + ((kt % NS) * 8 + t) * 1024);
+            copy_tile_to_lds(xsrc + ((size_t)t * KT + kc) * 64, lane * 16, lds0 + ((kt % NS) * XT + t) * 1024);
         }
     };
 
@@ -353,27 +357,27 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p) issue_x(p);
 
-    // A wavefront issues per iteration 2 copies (after the barrier) and 4 loads (at the end).  What it has
+    // A wavefront issues per iteration CP copies (after the barrier) and 4 loads (at the end).  What it has
     // issued after the copies of stage kt when it reaches the top of iteration kt: for the stages of the
-    // prologue (kt <= NS - 2) the 2 (NS - 2 - kt) later prologue copies and 6 per iteration since, i.e.
-    // 2 (NS - 2) + 4 kt; afterwards the 4 loads of the copies' own iteration and NS - 2 whole iterations.
+    // prologue (kt <= NS - 2) the CP (NS - 2 - kt) later prologue copies and CP + 4 per iteration since, i.e.
+    // CP (NS - 2) + 4 kt; afterwards the 4 loads of the copies' own iteration and NS - 2 whole iterations.
     for (int kt0 = 0; kt0 < KT; kt0 += PW) {
 #pragma unroll
         for (int u = 0; u < PW; ++u) {
             const int kt = kt0 + u;
             if (kt == 0)
-                wait_vmcnt<2 * (NS - 2)>();
+                wait_vmcnt<CP * (NS - 2)>();
             else if (kt == 1)
-                wait_vmcnt<2 * (NS - 2) + 4>();
+                wait_vmcnt<CP * (NS - 2) + 4>();
             else if (kt == 2 && NS > 3)
-                wait_vmcnt<2 * (NS - 2) + 8>();
+                wait_vmcnt<CP * (NS - 2) + 8>();
             else if (kt == 3 && NS > 4)
-                wait_vmcnt<2 * (NS - 2) + 12>();
+                wait_vmcnt<CP * (NS - 2) + 12>();
             else
-                wait_vmcnt<6 * (NS - 2) + 4>();
+                wait_vmcnt<(CP + 4) * (NS - 2) + 4>();
             asm volatile("s_barrier" ::: "memory");
             issue_x(kt + NS - 1);
-            const uint4 *lx = lds + (kt % NS) * 512;
+            const uint4 *lx = lds + (kt % NS) * (XT * 64);
             v4i xf[2][TM];
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
@@ -396,14 +400,14 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wave * 64, mt * BM, wave, lane);
 }
 
-template <int NS, int PW, int OUT_MODE>
+template <int NS, int PW, int TM, int OUT_MODE>
 hipError_t launch_dw(GemmI8Args a, hipStream_t st) {
-    constexpr size_t lds_bytes = (size_t)NS * 8 * 1024;
+    constexpr size_t lds_bytes = (size_t)NS * (2 * TM) * 1024 < 4 * 32 * (64 + 8) * 2 ? 4 * 32 * (64 + 8) * 2 : (size_t)NS * (2 * TM) * 1024;
     static_assert(lds_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks in the same LDS");
     if ((a.Kp / 64) % PW != 0) return hipErrorInvalidValue;
     a.n_tiles = (a.N + 255) / 256;
-    a.m_tiles = (a.M + 127) / 128;
-    gemm_i8_dw_kernel<NS, PW, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
+    a.m_tiles = (a.M + 32 * TM - 1) / (32 * TM);
+    gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
     return hipGetLastError();
 }
 
@@ -427,16 +431,17 @@ hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
 
 template <int OUT_MODE>
 hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
-    // Tile shapes measured on MI355X.  The direct-weights kernel (256 x 128 tile, weights from memory
-    // into operand registers, activations through LDS) is the fastest wherever its tiles cover at
-    // least three quarters of the compute units: 1.7 POP/s on the gate+up shape at M = 1024 against
-    // 1.56 (128 x 128) and 1.50 (256 x 128 through LDS), 1.9-1.95 POP/s at M = 2048 and 4096.  Below
-    // that (N = 4096 at M = 1024 gives 128 such tiles) the 128 x 128 tile with its 64 x 64 outputs per
-    // wavefront spreads the work over more SIMDs and wins.  The others stay selectable for experiments.
+    // Tile shapes measured on MI355X.  The direct-weights kernel with the 256 x 128 tile is the fastest
+    // wherever its tiles cover at least three quarters of the compute units: 1.7 POP/s on the gate+up
+    // shape at M = 1024 against 1.6 (128 x 128, both operands through LDS) and 1.5 (256 x 128 through
+    // LDS), 1.9-2.0 POP/s at M = 2048 and 4096.  Below that (N = 4096 at M = 1024 gives 128 such
+    // tiles) its 256 x 64 form doubles the number of tiles and is as fast as or up to 8 % faster than
+    // the 128 x 128 kernel; with many tiles it is the slowest (two weight loads per MFMA pair).  The
+    // kernels that stage both operands stay selectable for experiments.
     int variant = tuning().gemm_variant;
     if (variant == 0) {
         const long big_tiles = (long)((a.N + 255) / 256) * ((a.M + 127) / 128);
-        variant = 4 * big_tiles >= 3L * num_cus ? 10 : 3;
+        variant = 4 * big_tiles >= 3L * num_cus ? 10 : 12;
     }
     switch (variant) {
         case 1: return launch_variant<256, 256, 1, 4, OUT_MODE>(a, st);
@@ -444,8 +449,9 @@ hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
         case 4: return launch_variant<128, 128, 2, 3, OUT_MODE>(a, st);
         case 5: return launch_variant<128, 256, 1, 3, OUT_MODE>(a, st);
         case 6: return launch_variant<256, 128, 1, 3, OUT_MODE>(a, st);
-        case 10: return launch_dw<4, 4, OUT_MODE>(a, st);
-        case 11: return launch_dw<5, 4, OUT_MODE>(a, st);
+        case 10: return launch_dw<4, 4, 4, OUT_MODE>(a, st);
+        case 11: return launch_dw<5, 4, 4, OUT_MODE>(a, st);
+        case 12: return launch_dw<4, 4, 2, OUT_MODE>(a, st);
         default: return launch_variant<128, 128, 1, 4, OUT_MODE>(a, st);
     }
 }
