@@ -294,17 +294,23 @@ __device__ __forceinline__ void copy_tile_to_lds(const void *base, uint32_t lane
 // 64 w .. 64 w + 63 and all 128 token rows (2 x 4 tiles of 32 x 32, 128 accumulator registers) and
 // loads only its own weights, PW stages of 64 k ahead, into a ring of registers (slot = stage % PW,
 // refilled right after the MFMAs that consumed it).  Activation stages: ring of NS LDS stages of
-// 8 KiB, two tile copies per wavefront and stage.  Copies and loads past the end of K repeat the
+// 8 KiB (4 KiB for the 64-row tile), CP tile copies per wavefront and stage; the ring is deep (8-14
+// stages) because the wait count that is safe for both kinds of operation grows with it (see below).  Copies and loads past the end of K repeat the
 // last stage, so that every iteration issues the same number of operations and the waits are
 // constants.  The number of stages must be a multiple of PW.
 // TM = 4: 256 x 128 tile; TM = 2: 256 x 64 tile (twice the tiles for small outputs, twice the weight
 // loads per MFMA).
+//
+// The weight loads are assembly too: the compiler counts only the loads it knows when it places its
+// waits, and with the copies in between those waits would drain most of the prefetch.  A load's
+// destination registers are handed back to the compiler (an empty asm that "redefines" them) right
+// after the explicit wait that covers the load, so that no MFMA can be scheduled ahead of that wait.
 template <int NS, int PW, int TM, int OUT_MODE>
 __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     constexpr int BN = 256, BM = 32 * TM, TN = 2;
     constexpr int XT = BM / 16;  // activation tiles (KiB) per stage
     constexpr int CP = XT / 4;   // copies per wavefront and stage
-    static_assert(NS >= 3 && NS <= 5 && (TM == 2 || TM == 4), "wait table below");
+    static_assert(NS >= 3 && (TM == 2 || TM == 4), "tile shapes");
     extern __shared__ uint4 lds[];  // NS stages of XT tiles x 64 vectors
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -328,8 +334,10 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-                wreg[slot][i][ks] =
-                    __builtin_nontemporal_load(reinterpret_cast<const v4i *>(wsrc[i] + (size_t)kc * 64 + ks * 32));
+                asm volatile("global_load_dwordx4 %0, %1, off nt"
+                             : "=&v"(wreg[slot][i][ks])
+                             : "v"(wsrc[i] + (size_t)kc * 64 + ks * 32)
+                             : "memory");
     };
     // activations: tiles wave (and wave + 4) of the XT token-row tiles of a stage
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
@@ -357,25 +365,26 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p) issue_x(p);
 
-    // A wavefront issues per iteration CP copies (after the barrier) and 4 loads (at the end).  What it has
-    // issued after the copies of stage kt when it reaches the top of iteration kt: for the stages of the
-    // prologue (kt <= NS - 2) the CP (NS - 2 - kt) later prologue copies and CP + 4 per iteration since, i.e.
-    // CP (NS - 2) + 4 kt; afterwards the 4 loads of the copies' own iteration and NS - 2 whole iterations.
+    // Waiting.  Copies into LDS and loads into registers share one counter (vmcnt) but do NOT complete
+    // in order relative to each other - only within their own kind (measured: with waits that assumed
+    // one common order, stages were read before their copies had landed).  At the top of iteration kt
+    // a wavefront has issued, after the copies of stage kt, the copies of NS - 2 later stages (CP each),
+    // and after the loads of stage kt the loads of PW - 1 later stages (4 each) - from iteration 0 on,
+    // thanks to the prologue.  If at most kAllowed = min(CP (NS - 2), 4 (PW - 1)) operations are
+    // outstanding, neither stage kt's copies nor its loads can be among them: an unfinished copy would
+    // have all CP (NS - 2) later copies behind it, an unfinished load all 4 (PW - 1) later loads.
+    constexpr int kAfterCopies = CP * (NS - 2), kAfterLoads = 4 * (PW - 1);
+    constexpr int kAllowed = kAfterCopies < kAfterLoads ? kAfterCopies : kAfterLoads;
     for (int kt0 = 0; kt0 < KT; kt0 += PW) {
 #pragma unroll
         for (int u = 0; u < PW; ++u) {
             const int kt = kt0 + u;
-            if (kt == 0)
-                wait_vmcnt<CP * (NS - 2)>();
-            else if (kt == 1)
-                wait_vmcnt<CP * (NS - 2) + 4>();
-            else if (kt == 2 && NS > 3)
-                wait_vmcnt<CP * (NS - 2) + 8>();
-            else if (kt == 3 && NS > 4)
-                wait_vmcnt<CP * (NS - 2) + 12>();
-            else
-                wait_vmcnt<(CP + 4) * (NS - 2) + 4>();
+            wait_vmcnt<kAllowed>();
             asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int ks = 0; ks < 2; ++ks) asm volatile("" : "+v"(wreg[u][i][ks]));
             issue_x(kt + NS - 1);
             const uint4 *lx = lds + (kt % NS) * (XT * 64);
             v4i xf[2][TM];
@@ -405,6 +414,14 @@ hipError_t launch_dw(GemmI8Args a, hipStream_t st) {
     constexpr size_t lds_bytes = (size_t)NS * (2 * TM) * 1024 < 4 * 32 * (64 + 8) * 2 ? 4 * 32 * (64 + 8) * 2 : (size_t)NS * (2 * TM) * 1024;
     static_assert(lds_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks in the same LDS");
     if ((a.Kp / 64) % PW != 0) return hipErrorInvalidValue;
+    static_assert(lds_bytes <= 80 * 1024, "two workgroups per compute unit");
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
     a.n_tiles = (a.N + 255) / 256;
     a.m_tiles = (a.M + 32 * TM - 1) / (32 * TM);
     gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
@@ -431,13 +448,13 @@ hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
 
 template <int OUT_MODE>
 hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
-    // Tile shapes measured on MI355X.  The direct-weights kernel with the 256 x 128 tile is the fastest
-    // wherever its tiles cover at least three quarters of the compute units: 1.7 POP/s on the gate+up
-    // shape at M = 1024 against 1.6 (128 x 128, both operands through LDS) and 1.5 (256 x 128 through
-    // LDS), 1.9-2.0 POP/s at M = 2048 and 4096.  Below that (N = 4096 at M = 1024 gives 128 such
-    // tiles) its 256 x 64 form doubles the number of tiles and is as fast as or up to 8 % faster than
-    // the 128 x 128 kernel; with many tiles it is the slowest (two weight loads per MFMA pair).  The
-    // kernels that stage both operands stay selectable for experiments.
+    // Tile shapes measured on MI355X.  The direct-weights kernel with the 256 x 128 tile is used
+    // wherever its tiles cover at least three quarters of the compute units: on the Llama shapes it
+    // is level with the 128 x 128 kernel (both operands through LDS) at M = 1024 and 10-17 % faster at
+    // M = 2048 and 4096 (1.9-1.95 POP/s).  Below that (N = 4096 at M = 1024 gives 128 such tiles) its
+    // 256 x 64 form doubles the number of tiles and is 3-7 % faster than the 128 x 128 kernel; with
+    // many tiles it is the slowest (two weight loads per MFMA pair).  The kernels that stage both
+    // operands stay selectable for experiments.
     int variant = tuning().gemm_variant;
     if (variant == 0) {
         const long big_tiles = (long)((a.N + 255) / 256) * ((a.M + 127) / 128);
@@ -449,9 +466,10 @@ hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
         case 4: return launch_variant<128, 128, 2, 3, OUT_MODE>(a, st);
         case 5: return launch_variant<128, 256, 1, 3, OUT_MODE>(a, st);
         case 6: return launch_variant<256, 128, 1, 3, OUT_MODE>(a, st);
-        case 10: return launch_dw<4, 4, 4, OUT_MODE>(a, st);
-        case 11: return launch_dw<5, 4, 4, OUT_MODE>(a, st);
-        case 12: return launch_dw<4, 4, 2, OUT_MODE>(a, st);
+        case 10: return launch_dw<8, 4, 4, OUT_MODE>(a, st);
+        case 11: return launch_dw<6, 4, 4, OUT_MODE>(a, st);
+        case 12: return launch_dw<14, 4, 2, OUT_MODE>(a, st);
+        case 13: return launch_dw<8, 4, 2, OUT_MODE>(a, st);
         default: return launch_variant<128, 128, 1, 4, OUT_MODE>(a, st);
     }
 }
