@@ -100,9 +100,10 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int m = lane & 15, r = lane >> 4;
     const int G = blockIdx.y;
-    const int part = blockIdx.x * 4 + wave, parts = a.splits * 4;
+    const int part = blockIdx.x, parts = a.splits;
     const int nb = (a.n_ctx + SP - 1) / SP;  // steps
-    const int b0 = (int)((long)part * nb / parts), b1 = (int)((long)(part + 1) * nb / parts);
+    // the workgroup takes a contiguous range of steps; its wavefronts take every fourth step of it
+    const int b0 = (int)((long)part * nb / parts) + wave, b1 = (int)((long)(part + 1) * nb / parts);
 
     // Q^T operand: lane (m, r) holds Q[m][32 j + 8 r .. + 7]; rows >= M are zero
     u32x4 qf[DJ];
@@ -142,7 +143,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
             const int pos = blk * SP + 32 * (t >> 1) + 8 * (m >> 2) + 4 * (t & 1) + (m & 3);
             const _Float16 *krow = kbase + (size_t)pos * D + 8 * r;
 #pragma unroll
-            for (int j = 0; j < DJ; ++j) kf[t][j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(krow + 32 * j));
+            for (int j = 0; j < DJ; ++j) kf[t][j] = *reinterpret_cast<const u32x4 *>(krow + 32 * j);
         }
     };
     auto load_v = [&](int blk) {
@@ -152,14 +153,14 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
             const _Float16 *vrow = vbase + ((size_t)(p0 / 64) * D + 16 * dt + m) * 64 + p0 % 64 + 8 * r;
 #pragma unroll
             for (int u = 0; u < TP; ++u)
-                vf[dt][u] = __builtin_nontemporal_load(reinterpret_cast<const u32x4 *>(vrow + 32 * u));
+                vf[dt][u] = *reinterpret_cast<const u32x4 *>(vrow + 32 * u);
         }
     };
     if (b0 < b1) {
         load_k(b0);
         load_v(b0);
     }
-    for (int blk = b0; blk < b1; ++blk) {
+    for (int blk = b0; blk < b1; blk += 4) {
         const int k0 = blk * SP;
         // ---- S^T = K Q^T; lane (m, r) holds positions k0 + 32 (t / 2) + 8 r + 4 (t % 2) + i
         v4f st[2 * TP];
@@ -171,7 +172,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
                 acc_s = __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(h8, kf[t][j]), __builtin_bit_cast(h8, qf[j]), acc_s, 0, 0, 0);
             st[t] = acc_s;
         }
-        if (blk + 1 < b1) load_k(blk + 1);
+        if (blk + 4 < b1) load_k(blk + 4);
         // ---- scaled (in units of log 2, so that exponentials are bare v_exp_f32) and, in the steps that
         // reach past the first query token's horizon, masked
         float sc[8 * TP];
@@ -241,7 +242,7 @@ __global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
             }
             acc[dt] = o;
         }
-        if (blk + 1 < b1) load_v(blk + 1);
+        if (blk + 4 < b1) load_v(blk + 4);
     }
     run_sum += __shfl_xor(run_sum, 16, 64);
     run_sum += __shfl_xor(run_sum, 32, 64);
