@@ -296,22 +296,6 @@ constexpr int DEX_BYTES = 64 * 64 * 4;            // half of a wavefront's accum
 constexpr int DEPI_PITCH = (64 + 8) * 2;
 static_assert(8 * DEX_BYTES <= kDirectLdsBytes && 32 * DEPI_PITCH <= DEX_BYTES, "exchange and store staging fit in the rings");
 
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {  // vmcnt <= N, LDS operations done
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
-}
-
-// Direct global -> LDS copy of one wavefront: lane l moves 16 bytes from
-// base + offset(l) to LDS byte address lds_base + 16 l.  Written as assembly
-// because the compiler, when it knows about such a copy, makes every later LDS
-// read wait for ALL outstanding copies (it cannot tell ring slots apart), which
-// would serialize the prefetch ring; the waits are explicit here instead.  M0
-// carries the LDS base (nothing else in this kernel uses M0).
-__device__ __forceinline__ void copy16_to_lds(const void *base, uint32_t lane_offset, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(base), "s"(lds_base)
-                 : "memory");
-}
-
 // eight biased codes -> eight scaled binary16 values (k ascending) as an MFMA operand
 __device__ __forceinline__ v8h dequant_frag(uint32_t w, h2 s) {
     const h2 c1032 = {(_Float16)1032.0f, (_Float16)1032.0f};

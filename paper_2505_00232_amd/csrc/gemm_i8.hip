@@ -30,14 +30,6 @@ typedef int v16i __attribute__((ext_vector_type(16)));
 typedef __attribute__((address_space(1))) const void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
-// Wait until at most N vector-memory operations are outstanding and all LDS
-// operations are done (gfx9 s_waitcnt encoding: vmcnt in bits 3:0 and 15:14,
-// lgkmcnt in bits 11:8, expcnt left at its maximum).
-template <int N>
-__device__ __forceinline__ void wait_vmcnt() {
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
-}
-
 __host__ __device__ inline int stages_total(int Kp, int bk) { return Kp / bk; }
 
 struct GemmI8Args {
@@ -279,14 +271,6 @@ __global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_ke
     epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wn * WN, mt * BM + wm * WM, wave, lane);
 }
 
-// Direct global -> LDS copy of one wavefront: lane l moves 16 bytes from base + 16 l to LDS byte
-// address lds_base + 16 l.  Assembly, so that the compiler's own waits for the register loads of the
-// kernel below do not have to account for it; M0 carries the LDS base (nothing else there uses M0).
-__device__ __forceinline__ void copy_tile_to_lds(const void *base, uint32_t lane_offset, uint32_t lds_base) {
-    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(base), "s"(lds_base)
-                 : "memory");
-}
-
 // Variant with the weights going from memory straight into the MFMA operand registers.  The packed
 // layout already is operand order (a lane's 16 bytes of a KiB tile are 16 consecutive k of one row),
 // so only the activations, which all four wavefronts share, pass through LDS: 64 instead of 96-128
@@ -347,7 +331,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
 #pragma unroll
         for (int h = 0; h < CP; ++h) {
             const int t = wave + 4 * h;
-            copy_tile_to_lds(xsrc + ((size_t)t * KT + kc) * 64, lane * 16, lds0 + ((kt % NS) * XT + t) * 1024);
+            copy16_to_lds(xsrc + ((size_t)t * KT + kc) * 64, lane * 16, lds0 + ((kt % NS) * XT + t) * 1024);
         }
     };
 

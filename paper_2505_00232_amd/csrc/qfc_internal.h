@@ -123,6 +123,25 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
                        hipStream_t st);
 hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void *scales,
                          hipStream_t st);
+// ---- helpers of the kernels that copy tiles from memory straight into LDS
+// Wait until at most N vector-memory operations are outstanding and all LDS operations are done
+// (gfx9 s_waitcnt encoding: vmcnt in bits 3:0 and 15:14, lgkmcnt in bits 11:8, expcnt left at its
+// maximum).
+template <int N>
+__device__ __forceinline__ void wait_vmcnt() {
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (0x7 << 4) | (0x0 << 8));
+}
+
+// Direct global -> LDS copy of one wavefront: lane l moves 16 bytes from base + lane_offset(l) to
+// LDS byte address lds_base + 16 l.  Written as assembly because the compiler, when it knows
+// about such a copy, makes every later LDS read wait for ALL outstanding copies (it cannot tell
+// ring slots apart), which would serialize a prefetch ring; the kernels place their waits
+// themselves.  M0 carries the LDS base (nothing else in those kernels uses M0).
+__device__ __forceinline__ void copy16_to_lds(const void *base, uint32_t lane_offset, uint32_t lds_base) {
+    asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(base), "s"(lds_base)
+                 : "memory");
+}
+
 // ---- per-token int8 quantization steps shared by the kernels that produce quantized activations
 typedef unsigned short us2 __attribute__((ext_vector_type(2)));
 
