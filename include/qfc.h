@@ -222,8 +222,10 @@ qfc_status_t qfc_attention_workspace_size(const qfc_attn_shape_t *shape, int32_t
 /* Attention with the KV cache in the role of weights (section 3.8):
  * out = softmax(q K^T / sqrt(d_head)) V per group, over the first n_ctx cache
  * positions; the S query tokens are the last S of them (token s sees positions
- * 0 .. n_ctx - S + s).  S * g <= 16 (decode: S = 1).  Positions >= n_ctx of the
- * caches are never used, whatever they hold.  The scores are not materialized.
+ * 0 .. n_ctx - S + s).  Up to 16 query rows per KV head (S * g <= 16, decode) the
+ * context is split over workgroups; with more (prefill) a wavefront owns 32 query rows
+ * and walks the positions they see.  Positions >= n_ctx of the caches are never used,
+ * whatever they hold.  The scores are not materialized.
  * workspace: device scratch of at least qfc_attention_workspace_size bytes, 16-byte aligned. */
 qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache, int32_t S, int32_t n_ctx,
                            const qfc_attn_shape_t *shape, void *workspace, size_t workspace_bytes,

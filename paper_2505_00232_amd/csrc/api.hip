@@ -250,6 +250,7 @@ qfc_status_t qfc_rope_qkv(const void *qkv_f16, int32_t S, int32_t pos0, const qf
 }
 
 static size_t attn_workspace(const qfc_attn_shape_t *a, int32_t S) {
+    if (S * (a->h_q / a->h_kv) > 16) return 256;  // many query rows: one pass per wavefront, no partial results
     const size_t rows = (size_t)a->batch * a->h_kv * kAttnMaxSplits * (size_t)(S * (a->h_q / a->h_kv));
     return rows * (a->d_head + 2) * sizeof(float);
 }
@@ -258,7 +259,6 @@ qfc_status_t qfc_attention_workspace_size(const qfc_attn_shape_t *a, int32_t S, 
     if (!bytes) return QFC_ERR_INVALID_ARG;
     const qfc_status_t s = check_attn_shape(a, S);
     if (s != QFC_OK) return s;
-    if (S * (a->h_q / a->h_kv) > 16) return QFC_ERR_UNSUPPORTED;
     *bytes = attn_workspace(a, S);
     return QFC_OK;
 }
@@ -271,7 +271,6 @@ qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache
     if (!q || !kcache || !vcache || !workspace || !out_f16 || n_ctx < S || n_ctx > a->cache_size)
         return QFC_ERR_INVALID_ARG;
     const int g = a->h_q / a->h_kv;
-    if (S * g > 16) return QFC_ERR_UNSUPPORTED;
     if (!aligned16(q) || !aligned16(kcache) || !aligned16(vcache) || !aligned16(workspace) || !aligned16(out_f16))
         return QFC_ERR_ALIGNMENT;
     if (workspace_bytes < attn_workspace(a, S)) return QFC_ERR_BUFFER_TOO_SMALL;

@@ -317,6 +317,232 @@ __global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
     a.out[((size_t)G * a.M + mm) * D + col] = (_Float16)(o / lsum);
 }
 
+// ---------------------------------------------------------------- attention, many query rows (prefill)
+// More than 16 query rows per KV head.  A workgroup of 4 wavefronts owns 128 query rows, a
+// wavefront 32 of them (the columns of v_mfma_f32_32x32x16_f16), and they walk the positions the
+// block may see together, in steps of 32: the step's K rows and V block are copied once into LDS
+// (direct-to-LDS copies, ring of NS stages, one bare s_barrier per step) and every wavefront reads
+// its MFMA operands from there: S^T = K Q^T (32 positions x 32 queries), running maximum / sum per
+// query (a query's 16 scores of a step sit in two lanes), O^T += V P^T.  As in the decode kernel
+// the rows of the score tile are assigned to positions so that a lane's eight probabilities of an
+// MFMA step are eight contiguous positions (row i = 16 c + 8 b + 4 h + r is position
+// k0 + 16 c + 8 h + 4 b + r): P goes from the first product's result registers into the second
+// product's operand registers as it is, and a lane's V operand is one 16-byte read.
+// LDS layouts (16-byte chunks, XOR-swizzled so that the operand reads are conflict free; the copy
+// writes LDS linearly, so the swizzle is applied to the address it reads from memory):
+//   K stage: row = position of the step (32), D / 8 chunks per row; chunk o of row p sits at o ^ swz(p)
+//   V stage: row = d (D), 4 chunks per row (32 positions); chunk c of row d sits at c ^ ((d >> 2) & 3)
+// Causal: rows of token s see positions 0 .. n_ctx - S + s; the block stops at the last position
+// its last row sees, rows that see less mask the rest.  grid = (blocks of 128 query rows, G), long
+// blocks first.
+template <int D>
+struct PrefillCfg {
+    static constexpr int CPR = D / 8;                   // 16-byte chunks per K row
+    static constexpr int KBYTES = 32 * D * 2;           // K rows of a step
+    static constexpr int STAGE = 2 * KBYTES;            // + the V block of the step
+    static constexpr int NS = D <= 128 ? 4 : 3;         // LDS stages
+    static constexpr int COPIES = STAGE / 1024 / 4;     // copies per wavefront and stage
+    __device__ static int swz(int p) { return D >= 128 ? (p & 15) : ((p >> 1) & 7); }
+};
+
+template <int D>
+__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
+    typedef float v16f __attribute__((ext_vector_type(16)));
+    typedef PrefillCfg<D> Cfg;
+    constexpr int DJ = D / 16;  // MFMA steps along d of the score product
+    constexpr int DT = D / 32;  // row tiles of O^T
+    constexpr int NS = Cfg::NS, CP = Cfg::COPIES;
+    extern __shared__ uint4 lds_raw[];
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int q = lane & 31, h = lane >> 5;
+    const int G = blockIdx.y;
+    const int block = (int)gridDim.x - 1 - (int)blockIdx.x;  // the blocks with the longest walks start first
+    const int r0 = (block * 4 + wave) * 32;                   // first query row of the wavefront
+    const int m = r0 + q;
+    const bool real = m < a.M;
+    const int lim = real ? a.n_ctx - a.S + m / a.g + 1 : a.n_ctx;
+    const int lo_full = a.n_ctx - a.S + min(r0, a.M - 1) / a.g + 1;  // positions every row of the wavefront sees
+    const int block_last = min(block * 128 + 127, a.M - 1);
+    const int nb = (a.n_ctx - a.S + block_last / a.g + 1 + 31) / 32;  // steps of the whole workgroup
+
+    // Q^T operand: lane (q, h) holds Q[m][16 j + 8 h .. + 7]
+    u32x4 qf[DJ];
+#pragma unroll
+    for (int j = 0; j < DJ; ++j) {
+        const u32x4 zero = {0, 0, 0, 0};
+        qf[j] = real ? *reinterpret_cast<const u32x4 *>(a.q + ((size_t)G * a.M + m) * D + 16 * j + 8 * h) : zero;
+    }
+    v16f acc[DT];
+#pragma unroll
+    for (int t = 0; t < DT; ++t)
+#pragma unroll
+        for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
+    float run_max = kNegBig, run_sum = 0.0f;
+
+    // ---- copies: the stage's bytes are CP * 4 KiB pieces; wavefront w issues pieces w, w + 4, ..
+    const char *kbase = reinterpret_cast<const char *>(a.kc + (size_t)G * a.C * D);
+    const char *vbase = reinterpret_cast<const char *>(a.vc + (size_t)G * D * a.C);
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds_raw;
+    uint32_t src_off[CP];  // byte offset of this lane's 16 bytes inside the step's K rows / V block (step-invariant part)
+#pragma unroll
+    for (int i = 0; i < CP; ++i) {
+        const int piece = wave + 4 * i;      // KiB piece of the stage
+        const int L = piece * 64 + lane;     // linear 16-byte chunk of the stage
+        if (piece < Cfg::KBYTES / 1024) {
+            const int p = L / Cfg::CPR, o = (L % Cfg::CPR) ^ Cfg::swz(p);
+            src_off[i] = (uint32_t)(p * (2 * D) + o * 16);
+        } else {
+            const int Lv = L - Cfg::KBYTES / 16;
+            const int d = Lv >> 2, c = (Lv & 3) ^ ((d >> 2) & 3);
+            src_off[i] = (uint32_t)(d * 128 + c * 16);
+        }
+    }
+    auto issue = [&](int blk) {
+        const int bc = min(blk, nb - 1);  // past the end the last step is copied again: constant operation counts
+        const int p0 = bc * 32;
+        const char *ksrc = kbase + (size_t)p0 * (2 * D);
+        const char *vsrc = vbase + (size_t)(p0 / 64) * D * 128 + (p0 % 64) * 2;
+#pragma unroll
+        for (int i = 0; i < CP; ++i) {
+            const int piece = wave + 4 * i;
+            const bool is_k = piece < Cfg::KBYTES / 1024;
+            // (the address is the same in every lane; saying so keeps it in scalar registers for the copy)
+            const uint64_t addr = reinterpret_cast<uint64_t>(is_k ? ksrc : vsrc);
+            const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)addr);
+            const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32));
+            copy16_to_lds(reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo), src_off[i],
+                          __builtin_amdgcn_readfirstlane(lds0 + (blk % NS) * Cfg::STAGE + piece * 1024));
+        }
+    };
+
+    // operand read offsets of this lane inside a stage
+    const int pp = 16 * (q >> 4) + 8 * ((q >> 2) & 1) + 4 * ((q >> 3) & 1) + (q & 3);  // position of score-tile row q
+    int koff[DJ];
+#pragma unroll
+    for (int j = 0; j < DJ; ++j) koff[j] = pp * (2 * D) + (((2 * j + h) ^ Cfg::swz(pp)) * 16);
+    int voff[DT][2];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int d = 32 * dt + q;
+            voff[dt][c] = Cfg::KBYTES + d * 64 + (((2 * c + h) ^ ((d >> 2) & 3)) * 16);
+        }
+
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p) issue(p);
+    for (int blk = 0; blk < nb; ++blk) {
+        const int k0 = blk * 32;
+        wait_vmcnt<(NS - 2) * CP>();
+        asm volatile("s_barrier" ::: "memory");
+        issue(blk + NS - 1);
+        const char *stage = reinterpret_cast<const char *>(lds_raw) + (blk % NS) * Cfg::STAGE;
+        v16f st;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) st[e] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) {
+            const u32x4 kf = *reinterpret_cast<const u32x4 *>(stage + koff[j]);
+            st = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, kf), __builtin_bit_cast(h8, qf[j]), st, 0, 0, 0);
+        }
+        u32x4 vf[DT][2];
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int c = 0; c < 2; ++c) vf[dt][c] = *reinterpret_cast<const u32x4 *>(stage + voff[dt][c]);
+        // register e = 8 c + 4 b + r of lane (q, h): position k0 + 16 c + 8 h + 4 b + r
+        float sc[16];
+        float bmax = kNegBig;
+        const bool edge = k0 + 32 > lo_full;  // same for the whole wavefront
+        if (!edge) {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                sc[e] = st[e] * a.scale;
+                bmax = fmaxf(bmax, sc[e]);
+            }
+        } else {
+#pragma unroll
+            for (int e = 0; e < 16; ++e) {
+                const int pos = k0 + 16 * (e >> 3) + 8 * h + (e & 7);
+                sc[e] = pos < lim ? st[e] * a.scale : kNegBig;
+                bmax = fmaxf(bmax, sc[e]);
+            }
+        }
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+        const float new_max = fmaxf(run_max, bmax);
+        const float corr = __builtin_amdgcn_exp2f(run_max - new_max);
+        run_max = new_max;
+        float psum = 0.0f;
+        h8 pv[2];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            float p = __builtin_amdgcn_exp2f(sc[e] - new_max);
+            if (edge) p = sc[e] > 0.5f * kNegBig ? p : 0.0f;
+            psum += p;
+            pv[e >> 3][e & 7] = (_Float16)p;
+        }
+        run_sum = run_sum * corr + psum;
+        if (k0 + 32 > a.n_ctx) {  // positions past the context may hold anything
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int c = 0; c < 2; ++c) {
+                    const int p0 = k0 + 16 * c + 8 * h;
+                    uint32_t w[4] = {vf[dt][c].x, vf[dt][c].y, vf[dt][c].z, vf[dt][c].w};
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) {
+                        if (p0 + 2 * e >= a.n_ctx) w[e] &= 0xFFFF0000u;
+                        if (p0 + 2 * e + 1 >= a.n_ctx) w[e] &= 0x0000FFFFu;
+                    }
+                    vf[dt][c] = u32x4{w[0], w[1], w[2], w[3]};
+                }
+        }
+        const bool rescale = __any(corr != 1.0f);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            v16f o = acc[dt];
+            if (rescale) {
+#pragma unroll
+                for (int e = 0; e < 16; ++e) o[e] *= corr;
+            }
+#pragma unroll
+            for (int c = 0; c < 2; ++c)
+                o = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, vf[dt][c]), pv[c], o, 0, 0, 0);
+            acc[dt] = o;
+        }
+    }
+    wait_vmcnt<0>();  // the redundant copies past the end have landed before the workgroup leaves
+    run_sum += __shfl_xor(run_sum, 32, 64);
+    if (!real) return;
+    const float inv = 1.0f / run_sum;
+    // lane (q, h) holds O^T rows d = 32 dt + 8 b + 4 h + r of column q: four consecutive d per b
+    _Float16 *dst = a.out + ((size_t)G * a.M + m) * D;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int b = 0; b < 4; ++b) {
+            const h4 v = {(_Float16)(acc[dt][4 * b + 0] * inv), (_Float16)(acc[dt][4 * b + 1] * inv),
+                          (_Float16)(acc[dt][4 * b + 2] * inv), (_Float16)(acc[dt][4 * b + 3] * inv)};
+            *reinterpret_cast<h4 *>(dst + 32 * dt + 8 * b + 4 * h) = v;
+        }
+}
+
+template <int D>
+hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
+    constexpr size_t lds = (size_t)PrefillCfg<D>::NS * PrefillCfg<D>::STAGE;
+    static_assert(lds <= 160 * 1024, "LDS budget");
+    static bool attr_set = false;
+    if (!attr_set) {
+        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_prefill_kernel<D>),
+                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    attn_prefill_kernel<D><<<dim3((unsigned)((a.M + 127) / 128), (unsigned)G), 256, lds, st>>>(a);
+    return hipGetLastError();
+}
+
 template <int D>
 hipError_t launch_attn(const AttnArgs &a, int G, hipStream_t st) {
     const size_t lds = (size_t)4 * 16 * (D + 4) * sizeof(float);
@@ -372,6 +598,14 @@ hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G
     a.ws_o = static_cast<float *>(workspace);
     a.ws_ml = a.ws_o + (size_t)G * kAttnMaxSplits * a.M * d;
     a.out = static_cast<_Float16 *>(out);
+    if (a.M > 16) {
+        switch (d) {
+            case 64: return launch_attn_prefill<64>(a, G, st);
+            case 128: return launch_attn_prefill<128>(a, G, st);
+            case 256: return launch_attn_prefill<256>(a, G, st);
+            default: return hipErrorInvalidValue;
+        }
+    }
     switch (d) {
         case 64: return launch_attn<64>(a, G, st);
         case 128: return launch_attn<128>(a, G, st);

@@ -103,7 +103,8 @@ def test_argument_errors_before_any_launch(L):
     assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 96, 4096)), 1, ctypes.byref(out)) == 2    # head size
     assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 128, 4128)), 1, ctypes.byref(out)) == 1   # cache % 64
     assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 6, 128, 4096)), 1, ctypes.byref(out)) == 1   # h_q % h_kv
-    assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 128, 4096)), 5, ctypes.byref(out)) == 2   # S * g > 16
+    assert L.qfc_attention_workspace_size(ctypes.byref(S8(1, 32, 8, 128, 4096)), 5, ctypes.byref(out)) == 0   # prefill path
+    assert out.value == 256
     sh = S8(1, 32, 8, 128, 4096)
     assert L.qfc_attention(A, A, A, 1, 0, ctypes.byref(sh), A, 1 << 30, A, s) == 1        # n_ctx < S
     assert L.qfc_attention(A, A, A, 1, 5000, ctypes.byref(sh), A, 1 << 30, A, s) == 1     # n_ctx > cache

@@ -753,6 +753,37 @@ def test_attention_over_the_cache(B, S, h_q, h_kv, d, C, n_ctx):
     assert oracle.floored_rel_error(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
 
 
+@pytest.mark.parametrize("B,S,h_q,h_kv,d,C,n_ctx", [(1, 5, 8, 2, 64, 64, 5), (1, 40, 4, 4, 128, 128, 40),
+                                                    (2, 33, 8, 2, 128, 192, 150), (1, 100, 8, 4, 256, 128, 100),
+                                                    (1, 256, 32, 8, 128, 512, 300), (1, 64, 16, 1, 64, 1024, 1000)])
+def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
+    """Prefill: more than 16 query rows per KV head, causal by token, ragged row and position counts."""
+    print(f"prefill attention B={B} S={S} h_q={h_q} h_kv={h_kv} d={d} C={C} n_ctx={n_ctx}", flush=True)
+    G, g = B * h_kv, h_q // h_kv
+    M = S * g
+    assert M > 16
+    rng = np.random.default_rng(n_ctx * 17 + S)
+    q = rng.standard_normal((G, M, d)).astype(np.float16)
+    K = rng.standard_normal((G, C, d)).astype(np.float16)
+    V = rng.standard_normal((G, d, C)).astype(np.float16)
+    Kd, Vd = K.copy(), V.copy()
+    Kd[:, n_ctx:] = np.float16(np.nan)
+    Vd[:, :, n_ctx:] = np.float16(np.inf)
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+    ws = torch.empty(binding.qfc_attention_workspace_size(shape, S), dtype=torch.uint8, device=DEV)
+    out = torch.full((G, M, d), 9.0, dtype=torch.float16, device=DEV)
+    binding.qfc_attention(torch.from_numpy(q).to(DEV), torch.from_numpy(Kd).to(DEV), binding.vcache_physical(torch.from_numpy(Vd).to(DEV)),
+                          S, n_ctx, shape, ws, out)
+    torch.cuda.synchronize()
+    ref = oracle.attention(q, K, V, n_ctx, S)
+    got = out.cpu().numpy()
+    assert np.all(np.isfinite(got))
+    assert oracle.floored_rel_error(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
+    # the first token's rows see n_ctx - S + 1 positions only: with one position the output is that value column
+    if n_ctx == S:
+        assert np.allclose(got[:, :g].astype(np.float64), np.repeat(V[:, None, :, 0], g, axis=1).astype(np.float64), rtol=2e-3, atol=2e-3)
+
+
 def test_rope_then_attention_decode_step():
     """One decode step end to end: the token's QKV row goes through the rotary kernel into the caches
     and attention reads them; compared with the oracle's pipeline on the same binary16 caches."""
