@@ -89,8 +89,11 @@ struct AttnArgs {
 
 // Workgroup = 4 wavefronts.  grid = (splits, G).  A step covers TP pairs of score tiles = 32 TP positions:
 // 64 for head sizes up to 128, 32 for 256 (whose operands of 64 positions would leave one wavefront per SIMD).
+// Two workgroups per compute unit (up to head size 128) are said in the launch bounds so that the accumulators stay in
+// ordinary registers (with the whole register file at its disposal the compiler parks them in
+// accumulation registers and copies them back and forth for the rescaling).
 template <int D>
-__global__ __launch_bounds__(256) void attn_partial_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_partial_kernel(AttnArgs a) {
     constexpr int TP = D <= 128 ? 2 : 1;
     constexpr int SP = 32 * TP;  // positions per step
     constexpr int DJ = D / 32;  // MFMA steps along d of the score product
@@ -345,8 +348,10 @@ struct PrefillCfg {
     __device__ static int swz(int p) { return D >= 128 ? (p & 15) : ((p >> 1) & 7); }
 };
 
+// (Two workgroups per compute unit up to head size 128: said in the launch bounds, so that the
+// accumulators stay in ordinary registers, where the softmax rescales them in place.)
 template <int D>
-__global__ __launch_bounds__(256) void attn_prefill_kernel(AttnArgs a) {
+__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(AttnArgs a) {
     typedef float v16f __attribute__((ext_vector_type(16)));
     typedef PrefillCfg<D> Cfg;
     constexpr int DJ = D / 16;  // MFMA steps along d of the score product
