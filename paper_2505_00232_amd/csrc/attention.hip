@@ -367,9 +367,11 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     const int m = r0 + q;
     const bool real = m < a.M;
     const int lim = real ? a.n_ctx - a.S + m / a.g + 1 : a.n_ctx;
-    const int lo_full = a.n_ctx - a.S + min(r0, a.M - 1) / a.g + 1;  // positions every row of the wavefront sees
+    // (the same in every lane: said explicitly, the divisions would otherwise be carried out per lane
+    // and drag the loop control and the copy addresses into vector registers)
+    const int lo_full = __builtin_amdgcn_readfirstlane(a.n_ctx - a.S + min(r0, a.M - 1) / a.g + 1);  // positions every row of the wavefront sees
     const int block_last = min(block * 128 + 127, a.M - 1);
-    const int nb = (a.n_ctx - a.S + block_last / a.g + 1 + 31) / 32;  // steps of the whole workgroup
+    const int nb = __builtin_amdgcn_readfirstlane((a.n_ctx - a.S + block_last / a.g + 1 + 31) / 32);  // steps of the whole workgroup
 
     // Q^T operand: lane (q, h) holds Q[m][16 j + 8 h .. + 7]
     u32x4 qf[DJ];
@@ -457,32 +459,33 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
 #pragma unroll
             for (int c = 0; c < 2; ++c) vf[dt][c] = *reinterpret_cast<const u32x4 *>(stage + voff[dt][c]);
         // register e = 8 c + 4 b + r of lane (q, h): position k0 + 16 c + 8 h + 4 b + r
+        // raw scores; the scale (in units of log 2) is applied inside the exponent: 2^(s scale - maximum)
         float sc[16];
         float bmax = kNegBig;
         const bool edge = k0 + 32 > lo_full;  // same for the whole wavefront
         if (!edge) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
-                sc[e] = st[e] * a.scale;
+                sc[e] = st[e];
                 bmax = fmaxf(bmax, sc[e]);
             }
         } else {
 #pragma unroll
             for (int e = 0; e < 16; ++e) {
                 const int pos = k0 + 16 * (e >> 3) + 8 * h + (e & 7);
-                sc[e] = pos < lim ? st[e] * a.scale : kNegBig;
+                sc[e] = pos < lim ? st[e] : kNegBig;
                 bmax = fmaxf(bmax, sc[e]);
             }
         }
         bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
-        const float new_max = fmaxf(run_max, bmax);
+        const float new_max = fmaxf(run_max, bmax * a.scale);  // kNegBig * scale stays hugely negative
         const float corr = __builtin_amdgcn_exp2f(run_max - new_max);
         run_max = new_max;
         float psum = 0.0f;
         h8 pv[2];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            float p = __builtin_amdgcn_exp2f(sc[e] - new_max);
+            float p = __builtin_amdgcn_exp2f(fmaf(sc[e], a.scale, -new_max));
             if (edge) p = sc[e] > 0.5f * kNegBig ? p : 0.0f;
             psum += p;
             pv[e >> 3][e & 7] = (_Float16)p;
