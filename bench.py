@@ -430,6 +430,27 @@ def main():
     extra["decode_attention_llama8b_b8_ctx8192"] = attention_line(8, 8192, 3)
     torch.cuda.empty_cache()
 
+    # Causal attention of a Llama-3.1-8B layer over a 2048-token prompt (prefill: 8192 query rows per KV head)
+    def prefill_attention_line(S=2048):
+        h_q, h_kv, d = 32, 8, 128
+        shape = binding.AttnShape(1, h_q, h_kv, d, S)
+        gen = torch.Generator(device=dev)
+        gen.manual_seed(SEED + 600)
+        kc = torch.randn((h_kv, S, d), generator=gen, device=dev, dtype=torch.float32).half()
+        vc = torch.randn((h_kv, S // 64, d, 64), generator=gen, device=dev, dtype=torch.float32).half()
+        q = torch.randn((h_kv, S * (h_q // h_kv), d), generator=gen, device=dev, dtype=torch.float32).half()
+        out = torch.empty_like(q)
+        ws = torch.empty(binding.qfc_attention_workspace_size(shape, S), dtype=torch.uint8, device=dev)
+        run = lambda: binding.qfc_attention(q, kc, vc, S, S, shape, ws, out)
+        run()
+        ms = event_ms(run, args.steps)
+        flops = 4.0 * d * h_q * (S * (S + 1) / 2)
+        return {"us": round(ms * 1e3, 1), "Tflops_causal": round(flops / (ms * 1e-3) / 1e12, 1),
+                "frac_mfma_fp16_peak": round(flops / (ms * 1e-3) / 1e12 / MFMA_F16_PEAK_TFLOPS, 4)}
+
+    if not args.skip_prefill:
+        extra["prefill_attention_llama8b_s2048"] = prefill_attention_line()
+
     # ------------------------------------------------------------ prefill (configs 4 and 5)
     if not args.skip_prefill:
         def prefill(fc_list, M, seed, reps=10):
