@@ -79,3 +79,19 @@ def rmsnorm(x_f16, gamma_f16, eps: float, gamma_offset: float = 0.0, residual_f1
     ms = np.mean(hd * hd, axis=1, keepdims=True)
     w = gamma_offset + np.asarray(gamma_f16, dtype=np.float16).astype(np.float64)
     return h, hd / np.sqrt(ms + eps) * w[None, :]
+
+
+def rms_scale(x_f16, eps: float) -> np.ndarray:
+    """rs[m] = 1 / sqrt(mean_k x[m, k]^2 + eps), fp64 [M]."""
+    x = np.asarray(x_f16, dtype=np.float16).astype(np.float64)
+    return 1.0 / np.sqrt(np.mean(x * x, axis=1) + eps)
+
+
+def norm_weighted_input(x_f16, gamma_f16, gamma_offset: float = 0.0) -> np.ndarray:
+    """x[m, k] * (gamma_offset + gamma[k]), rounded once to binary16: the input of a layer that has
+    the RMS normalization merged into it.  Normalizing scales a row by one number, which commutes
+    with the layer: rmsnorm(x) W^T = rs * ((x * weight) W^T), so the merged operator feeds the
+    weighted row to the layer and multiplies its output by rs (rms_scale)."""
+    x = np.asarray(x_f16, dtype=np.float16).astype(np.float64)
+    w = gamma_offset + np.asarray(gamma_f16, dtype=np.float16).astype(np.float64)
+    return (x * w[None, :]).astype(np.float16)

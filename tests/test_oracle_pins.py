@@ -449,3 +449,29 @@ def test_attention_hand_case_library_routine_and_special_cases():
         mask = torch.ones(S, n, dtype=torch.bool).tril(diagonal=n - S)
         ref = torch.nn.functional.scaled_dot_product_attention(qj, kj, vj, attn_mask=mask)
         assert np.allclose(got[:, j::g], ref.numpy(), rtol=1e-12, atol=1e-13)
+
+
+def test_norm_merged_into_layer_equals_norm_then_layer():
+    rng = np.random.default_rng(8)
+    x = rng.standard_normal((4, 64)).astype(np.float16)
+    g = rng.standard_normal(64).astype(np.float16)
+    eps = 1e-5
+    rs = oracle.rms_scale(x, eps)
+    # hand value: row (3, 4): mean of squares 12.5
+    assert abs(oracle.rms_scale(np.array([[3, 4]], dtype=np.float16), 0.0)[0] - 1 / np.sqrt(12.5)) < 1e-15
+    # unit weight: the weighted input is x itself, and rs * x is the normalization exactly
+    ones = np.ones(64, dtype=np.float16)
+    assert np.array_equal(oracle.norm_weighted_input(x, ones), x)
+    _, y = oracle.rmsnorm(x, ones, eps)
+    assert np.allclose(rs[:, None] * x.astype(np.float64), y, rtol=1e-14, atol=0)
+    # general weight (and the offset form): equal up to the one binary16 rounding of x * weight
+    for off in (0.0, 1.0):
+        xin = oracle.norm_weighted_input(x, g, off).astype(np.float64)
+        _, y = oracle.rmsnorm(x, g, eps, off)
+        assert np.all(np.abs(rs[:, None] * xin - y) <= np.abs(y) * 2.0 ** -11 + 1e-12)
+        # through a layer: scaling the rows commutes with the matrix product
+        wq = rng.integers(-127, 128, size=(7, 64), dtype=np.int8)
+        sw = (rng.random(7) * 0.01 + 0.001).astype(np.float32)
+        fused = rs[:, None] * oracle.fc_weight_only(oracle.norm_weighted_input(x, g, off), wq, sw)
+        a = oracle.dequantize(wq, sw)
+        assert np.allclose(fused, (rs[:, None] * xin) @ a.T, rtol=1e-12, atol=1e-12)
