@@ -147,6 +147,11 @@ qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, in
  *             [0, N/2) the gate and [N/2, N) the other one (N a multiple of 32), and
  *             y is binary16 [M, N/2]: y[m,n] = fp16(act(fc[m,n]) * fc[m,n + N/2]) with
  *             both fp32 results taken before any rounding.  Excludes the other two.
+ *   norm_gamma  binary16 [K]: the RMS normalization that precedes the layer is merged into it.
+ *             The layer's input is rmsnorm(x) * (norm_offset + gamma); since the normalization
+ *             scales a row by one number rs = 1 / sqrt(mean_k x^2 + norm_eps), the kernel feeds
+ *             in = fp16(x * (norm_offset + gamma)) to the product and multiplies the result by rs
+ *             (fp32) before the residual is added.  Decode kernels only; excludes gate.
  * Supported: the decode kernels of QFC_COMPUTE_FP16_DEQUANT / QFC_COMPUTE_INT8_ACT
  * handles (M <= 8; all parts), the int8 prefill path (gate and residual: the gate is
  * applied by the activation quantization kernel) and the fp16 prefill path
@@ -159,6 +164,9 @@ typedef struct qfc_fusion {
     int32_t activation;    /* QFC_ACT_*; read when gate or gated_output is given */
     const void *residual;  /* device, binary16 [M, N], or null */
     int32_t gated_output;  /* 0 or 1 */
+    const void *norm_gamma; /* device, binary16 [K], or null */
+    float norm_eps;         /* read when norm_gamma is given */
+    float norm_offset;      /* 0: weight gamma; 1: weight 1 + gamma */
 } qfc_fusion_t;
 
 /* qfc_forward with the fused element-wise parts `f` names (host pointer, read

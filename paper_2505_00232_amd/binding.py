@@ -32,7 +32,8 @@ class Desc(ctypes.Structure):
 class Fusion(ctypes.Structure):
     """qfc_fusion_t: element-wise parts fused with the layer (null = absent)."""
     _fields_ = [("gate", ctypes.c_void_p), ("activation", ctypes.c_int32), ("residual", ctypes.c_void_p),
-                ("gated_output", ctypes.c_int32)]
+                ("gated_output", ctypes.c_int32), ("norm_gamma", ctypes.c_void_p), ("norm_eps", ctypes.c_float),
+                ("norm_offset", ctypes.c_float)]
 
 
 class RmsNorm(ctypes.Structure):
@@ -161,9 +162,11 @@ def qfc_forward(h, x: torch.Tensor, y: torch.Tensor):
 
 def qfc_forward_fused(h, x: torch.Tensor, y: torch.Tensor, gate: torch.Tensor | None = None,
                       activation: int = QFC_ACT_SILU, residual: torch.Tensor | None = None,
-                      gated_output: bool = False):
+                      gated_output: bool = False, norm_gamma: torch.Tensor | None = None, norm_eps: float = 0.0,
+                      norm_offset: float = 0.0):
     f = Fusion(gate.data_ptr() if gate is not None else None, activation,
-               residual.data_ptr() if residual is not None else None, 1 if gated_output else 0)
+               residual.data_ptr() if residual is not None else None, 1 if gated_output else 0,
+               norm_gamma.data_ptr() if norm_gamma is not None else None, norm_eps, norm_offset)
     _check(lib().qfc_forward_fused(h, _ptr(x), x.shape[0], _ptr(y), ctypes.byref(f), _stream()), "qfc_forward_fused")
 
 

@@ -161,7 +161,9 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
     if ((f.gate || f.gated_output) && f.activation != QFC_ACT_SILU && f.activation != QFC_ACT_GELU_TANH)
         return QFC_ERR_INVALID_ARG;
     if (f.gated_output && (f.gate || f.residual || h->geo.N % 32 != 0)) return QFC_ERR_INVALID_ARG;
-    const bool fused = f.gate || f.residual || f.gated_output;
+    if (f.norm_gamma && (f.gate || !aligned16(f.norm_gamma) || !(f.norm_eps >= 0.0f))) return QFC_ERR_INVALID_ARG;
+    if (f.norm_gamma && M > kMaxDecodeM) return QFC_ERR_UNSUPPORTED;
+    const bool fused = f.gate || f.residual || f.gated_output || f.norm_gamma;
     if (M <= kMaxDecodeM) {
         if (h->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE) {
             if (fused) return QFC_ERR_UNSUPPORTED;
@@ -200,6 +202,9 @@ qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, voi
         f.activation = fusion->activation;
         f.residual = fusion->residual;
         f.gated_output = fusion->gated_output != 0;
+        f.norm_gamma = fusion->norm_gamma;
+        f.norm_eps = fusion->norm_eps;
+        f.norm_offset = fusion->norm_offset;
     }
     return forward_impl(h, x_f16, M, y_f16, f, static_cast<hipStream_t>(stream));
 }

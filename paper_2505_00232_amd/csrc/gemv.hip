@@ -96,10 +96,21 @@ __device__ __forceinline__ u32x4 gated_input8(const u32x4 &gate, const u32x4 &x,
     return __builtin_bit_cast(u32x4, gated_input8_u4(__builtin_bit_cast(uint4, gate), __builtin_bit_cast(uint4, x), act));
 }
 
+// eight binary16 pairs (weight, x) -> eight binary16 values fp16(x * (offset + weight))
+__device__ __forceinline__ u32x4 weighted_input8(const u32x4 &w, const u32x4 &x, float offset) {
+    const v8h wv = __builtin_bit_cast(v8h, w), xv = __builtin_bit_cast(v8h, x);
+    v8h r;
+#pragma unroll
+    for (int e = 0; e < 8; ++e) r[e] = (_Float16)((float)xv[e] * (offset + (float)wv[e]));
+    return __builtin_bit_cast(u32x4, r);
+}
+
 struct GemvArgs {
     const u32x4 *packed;
     const u32x4 *x;     // binary16 [M, K] as 16-byte vectors (8 values)
-    const u32x4 *gate;  // GLU kernels: binary16 [M, K]; the layer's input is fp16(act(gate) * x)
+    const u32x4 *gate;  // prologue 1: binary16 [M, K], the layer's input is fp16(act(gate) * x);
+                        // prologue 2: binary16 [K], the weight of the merged RMS normalization
+    float norm_eps, norm_offset;  // prologue 2
     const _Float16 *res;  // binary16 [M, N] added before the final rounding, or null
     int act;            // QFC_ACT_* of the gate
     _Float16 *y;        // [M, N]
@@ -114,15 +125,18 @@ struct GemvArgs {
 // LDS view of one wavefront's staged activations: vector (slot * M + m).
 // int4 unit: 1024 k = 128 octets, slot = octet index (4 * group + q).
 // W8C unit:   512 k =  64 octets, slot = tile * 8 + j * 4 + q for octet 2q + j of the tile.
-// GLU: the gate branch travels with x and the two are merged on the way into LDS (operator
+// Prologues.  PRO = 1: the gate branch travels with x and the two are merged on the way into LDS (operator
 // fusion, section 3.6 of the paper: element-wise operators of two branches merged into the
-// fully connected operator).
-template <int M, int FMT, bool GLU>
+// fully connected operator).  PRO = 2: RMS normalization merged into the layer: normalizing scales
+// a row by one number rs, which commutes with the product, so the row goes into LDS multiplied by
+// the normalization weight only and the output is multiplied by rs at the end; every workgroup
+// computes the rows' sums of squares for itself (one pass over x).
+template <int M, int FMT, int PRO>
 struct XStage {
     static constexpr int OCT = FMT == kW8C ? 64 : 128;  // octets per unit
     static constexpr int XV = M * OCT / 64;               // 16-byte vectors per lane per unit
     u32x4 v[XV];
-    u32x4 g[GLU ? XV : 1];
+    u32x4 g[PRO ? XV : 1];
 
     // global -> registers (zeros beyond K)
     __device__ __forceinline__ void load(const GemvArgs &a, int unit, int lane) {
@@ -134,24 +148,25 @@ struct XStage {
             const int m = p / OCT, o = p % OCT;
             const u32x4 zero = {0, 0, 0, 0};
             v[i] = o_base + o < K8 ? a.x[(size_t)m * K8 + o_base + o] : zero;
-            if (GLU) g[i] = o_base + o < K8 ? a.gate[(size_t)m * K8 + o_base + o] : zero;
+            if (PRO == 1) g[i] = o_base + o < K8 ? a.gate[(size_t)m * K8 + o_base + o] : zero;
+            if (PRO == 2) g[i] = o_base + o < K8 ? a.gate[o_base + o] : zero;
         }
     }
     // registers -> this wavefront's LDS region, A-operand order
-    __device__ __forceinline__ void store(u32x4 *lds, int lane, int act) const {
+    __device__ __forceinline__ void store(u32x4 *lds, int lane, int act, float offset) const {
 #pragma unroll
         for (int i = 0; i < XV; ++i) {
             const int p = i * 64 + lane;
             const int m = p / OCT, o = p % OCT;
             int slot = o;
             if (FMT == kW8C) slot = (o & ~7) | ((o & 1) << 2) | ((o >> 1) & 3);
-            lds[slot * M + m] = GLU ? gated_input8(g[i], v[i], act) : v[i];
+            lds[slot * M + m] = PRO == 1 ? gated_input8(g[i], v[i], act) : PRO == 2 ? weighted_input8(g[i], v[i], offset) : v[i];
         }
     }
 };
 
-template <int M, int FMT, bool DB, bool GLU>
-__global__ __launch_bounds__(GLU && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs a) {
+template <int M, int FMT, bool DB, int PRO>
+__global__ __launch_bounds__(PRO && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs a) {
     constexpr int TILES = 8;                    // weight tiles per unit
     constexpr int NV = FMT == kW4G32 ? 12 : 8;  // 16-byte vectors per lane per (unit, row tile)
     constexpr int OCT = FMT == kW8C ? 64 : 128;
@@ -175,6 +190,34 @@ __global__ __launch_bounds__(GLU && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs
     for (int r = 0; r < 4; ++r)
 #pragma unroll
         for (int i = 0; i < 4; ++i) acc[r][i] = 0.0f;
+
+    // Merged RMS normalization: the rows' sums of squares, by the whole workgroup (fp32; partial
+    // sums of the wavefronts are added in fixed order where they are used, at the end).
+    __shared__ float s_ss[PRO == 2 ? 8 : 1][M];
+    if constexpr (PRO == 2) {
+        float ss[M];
+#pragma unroll
+        for (int m = 0; m < M; ++m) ss[m] = 0.0f;
+        const int K8 = a.K / 8;
+        for (int v = threadIdx.x; v < M * K8; v += blockDim.x) {
+            const int m = v / K8;
+            const v8h hx = __builtin_bit_cast(v8h, a.x[v]);
+            float t = 0.0f;
+#pragma unroll
+            for (int i = 0; i < 8; ++i) t = fmaf((float)hx[i], (float)hx[i], t);
+#pragma unroll
+            for (int mm = 0; mm < M; ++mm)
+                if (mm == m) ss[mm] += t;
+        }
+#pragma unroll
+        for (int m = 0; m < M; ++m) {
+            float t = ss[m];
+#pragma unroll
+            for (int off = 32; off > 0; off >>= 1) t += __shfl_xor(t, off, 64);
+            if (lane == 0) s_ss[wave][m] = t;
+        }
+        // (made visible to the other wavefronts by the barriers before the final reduction)
+    }
 
     // item = (unit, row tile); its vectors: (W4G32) 4 scale vectors, then weight tiles 0..nt-1.
     // `full` = all 8 tiles present: unconditional loads, so that the compiler can
@@ -203,7 +246,7 @@ __global__ __launch_bounds__(GLU && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs
     // one or two items.  DB = true: the next item's vectors are requested before
     // the current item is computed, for long-lived wavefronts.  Vector loads
     // return in order, so the (small) activation loads are issued first.
-    XStage<M, FMT, GLU> xs;
+    XStage<M, FMT, PRO> xs;
     u32x4 cur[NV];
     u32x4 nxt[DB ? NV : 1];
     const int items = (u1 - u0) * R;
@@ -217,7 +260,7 @@ __global__ __launch_bounds__(GLU && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs
     }
     auto stage = [&]() {
         // the wavefront's earlier LDS reads are done (same wavefront, in order)
-        xs.store(lds_x, lane, a.act);
+        xs.store(lds_x, lane, a.act, a.norm_offset);
         __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
         __builtin_amdgcn_wave_barrier();
         __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
@@ -364,6 +407,13 @@ __global__ __launch_bounds__(GLU && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs
                     sg *= a.sw[n];
                     su *= a.sw[n + half];
                 }
+                if constexpr (PRO == 2) {
+                    float tot = 0.0f;
+                    for (int w = 0; w < nwaves; ++w) tot += s_ss[w][m];
+                    const float rs = 1.0f / sqrtf(tot / (float)a.K + a.norm_eps);
+                    sg *= rs;
+                    su *= rs;
+                }
                 a.y[(size_t)m * half + n] = (_Float16)(gate_activation(sg, gc) * su);
             }
         }
@@ -376,13 +426,18 @@ __global__ __launch_bounds__(GLU && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs
         const int n = (rt0 + rr) * 16 + cc;
         if (n < a.N) {
             if (FMT != kW4G32) s *= a.sw[n];
+            if constexpr (PRO == 2) {
+                float tot = 0.0f;
+                for (int w = 0; w < nwaves; ++w) tot += s_ss[w][m];
+                s *= 1.0f / sqrtf(tot / (float)a.K + a.norm_eps);
+            }
             if (a.res) s += (float)a.res[(size_t)m * a.N + n];
             a.y[(size_t)m * a.N + n] = (_Float16)s;
         }
     }
 }
 
-template <int M, bool GLU>
+template <int M, int PRO>
 hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t st) {
     const dim3 grid((unsigned)(a.gated_out ? g.RT / 2 : (g.RT + a.row_tiles - 1) / a.row_tiles));
     const dim3 block((unsigned)(waves * 64));
@@ -395,34 +450,34 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t
     if constexpr (M <= 2) {
         if (items >= 3) {
             if (g.fmt == kW8C)
-                gemv_kernel<M, kW8C, true, GLU><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW8C, true, PRO><<<grid, block, lds, st>>>(a);
             else if (g.fmt == kW4C)
-                gemv_kernel<M, kW4C, true, GLU><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW4C, true, PRO><<<grid, block, lds, st>>>(a);
             else
-                gemv_kernel<M, kW4G32, true, GLU><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW4G32, true, PRO><<<grid, block, lds, st>>>(a);
             return hipGetLastError();
         }
     }
     if (g.fmt == kW8C)
-        gemv_kernel<M, kW8C, false, GLU><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW8C, false, PRO><<<grid, block, lds, st>>>(a);
     else if (g.fmt == kW4C)
-        gemv_kernel<M, kW4C, false, GLU><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW4C, false, PRO><<<grid, block, lds, st>>>(a);
     else
-        gemv_kernel<M, kW4G32, false, GLU><<<grid, block, lds, st>>>(a);
+        gemv_kernel<M, kW4G32, false, PRO><<<grid, block, lds, st>>>(a);
     return hipGetLastError();
 }
 
-template <bool GLU>
+template <int PRO>
 hipError_t launch_any_m(const Geometry &g, const GemvArgs &a, int M, int waves, hipStream_t st) {
     switch (M) {
-        case 1: return launch_m<1, GLU>(g, a, waves, st);
-        case 2: return launch_m<2, GLU>(g, a, waves, st);
-        case 3: return launch_m<3, GLU>(g, a, waves, st);
-        case 4: return launch_m<4, GLU>(g, a, waves, st);
-        case 5: return launch_m<5, GLU>(g, a, waves, st);
-        case 6: return launch_m<6, GLU>(g, a, waves, st);
-        case 7: return launch_m<7, GLU>(g, a, waves, st);
-        case 8: return launch_m<8, GLU>(g, a, waves, st);
+        case 1: return launch_m<1, PRO>(g, a, waves, st);
+        case 2: return launch_m<2, PRO>(g, a, waves, st);
+        case 3: return launch_m<3, PRO>(g, a, waves, st);
+        case 4: return launch_m<4, PRO>(g, a, waves, st);
+        case 5: return launch_m<5, PRO>(g, a, waves, st);
+        case 6: return launch_m<6, PRO>(g, a, waves, st);
+        case 7: return launch_m<7, PRO>(g, a, waves, st);
+        case 8: return launch_m<8, PRO>(g, a, waves, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -451,7 +506,13 @@ hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int
     a.gated_out = f.gated_output ? 1 : 0;
     a.units_q = g.KU / p.waves;
     a.units_rem = g.KU % p.waves;
-    return f.gate ? launch_any_m<true>(g, a, M, p.waves, st) : launch_any_m<false>(g, a, M, p.waves, st);
+    a.norm_eps = f.norm_eps;
+    a.norm_offset = f.norm_offset;
+    if (f.norm_gamma) {
+        a.gate = static_cast<const u32x4 *>(f.norm_gamma);
+        return launch_any_m<2>(g, a, M, p.waves, st);
+    }
+    return f.gate ? launch_any_m<1>(g, a, M, p.waves, st) : launch_any_m<0>(g, a, M, p.waves, st);
 }
 
 }  // namespace qfc

@@ -234,6 +234,8 @@ struct Fusion {
     int activation = 0;              // QFC_ACT_*
     const void *residual = nullptr;  // binary16 [M, N]
     bool gated_output = false;       // y [M, N/2] = fp16(act(rows [0, N/2)) * rows [N/2, N))
+    const void *norm_gamma = nullptr;  // binary16 [K]: the layer's input is rmsnorm(x) * (norm_offset + gamma)
+    float norm_eps = 0.0f, norm_offset = 0.0f;
 };
 
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,

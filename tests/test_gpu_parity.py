@@ -882,3 +882,55 @@ def test_decoder_layer_decode_step_chain():
     assert np.all(np.isfinite(N(h2)))
     for l in (l_qkv, l_o, l_gu, l_dn):
         l.close()
+
+
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
+@pytest.mark.parametrize("N,K", [(32, 96), (130, 256), (1000, 2304), (96, 14336)])
+def test_decode_norm_merged_into_layer(fmt, N, K):
+    """RMS normalization merged into the decode kernel: y = rs * fc(fp16(x * weight)) (+ residual),
+    also together with the gated output (the gate+up layer of a decoder layer)."""
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(3950, N, K, fc)
+    layer = _layer(wq, s, fmt)
+    gamma = (synth.activations(3951, N, K, 1, K)[0] * np.float16(0.5)).astype(np.float16)
+    gd = torch.from_numpy(gamma).to(DEV)
+    for M in (1, 2, 4, 5, 8):
+        print(f"decode norm merged {fmt} N={N} K={K} M={M}", flush=True)
+        x = synth.activations(3950, N, K + M, M, K)
+        res = synth.activations(3952, N, K + M, M, N)
+        off, eps = (1.0, 1e-6) if M % 2 else (0.0, 1e-5)
+        xd, rd = torch.from_numpy(x).to(DEV), torch.from_numpy(res).to(DEV)
+        y = torch.empty((M, N), dtype=torch.float16, device=DEV)
+        binding.qfc_forward_fused(layer.handle, xd, y, residual=rd, norm_gamma=gd, norm_eps=eps, norm_offset=off)
+        torch.cuda.synchronize()
+        x_in = oracle.norm_weighted_input(x, gamma, off)
+        rs = oracle.rms_scale(x, eps)
+        full = rs[:, None] * oracle.fc_weight_only(x_in, wq, s, _group(fmt))
+        assert oracle.floored_rel_error(y.cpu().numpy(), oracle.add_residual(full, res)) <= TOL, M
+        if N % 32 == 0:
+            yg = torch.empty((M, N // 2), dtype=torch.float16, device=DEV)
+            # a normalization weight scaled down (by a power of two) keeps the product of the two halves of order 1..64
+            # (the input's own scale cancels in the normalization)
+            mag = np.max(np.abs(rs[:, None] * oracle.fc_weight_only(oracle.norm_weighted_input(x, gamma, 0.0), wq, s, _group(fmt))))
+            shrink = 2.0 ** min(0, int(np.floor(np.log2(8.0 / mag))))
+            gs = (gamma.astype(np.float32) * shrink).astype(np.float16)
+            xs = x
+            binding.qfc_forward_fused(layer.handle, torch.from_numpy(xs).to(DEV), yg, activation=binding.QFC_ACT_SILU,
+                                      gated_output=True, norm_gamma=torch.from_numpy(gs).to(DEV), norm_eps=eps,
+                                      norm_offset=0.0)
+            torch.cuda.synchronize()
+            fulls = oracle.rms_scale(xs, eps)[:, None] * oracle.fc_weight_only(oracle.norm_weighted_input(xs, gs, 0.0), wq, s, _group(fmt))
+            assert oracle.floored_rel_error(yg.cpu().numpy(), oracle.gated_output(fulls, oracle.SILU)) <= TOL, M
+    # against the unfused sequence on the GPU: norm kernel, then the plain layer
+    x = synth.activations(3953, N, K, 3, K)
+    xd = torch.from_numpy(x).to(DEV)
+    yn = torch.empty((3, K), dtype=torch.float16, device=DEV)
+    y_a = torch.empty((3, N), dtype=torch.float16, device=DEV)
+    y_b = torch.empty((3, N), dtype=torch.float16, device=DEV)
+    if K <= 14336:
+        binding.qfc_rmsnorm(xd, gd, 1e-5, 0.0, y=yn)
+        binding.qfc_forward(layer.handle, yn, y_a)
+        binding.qfc_forward_fused(layer.handle, xd, y_b, norm_gamma=gd, norm_eps=1e-5, norm_offset=0.0)
+        torch.cuda.synchronize()
+        assert oracle.floored_rel_error(y_b.cpu().numpy(), y_a.cpu().numpy().astype(np.float64)) <= 2 * TOL
+    layer.close()
