@@ -755,7 +755,8 @@ def test_attention_over_the_cache(B, S, h_q, h_kv, d, C, n_ctx):
 
 @pytest.mark.parametrize("B,S,h_q,h_kv,d,C,n_ctx", [(1, 5, 8, 2, 64, 64, 5), (1, 40, 4, 4, 128, 128, 40),
                                                     (2, 33, 8, 2, 128, 192, 150), (1, 100, 8, 4, 256, 128, 100),
-                                                    (1, 256, 32, 8, 128, 512, 300), (1, 64, 16, 1, 64, 1024, 1000)])
+                                                    (1, 256, 32, 8, 128, 512, 300), (1, 64, 16, 1, 64, 1024, 1000),
+                                                    (1, 1024, 32, 8, 128, 1024, 1024)])
 def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
     """Prefill: more than 16 query rows per KV head, causal by token, ragged row and position counts."""
     print(f"prefill attention B={B} S={S} h_q={h_q} h_kv={h_kv} d={d} C={C} n_ctx={n_ctx}", flush=True)
