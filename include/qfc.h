@@ -245,48 +245,6 @@ qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache
 qfc_status_t qfc_forward_batch(const qfc_handle_t *handles, const void *const *xs, int32_t M,
                                void *const *ys, int32_t count, void *stream);
 
-/* A chain of decode layers in one persistent launch.
- *
- * The decode stage's layers are bound by the weight stream (section 3.7), and
- * a layer of a few MB launched on its own leaves the memory system idle while
- * its kernel starts and drains.  A chain is a recorded list of decode calls,
- * layer i reading what earlier layers wrote, that one resident grid of
- * workgroups walks through: the workgroups meet at a device-wide barrier after
- * every layer and request the next layer's first weights before they do, so
- * the weight stream continues across layer boundaries.  Every layer computes
- * exactly what qfc_forward_fused computes for it (bit-identical results).
- *
- * items: host array of n entries, read during qfc_chain_create; pointers in
- * them are device pointers that must stay valid while the chain is used (a
- * chain is bound to its buffers like a captured graph).  Every entry follows
- * the rules of qfc_forward_fused with these limits: M <= 4, handles of
- * QFC_COMPUTE_FP16_DEQUANT or QFC_COMPUTE_INT8_ACT, fusion parts residual and
- * gated_output only (gate, norm_gamma: QFC_ERR_UNSUPPORTED).  An entry's x, y
- * and residual may be any earlier entry's y.
- * device_buffer: qfc_chain_size(n) bytes of device memory, 16-byte aligned, owned
- * by the caller and used by the chain until qfc_chain_destroy (the layer records
- * and the barrier's counter live there); qfc_chain_create copies into it
- * synchronously.
- * qfc_chain_run enqueues two kernels on `stream`.  The grid is sized so that
- * all its workgroups are resident at once on an otherwise idle device; work of
- * other streams that occupies the device delays the barrier, and a wait that
- * exceeds 0.2 s ends the kernel with its outputs unspecified.  qfc_chain_status
- * synchronizes the device and reports whether the last run on it timed out
- * (*timed_out 0 or 1).  Runs of one chain must not overlap. */
-typedef struct qfc_chain_item {
-    qfc_handle_t layer;
-    const void *x_f16;    /* device, binary16 [M, K] */
-    void *y_f16;          /* device, binary16 [M, N] ([M, N/2] with gated_output) */
-    qfc_fusion_t fusion;
-} qfc_chain_item_t;
-typedef struct qfc_chain_s *qfc_chain_t;
-qfc_status_t qfc_chain_size(int32_t n, size_t *bytes);
-qfc_status_t qfc_chain_create(const qfc_chain_item_t *items, int32_t n, int32_t M, void *device_buffer,
-                              size_t buffer_bytes, qfc_chain_t *out);
-qfc_status_t qfc_chain_run(qfc_chain_t chain, void *stream);
-qfc_status_t qfc_chain_status(qfc_chain_t chain, int32_t *timed_out);
-qfc_status_t qfc_chain_destroy(qfc_chain_t chain);
-
 /* Free the host object.  Device buffers stay with the caller. */
 qfc_status_t qfc_destroy(qfc_handle_t h);
 

@@ -20,8 +20,7 @@ QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
            "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
-           "qfc_forward_acc_i32", "qfc_forward_batch", "qfc_chain_size", "qfc_chain_create", "qfc_chain_run",
-           "qfc_chain_status", "qfc_chain_destroy", "qfc_destroy", "qfc_status_string"]
+           "qfc_forward_acc_i32", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
 
 
 class Desc(ctypes.Structure):
@@ -35,12 +34,6 @@ class Fusion(ctypes.Structure):
     _fields_ = [("gate", ctypes.c_void_p), ("activation", ctypes.c_int32), ("residual", ctypes.c_void_p),
                 ("gated_output", ctypes.c_int32), ("norm_gamma", ctypes.c_void_p), ("norm_eps", ctypes.c_float),
                 ("norm_offset", ctypes.c_float)]
-
-
-class ChainItem(ctypes.Structure):
-    """qfc_chain_item_t."""
-    _fields_ = [("layer", ctypes.c_void_p), ("x_f16", ctypes.c_void_p), ("y_f16", ctypes.c_void_p),
-                ("fusion", Fusion)]
 
 
 class RmsNorm(ctypes.Structure):
@@ -88,11 +81,6 @@ def lib() -> ctypes.CDLL:
         L.qfc_forward_q8.argtypes = [vp, vp, vp, i32, vp, vp]
         L.qfc_forward_acc_i32.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_batch.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, vp]
-        L.qfc_chain_size.argtypes = [i32, ctypes.POINTER(sz)]
-        L.qfc_chain_create.argtypes = [ctypes.POINTER(ChainItem), i32, i32, vp, sz, ctypes.POINTER(vp)]
-        L.qfc_chain_run.argtypes = [vp, vp]
-        L.qfc_chain_status.argtypes = [vp, ctypes.POINTER(i32)]
-        L.qfc_chain_destroy.argtypes = [vp]
         L.qfc_destroy.argtypes = [vp]
         L.qfc_status_string.argtypes = [ctypes.c_int]
         L.qfc_status_string.restype = ctypes.c_char_p
@@ -244,44 +232,6 @@ class ForwardBatch:
 
     def run(self):
         _check(lib().qfc_forward_batch(self.h, self.x, self.M, self.y, self.n, _stream()), "qfc_forward_batch")
-
-
-def qfc_chain_size(n: int) -> int:
-    out = ctypes.c_size_t(0)
-    _check(lib().qfc_chain_size(n, ctypes.byref(out)), "qfc_chain_size")
-    return out.value
-
-
-def chain_item(h, x: torch.Tensor, y: torch.Tensor, residual: torch.Tensor | None = None, gated_output: bool = False,
-               activation: int = QFC_ACT_SILU, gate: torch.Tensor | None = None,
-               norm_gamma: torch.Tensor | None = None) -> ChainItem:
-    f = Fusion(gate.data_ptr() if gate is not None else None, activation,
-               residual.data_ptr() if residual is not None else None, 1 if gated_output else 0,
-               norm_gamma.data_ptr() if norm_gamma is not None else None, 0.0, 0.0)
-    return ChainItem(h.value if isinstance(h, ctypes.c_void_p) else h, x.data_ptr(), y.data_ptr(), f)
-
-
-def qfc_chain_create(items, M: int, device_buffer: torch.Tensor):
-    n = len(items)
-    arr = (ChainItem * n)(*items)
-    c = ctypes.c_void_p(0)
-    _check(lib().qfc_chain_create(arr, n, M, _ptr(device_buffer), device_buffer.numel() * device_buffer.element_size(),
-                                  ctypes.byref(c)), "qfc_chain_create")
-    return c
-
-
-def qfc_chain_run(c):
-    _check(lib().qfc_chain_run(c, _stream()), "qfc_chain_run")
-
-
-def qfc_chain_status(c) -> int:
-    out = ctypes.c_int32(0)
-    _check(lib().qfc_chain_status(c, ctypes.byref(out)), "qfc_chain_status")
-    return out.value
-
-
-def qfc_chain_destroy(c):
-    _check(lib().qfc_chain_destroy(c), "qfc_chain_destroy")
 
 
 def qfc_destroy(h):

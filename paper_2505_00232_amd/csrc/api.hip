@@ -17,22 +17,9 @@ struct qfc_weights_s {
     int num_cus;
 };
 
-struct qfc_chain_s {
-    uint32_t magic;
-    char *layers;    // device: n records of kSeqLayerBytes
-    unsigned *sync;  // device: (arrival counter, time-out flag) per run
-    int n, M, runs;
-    // a run = consecutive layers of one weight format = one persistent launch
-    struct {
-        int first, count, fmt, grid;
-    } run[kSeqMaxRuns];
-};
-
 namespace {
 
 constexpr uint32_t kMagic = 0x51464331u;  // "QFC1"
-constexpr uint32_t kChainMagic = 0x51464332u;
-constexpr size_t kChainSyncBytes = 256;
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -165,8 +152,9 @@ qfc_status_t qfc_quantize_activations(const void *x_f16, int32_t M, int32_t K, i
     return hip_status(launch_act_quant(x_f16, nullptr, 0, M, K, xq, sx, 0, M, K, cus, static_cast<hipStream_t>(stream)));
 }
 
-// Argument checks shared by qfc_forward, qfc_forward_fused and the chain.
-static qfc_status_t check_fusion(qfc_handle_t h, const void *x_f16, int32_t M, const void *y_f16, const Fusion &f) {
+// Shared body of qfc_forward and qfc_forward_fused.
+static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, const Fusion &f,
+                                 hipStream_t st) {
     if (!valid(h) || !x_f16 || !y_f16 || M < 1) return QFC_ERR_INVALID_ARG;
     if (!aligned16(x_f16) || !aligned16(y_f16)) return QFC_ERR_ALIGNMENT;
     if ((f.gate && !aligned16(f.gate)) || (f.residual && !aligned16(f.residual))) return QFC_ERR_ALIGNMENT;
@@ -175,27 +163,6 @@ static qfc_status_t check_fusion(qfc_handle_t h, const void *x_f16, int32_t M, c
     if (f.gated_output && (f.gate || f.residual || h->geo.N % 32 != 0)) return QFC_ERR_INVALID_ARG;
     if (f.norm_gamma && (f.gate || !aligned16(f.norm_gamma) || !(f.norm_eps >= 0.0f))) return QFC_ERR_INVALID_ARG;
     if (f.norm_gamma && M > kMaxDecodeM) return QFC_ERR_UNSUPPORTED;
-    return QFC_OK;
-}
-
-static Fusion to_fusion(const qfc_fusion_t *fusion) {
-    Fusion f;
-    if (fusion) {
-        f.gate = fusion->gate;
-        f.activation = fusion->activation;
-        f.residual = fusion->residual;
-        f.gated_output = fusion->gated_output != 0;
-        f.norm_gamma = fusion->norm_gamma;
-        f.norm_eps = fusion->norm_eps;
-        f.norm_offset = fusion->norm_offset;
-    }
-    return f;
-}
-
-static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, const Fusion &f,
-                                 hipStream_t st) {
-    const qfc_status_t chk = check_fusion(h, x_f16, M, y_f16, f);
-    if (chk != QFC_OK) return chk;
     const bool fused = f.gate || f.residual || f.gated_output || f.norm_gamma;
     if (M <= kMaxDecodeM) {
         if (h->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE) {
@@ -229,7 +196,17 @@ qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f
 
 qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16,
                                const qfc_fusion_t *fusion, void *stream) {
-    return forward_impl(h, x_f16, M, y_f16, to_fusion(fusion), static_cast<hipStream_t>(stream));
+    Fusion f;
+    if (fusion) {
+        f.gate = fusion->gate;
+        f.activation = fusion->activation;
+        f.residual = fusion->residual;
+        f.gated_output = fusion->gated_output != 0;
+        f.norm_gamma = fusion->norm_gamma;
+        f.norm_eps = fusion->norm_eps;
+        f.norm_offset = fusion->norm_offset;
+    }
+    return forward_impl(h, x_f16, M, y_f16, f, static_cast<hipStream_t>(stream));
 }
 
 qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *r, int32_t M, int32_t K, void *stream) {
@@ -352,115 +329,6 @@ qfc_status_t qfc_forward_batch(const qfc_handle_t *handles, const void *const *x
     return QFC_OK;
 }
 
-qfc_status_t qfc_chain_size(int32_t n, size_t *bytes) {
-    if (!bytes || n < 1) return QFC_ERR_INVALID_ARG;
-    *bytes = kChainSyncBytes + (size_t)n * kSeqLayerBytes;
-    return QFC_OK;
-}
-
-static bool valid_chain(qfc_chain_t c) { return c && c->magic == kChainMagic; }
-
-qfc_status_t qfc_chain_create(const qfc_chain_item_t *items, int32_t n, int32_t M, void *device_buffer,
-                              size_t buffer_bytes, qfc_chain_t *out) {
-    if (!out) return QFC_ERR_INVALID_ARG;
-    *out = nullptr;
-    if (!items || n < 1 || M < 1 || !device_buffer) return QFC_ERR_INVALID_ARG;
-    if (M > 4) return QFC_ERR_UNSUPPORTED;
-    if (!aligned16(device_buffer)) return QFC_ERR_ALIGNMENT;
-    if (buffer_bytes < kChainSyncBytes + (size_t)n * kSeqLayerBytes) return QFC_ERR_BUFFER_TOO_SMALL;
-    char *host = new (std::nothrow) char[(size_t)n * kSeqLayerBytes]();
-    qfc_chain_s *c = new (std::nothrow) qfc_chain_s;
-    if (!host || !c) {
-        delete[] host;
-        delete c;
-        return QFC_ERR_HIP;
-    }
-    c->runs = 0;
-    int num_cus = 0;
-    qfc_status_t s = QFC_OK;
-    for (int32_t i = 0; i < n && s == QFC_OK; ++i) {
-        const qfc_chain_item_t &it = items[i];
-        const Fusion f = to_fusion(&it.fusion);
-        s = check_fusion(it.layer, it.x_f16, M, it.y_f16, f);
-        if (s != QFC_OK) break;
-        if (f.gate || f.norm_gamma || it.layer->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE) {
-            s = QFC_ERR_UNSUPPORTED;
-            break;
-        }
-        num_cus = it.layer->num_cus;
-        int rounds = 0;
-        fill_seq_layer(host + (size_t)i * kSeqLayerBytes, it.layer->geo, it.layer->packed, it.x_f16, it.y_f16, f, M,
-                       num_cus, &rounds);
-        const int fmt = it.layer->geo.fmt;
-        if (c->runs == 0 || c->run[c->runs - 1].fmt != fmt) {
-            if (c->runs == kSeqMaxRuns) {
-                s = QFC_ERR_UNSUPPORTED;
-                break;
-            }
-            c->run[c->runs].first = i;
-            c->run[c->runs].count = 0;
-            c->run[c->runs].fmt = fmt;
-            c->run[c->runs].grid = 1;  // the largest number of rounds of its layers, for now
-            ++c->runs;
-        }
-        ++c->run[c->runs - 1].count;
-        if (rounds > c->run[c->runs - 1].grid) c->run[c->runs - 1].grid = rounds;
-    }
-    for (int r = 0; r < c->runs && s == QFC_OK; ++r) {
-        int resident = 0;
-        if (seq_resident_workgroups(M, c->run[r].fmt, num_cus, &resident) != hipSuccess) s = QFC_ERR_HIP;
-        if (c->run[r].grid > resident) c->run[r].grid = resident;
-    }
-    if (s == QFC_OK) {
-        char *dev = static_cast<char *>(device_buffer);
-        if (hipMemset(dev, 0, kChainSyncBytes) != hipSuccess ||
-            hipMemcpy(dev + kChainSyncBytes, host, (size_t)n * kSeqLayerBytes, hipMemcpyHostToDevice) != hipSuccess)
-            s = QFC_ERR_HIP;
-    }
-    delete[] host;
-    if (s != QFC_OK) {
-        delete c;
-        return s;
-    }
-    c->magic = kChainMagic;
-    c->sync = static_cast<unsigned *>(device_buffer);
-    c->layers = static_cast<char *>(device_buffer) + kChainSyncBytes;
-    c->n = n;
-    c->M = M;
-    *out = c;
-    return QFC_OK;
-}
-
-qfc_status_t qfc_chain_run(qfc_chain_t c, void *stream) {
-    if (!valid_chain(c)) return QFC_ERR_INVALID_ARG;
-    hipStream_t st = static_cast<hipStream_t>(stream);
-    if (launch_gemv_seq_reset(c->sync, st) != hipSuccess) return QFC_ERR_HIP;
-    for (int r = 0; r < c->runs; ++r) {
-        if (launch_gemv_seq(c->layers + (size_t)c->run[r].first * kSeqLayerBytes, c->run[r].count, c->M, c->run[r].fmt,
-                            c->sync + 2 * r, c->run[r].grid, st) != hipSuccess)
-            return QFC_ERR_HIP;
-    }
-    return QFC_OK;
-}
-
-qfc_status_t qfc_chain_status(qfc_chain_t c, int32_t *timed_out) {
-    if (!valid_chain(c) || !timed_out) return QFC_ERR_INVALID_ARG;
-    unsigned words[2 * kSeqMaxRuns];
-    if (hipDeviceSynchronize() != hipSuccess) return QFC_ERR_HIP;
-    if (hipMemcpy(words, c->sync, sizeof(words), hipMemcpyDeviceToHost) != hipSuccess) return QFC_ERR_HIP;
-    *timed_out = 0;
-    for (int r = 0; r < c->runs; ++r)
-        if (words[2 * r + 1] != 0u) *timed_out = 1;
-    return QFC_OK;
-}
-
-qfc_status_t qfc_chain_destroy(qfc_chain_t c) {
-    if (!valid_chain(c)) return QFC_ERR_INVALID_ARG;
-    c->magic = 0;
-    delete c;
-    return QFC_OK;
-}
-
 qfc_status_t qfc_destroy(qfc_handle_t h) {
     if (!valid(h)) return QFC_ERR_INVALID_ARG;
     h->magic = 0;
@@ -483,15 +351,13 @@ const char *qfc_status_string(qfc_status_t s) {
 // Tuning knob for experiments (not part of the documented interface):
 // key 0 = target wavefronts of a decode launch, 1 = max row tiles per
 // decode workgroup, 2 = prefill kernel variant, 3 = token rows per workgroup of the
-// activation quantization kernel (2, 4, 8; 0 = automatic), 4 = bound of a barrier wait of the
-// chain kernel in microseconds.
+// activation quantization kernel (2, 4, 8; 0 = automatic).
 void qfc_tune(int32_t key, int32_t value) {
     Tuning &t = tuning();
     if (key == 0) t.gemv_target_waves = value;
     if (key == 1) t.gemv_max_row_tiles = value;
     if (key == 2) t.gemm_variant = value;
     if (key == 3) t.act_quant_rows = value;
-    if (key == 4) t.seq_spin_limit_us = value;
 }
 
 }  // extern "C"

@@ -112,7 +112,6 @@ struct Tuning {
     int gemv_max_row_tiles = 2;
     int gemm_variant = 0;
     int act_quant_rows = 0;  // 0: automatic
-    int seq_spin_limit_us = 200000;  // bound of a barrier wait of the persistent decode kernel
 };
 Tuning &tuning();
 
@@ -241,17 +240,6 @@ struct Fusion {
 
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
                        const Fusion &f, int num_cus, hipStream_t st);
-// Persistent decode kernel over a chain of layers (M <= 4), one launch per run of consecutive
-// layers of one weight format.  A layer record of kSeqLayerBytes is filled on the host and copied
-// to device memory; every run has two words of `sync` (arrival counter, time-out flag), which
-// launch_gemv_seq_reset zeroes (64 words: up to kSeqMaxRuns runs).
-constexpr size_t kSeqLayerBytes = 144;
-constexpr int kSeqMaxRuns = 32;
-void fill_seq_layer(void *dst, const Geometry &g, const void *packed, const void *x, void *y, const Fusion &f,
-                    int M, int num_cus, int *rounds);
-hipError_t seq_resident_workgroups(int M, int fmt, int num_cus, int *grid);
-hipError_t launch_gemv_seq_reset(unsigned *sync, hipStream_t st);
-hipError_t launch_gemv_seq(const void *layers, int n, int M, int fmt, unsigned *sync, int grid, hipStream_t st);
 // Decode with 8-bit activations (per-channel weight formats).  src 0: x is binary16 and is
 // quantized in the kernel; 1: x is int8 with scales sx.  out_mode 0: binary16 y; 1: int32 sums.
 hipError_t launch_gemv_q8(const Geometry &g, const void *packed, const void *x, const float *sx, int src,
