@@ -32,13 +32,19 @@ Tuning &tuning() {
     return t;
 }
 
-static int wave_cap(int M) { return M > 4 ? 4 : 8; }
+// Wavefronts per workgroup at most.  Up to two token rows (and no prologue) the kernel needs few
+// enough registers for 16 wavefronts of a workgroup to be resident: a K of 9 to 16 units
+// (K = 14336: 14 units) then has one unit per wavefront and all its weight vectors in flight at
+// once, instead of two units per wavefront in turn.
+static int wave_cap(int M, bool plain, int KU) {
+    return M > 4 ? 4 : (M <= 2 && plain && KU > 8 && KU <= 16) ? 16 : 8;
+}
 
-GemvPlan plan_gemv(const Geometry &g, int M, int num_cus) {
+GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, bool plain) {
     (void)num_cus;
     const Tuning &t = tuning();
     GemvPlan p;
-    const int cap = wave_cap(M);
+    const int cap = wave_cap(M, plain, g.KU);
     const int per_wave = (g.KU + cap - 1) / cap;  // units per wavefront
     p.waves = (g.KU + per_wave - 1) / per_wave;
     const long waves_total = (long)g.RT * p.waves;
@@ -165,8 +171,8 @@ struct XStage {
     }
 };
 
-template <int M, int FMT, bool DB, int PRO>
-__global__ __launch_bounds__(PRO && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs a) {
+template <int M, int FMT, bool DB, int PRO, bool BIG = false>
+__global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs a) {
     constexpr int TILES = 8;                    // weight tiles per unit
     constexpr int NV = FMT == kW4G32 ? 12 : 8;  // 16-byte vectors per lane per (unit, row tile)
     constexpr int OCT = FMT == kW8C ? 64 : 128;
@@ -194,6 +200,7 @@ __global__ __launch_bounds__(PRO && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs
     // Merged RMS normalization: the rows' sums of squares, by the whole workgroup (fp32; partial
     // sums of the wavefronts are added in fixed order where they are used, at the end).
     __shared__ float s_ss[PRO == 2 ? 8 : 1][M];
+    static_assert(!(BIG && PRO), "up to 16 wavefronts only without a prologue");
     if constexpr (PRO == 2) {
         float ss[M];
 #pragma unroll
@@ -447,6 +454,17 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t
     if (red > lds) lds = red;
     // long-lived wavefronts (>= 3 items each) get the double-buffered variant
     const int items = ((g.KU + waves - 1) / waves) * (a.gated_out ? 2 : a.row_tiles);
+    if constexpr (M <= 2 && PRO == 0) {
+        if (waves > 8) {
+            if (g.fmt == kW8C)
+                gemv_kernel<M, kW8C, false, 0, true><<<grid, block, lds, st>>>(a);
+            else if (g.fmt == kW4C)
+                gemv_kernel<M, kW4C, false, 0, true><<<grid, block, lds, st>>>(a);
+            else
+                gemv_kernel<M, kW4G32, false, 0, true><<<grid, block, lds, st>>>(a);
+            return hipGetLastError();
+        }
+    }
     if constexpr (M <= 2) {
         if (items >= 3) {
             if (g.fmt == kW8C)
@@ -486,7 +504,7 @@ hipError_t launch_any_m(const Geometry &g, const GemvArgs &a, int M, int waves, 
 
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
                        const Fusion &f, int num_cus, hipStream_t st) {
-    const GemvPlan p = plan_gemv(g, M, num_cus);
+    const GemvPlan p = plan_gemv(g, M, num_cus, !f.gate && !f.norm_gamma);
     GemvArgs a;
     a.packed = static_cast<const u32x4 *>(packed);
     a.x = static_cast<const u32x4 *>(x);

@@ -115,7 +115,8 @@ struct Tuning {
 };
 Tuning &tuning();
 
-GemvPlan plan_gemv(const Geometry &g, int M, int num_cus);
+// plain: no prologue (gated input, merged normalization) is fused into the launch
+GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, bool plain = false);
 
 // Launchers.  Every one validates nothing (the C ABI layer did) and returns
 // the hipError_t of the launch.
