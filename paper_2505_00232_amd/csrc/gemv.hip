@@ -44,9 +44,17 @@ GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, bool plain) {
     (void)num_cus;
     const Tuning &t = tuning();
     GemvPlan p;
-    const int cap = wave_cap(M, plain, g.KU);
-    const int per_wave = (g.KU + cap - 1) / cap;  // units per wavefront
-    p.waves = (g.KU + per_wave - 1) / per_wave;
+    // Half-unit items (int4 formats, no prologue), where measured faster: launches of few
+    // wavefronts with a short K (O and QKV projections: twice the wavefronts, each with half the
+    // serial work), and for M > 4 a long K, where a wavefront's staged token rows (16 KB of LDS per
+    // unit at M = 8) limit the wavefronts a compute unit holds.
+    const long full_waves = (long)g.RT * g.KU;
+    const bool gain = M > 4 ? (g.KU > 4 || full_waves <= 1024) : (g.KU <= 4 && full_waves <= 2048);
+    p.half = plain && g.fmt != kW8C && (t.gemv_half >= 0 ? t.gemv_half != 0 : gain);
+    p.units = p.half ? (g.KT + 3) / 4 : g.KU;
+    const int cap = p.half ? 8 : wave_cap(M, plain, p.units);
+    const int per_wave = (p.units + cap - 1) / cap;  // items per wavefront and row tile
+    p.waves = (p.units + per_wave - 1) / per_wave;
     const long waves_total = (long)g.RT * p.waves;
     int r = (int)((waves_total + t.gemv_target_waves - 1) / t.gemv_target_waves);
     if (r > t.gemv_max_row_tiles) r = t.gemv_max_row_tiles;
@@ -137,9 +145,8 @@ struct GemvArgs {
 // a row by one number rs, which commutes with the product, so the row goes into LDS multiplied by
 // the normalization weight only and the output is multiplied by rs at the end; every workgroup
 // computes the rows' sums of squares for itself (one pass over x).
-template <int M, int FMT, int PRO>
+template <int M, int FMT, int PRO, int OCT>  // OCT: octets (8 k) per item
 struct XStage {
-    static constexpr int OCT = FMT == kW8C ? 64 : 128;  // octets per unit
     static constexpr int XV = M * OCT / 64;               // 16-byte vectors per lane per unit
     u32x4 v[XV];
     u32x4 g[PRO ? XV : 1];
@@ -171,11 +178,16 @@ struct XStage {
     }
 };
 
-template <int M, int FMT, bool DB, int PRO, bool BIG = false>
+// HALF (int4 formats): an item is half a unit, four weight tiles and the two scale vectors of their
+// 16 groups, and a wavefront stages 512 k of the token rows at a time: twice the wavefronts for
+// short K, and half the LDS and registers per wavefront for M > 4, where the staged rows limit
+// how many wavefronts a compute unit holds.  a.KU, a.units_q and a.units_rem then count half units.
+template <int M, int FMT, bool DB, int PRO, bool BIG = false, bool HALF = false>
 __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs a) {
-    constexpr int TILES = 8;                    // weight tiles per unit
-    constexpr int NV = FMT == kW4G32 ? 12 : 8;  // 16-byte vectors per lane per (unit, row tile)
-    constexpr int OCT = FMT == kW8C ? 64 : 128;
+    static_assert(!HALF || (FMT != kW8C && !DB), "half units: int4 formats, single buffer");
+    constexpr int TILES = HALF ? 4 : 8;         // weight tiles per item
+    constexpr int NV = FMT == kW4G32 ? TILES + TILES / 2 : TILES;  // 16-byte vectors per lane per (item, row tile)
+    constexpr int OCT = FMT == kW8C ? 64 : HALF ? 64 : 128;
     constexpr int MI = M < 4 ? M : 4;           // accumulator rows that matter on a lane
     extern __shared__ u32x4 lds_all[];
 
@@ -231,17 +243,19 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
     // count them and wait tile by tile instead of for everything.
     auto load_item = [&](u32x4(&buf)[NV], int u, int r, auto full) {
         const int nt = full ? TILES : min(TILES, a.KT - TILES * u);
-        const int pos = FMT == kW4G32 ? 9 * u : TILES * u;
+        const int U = HALF ? u >> 1 : u, h = HALF ? u & 1 : 0;  // unit, half of it
+        const int ntU = HALF ? min(8, a.KT - 8 * U) : nt;       // weight tiles before the unit's scale tile
+        const int pos = FMT == kW4G32 ? 9 * U : 8 * U;
         const u32x4 *base = a.packed + ((size_t)(rt0 + r * a.rt_step) * a.rt_stride + pos) * 64;
         // scales first: loads return in order, and the first tile's results need them
         if (FMT == kW4G32) {
 #pragma unroll
-            for (int p = 0; p < 4; ++p)
-                buf[TILES + p] = __builtin_nontemporal_load(base + nt * 64 + p * 16 + c);
+            for (int p = 0; p < TILES / 2; ++p)
+                buf[TILES + p] = __builtin_nontemporal_load(base + ntU * 64 + (h * 2 + p) * 16 + c);
         }
 #pragma unroll
         for (int t = 0; t < TILES; ++t)
-            if (full || t < nt) buf[t] = __builtin_nontemporal_load(base + t * 64 + lane);
+            if (full || t < nt) buf[t] = __builtin_nontemporal_load(base + (h * 4 + t) * 64 + lane);
     };
     constexpr std::false_type kMaybePartial{};
     constexpr std::true_type kFull{};
@@ -253,7 +267,7 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
     // one or two items.  DB = true: the next item's vectors are requested before
     // the current item is computed, for long-lived wavefronts.  Vector loads
     // return in order, so the (small) activation loads are issued first.
-    XStage<M, FMT, PRO> xs;
+    XStage<M, FMT, PRO, OCT> xs;
     u32x4 cur[NV];
     u32x4 nxt[DB ? NV : 1];
     const int items = (u1 - u0) * R;
@@ -445,15 +459,25 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
 }
 
 template <int M, int PRO>
-hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t st) {
+hipError_t launch_m(const Geometry &g, const GemvArgs &a, const GemvPlan &p, hipStream_t st) {
+    const int waves = p.waves;
     const dim3 grid((unsigned)(a.gated_out ? g.RT / 2 : (g.RT + a.row_tiles - 1) / a.row_tiles));
     const dim3 block((unsigned)(waves * 64));
-    const int oct = g.fmt == kW8C ? 64 : 128;
+    const int oct = g.fmt == kW8C || p.half ? 64 : 128;
     size_t lds = (size_t)waves * oct * M * 16;
     const size_t red = (size_t)waves * 4 * M * 16 * sizeof(float);
     if (red > lds) lds = red;
     // long-lived wavefronts (>= 3 items each) get the double-buffered variant
-    const int items = ((g.KU + waves - 1) / waves) * (a.gated_out ? 2 : a.row_tiles);
+    const int items = ((p.units + waves - 1) / waves) * (a.gated_out ? 2 : a.row_tiles);
+    if constexpr (PRO == 0) {
+        if (p.half) {
+            if (g.fmt == kW4C)
+                gemv_kernel<M, kW4C, false, 0, false, true><<<grid, block, lds, st>>>(a);
+            else
+                gemv_kernel<M, kW4G32, false, 0, false, true><<<grid, block, lds, st>>>(a);
+            return hipGetLastError();
+        }
+    }
     if constexpr (M <= 2 && PRO == 0) {
         if (waves > 8) {
             if (g.fmt == kW8C)
@@ -486,7 +510,7 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, int waves, hipStream_t
 }
 
 template <int PRO>
-hipError_t launch_any_m(const Geometry &g, const GemvArgs &a, int M, int waves, hipStream_t st) {
+hipError_t launch_any_m(const Geometry &g, const GemvArgs &a, int M, const GemvPlan &waves, hipStream_t st) {
     switch (M) {
         case 1: return launch_m<1, PRO>(g, a, waves, st);
         case 2: return launch_m<2, PRO>(g, a, waves, st);
@@ -517,20 +541,20 @@ hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int
     a.K = g.K;
     a.RT = g.RT;
     a.KT = g.KT;
-    a.KU = g.KU;
+    a.KU = p.units;
     a.rt_stride = g.rt_stride;
     a.row_tiles = p.row_tiles;
     a.rt_step = f.gated_output ? g.RT / 2 : 1;
     a.gated_out = f.gated_output ? 1 : 0;
-    a.units_q = g.KU / p.waves;
-    a.units_rem = g.KU % p.waves;
+    a.units_q = p.units / p.waves;
+    a.units_rem = p.units % p.waves;
     a.norm_eps = f.norm_eps;
     a.norm_offset = f.norm_offset;
     if (f.norm_gamma) {
         a.gate = static_cast<const u32x4 *>(f.norm_gamma);
-        return launch_any_m<2>(g, a, M, p.waves, st);
+        return launch_any_m<2>(g, a, M, p, st);
     }
-    return f.gate ? launch_any_m<1>(g, a, M, p.waves, st) : launch_any_m<0>(g, a, M, p.waves, st);
+    return f.gate ? launch_any_m<1>(g, a, M, p, st) : launch_any_m<0>(g, a, M, p, st);
 }
 
 }  // namespace qfc

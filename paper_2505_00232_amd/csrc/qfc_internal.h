@@ -104,6 +104,8 @@ inline Geometry make_geometry(int N, int K, int fmt) {
 struct GemvPlan {
     int waves;       // wavefronts per workgroup, each owning a range of units
     int row_tiles;   // row tiles a workgroup walks through (shares staged x)
+    bool half = false;  // items are half units (four weight tiles)
+    int units = 0;      // items per row tile along K
 };
 
 // Tunables (set through qfc_tune, used by the planners).
@@ -112,6 +114,7 @@ struct Tuning {
     int gemv_max_row_tiles = 2;
     int gemm_variant = 0;
     int act_quant_rows = 0;  // 0: automatic
+    int gemv_half = -1;      // half-unit items of the decode kernel: -1 automatic, 0 never, 1 where possible
 };
 Tuning &tuning();
 
