@@ -40,8 +40,9 @@ static int wave_cap(int M, bool plain, int KU) {
     return M > 4 ? 4 : (M <= 2 && plain && KU > 8 && KU <= 16) ? 16 : 8;
 }
 
-GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, bool plain) {
+GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, int pro) {
     (void)num_cus;
+    const bool plain = pro == 0;
     const Tuning &t = tuning();
     GemvPlan p;
     // Half-unit items (int4 formats, no prologue), where measured faster: launches of few
@@ -50,7 +51,8 @@ GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, bool plain) {
     // unit at M = 8) limit the wavefronts a compute unit holds.
     const long full_waves = (long)g.RT * g.KU;
     const bool gain = M > 4 ? (g.KU > 4 || full_waves <= 1024) : (g.KU <= 4 && full_waves <= 2048);
-    p.half = plain && g.fmt != kW8C && (t.gemv_half >= 0 ? t.gemv_half != 0 : gain);
+    const bool can = g.fmt != kW8C && (plain || (pro > 0 && M <= 4));  // kernels built with half-unit items
+    p.half = can && (t.gemv_half >= 0 ? t.gemv_half != 0 : gain);
     p.units = p.half ? (g.KT + 3) / 4 : g.KU;
     const int cap = p.half ? 8 : wave_cap(M, plain, p.units);
     const int per_wave = (p.units + cap - 1) / cap;  // items per wavefront and row tile
@@ -469,12 +471,12 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, const GemvPlan &p, hip
     if (red > lds) lds = red;
     // long-lived wavefronts (>= 3 items each) get the double-buffered variant
     const int items = ((p.units + waves - 1) / waves) * (a.gated_out ? 2 : a.row_tiles);
-    if constexpr (PRO == 0) {
+    if constexpr (PRO == 0 || M <= 4) {
         if (p.half) {
             if (g.fmt == kW4C)
-                gemv_kernel<M, kW4C, false, 0, false, true><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW4C, false, PRO, false, true><<<grid, block, lds, st>>>(a);
             else
-                gemv_kernel<M, kW4G32, false, 0, false, true><<<grid, block, lds, st>>>(a);
+                gemv_kernel<M, kW4G32, false, PRO, false, true><<<grid, block, lds, st>>>(a);
             return hipGetLastError();
         }
     }
@@ -528,7 +530,7 @@ hipError_t launch_any_m(const Geometry &g, const GemvArgs &a, int M, const GemvP
 
 hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int M, void *y,
                        const Fusion &f, int num_cus, hipStream_t st) {
-    const GemvPlan p = plan_gemv(g, M, num_cus, !f.gate && !f.norm_gamma);
+    const GemvPlan p = plan_gemv(g, M, num_cus, f.norm_gamma ? 2 : f.gate ? 1 : 0);
     GemvArgs a;
     a.packed = static_cast<const u32x4 *>(packed);
     a.x = static_cast<const u32x4 *>(x);

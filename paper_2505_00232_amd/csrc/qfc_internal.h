@@ -118,8 +118,9 @@ struct Tuning {
 };
 Tuning &tuning();
 
-// plain: no prologue (gated input, merged normalization) is fused into the launch
-GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, bool plain = false);
+// pro: the prologue fused into the launch (0 none, 1 gated input, 2 merged normalization); -1 for
+// the kernels that only take the basic plan
+GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, int pro = -1);
 
 // Launchers.  Every one validates nothing (the C ABI layer did) and returns
 // the hipError_t of the launch.
