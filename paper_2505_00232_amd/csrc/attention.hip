@@ -84,6 +84,7 @@ struct AttnArgs {
     float *ws_ml;        // [G, splits, M, 2] partial (maximum, sum)
     _Float16 *out;       // [G, M, D]
     int M, g, S, C, n_ctx, splits;
+    int num_cus;
     float scale;
 };
 
@@ -362,7 +363,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int q = lane & 31, h = lane >> 5;
     const int G = blockIdx.y;
-    const int block = (int)gridDim.x - 1 - (int)blockIdx.x;  // the blocks with the longest walks start first
+    // Causal walks grow with the block index.  The first workgroups (one per compute unit) take the
+    // blocks longest walk first; the next batch, which joins them on the same compute units, takes
+    // them shortest first, and so on in turns: two workgroups that share a compute unit have
+    // about the same work together everywhere.
+    const int linear = (int)(blockIdx.y * gridDim.x + blockIdx.x);
+    const bool ascending = ((linear / a.num_cus) & 1) != 0;
+    const int block = ascending ? (int)blockIdx.x : (int)gridDim.x - 1 - (int)blockIdx.x;
     const int r0 = (block * 4 + wave) * 32;                   // first query row of the wavefront
     const int m = r0 + q;
     const bool real = m < a.M;
@@ -602,6 +609,7 @@ hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G
     a.C = C;
     a.n_ctx = n_ctx;
     a.splits = attn_splits(G, n_ctx, num_cus);
+    a.num_cus = num_cus > 0 ? num_cus : 1;
     a.scale = 1.4426950408889634f / sqrtf((float)d);  // scores in units of log 2
     a.ws_o = static_cast<float *>(workspace);
     a.ws_ml = a.ws_o + (size_t)G * kAttnMaxSplits * a.M * d;
