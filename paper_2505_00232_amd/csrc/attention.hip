@@ -18,6 +18,8 @@
 //    the rows of the score tiles are assigned to positions so that lane (m, r) ends up with 2 x 8
 //    contiguous positions for query row m, and reads the same positions of its V rows, 16 bytes each).  The context is split over workgroups and
 //    wavefronts; partial (maximum, sum, O) triples meet in LDS and then in a second small kernel.
+#include <type_traits>
+
 #include "qfc_internal.h"
 
 namespace qfc {
@@ -233,6 +235,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_partial_kernel(Att
         }
         // ---- O^T = O^T corr + V P^T (the running maxima settle early: most steps have corr = 1 in every lane)
         const bool rescale = __any(corr != 1.0f);
+        __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             v4f o = acc[dt];
@@ -344,7 +347,7 @@ struct PrefillCfg {
     static constexpr int CPR = D / 8;                   // 16-byte chunks per K row
     static constexpr int KBYTES = 32 * D * 2;           // K rows of a step
     static constexpr int STAGE = 2 * KBYTES;            // + the V block of the step
-    static constexpr int NS = D <= 128 ? 4 : 3;         // LDS stages
+    static constexpr int NS = 4;                        // LDS stages
     static constexpr int COPIES = STAGE / 1024 / 4;     // copies per wavefront and stage
     __device__ static int swz(int p) { return D >= 128 ? (p & 15) : ((p >> 1) & 7); }
 };
@@ -446,43 +449,53 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
 
 #pragma unroll
     for (int p = 0; p < NS - 1; ++p) issue(p);
-    for (int blk = 0; blk < nb; ++blk) {
+    // The scores of step blk + 1 are computed while the softmax of step blk runs: their MFMAs do
+    // not depend on it, so the matrix core works through them while the vector unit does the
+    // exponentials (from one wavefront the two would otherwise take turns).
+    auto scores = [&](int blk_) {
+        const char *stage_ = reinterpret_cast<const char *>(lds_raw) + (blk_ % NS) * Cfg::STAGE;
+        u32x4 kf[DJ];
+#pragma unroll
+        for (int j = 0; j < DJ; ++j) kf[j] = *reinterpret_cast<const u32x4 *>(stage_ + koff[j]);
+        v16f r;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) r[e] = 0.0f;
+#pragma unroll
+        for (int j = 0; j < DJ; ++j)
+            r = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, kf[j]), __builtin_bit_cast(h8, qf[j]), r, 0, 0, 0);
+        return r;
+    };
+    wait_vmcnt<(NS - 2) * CP>();
+    asm volatile("s_barrier" ::: "memory");
+    v16f st = scores(0);
+    // One step; EDGE = some row of the wavefront does not see all 32 positions (causal horizon, or
+    // the end of the context).  The steps before a wavefront's first such step run a branch-free
+    // body, in which the compiler is told to issue the next step's score MFMAs one at a time between
+    // the vector instructions of the softmax.
+    auto step = [&](int blk, auto edge_c) {
+        constexpr bool EDGE = decltype(edge_c)::value;
         const int k0 = blk * 32;
-        wait_vmcnt<(NS - 2) * CP>();
+        // stage blk + 1 has landed (past the end: a copy of the last stage), and every wavefront is
+        // done with stage blk - 1, whose slot the next copies overwrite
+        wait_vmcnt<(NS - 3) * CP>();
         asm volatile("s_barrier" ::: "memory");
         issue(blk + NS - 1);
         const char *stage = reinterpret_cast<const char *>(lds_raw) + (blk % NS) * Cfg::STAGE;
-        v16f st;
-#pragma unroll
-        for (int e = 0; e < 16; ++e) st[e] = 0.0f;
-#pragma unroll
-        for (int j = 0; j < DJ; ++j) {
-            const u32x4 kf = *reinterpret_cast<const u32x4 *>(stage + koff[j]);
-            st = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, kf), __builtin_bit_cast(h8, qf[j]), st, 0, 0, 0);
-        }
         u32x4 vf[DT][2];
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int c = 0; c < 2; ++c) vf[dt][c] = *reinterpret_cast<const u32x4 *>(stage + voff[dt][c]);
+        const v16f st_next = scores(blk + 1);
         // register e = 8 c + 4 b + r of lane (q, h): position k0 + 16 c + 8 h + 4 b + r
         // raw scores; the scale (in units of log 2) is applied inside the exponent: 2^(s scale - maximum)
         float sc[16];
         float bmax = kNegBig;
-        const bool edge = k0 + 32 > lo_full;  // same for the whole wavefront
-        if (!edge) {
+        const int room = lim - k0 - 8 * h;  // register e stands for the position k0 + 8 h + (16 (e >> 3) + (e & 7))
 #pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                sc[e] = st[e];
-                bmax = fmaxf(bmax, sc[e]);
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 16; ++e) {
-                const int pos = k0 + 16 * (e >> 3) + 8 * h + (e & 7);
-                sc[e] = pos < lim ? st[e] : kNegBig;
-                bmax = fmaxf(bmax, sc[e]);
-            }
+        for (int e = 0; e < 16; ++e) {
+            sc[e] = !EDGE || 16 * (e >> 3) + (e & 7) < room ? st[e] : kNegBig;
+            bmax = fmaxf(bmax, sc[e]);
         }
         bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
         const float new_max = fmaxf(run_max, bmax * a.scale);  // kNegBig * scale stays hugely negative
@@ -493,12 +506,12 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
             float p = __builtin_amdgcn_exp2f(fmaf(sc[e], a.scale, -new_max));
-            if (edge) p = sc[e] > 0.5f * kNegBig ? p : 0.0f;
+            if (EDGE) p = sc[e] > 0.5f * kNegBig ? p : 0.0f;
             psum += p;
             pv[e >> 3][e & 7] = (_Float16)p;
         }
         run_sum = run_sum * corr + psum;
-        if (k0 + 32 > a.n_ctx) {  // positions past the context may hold anything
+        if (EDGE && k0 + 32 > a.n_ctx) {  // positions past the context may hold anything
 #pragma unroll
             for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -514,19 +527,33 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
                 }
         }
         const bool rescale = __any(corr != 1.0f);
+        if (!EDGE) {
+            // DJ groups of (one MFMA, a share of the softmax's vector instructions)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-            v16f o = acc[dt];
-            if (rescale) {
-#pragma unroll
-                for (int e = 0; e < 16; ++e) o[e] *= corr;
+            for (int j = 0; j < DJ; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 72 / DJ, 0);
             }
+        }
+        if (rescale) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[dt][e] *= corr;
+        }
+        __builtin_amdgcn_s_setprio(1);
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
-                o = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, vf[dt][c]), pv[c], o, 0, 0, 0);
-            acc[dt] = o;
-        }
-    }
+                acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, vf[dt][c]), pv[c], acc[dt], 0, 0, 0);
+        __builtin_amdgcn_s_setprio(0);
+        st = st_next;
+    };
+    const int nfull = min(nb, lo_full / 32);  // steps in which every row of the wavefront sees all positions
+    int blk = 0;
+    for (; blk < nfull; ++blk) step(blk, std::false_type{});
+    for (; blk < nb; ++blk) step(blk, std::true_type{});
     wait_vmcnt<0>();  // the redundant copies past the end have landed before the workgroup leaves
     run_sum += __shfl_xor(run_sum, 32, 64);
     if (!real) return;
