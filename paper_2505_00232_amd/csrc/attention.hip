@@ -468,11 +468,29 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     wait_vmcnt<(NS - 2) * CP>();
     asm volatile("s_barrier" ::: "memory");
     v16f st = scores(0);
-    // One step; EDGE = some row of the wavefront does not see all 32 positions (causal horizon, or
-    // the end of the context).  The steps before a wavefront's first such step run a branch-free
-    // body, in which the compiler is told to issue the next step's score MFMAs one at a time between
-    // the vector instructions of the softmax.
-    auto step = [&](int blk, auto edge_c) {
+    // The softmax of a step is cut in two.  Its first part (running maximum and the correction of
+    // the sums so far) only needs the step's scores, so it runs a step ahead, between the MFMAs of
+    // the previous step's second product; its second part (exponentials, sums, conversion) runs
+    // between the MFMAs of the next step's scores.  From one wavefront the matrix core and the
+    // vector unit would otherwise take turns.
+    // EDGE = some row of the wavefront does not see all 32 positions of the step (causal horizon or
+    // end of the context); the steps before a wavefront's first such step run branch-free bodies in
+    // which the compiler is told to issue the MFMAs one at a time between the vector instructions.
+    auto max_part = [&](const v16f &sv, int k0, auto edge_c) {
+        constexpr bool EDGE = decltype(edge_c)::value;
+        // register e = 8 c + 4 b + r of lane (q, h): position k0 + 8 h + (16 c + 4 b + r)
+        const int room = lim - k0 - 8 * h;
+        float bmax = kNegBig;
+#pragma unroll
+        for (int e = 0; e < 16; ++e) bmax = fmaxf(bmax, !EDGE || 16 * (e >> 3) + (e & 7) < room ? sv[e] : kNegBig);
+        bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
+        const float new_max = fmaxf(run_max, bmax * a.scale);  // kNegBig * scale stays hugely negative
+        const float c = __builtin_amdgcn_exp2f(run_max - new_max);
+        run_max = new_max;
+        return c;
+    };
+    float corr = max_part(st, 0, std::true_type{});
+    auto step = [&](int blk, auto edge_c, auto edge_next_c) {
         constexpr bool EDGE = decltype(edge_c)::value;
         const int k0 = blk * 32;
         // stage blk + 1 has landed (past the end: a copy of the last stage), and every wavefront is
@@ -480,6 +498,13 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
         wait_vmcnt<(NS - 3) * CP>();
         asm volatile("s_barrier" ::: "memory");
         issue(blk + NS - 1);
+        // (the one branch of a step comes first, so that the rest is one block for the scheduler)
+        if (__any(corr != 1.0f)) {
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+                for (int e = 0; e < 16; ++e) acc[dt][e] *= corr;
+        }
         const char *stage = reinterpret_cast<const char *>(lds_raw) + (blk % NS) * Cfg::STAGE;
         u32x4 vf[DT][2];
 #pragma unroll
@@ -487,26 +512,15 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
 #pragma unroll
             for (int c = 0; c < 2; ++c) vf[dt][c] = *reinterpret_cast<const u32x4 *>(stage + voff[dt][c]);
         const v16f st_next = scores(blk + 1);
-        // register e = 8 c + 4 b + r of lane (q, h): position k0 + 16 c + 8 h + 4 b + r
         // raw scores; the scale (in units of log 2) is applied inside the exponent: 2^(s scale - maximum)
-        float sc[16];
-        float bmax = kNegBig;
-        const int room = lim - k0 - 8 * h;  // register e stands for the position k0 + 8 h + (16 (e >> 3) + (e & 7))
-#pragma unroll
-        for (int e = 0; e < 16; ++e) {
-            sc[e] = !EDGE || 16 * (e >> 3) + (e & 7) < room ? st[e] : kNegBig;
-            bmax = fmaxf(bmax, sc[e]);
-        }
-        bmax = fmaxf(bmax, __shfl_xor(bmax, 32, 64));
-        const float new_max = fmaxf(run_max, bmax * a.scale);  // kNegBig * scale stays hugely negative
-        const float corr = __builtin_amdgcn_exp2f(run_max - new_max);
-        run_max = new_max;
+        const int room = lim - k0 - 8 * h;
+        const float cur_max = run_max;
         float psum = 0.0f;
         h8 pv[2];
 #pragma unroll
         for (int e = 0; e < 16; ++e) {
-            float p = __builtin_amdgcn_exp2f(fmaf(sc[e], a.scale, -new_max));
-            if (EDGE) p = sc[e] > 0.5f * kNegBig ? p : 0.0f;
+            float p = __builtin_amdgcn_exp2f(fmaf(st[e], a.scale, -cur_max));
+            if (EDGE) p = 16 * (e >> 3) + (e & 7) < room ? p : 0.0f;
             psum += p;
             pv[e >> 3][e & 7] = (_Float16)p;
         }
@@ -526,34 +540,38 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
                     vf[dt][c] = u32x4{w[0], w[1], w[2], w[3]};
                 }
         }
-        const bool rescale = __any(corr != 1.0f);
-        if (!EDGE) {
-            // DJ groups of (one MFMA, a share of the softmax's vector instructions)
-#pragma unroll
-            for (int j = 0; j < DJ; ++j) {
-                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 72 / DJ, 0);
-            }
-        }
-        if (rescale) {
-#pragma unroll
-            for (int dt = 0; dt < DT; ++dt)
-#pragma unroll
-                for (int e = 0; e < 16; ++e) acc[dt][e] *= corr;
-        }
         __builtin_amdgcn_s_setprio(1);
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int c = 0; c < 2; ++c)
                 acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, vf[dt][c]), pv[c], acc[dt], 0, 0, 0);
+        // first part of the next step's softmax (past the last step: of scores nobody uses)
+        corr = max_part(st_next, k0 + 32, edge_next_c);
         __builtin_amdgcn_s_setprio(0);
+        if (!EDGE && !decltype(edge_next_c)::value) {
+            // order asked of the scheduler: the operand reads, then every score MFMA followed by a
+            // share of the exponential part, then every MFMA of the second product followed by a
+            // share of the maximum part
+            __builtin_amdgcn_sched_group_barrier(0x100, DJ + 2 * DT, 0);
+#pragma unroll
+            for (int j = 0; j < DJ; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 64 / DJ, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < 2 * DT; ++j) {
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+            }
+        }
         st = st_next;
     };
     const int nfull = min(nb, lo_full / 32);  // steps in which every row of the wavefront sees all positions
     int blk = 0;
-    for (; blk < nfull; ++blk) step(blk, std::false_type{});
-    for (; blk < nb; ++blk) step(blk, std::true_type{});
+    for (; blk < nfull - 1; ++blk) step(blk, std::false_type{}, std::false_type{});
+    for (; blk < nfull; ++blk) step(blk, std::false_type{}, std::true_type{});
+    for (; blk < nb; ++blk) step(blk, std::true_type{}, std::true_type{});
     wait_vmcnt<0>();  // the redundant copies past the end have landed before the workgroup leaves
     run_sum += __shfl_xor(run_sum, 32, 64);
     if (!real) return;
