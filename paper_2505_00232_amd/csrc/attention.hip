@@ -541,10 +541,11 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
                 }
         }
         __builtin_amdgcn_s_setprio(1);
+        // (positions 0..15 of the step first: their probabilities are ready first)
 #pragma unroll
-        for (int dt = 0; dt < DT; ++dt)
+        for (int c = 0; c < 2; ++c)
 #pragma unroll
-            for (int c = 0; c < 2; ++c)
+            for (int dt = 0; dt < DT; ++dt)
                 acc[dt] = __builtin_amdgcn_mfma_f32_32x32x16_f16(__builtin_bit_cast(h8, vf[dt][c]), pv[c], acc[dt], 0, 0, 0);
         // first part of the next step's softmax (past the last step: of scores nobody uses)
         corr = max_part(st_next, k0 + 32, edge_next_c);
@@ -555,14 +556,19 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
             // share of the maximum part
             __builtin_amdgcn_sched_group_barrier(0x100, DJ + 2 * DT, 0);
 #pragma unroll
-            for (int j = 0; j < DJ; ++j) {
+            for (int j = 0; j < DJ; ++j) {  // score MFMAs, the exponentials of the step's first 16 positions
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 64 / DJ, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 32 / DJ, 0);
             }
 #pragma unroll
-            for (int j = 0; j < 2 * DT; ++j) {
+            for (int j = 0; j < DT; ++j) {  // second product over those positions, the other exponentials
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
-                __builtin_amdgcn_sched_group_barrier(0x002, 2, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 32 / DT, 0);
+            }
+#pragma unroll
+            for (int j = 0; j < DT; ++j) {  // second product over the rest, the next step's maximum part
+                __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
+                __builtin_amdgcn_sched_group_barrier(0x002, 16 / DT, 0);
             }
         }
         st = st_next;
