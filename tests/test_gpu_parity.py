@@ -61,7 +61,9 @@ def test_pack_unpack_round_trip_bit_exact(fmt, N, K):
 
 
 # ------------------------------------------------------------------ A2 decode
-DECODE_SHAPES = [(1, 32), (17, 96), (130, 256), (1000, 2304), (96, 14336), (1024, 512)]
+# (48, 6144): 12 units of the int8 format, 6 of the int4 formats, i.e. the plans with more than 8
+# wavefronts (int8) and with full units at a medium K (int4); (96, 14336): 14 / 28 units
+DECODE_SHAPES = [(1, 32), (17, 96), (130, 256), (1000, 2304), (96, 14336), (1024, 512), (48, 6144)]
 
 
 @pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
