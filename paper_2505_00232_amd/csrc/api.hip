@@ -359,6 +359,7 @@ void qfc_tune(int32_t key, int32_t value) {
     if (key == 2) t.gemm_variant = value;
     if (key == 3) t.act_quant_rows = value;
     if (key == 4) t.gemv_half = value;
+    if (key == 5) t.attn_pair = value;
 }
 
 }  // extern "C"

@@ -87,6 +87,7 @@ struct AttnArgs {
     _Float16 *out;       // [G, M, D]
     int M, g, S, C, n_ctx, splits;
     int num_cus;
+    int pair;  // prefill: a workgroup takes blocks (last - i, i) in turn
     float scale;
 };
 
@@ -372,7 +373,16 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     // about the same work together everywhere.
     const int linear = (int)(blockIdx.y * gridDim.x + blockIdx.x);
     const bool ascending = ((linear / a.num_cus) & 1) != 0;
-    const int block = ascending ? (int)blockIdx.x : (int)gridDim.x - 1 - (int)blockIdx.x;
+    // a.pair (launches of more than two workgroups per compute unit): a workgroup takes a long and a
+    // short block, one after the other, so that all workgroups have the same work and there are
+    // half as many (measured: S = 4096 231 -> 180 us, S = 8192 740 -> 645 us; slower for launches
+    // that are a single batch anyway).
+    const int nblocks = (a.M + 127) / 128;
+    const int reps = a.pair && 2 * (int)blockIdx.x + 1 < nblocks ? 2 : 1;
+  for (int rep = 0; rep < reps; ++rep) {
+    if (rep > 0) asm volatile("s_barrier" ::: "memory");  // every wavefront is done with the ring
+    const int block = a.pair ? (rep == 0 ? nblocks - 1 - (int)blockIdx.x : (int)blockIdx.x)
+                             : ascending ? (int)blockIdx.x : (int)gridDim.x - 1 - (int)blockIdx.x;
     const int r0 = (block * 4 + wave) * 32;                   // first query row of the wavefront
     const int m = r0 + q;
     const bool real = m < a.M;
@@ -580,18 +590,20 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     for (; blk < nb; ++blk) step(blk, std::true_type{}, std::true_type{});
     wait_vmcnt<0>();  // the redundant copies past the end have landed before the workgroup leaves
     run_sum += __shfl_xor(run_sum, 32, 64);
-    if (!real) return;
-    const float inv = 1.0f / run_sum;
-    // lane (q, h) holds O^T rows d = 32 dt + 8 b + 4 h + r of column q: four consecutive d per b
-    _Float16 *dst = a.out + ((size_t)G * a.M + m) * D;
+    if (real) {
+        const float inv = 1.0f / run_sum;
+        // lane (q, h) holds O^T rows d = 32 dt + 8 b + 4 h + r of column q: four consecutive d per b
+        _Float16 *dst = a.out + ((size_t)G * a.M + m) * D;
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt)
+        for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const h4 v = {(_Float16)(acc[dt][4 * b + 0] * inv), (_Float16)(acc[dt][4 * b + 1] * inv),
-                          (_Float16)(acc[dt][4 * b + 2] * inv), (_Float16)(acc[dt][4 * b + 3] * inv)};
-            *reinterpret_cast<h4 *>(dst + 32 * dt + 8 * b + 4 * h) = v;
-        }
+            for (int b = 0; b < 4; ++b) {
+                const h4 v = {(_Float16)(acc[dt][4 * b + 0] * inv), (_Float16)(acc[dt][4 * b + 1] * inv),
+                              (_Float16)(acc[dt][4 * b + 2] * inv), (_Float16)(acc[dt][4 * b + 3] * inv)};
+                *reinterpret_cast<h4 *>(dst + 32 * dt + 8 * b + 4 * h) = v;
+            }
+    }
+  }
 }
 
 template <int D>
@@ -605,7 +617,8 @@ hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    attn_prefill_kernel<D><<<dim3((unsigned)((a.M + 127) / 128), (unsigned)G), 256, lds, st>>>(a);
+    const int nblocks = (a.M + 127) / 128;
+    attn_prefill_kernel<D><<<dim3((unsigned)(a.pair ? (nblocks + 1) / 2 : nblocks), (unsigned)G), 256, lds, st>>>(a);
     return hipGetLastError();
 }
 
@@ -661,6 +674,11 @@ hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G
     a.n_ctx = n_ctx;
     a.splits = attn_splits(G, n_ctx, num_cus);
     a.num_cus = num_cus > 0 ? num_cus : 1;
+    {
+        const long wgs = (long)((a.M + 127) / 128) * G;
+        const int forced = tuning().attn_pair;
+        a.pair = forced >= 0 ? forced : (wgs > 2L * a.num_cus ? 1 : 0);
+    }
     a.scale = 1.4426950408889634f / sqrtf((float)d);  // scores in units of log 2
     a.ws_o = static_cast<float *>(workspace);
     a.ws_ml = a.ws_o + (size_t)G * kAttnMaxSplits * a.M * d;

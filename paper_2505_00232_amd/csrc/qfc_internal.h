@@ -114,6 +114,7 @@ struct Tuning {
     int gemv_max_row_tiles = 2;
     int gemm_variant = 0;
     int act_quant_rows = 0;  // 0: automatic
+    int attn_pair = -1;      // prefill attention, two blocks per workgroup: -1 automatic, 0 never, 1 always
     int gemv_half = -1;      // half-unit items of the decode kernel: -1 automatic, 0 never, 1 where possible
 };
 Tuning &tuning();

@@ -775,13 +775,23 @@ def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
     shape = _attn_shape(B, h_q, h_kv, d, C)
     ws = torch.empty(binding.qfc_attention_workspace_size(shape, S), dtype=torch.uint8, device=DEV)
     out = torch.full((G, M, d), 9.0, dtype=torch.float16, device=DEV)
-    binding.qfc_attention(torch.from_numpy(q).to(DEV), torch.from_numpy(Kd).to(DEV), binding.vcache_physical(torch.from_numpy(Vd).to(DEV)),
-                          S, n_ctx, shape, ws, out)
+    qd, kd, vd = torch.from_numpy(q).to(DEV), torch.from_numpy(Kd).to(DEV), binding.vcache_physical(torch.from_numpy(Vd).to(DEV))
+    binding.qfc_attention(qd, kd, vd, S, n_ctx, shape, ws, out)
     torch.cuda.synchronize()
     ref = oracle.attention(q, K, V, n_ctx, S)
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got))
     assert oracle.floored_rel_error(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
+    # the launch form of large grids (a workgroup takes a long and a short block of query rows in
+    # turn), forced on this small case: every row is computed as before, so the bits are the same
+    out2 = torch.full((G, M, d), 9.0, dtype=torch.float16, device=DEV)
+    binding.qfc_tune(5, 1)
+    try:
+        binding.qfc_attention(qd, kd, vd, S, n_ctx, shape, ws, out2)
+        torch.cuda.synchronize()
+    finally:
+        binding.qfc_tune(5, -1)
+    assert torch.equal(out, out2)
     # the first token's rows see n_ctx - S + 1 positions only: with one position the output is that value column
     if n_ctx == S:
         assert np.allclose(got[:, :g].astype(np.float64), np.repeat(V[:, None, :, 0], g, axis=1).astype(np.float64), rtol=2e-3, atol=2e-3)
