@@ -450,6 +450,7 @@ def main():
 
     if not args.skip_prefill:
         extra["prefill_attention_llama8b_s2048"] = prefill_attention_line()
+        extra["prefill_attention_llama8b_s8192"] = prefill_attention_line(8192)
 
     # ------------------------------------------------------------ prefill (configs 4 and 5)
     if not args.skip_prefill:
