@@ -78,12 +78,13 @@ def main():
             fcs.append((layer, i, fc))
     fcs.append((args.layers, 4, synth.LLAMA_LM_HEAD))
     workspace = torch.empty(1 << 20, dtype=torch.uint8, device=dev)
-    layers, x1, x4 = [], [], []
+    layers, x1, x4, x8 = [], [], [], []
     for layer, i, fc in fcs:
         wq, s = synth.weights(SEED, layer, i, fc)
         layers.append(binding.QuantLinear(wq, s, fc.fmt, max_m=8, workspace=workspace if fc.fmt == "w4g32" else None))
         x1.append(torch.from_numpy(synth.activations(SEED, layer, i, 1, fc.K)).to(dev))
         x4.append(torch.from_numpy(synth.activations(SEED, layer, i + 8, 4, fc.K)).to(dev))
+        x8.append(torch.from_numpy(synth.activations(SEED, layer, i + 16, 8, fc.K)).to(dev))
         del wq, s
     setup_s = time.time() - t_setup
 
@@ -145,10 +146,16 @@ def main():
     fb4, _ = step_runner(x4, 4)
     fb4.run()
     ms_m4 = event_ms(fb4.run, max(3, args.steps // 2))
+    fb8, _ = step_runner(x8, 8)
+    fb8.run()
+    ms_m8 = event_ms(fb8.run, max(3, args.steps // 2))
+    bytes_m8 = sum(synth.algorithmic_bytes(fc, 8) for _, _, fc in fcs)
     extra = {
         "lm_head_w8c_m1": {"us": round(ms_lm * 1e3, 2), "GB/s": round(lm_gbs, 1), "frac_hbm_peak": round(lm_gbs / HBM_PEAK_GBS, 4)},
         "decode_m4": {"ms_per_step": round(ms_m4, 4), "GB/s": round(bytes_m4 / (ms_m4 * 1e-3) / 1e9, 1),
                       "tokens_per_s": round(4 / (ms_m4 * 1e-3), 1)},
+        "decode_m8": {"ms_per_step": round(ms_m8, 4), "GB/s": round(bytes_m8 / (ms_m8 * 1e-3) / 1e9, 1),
+                      "tokens_per_s": round(8 / (ms_m8 * 1e-3), 1)},
         "decode_m1_tokens_per_s": round(1 / (ms_per_step * 1e-3), 1),
         "setup_s": round(setup_s, 1),
     }
@@ -175,7 +182,7 @@ def main():
 
     for l in layers:
         l.close()
-    del layers, fb1, fb4, fb_w4, fb_lm
+    del layers, fb1, fb4, fb8, fb_w4, fb_lm
     torch.cuda.empty_cache()
 
     # ------------------------------------------------------------ configs 1 and 2: small decode workloads, cold cache
