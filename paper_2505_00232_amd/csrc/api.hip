@@ -351,7 +351,8 @@ const char *qfc_status_string(qfc_status_t s) {
 // Tuning knob for experiments (not part of the documented interface):
 // key 0 = target wavefronts of a decode launch, 1 = max row tiles per
 // decode workgroup, 2 = prefill kernel variant, 3 = token rows per workgroup of the
-// activation quantization kernel (2, 4, 8; 0 = automatic).
+// activation quantization kernel (2, 4, 8; 0 = automatic), 4 = half-unit items of the decode
+// kernel and 5 = two blocks per workgroup in prefill attention (-1 automatic, 0 off, 1 on).
 void qfc_tune(int32_t key, int32_t value) {
     Tuning &t = tuning();
     if (key == 0) t.gemv_target_waves = value;

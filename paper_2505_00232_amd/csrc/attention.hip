@@ -341,8 +341,9 @@ __global__ __launch_bounds__(64) void attn_combine_kernel(AttnArgs a) {
 //   K stage: row = position of the step (32), D / 8 chunks per row; chunk o of row p sits at o ^ swz(p)
 //   V stage: row = d (D), 4 chunks per row (32 positions); chunk c of row d sits at c ^ ((d >> 2) & 3)
 // Causal: rows of token s see positions 0 .. n_ctx - S + s; the block stops at the last position
-// its last row sees, rows that see less mask the rest.  grid = (blocks of 128 query rows, G), long
-// blocks first.
+// its last row sees, rows that see less mask the rest.  grid = (blocks of 128 query rows, or pairs
+// of a long and a short block in large launches, G); which block a workgroup takes is decided at
+// the start of the kernel.
 template <int D>
 struct PrefillCfg {
     static constexpr int CPR = D / 8;                   // 16-byte chunks per K row
