@@ -438,8 +438,7 @@ def main():
     torch.cuda.empty_cache()
 
     # Causal attention of a Llama-3.1-8B layer over a 2048-token prompt (prefill: 8192 query rows per KV head)
-    def prefill_attention_line(S=2048):
-        h_q, h_kv, d = 32, 8, 128
+    def prefill_attention_line(S=2048, h_q=32, h_kv=8, d=128):
         shape = binding.AttnShape(1, h_q, h_kv, d, S)
         gen = torch.Generator(device=dev)
         gen.manual_seed(SEED + 600)
@@ -458,6 +457,7 @@ def main():
     if not args.skip_prefill:
         extra["prefill_attention_llama8b_s2048"] = prefill_attention_line()
         extra["prefill_attention_llama8b_s8192"] = prefill_attention_line(8192)
+        extra["prefill_attention_gemma2_2b_s2048"] = prefill_attention_line(2048, 8, 4, 256)
 
     # ------------------------------------------------------------ prefill (configs 4 and 5)
     if not args.skip_prefill:

@@ -254,8 +254,17 @@ qfc_status_t qfc_rope_qkv(const void *qkv_f16, int32_t S, int32_t pos0, const qf
                                       q_out, kcache, vcache, static_cast<hipStream_t>(stream)));
 }
 
+static int device_cus() {
+    int dev = 0, cus = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return 0;
+    if (hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess) return 0;
+    return cus;
+}
+
 static size_t attn_workspace(const qfc_attn_shape_t *a, int32_t S) {
-    if (S * (a->h_q / a->h_kv) > 16) return 256;  // many query rows: one pass per wavefront, no partial results
+    // many query rows: partial results only for launches of few blocks (whose walks are cut into chunks)
+    if (S * (a->h_q / a->h_kv) > 16)
+        return attn_prefill_workspace(a->batch * a->h_kv, S * (a->h_q / a->h_kv), a->d_head, device_cus());
     const size_t rows = (size_t)a->batch * a->h_kv * kAttnMaxSplits * (size_t)(S * (a->h_q / a->h_kv));
     return rows * (a->d_head + 2) * sizeof(float);
 }
@@ -361,6 +370,7 @@ void qfc_tune(int32_t key, int32_t value) {
     if (key == 3) t.act_quant_rows = value;
     if (key == 4) t.gemv_half = value;
     if (key == 5) t.attn_pair = value;
+    if (key == 6) t.attn_chunks = value;
 }
 
 }  // extern "C"

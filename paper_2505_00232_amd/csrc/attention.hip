@@ -88,6 +88,8 @@ struct AttnArgs {
     int M, g, S, C, n_ctx, splits;
     int num_cus;
     int pair;  // prefill: a workgroup takes blocks (last - i, i) in turn
+    int chunk_steps;  // prefill: > 0 = walks are cut into chunks of this many steps (one workgroup each)
+    int max_chunks;   // prefill: chunk slots per query row in the workspace
     float scale;
 };
 
@@ -380,10 +382,30 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     // that are a single batch anyway).
     const int nblocks = (a.M + 127) / 128;
     const int reps = a.pair && 2 * (int)blockIdx.x + 1 < nblocks ? 2 : 1;
+    // a.chunk_steps > 0 (launches with fewer blocks than compute units): the walk of a block is cut
+    // into chunks of that many steps, one workgroup each, longest blocks first; a block with more
+    // than one chunk leaves unnormalized partial results that a second kernel combines.
+    int chunk_block = 0, chunk = 0, chunks = 1;
+    if (a.chunk_steps > 0) {
+        int w = blockIdx.x;
+        for (int j = nblocks - 1;; --j) {
+            const int last = min(j * 128 + 127, a.M - 1);
+            const int cj = ((a.n_ctx - a.S + last / a.g + 1 + 31) / 32 + a.chunk_steps - 1) / a.chunk_steps;
+            if (w < cj || j == 0) {
+                chunk_block = j;
+                chunk = w;
+                chunks = cj;
+                break;
+            }
+            w -= cj;
+        }
+        if (chunk >= chunks) return;  // (a grid larger than the chunk count: nothing to do)
+    }
   for (int rep = 0; rep < reps; ++rep) {
     if (rep > 0) asm volatile("s_barrier" ::: "memory");  // every wavefront is done with the ring
-    const int block = a.pair ? (rep == 0 ? nblocks - 1 - (int)blockIdx.x : (int)blockIdx.x)
-                             : ascending ? (int)blockIdx.x : (int)gridDim.x - 1 - (int)blockIdx.x;
+    const int block = a.chunk_steps > 0 ? chunk_block
+                      : a.pair ? (rep == 0 ? nblocks - 1 - (int)blockIdx.x : (int)blockIdx.x)
+                      : ascending ? (int)blockIdx.x : (int)gridDim.x - 1 - (int)blockIdx.x;
     const int r0 = (block * 4 + wave) * 32;                   // first query row of the wavefront
     const int m = r0 + q;
     const bool real = m < a.M;
@@ -392,7 +414,10 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     // and drag the loop control and the copy addresses into vector registers)
     const int lo_full = __builtin_amdgcn_readfirstlane(a.n_ctx - a.S + min(r0, a.M - 1) / a.g + 1);  // positions every row of the wavefront sees
     const int block_last = min(block * 128 + 127, a.M - 1);
-    const int nb = __builtin_amdgcn_readfirstlane((a.n_ctx - a.S + block_last / a.g + 1 + 31) / 32);  // steps of the whole workgroup
+    const int nb_all = __builtin_amdgcn_readfirstlane((a.n_ctx - a.S + block_last / a.g + 1 + 31) / 32);  // steps of the block's walk
+    // the steps this workgroup takes: [sb, nb)
+    const int sb = a.chunk_steps > 0 ? chunk * a.chunk_steps : 0;
+    const int nb = a.chunk_steps > 0 ? min(nb_all, sb + a.chunk_steps) : nb_all;
 
     // Q^T operand: lane (q, h) holds Q[m][16 j + 8 h .. + 7]
     u32x4 qf[DJ];
@@ -407,6 +432,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
 #pragma unroll
         for (int e = 0; e < 16; ++e) acc[t][e] = 0.0f;
     float run_max = kNegBig, run_sum = 0.0f;
+    float run_max_final = kNegBig;  // the maximum over the steps actually taken (run_max runs a step ahead)
 
     // ---- copies: the stage's bytes are CP * 4 KiB pieces; wavefront w issues pieces w, w + 4, ..
     const char *kbase = reinterpret_cast<const char *>(a.kc + (size_t)G * a.C * D);
@@ -459,7 +485,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
         }
 
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p) issue(p);
+    for (int p = 0; p < NS - 1; ++p) issue(sb + p);
     // The scores of step blk + 1 are computed while the softmax of step blk runs: their MFMAs do
     // not depend on it, so the matrix core works through them while the vector unit does the
     // exponentials (from one wavefront the two would otherwise take turns).
@@ -478,7 +504,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     };
     wait_vmcnt<(NS - 2) * CP>();
     asm volatile("s_barrier" ::: "memory");
-    v16f st = scores(0);
+    v16f st = scores(sb);
     // The softmax of a step is cut in two.  Its first part (running maximum and the correction of
     // the sums so far) only needs the step's scores, so it runs a step ahead, between the MFMAs of
     // the previous step's second product; its second part (exponentials, sums, conversion) runs
@@ -500,7 +526,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
         run_max = new_max;
         return c;
     };
-    float corr = max_part(st, 0, std::true_type{});
+    float corr = max_part(st, sb * 32, std::true_type{});
     auto step = [&](int blk, auto edge_c, auto edge_next_c) {
         constexpr bool EDGE = decltype(edge_c)::value;
         const int k0 = blk * 32;
@@ -526,6 +552,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
         // raw scores; the scale (in units of log 2) is applied inside the exponent: 2^(s scale - maximum)
         const int room = lim - k0 - 8 * h;
         const float cur_max = run_max;
+        run_max_final = cur_max;
         float psum = 0.0f;
         h8 pv[2];
 #pragma unroll
@@ -585,13 +612,27 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
         st = st_next;
     };
     const int nfull = min(nb, lo_full / 32);  // steps in which every row of the wavefront sees all positions
-    int blk = 0;
+    int blk = sb;
     for (; blk < nfull - 1; ++blk) step(blk, std::false_type{}, std::false_type{});
     for (; blk < nfull; ++blk) step(blk, std::false_type{}, std::true_type{});
     for (; blk < nb; ++blk) step(blk, std::true_type{}, std::true_type{});
     wait_vmcnt<0>();  // the redundant copies past the end have landed before the workgroup leaves
     run_sum += __shfl_xor(run_sum, 32, 64);
-    if (real) {
+    if (real && chunks > 1) {
+        // partial result of this chunk: unnormalized O^T column, maximum (in units of log 2) and sum
+        const size_t slot = ((size_t)G * a.M + m) * a.max_chunks + chunk;
+        float *dst = a.ws_o + slot * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int b = 0; b < 4; ++b)
+                *reinterpret_cast<v4f *>(dst + 32 * dt + 8 * b + 4 * h) =
+                    v4f{acc[dt][4 * b + 0], acc[dt][4 * b + 1], acc[dt][4 * b + 2], acc[dt][4 * b + 3]};
+        if (h == 0) {
+            a.ws_ml[slot * 2] = run_max_final;
+            a.ws_ml[slot * 2 + 1] = run_sum;
+        }
+    } else if (real) {
         const float inv = 1.0f / run_sum;
         // lane (q, h) holds O^T rows d = 32 dt + 8 b + 4 h + r of column q: four consecutive d per b
         _Float16 *dst = a.out + ((size_t)G * a.M + m) * D;
@@ -607,6 +648,66 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
   }
 }
 
+// steps of the walk of block j, and the chunks it is cut into (host side of what the kernels compute)
+inline int prefill_steps(const AttnArgs &a, int j) {
+    const int last = (j * 128 + 127 < a.M - 1) ? j * 128 + 127 : a.M - 1;
+    return (a.n_ctx - a.S + last / a.g + 1 + 31) / 32;
+}
+inline int prefill_chunks(const AttnArgs &a, int j) {
+    return (prefill_steps(a, j) + a.chunk_steps - 1) / a.chunk_steps;
+}
+
+// Chunked walks: the rows of blocks with more than one chunk.  One wavefront per query row; lane l
+// takes the D / 64 consecutive values from d = l D / 64.
+template <int D>
+__global__ __launch_bounds__(256) void attn_prefill_combine_kernel(AttnArgs a) {
+    constexpr int PER = D / 64;
+    const int lane = threadIdx.x & 63;
+    const int m = blockIdx.x * 4 + (threadIdx.x >> 6);
+    const int G = blockIdx.y;
+    if (m >= a.M) return;
+    const int last = min((m / 128) * 128 + 127, a.M - 1);
+    const int chunks = ((a.n_ctx - a.S + last / a.g + 1 + 31) / 32 + a.chunk_steps - 1) / a.chunk_steps;
+    if (chunks <= 1) return;  // written by the first kernel
+    const size_t slot0 = ((size_t)G * a.M + m) * a.max_chunks;
+    // lane c < chunks holds chunk c's (maximum, sum); all loads of the row are requested at once
+    static_assert(kPrefillMaxChunks == 8, "the reductions below cover eight lanes");
+    float mx = kNegBig, l = 0.0f;
+    if (lane < chunks) {
+        mx = a.ws_ml[(slot0 + lane) * 2];
+        l = a.ws_ml[(slot0 + lane) * 2 + 1];
+    }
+    float part[kPrefillMaxChunks][PER];
+#pragma unroll
+    for (int c = 0; c < kPrefillMaxChunks; ++c) {
+        const float *src = a.ws_o + (slot0 + min(c, chunks - 1)) * D + lane * PER;
+#pragma unroll
+        for (int e = 0; e < PER; ++e) part[c][e] = src[e];
+    }
+    float top = mx;
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) top = fmaxf(top, __shfl_xor(top, off, 64));
+    top = __shfl(top, 0, 64);
+    const float f = lane < chunks ? __builtin_amdgcn_exp2f(mx - top) : 0.0f;
+    float den = f * l;
+#pragma unroll
+    for (int off = 1; off < 8; off <<= 1) den += __shfl_xor(den, off, 64);
+    den = __shfl(den, 0, 64);
+    float o[PER];
+#pragma unroll
+    for (int e = 0; e < PER; ++e) o[e] = 0.0f;
+#pragma unroll
+    for (int c = 0; c < kPrefillMaxChunks; ++c) {
+        const float fc = __shfl(f, c, 64);  // 0 for c >= chunks (whose loads repeated the last chunk)
+#pragma unroll
+        for (int e = 0; e < PER; ++e) o[e] = fmaf(fc, part[c][e], o[e]);
+    }
+    const float inv = 1.0f / den;
+    _Float16 *dst = a.out + ((size_t)G * a.M + m) * D + lane * PER;
+#pragma unroll
+    for (int e = 0; e < PER; ++e) dst[e] = (_Float16)(o[e] * inv);
+}
+
 template <int D>
 hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
     constexpr size_t lds = (size_t)PrefillCfg<D>::NS * PrefillCfg<D>::STAGE;
@@ -619,6 +720,15 @@ hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
         attr_set = true;
     }
     const int nblocks = (a.M + 127) / 128;
+    if (a.chunk_steps > 0) {
+        int total = 0;
+        for (int j = 0; j < nblocks; ++j) total += prefill_chunks(a, j);
+        attn_prefill_kernel<D><<<dim3((unsigned)total, (unsigned)G), 256, lds, st>>>(a);
+        const hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+        attn_prefill_combine_kernel<D><<<dim3((unsigned)((a.M + 3) / 4), (unsigned)G), 256, 0, st>>>(a);
+        return hipGetLastError();
+    }
     attn_prefill_kernel<D><<<dim3((unsigned)(a.pair ? (nblocks + 1) / 2 : nblocks), (unsigned)G), 256, lds, st>>>(a);
     return hipGetLastError();
 }
@@ -653,6 +763,19 @@ int attn_splits(int G, int n_ctx, int num_cus) {
     return s;
 }
 
+// The many-query-rows path needs partial results only where it may cut walks into chunks: launches
+// with no more blocks of 128 query rows than compute units.
+static bool prefill_may_chunk(int G, int M, int num_cus) {
+    const long wgs = (long)((M + 127) / 128) * G;
+    const int forced = tuning().attn_chunks;
+    return forced >= 0 ? forced != 0 : wgs <= num_cus;
+}
+
+size_t attn_prefill_workspace(int G, int M, int d, int num_cus) {
+    if (!prefill_may_chunk(G, M, num_cus)) return 256;
+    return (size_t)G * M * kPrefillMaxChunks * (d + 2) * sizeof(float);
+}
+
 hipError_t launch_rope_qkv(const void *qkv, int B, int S, int h_q, int h_kv, int d, int C, int pos0, float base,
                            void *q_out, void *kc, void *vc, hipStream_t st) {
     const long total = (long)B * S * (h_q + 2 * h_kv) * (d / 2);
@@ -679,10 +802,63 @@ hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G
         const long wgs = (long)((a.M + 127) / 128) * G;
         const int forced = tuning().attn_pair;
         a.pair = forced >= 0 ? forced : (wgs > 2L * a.num_cus ? 1 : 0);
+        // fewer blocks than compute units: cut the walks into chunks (at most kPrefillMaxChunks per
+        // block, at least 4 steps each) that fill the chip in one batch
+        a.chunk_steps = 0;
+        a.max_chunks = kPrefillMaxChunks;
+        if (a.M > 16 && prefill_may_chunk(G, a.M, a.num_cus)) {
+            const int nblocks = (a.M + 127) / 128;
+            long steps_total = 0;
+            int longest = 0;
+            for (int j = 0; j < nblocks; ++j) {
+                const int last = (j * 128 + 127 < a.M - 1) ? j * 128 + 127 : a.M - 1;
+                const int nbj = (n_ctx - S + last / g + 1 + 31) / 32;
+                steps_total += nbj;
+                if (nbj > longest) longest = nbj;
+            }
+            // the shortest chunk length whose chunks are all resident at once (two workgroups per
+            // compute unit up to head size 128, one above)
+            const long slots = (long)a.num_cus * (d <= 128 ? 2 : 1);
+            long len = (steps_total * G + slots - 1) / slots;
+            const int floor_len = (longest + kPrefillMaxChunks - 1) / kPrefillMaxChunks;
+            if (len < floor_len) len = floor_len;
+            if (len < 4) len = 4;
+            for (; len < longest; ++len) {
+                long total = 0;
+                for (int j = 0; j < nblocks; ++j) {
+                    const int last = (j * 128 + 127 < a.M - 1) ? j * 128 + 127 : a.M - 1;
+                    const int nbj = (n_ctx - S + last / g + 1 + 31) / 32;
+                    total += (nbj + len - 1) / len;
+                }
+                if (total * G <= slots) break;
+            }
+            if (len < longest) {  // else every block is one chunk anyway
+                // Worth it?  The launch ends with its longest walk: chunks save (longest - len) steps
+                // of a workgroup (measured: about 0.6 / 0.9 / 1.7 us per step at head size 64 / 128 /
+                // 256) and cost a second launch plus the partial results written and read again
+                // (taken at 4 TB/s).  Many query heads per KV head with short heads lose, few heads
+                // with long ones (one step is twice the work) win by up to 2x.
+                double partial_bytes = 0.0;
+                for (int j = 0; j < nblocks; ++j) {
+                    const int last = (j * 128 + 127 < a.M - 1) ? j * 128 + 127 : a.M - 1;
+                    const int nbj = (n_ctx - S + last / g + 1 + 31) / 32;
+                    const long cj = (nbj + len - 1) / len;
+                    if (cj > 1) partial_bytes += (double)(last - j * 128 + 1) * cj * (d + 2) * 8.0;
+                }
+                partial_bytes *= G;
+                const double step_us = d <= 64 ? 0.6 : d <= 128 ? 0.9 : 1.7;
+                const double gain_us = (double)(longest - len) * step_us;
+                const double cost_us = 3.0 + partial_bytes / 4.0e6;
+                if (tuning().attn_chunks > 0 || gain_us > 1.2 * cost_us) {
+                    a.chunk_steps = (int)len;
+                    a.pair = 0;
+                }
+            }
+        }
     }
     a.scale = 1.4426950408889634f / sqrtf((float)d);  // scores in units of log 2
     a.ws_o = static_cast<float *>(workspace);
-    a.ws_ml = a.ws_o + (size_t)G * kAttnMaxSplits * a.M * d;
+    a.ws_ml = a.ws_o + (size_t)G * (a.M > 16 ? kPrefillMaxChunks : kAttnMaxSplits) * a.M * d;
     a.out = static_cast<_Float16 *>(out);
     if (a.M > 16) {
         switch (d) {

@@ -114,6 +114,7 @@ struct Tuning {
     int gemv_max_row_tiles = 2;
     int gemm_variant = 0;
     int act_quant_rows = 0;  // 0: automatic
+    int attn_chunks = -1;    // prefill attention, walks cut into chunks: -1 automatic, 0 never, 1 always
     int attn_pair = -1;      // prefill attention, two blocks per workgroup: -1 automatic, 0 never, 1 always
     int gemv_half = -1;      // half-unit items of the decode kernel: -1 automatic, 0 never, 1 where possible
 };
@@ -264,6 +265,9 @@ struct RmsNormArgs {
 hipError_t launch_rmsnorm(const RmsNormArgs &a, int M, int K, int num_cus, hipStream_t st);
 // Attention-side operators (see qfc_rope_qkv / qfc_attention).  G = batch * h_kv groups.
 constexpr int kAttnMaxSplits = 64;
+constexpr int kPrefillMaxChunks = 8;  // chunks a block's walk is cut into at most (prefill, few blocks)
+// Bytes of workspace the many-query-rows path needs for G groups of M query rows of d values.
+size_t attn_prefill_workspace(int G, int M, int d, int num_cus);
 int attn_splits(int G, int n_ctx, int num_cus);
 hipError_t launch_rope_qkv(const void *qkv, int B, int S, int h_q, int h_kv, int d, int C, int pos0, float base,
                            void *q_out, void *kc, void *vc, hipStream_t st);

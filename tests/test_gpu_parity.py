@@ -792,6 +792,19 @@ def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
     finally:
         binding.qfc_tune(5, -1)
     assert torch.equal(out, out2)
+    # the launch form of few blocks (walks cut into chunks, partial results combined by a second
+    # kernel), forced on: same values within the tolerance, finite, and nothing from past the context
+    binding.qfc_tune(6, 1)
+    try:
+        ws3 = torch.empty(binding.qfc_attention_workspace_size(shape, S), dtype=torch.uint8, device=DEV)
+        out3 = torch.full((G, M, d), 9.0, dtype=torch.float16, device=DEV)
+        binding.qfc_attention(qd, kd, vd, S, n_ctx, shape, ws3, out3)
+        torch.cuda.synchronize()
+    finally:
+        binding.qfc_tune(6, -1)
+    got3 = out3.cpu().numpy()
+    assert np.all(np.isfinite(got3))
+    assert oracle.floored_rel_error(got3.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
     # the first token's rows see n_ctx - S + 1 positions only: with one position the output is that value column
     if n_ctx == S:
         assert np.allclose(got[:, :g].astype(np.float64), np.repeat(V[:, None, :, 0], g, axis=1).astype(np.float64), rtol=2e-3, atol=2e-3)
