@@ -232,7 +232,9 @@ qfc_status_t qfc_attention_workspace_size(const qfc_attn_shape_t *shape, int32_t
  * positions; the S query tokens are the last S of them (token s sees positions
  * 0 .. n_ctx - S + s).  Up to 16 query rows per KV head (S * g <= 16, decode) the
  * context is split over workgroups; with more (prefill) a wavefront owns 32 query rows
- * and walks the positions they see.  Positions >= n_ctx of the caches are never used,
+ * and walks the positions they see (launches with fewer blocks of 128 query rows than
+ * compute units may cut those walks into chunks whose partial results, kept in the
+ * workspace, a second kernel combines).  Positions >= n_ctx of the caches are never used,
  * whatever they hold.  The scores are not materialized.
  * workspace: device scratch of at least qfc_attention_workspace_size bytes, 16-byte aligned. */
 qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache, int32_t S, int32_t n_ctx,
