@@ -352,18 +352,25 @@ struct PrefillCfg {
     static constexpr int KBYTES = 32 * D * 2;           // K rows of a step
     static constexpr int STAGE = 2 * KBYTES;            // + the V block of the step
     static constexpr int NS = 4;                        // LDS stages
-    static constexpr int COPIES = STAGE / 1024 / 4;     // copies per wavefront and stage
+    static constexpr int HALVES = D > 128 ? 2 : 1;      // wavefronts that share 32 query rows (each a part of d)
+    static constexpr int NW = 4 * HALVES;               // wavefronts per workgroup
+    static constexpr int COPIES = STAGE / 1024 / NW;    // copies per wavefront and stage
     __device__ static int swz(int p) { return D >= 128 ? (p & 15) : ((p >> 1) & 7); }
 };
 
 // (Two workgroups per compute unit up to head size 128: said in the launch bounds, so that the
 // accumulators stay in ordinary registers, where the softmax rescales them in place.)
 template <int D>
-__global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(AttnArgs a) {
+__global__ __launch_bounds__(64 * PrefillCfg<D>::NW, 2) void attn_prefill_kernel(AttnArgs a) {
     typedef float v16f __attribute__((ext_vector_type(16)));
     typedef PrefillCfg<D> Cfg;
     constexpr int DJ = D / 16;  // MFMA steps along d of the score product
-    constexpr int DT = D / 32;  // row tiles of O^T
+    // Head size 256: eight wavefronts; wavefronts w and w + 4 own the same 32 query rows and both
+    // compute their scores and probabilities, but each accumulates one half of the d range of O^T
+    // (with all of it a wavefront would need more than half the register file, i.e. one wavefront
+    // per SIMD with nothing to overlap with).
+    constexpr int HALVES = Cfg::HALVES, NW = Cfg::NW;
+    constexpr int DT = D / 32 / HALVES;  // row tiles of O^T of this wavefront
     constexpr int NS = Cfg::NS, CP = Cfg::COPIES;
     extern __shared__ uint4 lds_raw[];
     const int lane = threadIdx.x & 63;
@@ -406,7 +413,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     const int block = a.chunk_steps > 0 ? chunk_block
                       : a.pair ? (rep == 0 ? nblocks - 1 - (int)blockIdx.x : (int)blockIdx.x)
                       : ascending ? (int)blockIdx.x : (int)gridDim.x - 1 - (int)blockIdx.x;
-    const int r0 = (block * 4 + wave) * 32;                   // first query row of the wavefront
+    const int r0 = (block * 4 + (wave & 3)) * 32;             // first query row of the wavefront
     const int m = r0 + q;
     const bool real = m < a.M;
     const int lim = real ? a.n_ctx - a.S + m / a.g + 1 : a.n_ctx;
@@ -441,7 +448,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     uint32_t src_off[CP];  // byte offset of this lane's 16 bytes inside the step's K rows / V block (step-invariant part)
 #pragma unroll
     for (int i = 0; i < CP; ++i) {
-        const int piece = wave + 4 * i;      // KiB piece of the stage
+        const int piece = wave + NW * i;     // KiB piece of the stage
         const int L = piece * 64 + lane;     // linear 16-byte chunk of the stage
         if (piece < Cfg::KBYTES / 1024) {
             const int p = L / Cfg::CPR, o = (L % Cfg::CPR) ^ Cfg::swz(p);
@@ -459,7 +466,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
         const char *vsrc = vbase + (size_t)(p0 / 64) * D * 128 + (p0 % 64) * 2;
 #pragma unroll
         for (int i = 0; i < CP; ++i) {
-            const int piece = wave + 4 * i;
+            const int piece = wave + NW * i;
             const bool is_k = piece < Cfg::KBYTES / 1024;
             // (the address is the same in every lane; saying so keeps it in scalar registers for the copy)
             const uint64_t addr = reinterpret_cast<uint64_t>(is_k ? ksrc : vsrc);
@@ -480,7 +487,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
     for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
         for (int c = 0; c < 2; ++c) {
-            const int d = 32 * dt + q;
+            const int d = 32 * (dt + (wave >> 2) * DT) + q;
             voff[dt][c] = Cfg::KBYTES + d * 64 + (((2 * c + h) ^ ((d >> 2) & 3)) * 16);
         }
 
@@ -592,7 +599,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
             // order asked of the scheduler: the operand reads, then every score MFMA followed by a
             // share of the exponential part, then every MFMA of the second product followed by a
             // share of the maximum part
-            __builtin_amdgcn_sched_group_barrier(0x100, DJ + 2 * DT, 0);
+            if (HALVES == 1) __builtin_amdgcn_sched_group_barrier(0x100, DJ + 2 * DT, 0);
 #pragma unroll
             for (int j = 0; j < DJ; ++j) {  // score MFMAs, the exponentials of the step's first 16 positions
                 __builtin_amdgcn_sched_group_barrier(0x008, 1, 0);
@@ -626,9 +633,9 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
             for (int b = 0; b < 4; ++b)
-                *reinterpret_cast<v4f *>(dst + 32 * dt + 8 * b + 4 * h) =
+                *reinterpret_cast<v4f *>(dst + 32 * (dt + (wave >> 2) * DT) + 8 * b + 4 * h) =
                     v4f{acc[dt][4 * b + 0], acc[dt][4 * b + 1], acc[dt][4 * b + 2], acc[dt][4 * b + 3]};
-        if (h == 0) {
+        if (h == 0 && wave < 4) {
             a.ws_ml[slot * 2] = run_max_final;
             a.ws_ml[slot * 2 + 1] = run_sum;
         }
@@ -642,7 +649,7 @@ __global__ __launch_bounds__(256, D <= 128 ? 2 : 1) void attn_prefill_kernel(Att
             for (int b = 0; b < 4; ++b) {
                 const h4 v = {(_Float16)(acc[dt][4 * b + 0] * inv), (_Float16)(acc[dt][4 * b + 1] * inv),
                               (_Float16)(acc[dt][4 * b + 2] * inv), (_Float16)(acc[dt][4 * b + 3] * inv)};
-                *reinterpret_cast<h4 *>(dst + 32 * dt + 8 * b + 4 * h) = v;
+                *reinterpret_cast<h4 *>(dst + 32 * (dt + (wave >> 2) * DT) + 8 * b + 4 * h) = v;
             }
     }
   }
@@ -723,13 +730,13 @@ hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
     if (a.chunk_steps > 0) {
         int total = 0;
         for (int j = 0; j < nblocks; ++j) total += prefill_chunks(a, j);
-        attn_prefill_kernel<D><<<dim3((unsigned)total, (unsigned)G), 256, lds, st>>>(a);
+        attn_prefill_kernel<D><<<dim3((unsigned)total, (unsigned)G), 64 * PrefillCfg<D>::NW, lds, st>>>(a);
         const hipError_t e = hipGetLastError();
         if (e != hipSuccess) return e;
         attn_prefill_combine_kernel<D><<<dim3((unsigned)((a.M + 3) / 4), (unsigned)G), 256, 0, st>>>(a);
         return hipGetLastError();
     }
-    attn_prefill_kernel<D><<<dim3((unsigned)(a.pair ? (nblocks + 1) / 2 : nblocks), (unsigned)G), 256, lds, st>>>(a);
+    attn_prefill_kernel<D><<<dim3((unsigned)(a.pair ? (nblocks + 1) / 2 : nblocks), (unsigned)G), 64 * PrefillCfg<D>::NW, lds, st>>>(a);
     return hipGetLastError();
 }
 
@@ -834,7 +841,7 @@ hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G
             }
             if (len < longest) {  // else every block is one chunk anyway
                 // Worth it?  The launch ends with its longest walk: chunks save (longest - len) steps
-                // of a workgroup (measured: about 0.6 / 0.9 / 1.7 us per step at head size 64 / 128 /
+                // of a workgroup (measured: about 0.6 / 0.9 / 1.4 us per step at head size 64 / 128 /
                 // 256) and cost a second launch plus the partial results written and read again
                 // (taken at 4 TB/s).  Many query heads per KV head with short heads lose, few heads
                 // with long ones (one step is twice the work) win by up to 2x.
@@ -846,7 +853,7 @@ hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G
                     if (cj > 1) partial_bytes += (double)(last - j * 128 + 1) * cj * (d + 2) * 8.0;
                 }
                 partial_bytes *= G;
-                const double step_us = d <= 64 ? 0.6 : d <= 128 ? 0.9 : 1.7;
+                const double step_us = d <= 64 ? 0.6 : d <= 128 ? 0.9 : 1.4;
                 const double gain_us = (double)(longest - len) * step_us;
                 const double cost_us = 3.0 + partial_bytes / 4.0e6;
                 if (tuning().attn_chunks > 0 || gain_us > 1.2 * cost_us) {
