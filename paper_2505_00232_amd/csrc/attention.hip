@@ -719,13 +719,7 @@ template <int D>
 hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
     constexpr size_t lds = (size_t)PrefillCfg<D>::NS * PrefillCfg<D>::STAGE;
     static_assert(lds <= 160 * 1024, "LDS budget");
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_prefill_kernel<D>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (const hipError_t e = allow_dynamic_lds<attn_prefill_kernel<D>>(lds); e != hipSuccess) return e;
     const int nblocks = (a.M + 127) / 128;
     if (a.chunk_steps > 0) {
         int total = 0;
@@ -743,13 +737,7 @@ hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
 template <int D>
 hipError_t launch_attn(const AttnArgs &a, int G, hipStream_t st) {
     const size_t lds = (size_t)4 * 16 * (D + 4) * sizeof(float);
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(attn_partial_kernel<D>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (const hipError_t e = allow_dynamic_lds<attn_partial_kernel<D>>(lds); e != hipSuccess) return e;
     attn_partial_kernel<D><<<dim3((unsigned)a.splits, (unsigned)G), 256, lds, st>>>(a);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess || a.splits == 1) return e;

@@ -652,13 +652,7 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
 
 template <bool PC>
 hipError_t launch_direct(GemmF16Args a, int M, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_direct_kernel<PC>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, kDirectLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (const hipError_t e = allow_dynamic_lds<gemm_f16_w4_direct_kernel<PC>>(kDirectLdsBytes); e != hipSuccess) return e;
     a.n_tiles = (a.N + DBN - 1) / DBN;
     a.m_tiles = (M + DBM - 1) / DBM;
     gemm_f16_w4_direct_kernel<PC><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 512, kDirectLdsBytes, st>>>(a);
@@ -667,13 +661,7 @@ hipError_t launch_direct(GemmF16Args a, int M, hipStream_t st) {
 
 template <bool PC>
 hipError_t launch_fallback(GemmF16Args a, int M, hipStream_t st) {
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_f16_w4_kernel<PC>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)kLdsBytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (const hipError_t e = allow_dynamic_lds<gemm_f16_w4_kernel<PC>>(kLdsBytes); e != hipSuccess) return e;
     a.n_tiles = (a.N + BN - 1) / BN;
     a.m_tiles = (M + BM - 1) / BM;
     gemm_f16_w4_kernel<PC><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, kLdsBytes, st>>>(a);

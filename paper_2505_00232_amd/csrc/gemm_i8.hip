@@ -399,13 +399,7 @@ hipError_t launch_dw(GemmI8Args a, hipStream_t st) {
     static_assert(lds_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks in the same LDS");
     if ((a.Kp / 64) % PW != 0) return hipErrorInvalidValue;
     static_assert(lds_bytes <= 80 * 1024, "two workgroups per compute unit");
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e = hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE>),
-                                                 hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (const hipError_t e = allow_dynamic_lds<gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE>>(lds_bytes); e != hipSuccess) return e;
     a.n_tiles = (a.N + 255) / 256;
     a.m_tiles = (a.M + 32 * TM - 1) / (32 * TM);
     gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
@@ -416,14 +410,7 @@ template <int BN, int BM, int KTS, int NS, int OUT_MODE>
 hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
     constexpr size_t lds_bytes = (size_t)NS * ((BN + BM) / 16 * KTS) * 1024;
     static_assert(lds_bytes <= 160 * 1024, "LDS budget");
-    static bool attr_set = false;
-    if (!attr_set) {
-        const hipError_t e =
-            hipFuncSetAttribute(reinterpret_cast<const void *>(gemm_i8_kernel<BN, BM, KTS, NS, OUT_MODE>),
-                                hipFuncAttributeMaxDynamicSharedMemorySize, (int)lds_bytes);
-        if (e != hipSuccess) return e;
-        attr_set = true;
-    }
+    if (const hipError_t e = allow_dynamic_lds<gemm_i8_kernel<BN, BM, KTS, NS, OUT_MODE>>(lds_bytes); e != hipSuccess) return e;
     a.n_tiles = (a.N + BN - 1) / BN;
     a.m_tiles = (a.M + BM - 1) / BM;
     gemm_i8_kernel<BN, BM, KTS, NS, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);

@@ -41,6 +41,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <atomic>
+
 #include "../../include/qfc.h"
 
 namespace qfc {
@@ -130,6 +132,22 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
                        hipStream_t st);
 hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void *scales,
                          hipStream_t st);
+// Allow kernel Kernel `bytes` of dynamic LDS (above the default limit of 64 KiB): set once per
+// kernel and device, from whichever thread gets there first (setting it twice is harmless).
+template <auto Kernel>
+hipError_t allow_dynamic_lds(size_t bytes) {
+    static std::atomic<uint64_t> done{0};  // one bit per device (devices beyond 63 set it every time)
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    const uint64_t bit = dev >= 0 && dev < 64 ? uint64_t(1) << dev : 0;
+    if (bit && (done.load(std::memory_order_acquire) & bit)) return hipSuccess;
+    e = hipFuncSetAttribute(reinterpret_cast<const void *>(Kernel), hipFuncAttributeMaxDynamicSharedMemorySize,
+                            (int)bytes);
+    if (e == hipSuccess && bit) done.fetch_or(bit, std::memory_order_release);
+    return e;
+}
+
 // ---- helpers of the kernels that copy tiles from memory straight into LDS
 // Wait until at most N vector-memory operations are outstanding and all LDS operations are done
 // (gfx9 s_waitcnt encoding: vmcnt in bits 3:0 and 15:14, lgkmcnt in bits 11:8, expcnt left at its
