@@ -758,7 +758,8 @@ def test_attention_over_the_cache(B, S, h_q, h_kv, d, C, n_ctx):
 @pytest.mark.parametrize("B,S,h_q,h_kv,d,C,n_ctx", [(1, 5, 8, 2, 64, 64, 5), (1, 40, 4, 4, 128, 128, 40),
                                                     (2, 33, 8, 2, 128, 192, 150), (1, 100, 8, 4, 256, 128, 100),
                                                     (1, 256, 32, 8, 128, 512, 300), (1, 64, 16, 1, 64, 1024, 1000),
-                                                    (1, 1024, 32, 8, 128, 1024, 1024)])
+                                                    (1, 1024, 32, 8, 128, 1024, 1024),
+                                                    (1, 640, 8, 4, 256, 640, 640)])
 def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
     """Prefill: more than 16 query rows per KV head, causal by token, ragged row and position counts."""
     print(f"prefill attention B={B} S={S} h_q={h_q} h_kv={h_kv} d={d} C={C} n_ctx={n_ctx}", flush=True)
@@ -808,6 +809,27 @@ def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
     # the first token's rows see n_ctx - S + 1 positions only: with one position the output is that value column
     if n_ctx == S:
         assert np.allclose(got[:, :g].astype(np.float64), np.repeat(V[:, None, :, 0], g, axis=1).astype(np.float64), rtol=2e-3, atol=2e-3)
+
+
+def test_attention_few_blocks_needs_the_larger_workspace():
+    """Few blocks of query rows (fewer than compute units): the walks may be cut into chunks, whose
+    partial results live in the workspace; the size query says how much, a smaller one is refused."""
+    B, S, h_q, h_kv, d, C = 1, 640, 8, 4, 256, 640
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+    need = binding.qfc_attention_workspace_size(shape, S)
+    G, M = B * h_kv, S * (h_q // h_kv)
+    assert need == G * M * 8 * (d + 2) * 4
+    q = torch.zeros((G, M, d), dtype=torch.float16, device=DEV)
+    kc = torch.zeros((G, C, d), dtype=torch.float16, device=DEV)
+    vc = torch.zeros((G, C // 64, d, 64), dtype=torch.float16, device=DEV)
+    out = torch.empty_like(q)
+    ws = torch.empty(need - 16, dtype=torch.uint8, device=DEV)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_attention(q, kc, vc, S, S, shape, ws, out)
+    assert e.value.code == binding.QFC_ERR_BUFFER_TOO_SMALL
+    # many blocks: no partial results, the minimum suffices
+    big = _attn_shape(1, 32, 8, 128, 4096)
+    assert binding.qfc_attention_workspace_size(big, 4096) == 256
 
 
 def test_rope_then_attention_decode_step():
