@@ -241,6 +241,14 @@ qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache
                            const qfc_attn_shape_t *shape, void *workspace, size_t workspace_bytes,
                            void *out_f16, void *stream);
 
+/* Embedding lookup from a packed layer (section 4.2: the schemes quantize the
+ * embedding table like the layers, and models tie it to the LM head, so the
+ * table is the LM head's handle): y[m, k] = fp16(s * Wq[ids[m], k]) with the
+ * row's channel scale or the group scales, the product taken in fp32.
+ * ids: device, int32 [M]; an id outside [0, N) gives a row of zeros.
+ * y_f16: device, binary16 [M, K], 16-byte aligned.  M <= 65535. */
+qfc_status_t qfc_embedding(qfc_handle_t h, const int32_t *ids, int32_t M, void *y_f16, void *stream);
+
 /* `count` forward calls issued in order on one stream: handles, xs and ys are
  * host arrays of `count` entries; every call uses the same M.  Stops at the
  * first error and returns it. */

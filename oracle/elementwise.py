@@ -95,3 +95,23 @@ def norm_weighted_input(x_f16, gamma_f16, gamma_offset: float = 0.0) -> np.ndarr
     x = np.asarray(x_f16, dtype=np.float16).astype(np.float64)
     w = gamma_offset + np.asarray(gamma_f16, dtype=np.float16).astype(np.float64)
     return (x * w[None, :]).astype(np.float16)
+
+
+def embedding(ids, wq, scales, group_size: int = 0) -> np.ndarray:
+    """Rows ``ids`` of the quantized table as binary16, [M, K] (section 4.2 of the paper: the
+    embedding table is quantized like the layers): fp16(s * q) with the product taken in fp32, the
+    precision the lookup computes in (exact for binary16 group scales; one rounding to fp32 before
+    the rounding to binary16 for fp32 channel scales).  An id outside [0, N) gives zeros."""
+    wq = np.asarray(wq, dtype=np.int8)
+    ids = np.asarray(ids, dtype=np.int64)
+    N, K = wq.shape
+    ok = (ids >= 0) & (ids < N)
+    safe = np.where(ok, ids, 0)
+    q = wq[safe].astype(np.float32)
+    if group_size == 0:
+        s = np.asarray(scales, dtype=np.float32)[safe][:, None]
+    else:
+        s = np.repeat(np.asarray(scales, dtype=np.float16)[safe].astype(np.float32), group_size, axis=1)
+    out = (s * q).astype(np.float16)
+    out[~ok] = np.float16(0)
+    return out

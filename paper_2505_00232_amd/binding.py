@@ -20,7 +20,7 @@ QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
            "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
-           "qfc_forward_acc_i32", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
+           "qfc_forward_acc_i32", "qfc_embedding", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
 
 
 class Desc(ctypes.Structure):
@@ -80,6 +80,7 @@ def lib() -> ctypes.CDLL:
         L.qfc_attention.argtypes = [vp, vp, vp, i32, i32, ctypes.POINTER(AttnShape), vp, sz, vp, vp]
         L.qfc_forward_q8.argtypes = [vp, vp, vp, i32, vp, vp]
         L.qfc_forward_acc_i32.argtypes = [vp, vp, i32, vp, vp]
+        L.qfc_embedding.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_batch.argtypes = [ctypes.POINTER(vp), ctypes.POINTER(vp), i32, ctypes.POINTER(vp), i32, vp]
         L.qfc_destroy.argtypes = [vp]
         L.qfc_status_string.argtypes = [ctypes.c_int]
@@ -216,6 +217,10 @@ def qfc_forward_q8(h, xq: torch.Tensor, sx: torch.Tensor, y: torch.Tensor):
 
 def qfc_forward_acc_i32(h, xq: torch.Tensor, acc: torch.Tensor):
     _check(lib().qfc_forward_acc_i32(h, _ptr(xq), xq.shape[0], _ptr(acc), _stream()), "qfc_forward_acc_i32")
+
+
+def qfc_embedding(h, ids: torch.Tensor, y: torch.Tensor):
+    _check(lib().qfc_embedding(h, _ptr(ids), ids.shape[0], _ptr(y), _stream()), "qfc_embedding")
 
 
 class ForwardBatch:

@@ -328,6 +328,13 @@ qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, in
     return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, nullptr, h->num_cus, st));
 }
 
+qfc_status_t qfc_embedding(qfc_handle_t h, const int32_t *ids, int32_t M, void *y_f16, void *stream) {
+    if (!valid(h) || !ids || !y_f16 || M < 1) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(y_f16) || (reinterpret_cast<uintptr_t>(ids) & 3u)) return QFC_ERR_ALIGNMENT;
+    if (M > 65535) return QFC_ERR_UNSUPPORTED;  // one grid row per token
+    return hip_status(launch_embedding(h->geo, h->packed, ids, M, y_f16, static_cast<hipStream_t>(stream)));
+}
+
 qfc_status_t qfc_forward_batch(const qfc_handle_t *handles, const void *const *xs, int32_t M,
                                void *const *ys, int32_t count, void *stream) {
     if (!handles || !xs || !ys || count < 0) return QFC_ERR_INVALID_ARG;

@@ -221,6 +221,72 @@ __global__ __launch_bounds__(256) void unpack_w4c_kernel(const uint4 *__restrict
     }
 }
 
+// ---------------------------------------------------------------- embedding lookup
+// Rows ids[m] of the quantized table as binary16: y[m, k] = fp16(s * q), the product taken in fp32
+// (exact for binary16 group scales; rounded to fp32 first for fp32 channel scales).  The table is
+// the packed layer itself (the tied embedding / LM-head matrix of the int4 and int8 schemes of
+// section 4.2 of the paper): one thread per 16-byte vector of the row's tiles.  Ids outside
+// [0, N) give a row of zeros.
+template <int FMT>
+__global__ __launch_bounds__(256) void embedding_kernel(const uint4 *__restrict__ packed, const float *__restrict__ ps,
+                                                        const int32_t *__restrict__ ids, _Float16 *__restrict__ y,
+                                                        int N, int K, int KT, int rt_stride) {
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const int m = blockIdx.y;
+    const int v = blockIdx.x * 256 + threadIdx.x;  // vector of the row: tile v / 4, quarter v % 4
+    if (v >= KT * 4) return;
+    const int kt = v >> 2, q = v & 3;
+    const int n = ids[m];
+    const bool valid = n >= 0 && n < N;
+    const int rt = valid ? n >> 4 : 0, c = n & 15;
+    _Float16 *row = y + (size_t)m * K;
+    if (FMT == kW8C) {
+        const int k0 = kt * 64 + q * 16;
+        if (k0 >= K) return;
+        const uint4 in = packed[((size_t)rt * rt_stride + kt) * 64 + q * 16 + c];
+        const float sc = valid ? ps[n] : 0.0f;
+        const uint32_t w[4] = {in.x, in.y, in.z, in.w};
+        half8 o[2];
+#pragma unroll
+        for (int e = 0; e < 16; ++e) {
+            const int code = (int)(int8_t)((w[e >> 2] >> (8 * (e & 3))) & 0xFFu);
+            o[e >> 3][e & 7] = (_Float16)(valid ? sc * (float)code : 0.0f);
+        }
+        *reinterpret_cast<half8 *>(row + k0) = o[0];
+        *reinterpret_cast<half8 *>(row + k0 + 8) = o[1];
+        return;
+    }
+    // int4 formats: dword j of the lane's vector = codes k = 128 kt + 32 j + 8 q .. + 7
+    const int pos = FMT == kW4G32 ? kt + (kt >> 3) : kt;  // a scale tile follows every 8 weight tiles
+    const uint4 in = packed[((size_t)rt * rt_stride + pos) * 64 + q * 16 + c];
+    const uint32_t w[4] = {in.x, in.y, in.z, in.w};
+    uint4 sv = make_uint4(0, 0, 0, 0);
+    float sc = 0.0f;
+    if (FMT == kW4G32) {
+        const int u = kt >> 3, ntu = min(8, KT - 8 * u);  // the unit's scale tile: after its ntu weight tiles
+        const int gl0 = 4 * (kt & 7);                      // first group of this tile inside the unit
+        sv = packed[((size_t)rt * rt_stride + 9 * u + ntu) * 64 + (gl0 >> 3) * 16 + c];
+    } else if (valid) {
+        sc = ps[n];
+    }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int k0 = kt * 128 + 32 * j + 8 * q;
+        if (k0 >= K) continue;
+        if (FMT == kW4G32) {
+            const int gi = (4 * (kt & 7) + j) & 7;  // group inside the scale vector
+            const uint32_t sd = gi < 2 ? sv.x : gi < 4 ? sv.y : gi < 6 ? sv.z : sv.w;
+            sc = (float)__builtin_bit_cast(_Float16, (uint16_t)(sd >> (16 * (gi & 1))));
+        }
+        alignas(8) int8_t code[8];
+        unpack8(w[j], code);
+        half8 o;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) o[e] = (_Float16)(valid ? sc * (float)code[e] : 0.0f);
+        *reinterpret_cast<half8 *>(row + k0) = o;
+    }
+}
+
 inline unsigned blocks_for(size_t threads) { return (unsigned)((threads + 255) / 256); }
 
 }  // namespace
@@ -243,6 +309,21 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
             wq, static_cast<const uint16_t *>(scales), static_cast<uint4 *>(packed), g.N, g.K, g.RTp, g.KT,
             g.rt_stride);
     }
+    return hipGetLastError();
+}
+
+hipError_t launch_embedding(const Geometry &g, const void *packed, const int32_t *ids, int M, void *y,
+                            hipStream_t st) {
+    const uint4 *pv = static_cast<const uint4 *>(packed);
+    const float *ps = reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off);
+    _Float16 *yo = static_cast<_Float16 *>(y);
+    const dim3 grid(blocks_for((size_t)g.KT * 4), (unsigned)M);
+    if (g.fmt == kW8C)
+        embedding_kernel<kW8C><<<grid, 256, 0, st>>>(pv, ps, ids, yo, g.N, g.K, g.KT, g.rt_stride);
+    else if (g.fmt == kW4C)
+        embedding_kernel<kW4C><<<grid, 256, 0, st>>>(pv, ps, ids, yo, g.N, g.K, g.KT, g.rt_stride);
+    else
+        embedding_kernel<kW4G32><<<grid, 256, 0, st>>>(pv, ps, ids, yo, g.N, g.K, g.KT, g.rt_stride);
     return hipGetLastError();
 }
 

@@ -132,6 +132,9 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
                        hipStream_t st);
 hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void *scales,
                          hipStream_t st);
+// rows ids[0 .. M) of the table as binary16 [M, K]
+hipError_t launch_embedding(const Geometry &g, const void *packed, const int32_t *ids, int M, void *y,
+                            hipStream_t st);
 // Allow kernel Kernel `bytes` of dynamic LDS (above the default limit of 64 KiB): set once per
 // kernel and device, from whichever thread gets there first (setting it twice is harmless).
 template <auto Kernel>

@@ -73,7 +73,8 @@ def test_argument_errors_before_any_launch(L):
     assert h.value is None
     for fn, args in [(L.qfc_forward, (None, a, 1, a, s)), (L.qfc_unpack_weights, (None, a, a, s)),
                      (L.qfc_bind_workspace, (None, a, 1024, s)), (L.qfc_forward_q8, (None, a, a, 1, a, s)),
-                     (L.qfc_forward_acc_i32, (None, a, 1, a, s)), (L.qfc_destroy, (None,))]:
+                     (L.qfc_forward_acc_i32, (None, a, 1, a, s)), (L.qfc_embedding, (None, a, 1, a, s)),
+                     (L.qfc_destroy, (None,))]:
         assert fn(*args) == 1
     out = ctypes.c_size_t(0)
     assert L.qfc_workspace_size(None, 1, ctypes.byref(out)) == 1

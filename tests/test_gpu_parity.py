@@ -60,6 +60,28 @@ def test_pack_unpack_round_trip_bit_exact(fmt, N, K):
     layer.close()
 
 
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
+@pytest.mark.parametrize("N,K", [(17, 96), (300, 512), (1000, 2304), (129, 14336)])
+def test_embedding_lookup_bit_exact(fmt, N, K):
+    """Rows of the packed table as binary16: the same bits as the oracle (fp32 product, one rounding to
+    binary16), ids out of range give zeros, the rows of y past M stay untouched."""
+    print(f"embedding {fmt} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(2500, N, K, fc)
+    layer = _layer(wq, s, fmt)
+    rng = np.random.default_rng(N + K)
+    ids = np.concatenate([[0, N - 1, -3, N], rng.integers(0, N, size=9)]).astype(np.int32)
+    M = len(ids)
+    y = torch.full((M + 1, K), 3.0, dtype=torch.float16, device=DEV)
+    binding.qfc_embedding(layer.handle, torch.from_numpy(ids).to(DEV), y)
+    torch.cuda.synchronize()
+    got = y.cpu().numpy()
+    ref = oracle.embedding(ids, wq, s, _group(fmt))
+    assert np.array_equal(got[:M].view(np.uint16), ref.view(np.uint16))
+    assert np.all(got[M] == np.float16(3.0))
+    layer.close()
+
+
 # ------------------------------------------------------------------ A2 decode
 # (48, 6144): 12 units of the int8 format, 6 of the int4 formats, i.e. the plans with more than 8
 # wavefronts (int8) and with full units at a medium K (int4); (96, 14336): 14 / 28 units

@@ -475,3 +475,33 @@ def test_norm_merged_into_layer_equals_norm_then_layer():
         fused = rs[:, None] * oracle.fc_weight_only(oracle.norm_weighted_input(x, g, off), wq, sw)
         a = oracle.dequantize(wq, sw)
         assert np.allclose(fused, (rs[:, None] * xin) @ a.T, rtol=1e-12, atol=1e-12)
+
+
+def test_embedding_lookup_against_the_dequantized_table():
+    """Pins of the embedding lookup: with binary16 group scales every product s * q is exact, so the
+    row is the correctly rounded binary16 of the C routine's fp64 dequantized table, bit for bit;
+    with fp32 channel scales it is within half a binary16 unit in the last place of it (plus the
+    fp32 rounding of the product); powers of two as scales are exact again; a hand case; ids out
+    of range give zeros."""
+    rng = np.random.default_rng(8)
+    N, K = 37, 96
+    ids = np.array([0, 36, 5, 5, 17], dtype=np.int64)
+    wq4 = rng.integers(-8, 8, size=(N, K), dtype=np.int8)
+    sg = np.exp(rng.uniform(np.log(2e-3), np.log(2e-2), size=(N, K // 32))).astype(np.float16)
+    got = oracle.embedding(ids, wq4, sg, 32)
+    want = oracle.dequantize(wq4, sg, 32)[ids].astype(np.float16)
+    assert got.dtype == np.float16 and np.array_equal(got.view(np.uint16), want.view(np.uint16))
+    wq8 = rng.integers(-127, 128, size=(N, K), dtype=np.int8)
+    sc = np.exp(rng.uniform(np.log(1e-3), np.log(1e-1), size=N)).astype(np.float32)
+    got = oracle.embedding(ids, wq8, sc, 0).astype(np.float64)
+    exact = oracle.dequantize(wq8, sc, 0)[ids]
+    ulp = np.maximum(2.0 ** (np.floor(np.log2(np.maximum(np.abs(exact), 2.0 ** -14))) - 10), 2.0 ** -24)
+    assert np.all(np.abs(got - exact) <= 0.5 * ulp + np.abs(exact) * 2.0 ** -24)
+    p2 = (2.0 ** rng.integers(-9, -3, size=N)).astype(np.float32)
+    got = oracle.embedding(ids, wq8, p2, 0)
+    assert np.array_equal(got.astype(np.float64), oracle.dequantize(wq8, p2, 0)[ids])
+    # by hand: row 1 of [[1, -2], [3, 4]] with channel scales (0.5, 0.25) is (0.75, 1.0)
+    hand = oracle.embedding(np.array([1]), np.array([[1, -2] * 16, [3, 4] * 16], np.int8), np.array([0.5, 0.25], np.float32), 0)
+    assert np.array_equal(hand[0, :4].astype(np.float64), [0.75, 1.0, 0.75, 1.0])
+    out = oracle.embedding(np.array([-1, N, 2]), wq8, sc, 0)
+    assert np.all(out[:2] == 0) and np.any(out[2] != 0)
