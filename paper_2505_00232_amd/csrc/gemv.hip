@@ -53,6 +53,7 @@ GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, int pro) {
     const bool gain = M > 4 ? (g.KU > 4 || full_waves <= 1024) : (g.KU <= 4 && full_waves <= 2048);
     const bool can = g.fmt != kW8C && (plain || (pro > 0 && M <= 4));  // kernels built with half-unit items
     p.half = can && (t.gemv_half >= 0 ? t.gemv_half != 0 : gain);
+    p.copy = p.half && plain && M > 4 && g.KU > 4;  // long K at M > 4: token rows staged by direct copies
     p.units = p.half ? (g.KT + 3) / 4 : g.KU;
     const int cap = p.half ? 8 : wave_cap(M, plain, p.units);
     const int per_wave = (p.units + cap - 1) / cap;  // items per wavefront and row tile
@@ -167,6 +168,24 @@ struct XStage {
             if (PRO == 2) g[i] = o_base + o < K8 ? a.gate[o_base + o] : zero;
         }
     }
+    // global -> this wavefront's LDS region without passing registers (no prologue): vector p of
+    // the region (p = 64 i + lane = slot * M + m) is copied from wherever its token row keeps that
+    // octet.  Octets beyond K are read from the start of the row instead (finite values that only
+    // meet zero weights of the padding).
+    __device__ __forceinline__ void copy(const GemvArgs &a, int unit, int lane, u32x4 *lds) const {
+        const int K8 = a.K / 8;
+        const uint32_t lds_base = (uint32_t)(uintptr_t)(__attribute__((address_space(3))) void *)lds;
+#pragma unroll
+        for (int i = 0; i < XV; ++i) {
+            const int p = i * 64 + lane;
+            const int slot = p / M, m = p % M;
+            int o = slot;
+            if (FMT == kW8C) o = (slot & ~7) | ((slot >> 2) & 1) | ((slot & 3) << 1);
+            const int oo = unit * OCT + o;
+            const uint32_t off = (uint32_t)(((size_t)m * K8 + (oo < K8 ? oo : 0)) * 16);
+            copy16_to_lds(a.x, off, __builtin_amdgcn_readfirstlane(lds_base + i * 1024));
+        }
+    }
     // registers -> this wavefront's LDS region, A-operand order
     __device__ __forceinline__ void store(u32x4 *lds, int lane, int act, float offset) const {
 #pragma unroll
@@ -184,9 +203,14 @@ struct XStage {
 // 16 groups, and a wavefront stages 512 k of the token rows at a time: twice the wavefronts for
 // short K, and half the LDS and registers per wavefront for M > 4, where the staged rows limit
 // how many wavefronts a compute unit holds.  a.KU, a.units_q and a.units_rem then count half units.
-template <int M, int FMT, bool DB, int PRO, bool BIG = false, bool HALF = false>
+// COPY (with HALF, M > 4, long K): the token rows go from memory into LDS by direct copies instead of
+// through registers (a third of the registers of M = 8 otherwise hold them).  Such copies and the
+// weight loads complete in order only among their own kind, so the wavefront waits for an empty
+// counter before its first tile: slower for short K, faster for the down projections (M = 8: -17 %).
+template <int M, int FMT, bool DB, int PRO, bool BIG = false, bool HALF = false, bool COPY = false>
 __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_kernel(GemvArgs a) {
     static_assert(!HALF || (FMT != kW8C && !DB), "half units: int4 formats, single buffer");
+    static_assert(!COPY || (HALF && PRO == 0), "direct copies: half units without a prologue");
     constexpr int TILES = HALF ? 4 : 8;         // weight tiles per item
     constexpr int NV = FMT == kW4G32 ? TILES + TILES / 2 : TILES;  // 16-byte vectors per lane per (item, row tile)
     constexpr int OCT = FMT == kW8C ? 64 : HALF ? 64 : 128;
@@ -364,14 +388,29 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
                 compute_tail();
         } else {
             // single buffer: request, stage and compute inside one branch
-            if (r == 0) xs.load(a, u, lane);
+            if (r == 0) {
+                if constexpr (COPY)
+                    xs.copy(a, u, lane, lds_x);
+                else
+                    xs.load(a, u, lane);
+            }
+            auto staged = [&]() {
+                if constexpr (COPY) {
+                    wait_vmcnt<0>();  // only an empty counter says that the copies have landed
+                    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+                    __builtin_amdgcn_wave_barrier();
+                    __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+                } else {
+                    stage();
+                }
+            };
             if (nt == TILES) {
                 load_item(cur, u, r, kFull);
-                if (r == 0) stage();
+                if (r == 0) staged();
                 compute_full();
             } else {
                 load_item(cur, u, r, kMaybePartial);
-                if (r == 0) stage();
+                if (r == 0) staged();
                 compute_tail();
             }
         }
@@ -471,6 +510,15 @@ hipError_t launch_m(const Geometry &g, const GemvArgs &a, const GemvPlan &p, hip
     if (red > lds) lds = red;
     // long-lived wavefronts (>= 3 items each) get the double-buffered variant
     const int items = ((p.units + waves - 1) / waves) * (a.gated_out ? 2 : a.row_tiles);
+    if constexpr (PRO == 0 && M > 4) {
+        if (p.half && p.copy) {
+            if (g.fmt == kW4C)
+                gemv_kernel<M, kW4C, false, 0, false, true, true><<<grid, block, lds, st>>>(a);
+            else
+                gemv_kernel<M, kW4G32, false, 0, false, true, true><<<grid, block, lds, st>>>(a);
+            return hipGetLastError();
+        }
+    }
     if constexpr (PRO == 0 || M <= 4) {
         if (p.half) {
             if (g.fmt == kW4C)

@@ -107,6 +107,7 @@ struct GemvPlan {
     int waves;       // wavefronts per workgroup, each owning a range of units
     int row_tiles;   // row tiles a workgroup walks through (shares staged x)
     bool half = false;  // items are half units (four weight tiles)
+    bool copy = false;  // token rows staged by direct global -> LDS copies
     int units = 0;      // items per row tile along K
 };
 
