@@ -460,7 +460,9 @@ __global__ __launch_bounds__(64 * PrefillCfg<D>::NW, 2) void attn_prefill_kernel
         }
     }
     auto issue = [&](int blk) {
-        const int bc = min(blk, nb - 1);  // past the end the last step is copied again: constant operation counts
+        // past the end the walk's first steps are copied again (constant operation counts; distinct
+        // sources, since many copies of the same lines in flight have been seen to land late)
+        const int bc = blk < nb ? blk : min(sb + (blk - nb), nb - 1);
         const int p0 = bc * 32;
         const char *ksrc = kbase + (size_t)p0 * (2 * D);
         const char *vsrc = vbase + (size_t)(p0 / 64) * D * 128 + (p0 % 64) * 2;

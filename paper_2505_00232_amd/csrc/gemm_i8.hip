@@ -279,11 +279,19 @@ __global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_ke
 // loads only its own weights, PW stages of 64 k ahead, into a ring of registers (slot = stage % PW,
 // refilled right after the MFMAs that consumed it).  Activation stages: ring of NS LDS stages of
 // 8 KiB (4 KiB for the 64-row tile), CP tile copies per wavefront and stage; the ring is deep (8-14
-// stages) because the wait count that is safe for both kinds of operation grows with it (see below).  Copies and loads past the end of K repeat the
-// last stage, so that every iteration issues the same number of operations and the waits are
-// constants.  The number of stages must be a multiple of PW.
+// stages) because the wait count that is safe for both kinds of operation grows with it (see below).  Copies and loads past the end of K start
+// over at stage 0, so that every iteration issues the same number of operations and the waits are
+// constants.  They must not all repeat one stage: with about ten copies of the same lines in flight
+// from one wavefront, some of their data reached LDS after the counter had already dropped to zero
+// (measured with a 14-stage ring: the staging area of the store phase, which reuses the ring, came
+// back holding activation bytes of the repeated stage; with distinct sources it does not happen).
+// The number of stages must be a multiple of PW.
 // TM = 4: 256 x 128 tile; TM = 2: 256 x 64 tile (twice the tiles for small outputs, twice the weight
 // loads per MFMA).
+//
+// The weight loads carry no streaming hint: the workgroups of the same weight tile (one per token tile)
+// run side by side on one XCD, and with the lines marked evict-first the later ones miss in L2
+// (measured: 4-19 % slower on every shape).
 //
 // The weight loads are assembly too: the compiler counts only the loads it knows when it places its
 // waits, and with the copies in between those waits would drain most of the prefetch.  A load's
@@ -313,12 +321,12 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     }
     v4i wreg[PW][TN][2];
     auto load_w = [&](int slot, int kt) {
-        const int kc = min(kt, KT - 1);
+        const int kc = kt < KT ? kt : (kt - KT) % KT;
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int ks = 0; ks < 2; ++ks)
-                asm volatile("global_load_dwordx4 %0, %1, off nt"
+                asm volatile("global_load_dwordx4 %0, %1, off"
                              : "=&v"(wreg[slot][i][ks])
                              : "v"(wsrc[i] + (size_t)kc * 64 + ks * 32)
                              : "memory");
@@ -327,7 +335,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
     const uint4 *xsrc = a.x + ((size_t)(mt * (BM / 16)) * KT) * 64;
     auto issue_x = [&](int kt) {
-        const int kc = min(kt, KT - 1);
+        const int kc = kt < KT ? kt : (kt - KT) % KT;
 #pragma unroll
         for (int h = 0; h < CP; ++h) {
             const int t = wave + 4 * h;
