@@ -397,17 +397,17 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     // lines in flight from one wavefront have been seen to reach LDS after the
     // counter said they were done).
     auto issue_w = [&](int t, int i) {  // codes of tile t, row tile 2 ks + i of the channel group
-        const int tc = t < KT ? t : (t - KT) % KT;
+        const int tc = t < KT ? t : min(t - KT, KT - 1);
         const size_t wpos = (size_t)(PC ? tc : tc + (tc >> 3)) * 1024;
         copy16_to_lds(wbase + i * rt_bytes + wpos, wlane, lds0 + DW_OFF + (t % DRING) * DW_BYTES + (ng * 4 + ks * 2 + i) * 1024);
     };
     auto issue_s = [&](int t) {  // scales of tile t: vector (t % 8) / 2 * 16 + row of the unit's scale tile (8 groups = 2 tiles)
-        const int tc = t < KT ? t : (t - KT) % KT, u = tc >> 3;
+        const int tc = t < KT ? t : min(t - KT, KT - 1), u = tc >> 3;
         const size_t spos = (size_t)(min(8 * u + 8, KT) + u) * 1024 + (size_t)((tc & 7) >> 1) * 256;
         copy16_to_lds(sbase + spos, slane, lds0 + DS_OFF + (t % DRING) * DS_BYTES + ng * 1024);
     };
     auto issue_x = [&](int t, int i) {  // activation stage t, block wave + 8 (i % 2) of half i / 2
-        const int tc = t < KT ? t : (t - KT) % KT;
+        const int tc = t < KT ? t : min(t - KT, KT - 1);
         copy16_to_lds(xbase + (size_t)tc * 256 + (i >> 1) * 128, xlane[i & 1],
                       lds0 + (t % DRING) * DX_BYTES + wave * 1024 + (i >> 1) * (DX_BYTES / 2) + (i & 1) * 8192);
     };

@@ -321,7 +321,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     }
     v4i wreg[PW][TN][2];
     auto load_w = [&](int slot, int kt) {
-        const int kc = kt < KT ? kt : (kt - KT) % KT;
+        const int kc = kt < KT ? kt : min(kt - KT, KT - 1);
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -335,7 +335,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
     const uint4 *xsrc = a.x + ((size_t)(mt * (BM / 16)) * KT) * 64;
     auto issue_x = [&](int kt) {
-        const int kc = kt < KT ? kt : (kt - KT) % KT;
+        const int kc = kt < KT ? kt : min(kt - KT, KT - 1);
 #pragma unroll
         for (int h = 0; h < CP; ++h) {
             const int t = wave + 4 * h;
