@@ -317,6 +317,51 @@ def test_int8_prefill_config5_lm_head_sampled():
     layer.close()
 
 
+@pytest.mark.parametrize("M,N,K", [(2048, 28672, 4096), (1024, 4096, 14336)])
+def test_int8_prefill_whole_output_at_many_workgroups_per_compute_unit(M, N, K):
+    """Launches of several rounds of workgroups per compute unit (the store phase of a workgroup
+    reuses the LDS ring that its own last copies still target).  Sampled accumulators against the
+    exact contraction; then, over the whole output: the two kernel families (weights straight into
+    registers / both operands through LDS) give the same accumulators, and y is the scaled
+    accumulator bit for bit (two fp32 multiplications and one rounding to binary16, in that
+    order; no oracle value is involved in that last comparison, only the definition)."""
+    print(f"int8 prefill whole output M={M} N={N} K={K}", flush=True)
+    rng = np.random.default_rng(M + N)
+    fc = synth.FC("t", K, N, "w8c")
+    wq, sw = synth.weights(4200, M, N, fc)
+    x = synth.activations(4200, M, N, M, K)
+    layer = _layer(wq, sw, "w8c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    xd = torch.from_numpy(x).to(DEV)
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    binding.qfc_quantize_activations(xd, xq, sx)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    acc_lds = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    y = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    for rep in range(3):  # (the failure this guards against depended on timing)
+        acc.fill_(-1)
+        y.fill_(-1.0)
+        binding.qfc_forward_acc_i32(layer.handle, xq, acc)
+        binding.qfc_forward_q8(layer.handle, xq, sx, y)
+        binding.qfc_tune(2, 4)
+        try:
+            binding.qfc_forward_acc_i32(layer.handle, xq, acc_lds)
+        finally:
+            binding.qfc_tune(2, 0)
+        torch.cuda.synchronize()
+        if rep == 0:
+            xq_ref, _ = oracle.quantize_activations(x)
+            rows = np.sort(rng.choice(M, size=8, replace=False))
+            cols = np.sort(rng.choice(N, size=512, replace=False))
+            acc_ref = oracle.int_contract(xq_ref[rows], wq[cols])
+            ri, ci = torch.from_numpy(rows).to(DEV), torch.from_numpy(cols).to(DEV)
+            assert np.array_equal(acc[ri][:, ci].cpu().numpy().astype(np.int64), acc_ref)
+        assert torch.equal(acc, acc_lds)
+        expected = ((acc.float() * sx[:, None]) * torch.from_numpy(sw).to(DEV)[None, :]).half()
+        assert torch.equal(y, expected)
+    layer.close()
+
+
 # ------------------------------------------------------------------ A6 fp16 MFMA prefill with in-LDS dequantization
 @pytest.mark.parametrize("fmt", ["w4g32", "w4c"])
 @pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (130, 1000, 2304),
@@ -349,6 +394,39 @@ def test_fp16_prefill_config5_shapes_sampled():
         ref = oracle.fc_weight_only(x[rows], wq[cols], s[cols], 32)
         assert oracle.floored_rel_error(y[np.ix_(rows, cols)], ref) <= TOL
         layer.close()
+
+
+@pytest.mark.parametrize("fmt", ["w4g32", "w4c"])
+def test_fp16_prefill_whole_output_two_kernels_agree(fmt):
+    """Gemma2-2B gate+up shape at M = 2048 (several rounds of workgroups per compute unit): the
+    whole output of the kernel that converts weights in registers against the whole output of the
+    kernel that writes dequantized weights to LDS (different pipelines, different summation
+    orders: each is within the tolerance of the exact result, so they agree within twice that),
+    and a sample of it against the oracle."""
+    print(f"fp16 prefill whole output {fmt}", flush=True)
+    rng = np.random.default_rng(77)
+    M, fc = 2048, synth.FC("t", 2304, 18432, fmt)
+    wq, s = synth.weights(4300, M, 0, fc)
+    x = synth.activations(4300, M, 0, M, fc.K)
+    layer = _layer(wq, s, fmt, max_m=M)
+    xd = torch.from_numpy(x).to(DEV)
+    for rep in range(2):
+        y = layer.forward(xd)
+        binding.qfc_tune(2, 9)
+        try:
+            y_other = layer.forward(xd)
+        finally:
+            binding.qfc_tune(2, 0)
+        torch.cuda.synchronize()
+        a, b = y.float(), y_other.float()
+        rho = b.pow(2).mean(dim=1, keepdim=True).sqrt()
+        err = ((a - b).abs() / torch.maximum(b.abs(), rho)).max().item()
+        assert err <= 2 * TOL, err
+    rows = np.sort(rng.choice(M, size=16, replace=False))
+    cols = np.sort(rng.choice(fc.N, size=512, replace=False))
+    ref = oracle.fc_weight_only(x[rows], wq[cols], s[cols], _group(fmt))
+    assert oracle.floored_rel_error(y.cpu().numpy()[np.ix_(rows, cols)], ref) <= TOL
+    layer.close()
 
 
 # ------------------------------------------------------------------ decode with 8-bit activations (the paper's decode design)
