@@ -396,21 +396,23 @@ def test_fp16_prefill_config5_shapes_sampled():
         layer.close()
 
 
+@pytest.mark.parametrize("M", [2048, 2051])
 @pytest.mark.parametrize("fmt", ["w4g32", "w4c"])
-def test_fp16_prefill_whole_output_two_kernels_agree(fmt):
-    """Gemma2-2B gate+up shape at M = 2048 (several rounds of workgroups per compute unit): the
+def test_fp16_prefill_whole_output_two_kernels_agree(fmt, M):
+    """Gemma2-2B gate+up shape at M = 2048 and at a ragged M whose last token tile is almost all
+    padding (several rounds of workgroups per compute unit): the
     whole output of the kernel that converts weights in registers against the whole output of the
     kernel that writes dequantized weights to LDS (different pipelines, different summation
     orders: each is within the tolerance of the exact result, so they agree within twice that),
     and a sample of it against the oracle."""
-    print(f"fp16 prefill whole output {fmt}", flush=True)
+    print(f"fp16 prefill whole output {fmt} M={M}", flush=True)
     rng = np.random.default_rng(77)
-    M, fc = 2048, synth.FC("t", 2304, 18432, fmt)
+    fc = synth.FC("t", 2304, 18432, fmt)
     wq, s = synth.weights(4300, M, 0, fc)
     x = synth.activations(4300, M, 0, M, fc.K)
     layer = _layer(wq, s, fmt, max_m=M)
     xd = torch.from_numpy(x).to(DEV)
-    for rep in range(2):
+    for rep in range(3):
         y = layer.forward(xd)
         binding.qfc_tune(2, 9)
         try:
