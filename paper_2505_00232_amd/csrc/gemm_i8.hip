@@ -289,6 +289,12 @@ __global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_ke
 // TM = 4: 256 x 128 tile; TM = 2: 256 x 64 tile (twice the tiles for small outputs, twice the weight
 // loads per MFMA).
 //
+// PIPE: the operand reads of stage kt + 1 are issued in the middle of the MFMAs of stage kt (second set
+// of fragment registers; the ring is one stage deeper because a stage must have landed one step
+// earlier).  A wavefront that is alone on its SIMD (launches of at most one workgroup per compute unit)
+// otherwise spends 180 of its ~640 clocks per stage between the barrier and the first MFMA waiting
+// for LDS (cycle counters inside the kernel); measured 7-10 % on such launches, level elsewhere.
+//
 // The weight loads carry no streaming hint: the workgroups of the same weight tile (one per token tile)
 // run side by side on one XCD, and with the lines marked evict-first the later ones miss in L2
 // (measured: 4-19 % slower on every shape).
@@ -297,7 +303,7 @@ __global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_ke
 // waits, and with the copies in between those waits would drain most of the prefetch.  A load's
 // destination registers are handed back to the compiler (an empty asm that "redefines" them) right
 // after the explicit wait that covers the load, so that no MFMA can be scheduled ahead of that wait.
-template <int NS, int PW, int TM, int OUT_MODE>
+template <int NS, int PW, int TM, int OUT_MODE, bool PIPE = false>
 __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     constexpr int BN = 256, BM = 32 * TM, TN = 2;
     constexpr int XT = BM / 16;  // activation tiles (KiB) per stage
@@ -365,35 +371,51 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     // thanks to the prologue.  If at most kAllowed = min(CP (NS - 2), 4 (PW - 1)) operations are
     // outstanding, neither stage kt's copies nor its loads can be among them: an unfinished copy would
     // have all CP (NS - 2) later copies behind it, an unfinished load all 4 (PW - 1) later loads.
-    constexpr int kAfterCopies = CP * (NS - 2), kAfterLoads = 4 * (PW - 1);
+    // With PIPE it is stage kt + 1 whose copies must have landed (its operands are read during stage
+    // kt), which has one stage fewer behind it.
+    constexpr int kAfterCopies = CP * (NS - (PIPE ? 3 : 2)), kAfterLoads = 4 * (PW - 1);
     constexpr int kAllowed = kAfterCopies < kAfterLoads ? kAfterCopies : kAfterLoads;
+    v4i xf[PIPE ? 2 : 1][2][TM];
+    auto read_x = [&](int b, int kt) {
+        const uint4 *lx = lds + (kt % NS) * (XT * 64);
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+            for (int j = 0; j < TM; ++j) {
+                const int row = 32 * j + (lane & 31);
+                xf[b][ks][j] = __builtin_bit_cast(v4i, lx[(row >> 4) * 64 + (2 * ks + (lane >> 5)) * 16 + (row & 15)]);
+            }
+    };
+    if (PIPE) {
+        wait_vmcnt<kAfterCopies + CP < 4 * PW ? kAfterCopies + CP : 4 * PW>();  // stage 0's copies have landed
+        asm volatile("s_barrier" ::: "memory");
+        read_x(0, 0);
+    }
     for (int kt0 = 0; kt0 < KT; kt0 += PW) {
 #pragma unroll
         for (int u = 0; u < PW; ++u) {
             const int kt = kt0 + u;
-            wait_vmcnt<kAllowed>();
+            if (PIPE)
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(kAllowed) : "memory");  // (not the LDS counter: the next stage's operand reads stay in flight)
+            else
+                wait_vmcnt<kAllowed>();
             asm volatile("s_barrier" ::: "memory");
 #pragma unroll
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) asm volatile("" : "+v"(wreg[u][i][ks]));
             issue_x(kt + NS - 1);
-            const uint4 *lx = lds + (kt % NS) * (XT * 64);
-            v4i xf[2][TM];
+            const int cur = PIPE ? (u & 1) : 0;
+            if (!PIPE) read_x(0, kt);
 #pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int j = 0; j < TM; ++j) {
-                    const int row = 32 * j + (lane & 31);
-                    xf[ks][j] = __builtin_bit_cast(v4i, lx[(row >> 4) * 64 + (2 * ks + (lane >> 5)) * 16 + (row & 15)]);
-                }
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
+            for (int ks = 0; ks < 2; ++ks) {
 #pragma unroll
                 for (int i = 0; i < TN; ++i)
 #pragma unroll
                     for (int j = 0; j < TM; ++j)
-                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[u][i][ks], xf[ks][j], acc[i][j], 0, 0, 0);
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[u][i][ks], xf[cur][ks][j], acc[i][j], 0, 0, 0);
+                if (PIPE && ks == 0) read_x(cur ^ 1, kt + 1);
+            }
             load_w(u, kt + PW);
         }
     }
@@ -401,16 +423,16 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wave * 64, mt * BM, wave, lane);
 }
 
-template <int NS, int PW, int TM, int OUT_MODE>
+template <int NS, int PW, int TM, int OUT_MODE, bool PIPE = false>
 hipError_t launch_dw(GemmI8Args a, hipStream_t st) {
     constexpr size_t lds_bytes = (size_t)NS * (2 * TM) * 1024 < 4 * 32 * (64 + 8) * 2 ? 4 * 32 * (64 + 8) * 2 : (size_t)NS * (2 * TM) * 1024;
     static_assert(lds_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks in the same LDS");
     if ((a.Kp / 64) % PW != 0) return hipErrorInvalidValue;
     static_assert(lds_bytes <= 80 * 1024, "two workgroups per compute unit");
-    if (const hipError_t e = allow_dynamic_lds<gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE>>(lds_bytes); e != hipSuccess) return e;
+    if (const hipError_t e = allow_dynamic_lds<gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE, PIPE>>(lds_bytes); e != hipSuccess) return e;
     a.n_tiles = (a.N + 255) / 256;
     a.m_tiles = (a.M + 32 * TM - 1) / (32 * TM);
-    gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
+    gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE, PIPE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
     return hipGetLastError();
 }
 
@@ -445,10 +467,12 @@ hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
         case 4: return launch_variant<128, 128, 2, 3, OUT_MODE>(a, st);
         case 5: return launch_variant<128, 256, 1, 3, OUT_MODE>(a, st);
         case 6: return launch_variant<256, 128, 1, 3, OUT_MODE>(a, st);
-        case 10: return launch_dw<8, 4, 4, OUT_MODE>(a, st);
+        case 10: return launch_dw<9, 4, 4, OUT_MODE, true>(a, st);
         case 11: return launch_dw<6, 4, 4, OUT_MODE>(a, st);
-        case 12: return launch_dw<14, 4, 2, OUT_MODE>(a, st);
+        case 12: return launch_dw<15, 4, 2, OUT_MODE, true>(a, st);
         case 13: return launch_dw<8, 4, 2, OUT_MODE>(a, st);
+        case 14: return launch_dw<8, 4, 4, OUT_MODE>(a, st);
+        case 15: return launch_dw<14, 4, 2, OUT_MODE>(a, st);
         default: return launch_variant<128, 128, 1, 4, OUT_MODE>(a, st);
     }
 }

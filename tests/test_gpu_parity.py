@@ -229,7 +229,7 @@ def test_int8_prefill_matches_oracle(M, N, K):
     layer.close()
 
 
-@pytest.mark.parametrize("variant", [1, 4, 5, 6, 10, 11, 12, 13])
+@pytest.mark.parametrize("variant", [1, 4, 5, 6, 10, 11, 12, 13, 14, 15])
 def test_int8_prefill_other_tile_shapes_bit_exact(variant):
     """The tile shapes the dispatcher picks for larger problems (and the selectable ones),
     forced on a ragged shape."""
