@@ -55,16 +55,29 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
     // each.  The scaled binary16 values therefore take a detour through LDS (one
     // block of 32 token rows x WN channels per wavefront at a time) and leave as
     // 16-byte stores that cover whole rows segments of 2 * WN contiguous bytes.
-    asm volatile("s_barrier" ::: "memory");  // all wavefronts are done with the stage buffers
     if (OUT_MODE == 0 && (a.N % 8) == 0) {
         constexpr int PITCH = (WN + 8) * 2;  // bytes per staged row
         char *region = reinterpret_cast<char *>(lds) + wave * (32 * PITCH);
         const int n0 = n_base;
+        // the scales of the lane's channels and token rows, requested once and before the barrier
+        // (inside the loop over the row blocks they would be fetched again after every fence)
+        float4 scw[TN][4];
+        float sxr[TM];
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int q = 0; q < 4; ++q)
+                scw[i][q] = *reinterpret_cast<const float4 *>(a.sw + n0 + i * 32 + 8 * q + 4 * (lane >> 5));
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int m = m_base + j * 32 + (lane & 31);
+            sxr[j] = m < a.M ? a.sx[m] : 0.0f;
+        }
+        asm volatile("s_barrier" ::: "memory");  // all wavefronts are done with the stage buffers
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             const int mrow0 = m_base + j * 32;
-            const int m = mrow0 + (lane & 31);
-            const float sxm = m < a.M ? a.sx[m] : 0.0f;
+            const float sxm = sxr[j];
             const bool has_res = a.res != nullptr;
             if (has_res) stage_residual_block<WN / 8, PITCH>(region, a.res, mrow0, n0, a.M, a.N, lane);
 #pragma unroll
@@ -72,7 +85,7 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
 #pragma unroll
                 for (int q = 0; q < 4; ++q) {
                     const int nl = i * 32 + 8 * q + 4 * (lane >> 5);
-                    const float4 sc = *reinterpret_cast<const float4 *>(a.sw + n0 + nl);
+                    const float4 sc = scw[i][q];
                     typedef _Float16 h4 __attribute__((ext_vector_type(4)));
                     float v[4] = {(float)acc[i][j][4 * q + 0] * sxm * sc.x, (float)acc[i][j][4 * q + 1] * sxm * sc.y,
                                   (float)acc[i][j][4 * q + 2] * sxm * sc.z, (float)acc[i][j][4 * q + 3] * sxm * sc.w};
@@ -105,6 +118,7 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
         }
         return;
     }
+    asm volatile("s_barrier" ::: "memory");  // all wavefronts are done with the stage buffers
     // generic path (raw accumulators, or N not a multiple of 8): direct stores
     const bool vec_ok = (a.N % 4) == 0;
 #pragma unroll
@@ -420,6 +434,16 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
         }
     }
     wait_vmcnt<0>();
+    // The loads issued past the end of K are still writing their destination registers until this
+    // wait returns, and the compiler does not know (it sees registers that nobody reads any more).
+    // Naming them as inputs here keeps them allocated until after the wait, and the memory clobber
+    // keeps the store phase's own loads from being moved above it.
+#pragma unroll
+    for (int p = 0; p < PW; ++p)
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int ks = 0; ks < 2; ++ks) asm volatile("" ::"v"(wreg[p][i][ks]) : "memory");
     epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wave * 64, mt * BM, wave, lane);
 }
 
