@@ -242,13 +242,16 @@ def test_int8_prefill_other_tile_shapes_bit_exact(variant):
     layer = _layer(wq, sw, "w8c", max_m=M)
     binding.qfc_tune(2, variant)
     try:
-        acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
-        binding.qfc_forward_acc_i32(layer.handle, torch.from_numpy(xq_ref).to(DEV), acc)
-        y = _forward(layer, x)
+        # (three times: a launch that is not the first of its kernel in the process runs with warm
+        # caches and different timing, which once exposed a register reused under an unfinished load)
+        for rep in range(3):
+            acc = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+            binding.qfc_forward_acc_i32(layer.handle, torch.from_numpy(xq_ref).to(DEV), acc)
+            y = _forward(layer, x)
+            assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), rep
+            assert oracle.floored_rel_error(y, y_ref) <= TOL, rep
     finally:
         binding.qfc_tune(2, 0)
-    assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref)
-    assert oracle.floored_rel_error(y, y_ref) <= TOL
     layer.close()
 
 
