@@ -165,10 +165,10 @@ __device__ __forceinline__ void wait_vmcnt() {
 // LDS byte address lds_base + 16 l.  Written as assembly because the compiler, when it knows
 // about such a copy, makes every later LDS read wait for ALL outstanding copies (it cannot tell
 // ring slots apart), which would serialize a prefetch ring; the kernels place their waits
-// themselves.  M0 carries the LDS base (nothing else in those kernels uses M0).
+// themselves.  M0 carries the LDS base (declared as clobbered; nothing else in those kernels uses M0).
 __device__ __forceinline__ void copy16_to_lds(const void *base, uint32_t lane_offset, uint32_t lds_base) {
     asm volatile("s_mov_b32 m0, %2\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %0, %1" ::"v"(lane_offset), "s"(base), "s"(lds_base)
-                 : "memory");
+                 : "memory", "m0");
 }
 
 // ---- per-token int8 quantization steps shared by the kernels that produce quantized activations
