@@ -103,10 +103,10 @@ qfc_status_t qfc_unpack_weights(qfc_handle_t h, int8_t *wq_logical, void *scales
  * `bytes` is a host pointer. */
 qfc_status_t qfc_workspace_size(qfc_handle_t h, int32_t M, size_t *bytes);
 
-/* Lend a workspace to the handle (nothing is enqueued; `stream` is reserved).
+/* Lend a workspace to the handle (host bookkeeping only: nothing is enqueued).
  * One workspace may be bound to many handles as long as their calls do not
  * overlap. */
-qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes, void *stream);
+qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes);
 
 /* Activation quantization kernel of the prefill stage (section 3.7): per token
  * row m, a = max|x[m,:]|, sx[m] = a/127 (fp32), xq[m,k] = clamp(rne(x[m,k] * (127/a)), +-127);

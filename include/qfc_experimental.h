@@ -1,0 +1,35 @@
+/*
+ * qfc_experimental - knobs of libqfc.so that are NOT part of its interface.
+ *
+ * Used by this repository's tests and parameter sweeps to force a kernel
+ * variant that the dispatcher would not pick for a given shape (so that every
+ * variant can be checked on small inputs).  Nothing here follows a passage of
+ * the paper, nothing here is needed to use the library, and it may change
+ * without notice.  Production callers include qfc.h only.
+ */
+#ifndef QFC_EXPERIMENTAL_H
+#define QFC_EXPERIMENTAL_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+/* Set one process-wide tunable (each is a single atomic integer; a call that is
+ * being enqueued on another thread sees either the old or the new value of each
+ * key, never a torn one).  Unknown keys are ignored.
+ *   key 0  target number of wavefronts of a decode launch (default 8192)
+ *   key 1  most row tiles a decode workgroup walks (default 2)
+ *   key 2  prefill kernel variant (0 = automatic)
+ *   key 3  token rows per workgroup of the activation quantization kernel (0 = automatic; 2, 4, 8)
+ *   key 4  half-unit items of the decode kernel (-1 automatic, 0 never, 1 where possible)
+ *   key 5  two blocks per workgroup in prefill attention (-1 automatic, 0 never, 1 always)
+ *   key 6  causal walks of prefill attention cut into chunks (-1 automatic, 0 never, 1 always);
+ *          qfc_attention_workspace_size follows the value set when it is called */
+void qfc_tune(int32_t key, int32_t value);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* QFC_EXPERIMENTAL_H */

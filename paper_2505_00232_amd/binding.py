@@ -70,7 +70,7 @@ def lib() -> ctypes.CDLL:
         L.qfc_pack_weights.argtypes = [ctypes.POINTER(Desc), vp, vp, vp, sz, vp, ctypes.POINTER(vp)]
         L.qfc_unpack_weights.argtypes = [vp, vp, vp, vp]
         L.qfc_workspace_size.argtypes = [vp, i32, ctypes.POINTER(sz)]
-        L.qfc_bind_workspace.argtypes = [vp, vp, sz, vp]
+        L.qfc_bind_workspace.argtypes = [vp, vp, sz]
         L.qfc_quantize_activations.argtypes = [vp, i32, i32, vp, vp, vp]
         L.qfc_forward.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_fused.argtypes = [vp, vp, i32, vp, ctypes.POINTER(Fusion), vp]
@@ -107,6 +107,30 @@ def _ptr(t):
     return ctypes.c_void_p(t.data_ptr() if t is not None else 0)
 
 
+def _want(t: torch.Tensor, dtype, shape, what: str):
+    """The C ABI sees pointers and sizes only: dtype, device, contiguity and the dimensions a
+    kernel derives its addresses from are checked here, before anything is launched."""
+    if not isinstance(t, torch.Tensor) or not t.is_cuda:
+        raise ValueError(f"{what}: a CUDA tensor is required")
+    if t.dtype != dtype:
+        raise ValueError(f"{what}: dtype {t.dtype}, expected {dtype}")
+    if not t.is_contiguous():
+        raise ValueError(f"{what}: must be contiguous (row-major, no strides)")
+    if shape is not None:
+        if t.dim() != len(shape) or any(w is not None and int(d) != int(w) for d, w in zip(t.shape, shape)):
+            raise ValueError(f"{what}: shape {tuple(t.shape)}, expected {tuple('*' if w is None else w for w in shape)}")
+
+
+_dims: dict[int, tuple[int, int]] = {}  # handle value -> (N, K), kept from qfc_pack_weights to qfc_destroy
+
+
+def _nk(h):
+    try:
+        return _dims[h.value]
+    except KeyError:
+        raise ValueError("unknown handle (not created by qfc_pack_weights of this binding, or destroyed)") from None
+
+
 def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -131,14 +155,27 @@ def qfc_packed_size(desc: Desc) -> int:
 
 
 def qfc_pack_weights(desc: Desc, wq_logical: torch.Tensor, scales: torch.Tensor, packed: torch.Tensor):
+    _want(wq_logical, torch.int8, (desc.N, desc.K), "wq_logical")
+    if desc.group_size:
+        _want(scales, torch.float16, (desc.N, desc.K // desc.group_size), "scales")
+    else:
+        _want(scales, torch.float32, (desc.N,), "scales")
+    _want(packed, torch.uint8, None, "packed")
     h = ctypes.c_void_p(0)
     _check(lib().qfc_pack_weights(ctypes.byref(desc), _ptr(wq_logical), _ptr(scales), _ptr(packed),
                                   packed.numel() * packed.element_size(), _stream(), ctypes.byref(h)),
            "qfc_pack_weights")
+    _dims[h.value] = (int(desc.N), int(desc.K))
     return h
 
 
 def qfc_unpack_weights(h, wq_logical: torch.Tensor, scales: torch.Tensor):
+    N, K = _nk(h)
+    _want(wq_logical, torch.int8, (N, K), "wq_logical")
+    if scales.dtype == torch.float16:
+        _want(scales, torch.float16, (N, None), "scales")
+    else:
+        _want(scales, torch.float32, (N,), "scales")
     _check(lib().qfc_unpack_weights(h, _ptr(wq_logical), _ptr(scales), _stream()), "qfc_unpack_weights")
 
 
@@ -149,15 +186,21 @@ def qfc_workspace_size(h, M: int) -> int:
 
 
 def qfc_bind_workspace(h, ws: torch.Tensor):
-    _check(lib().qfc_bind_workspace(h, _ptr(ws), ws.numel() * ws.element_size(), _stream()), "qfc_bind_workspace")
+    _check(lib().qfc_bind_workspace(h, _ptr(ws), ws.numel() * ws.element_size()), "qfc_bind_workspace")
 
 
 def qfc_quantize_activations(x: torch.Tensor, xq: torch.Tensor, sx: torch.Tensor):
+    _want(x, torch.float16, (None, None), "x")
     M, K = x.shape
+    _want(xq, torch.int8, (M, K), "xq")
+    _want(sx, torch.float32, (M,), "sx")
     _check(lib().qfc_quantize_activations(_ptr(x), M, K, _ptr(xq), _ptr(sx), _stream()), "qfc_quantize_activations")
 
 
 def qfc_forward(h, x: torch.Tensor, y: torch.Tensor):
+    N, K = _nk(h)
+    _want(x, torch.float16, (None, K), "x")
+    _want(y, torch.float16, (x.shape[0], N), "y")
     _check(lib().qfc_forward(h, _ptr(x), x.shape[0], _ptr(y), _stream()), "qfc_forward")
 
 
@@ -165,6 +208,16 @@ def qfc_forward_fused(h, x: torch.Tensor, y: torch.Tensor, gate: torch.Tensor | 
                       activation: int = QFC_ACT_SILU, residual: torch.Tensor | None = None,
                       gated_output: bool = False, norm_gamma: torch.Tensor | None = None, norm_eps: float = 0.0,
                       norm_offset: float = 0.0):
+    N, K = _nk(h)
+    _want(x, torch.float16, (None, K), "x")
+    M = x.shape[0]
+    _want(y, torch.float16, (M, N // 2 if gated_output else N), "y")
+    if gate is not None:
+        _want(gate, torch.float16, (M, K), "gate")
+    if residual is not None and not gated_output:  # (the library rejects that combination itself)
+        _want(residual, torch.float16, (M, N), "residual")
+    if norm_gamma is not None:
+        _want(norm_gamma, torch.float16, (K,), "norm_gamma")
     f = Fusion(gate.data_ptr() if gate is not None else None, activation,
                residual.data_ptr() if residual is not None else None, 1 if gated_output else 0,
                norm_gamma.data_ptr() if norm_gamma is not None else None, norm_eps, norm_offset)
@@ -175,7 +228,16 @@ def qfc_rmsnorm(x: torch.Tensor, gamma: torch.Tensor, eps: float, gamma_offset: 
                 h_out=None, y=None, xq=None, sx=None):
     def p(t):
         return t.data_ptr() if t is not None else None
+    _want(x, torch.float16, (None, None), "x")
     M, K = x.shape
+    _want(gamma, torch.float16, (K,), "gamma")
+    for t, name in ((residual, "residual"), (h_out, "h_out"), (y, "y")):
+        if t is not None:
+            _want(t, torch.float16, (M, K), name)
+    if xq is not None:
+        _want(xq, torch.int8, (M, K), "xq")
+    if sx is not None:
+        _want(sx, torch.float32, (M,), "sx")
     a = RmsNorm(p(x), p(residual), p(gamma), eps, gamma_offset, p(h_out), p(y), p(xq), p(sx))
     _check(lib().qfc_rmsnorm(ctypes.byref(a), M, K, _stream()), "qfc_rmsnorm")
 
@@ -212,14 +274,24 @@ def qfc_attention(q: torch.Tensor, kcache: torch.Tensor, vcache: torch.Tensor, S
 
 
 def qfc_forward_q8(h, xq: torch.Tensor, sx: torch.Tensor, y: torch.Tensor):
+    N, K = _nk(h)
+    _want(xq, torch.int8, (None, K), "xq")
+    _want(sx, torch.float32, (xq.shape[0],), "sx")
+    _want(y, torch.float16, (xq.shape[0], N), "y")
     _check(lib().qfc_forward_q8(h, _ptr(xq), _ptr(sx), xq.shape[0], _ptr(y), _stream()), "qfc_forward_q8")
 
 
 def qfc_forward_acc_i32(h, xq: torch.Tensor, acc: torch.Tensor):
+    N, K = _nk(h)
+    _want(xq, torch.int8, (None, K), "xq")
+    _want(acc, torch.int32, (xq.shape[0], N), "acc")
     _check(lib().qfc_forward_acc_i32(h, _ptr(xq), xq.shape[0], _ptr(acc), _stream()), "qfc_forward_acc_i32")
 
 
 def qfc_embedding(h, ids: torch.Tensor, y: torch.Tensor):
+    N, K = _nk(h)
+    _want(ids, torch.int32, (None,), "ids")
+    _want(y, torch.float16, (ids.shape[0], K), "y")
     _check(lib().qfc_embedding(h, _ptr(ids), ids.shape[0], _ptr(y), _stream()), "qfc_embedding")
 
 
@@ -228,6 +300,12 @@ class ForwardBatch:
 
     def __init__(self, handles, xs, ys, M: int):
         n = len(handles)
+        if len(xs) != n or len(ys) != n:
+            raise ValueError("handles, xs and ys must have one entry per layer")
+        for h, x, y in zip(handles, xs, ys):
+            N, K = _nk(h)
+            _want(x, torch.float16, (M, K), "x")
+            _want(y, torch.float16, (M, N), "y")
         arr = ctypes.c_void_p * n
         self.h = arr(*[h.value for h in handles])
         self.x = arr(*[x.data_ptr() for x in xs])
@@ -241,6 +319,7 @@ class ForwardBatch:
 
 def qfc_destroy(h):
     _check(lib().qfc_destroy(h), "qfc_destroy")
+    _dims.pop(h.value, None)
 
 
 def qfc_tune(key: int, value: int):

@@ -56,8 +56,8 @@ __global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__re
         v1 = row[off + 1];
         if (GLU) {
             const uint4 *grow = gate + (size_t)(real ? m : 0) * (K / 8);
-            v0 = gated_input8_u4(grow[off], v0, act);
-            v1 = gated_input8_u4(grow[off + 1], v1, act);
+            v0 = gated_input8_u4<true>(grow[off], v0, act);
+            v1 = gated_input8_u4<true>(grow[off + 1], v1, act);
         }
         if (!in) v0 = v1 = make_uint4(0, 0, 0, 0);
     };

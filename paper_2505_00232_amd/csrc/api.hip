@@ -3,6 +3,7 @@
 // the stage decides the kernel).  All arithmetic is in the kernels' files.
 #include <new>
 
+#include "../../include/qfc_experimental.h"
 #include "qfc_internal.h"
 
 using namespace qfc;
@@ -132,10 +133,9 @@ qfc_status_t qfc_workspace_size(qfc_handle_t h, int32_t M, size_t *bytes) {
     return QFC_OK;
 }
 
-qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes, void *stream) {
+qfc_status_t qfc_bind_workspace(qfc_handle_t h, void *workspace, size_t bytes) {
     if (!valid(h) || !workspace) return QFC_ERR_INVALID_ARG;
     if (!aligned16(workspace)) return QFC_ERR_ALIGNMENT;
-    (void)stream;
     if (bytes < 256) return QFC_ERR_BUFFER_TOO_SMALL;
     h->workspace = workspace;
     h->workspace_bytes = bytes;
@@ -364,11 +364,7 @@ const char *qfc_status_string(qfc_status_t s) {
     return "unknown status";
 }
 
-// Tuning knob for experiments (not part of the documented interface):
-// key 0 = target wavefronts of a decode launch, 1 = max row tiles per
-// decode workgroup, 2 = prefill kernel variant, 3 = token rows per workgroup of the
-// activation quantization kernel (2, 4, 8; 0 = automatic), 4 = half-unit items of the decode
-// kernel and 5 = two blocks per workgroup in prefill attention (-1 automatic, 0 off, 1 on).
+// Tunables for tests and sweeps (include/qfc_experimental.h; not part of the interface).
 void qfc_tune(int32_t key, int32_t value) {
     Tuning &t = tuning();
     if (key == 0) t.gemv_target_waves = value;

@@ -111,15 +111,25 @@ struct GemvPlan {
     int units = 0;      // items per row tile along K
 };
 
-// Tunables (set through qfc_tune, used by the planners).
+// Tunables (set through qfc_tune of qfc_experimental.h by tests and sweeps, read by the planners).
+// Each is one relaxed atomic: a launch being planned on another thread reads whole values.
+struct Tunable {
+    std::atomic<int> v;
+    Tunable(int init) : v(init) {}
+    operator int() const { return v.load(std::memory_order_relaxed); }
+    Tunable &operator=(int x) {
+        v.store(x, std::memory_order_relaxed);
+        return *this;
+    }
+};
 struct Tuning {
-    int gemv_target_waves = 8192;
-    int gemv_max_row_tiles = 2;
-    int gemm_variant = 0;
-    int act_quant_rows = 0;  // 0: automatic
-    int attn_chunks = -1;    // prefill attention, walks cut into chunks: -1 automatic, 0 never, 1 always
-    int attn_pair = -1;      // prefill attention, two blocks per workgroup: -1 automatic, 0 never, 1 always
-    int gemv_half = -1;      // half-unit items of the decode kernel: -1 automatic, 0 never, 1 where possible
+    Tunable gemv_target_waves{8192};
+    Tunable gemv_max_row_tiles{2};
+    Tunable gemm_variant{0};
+    Tunable act_quant_rows{0};  // 0: automatic
+    Tunable attn_chunks{-1};    // prefill attention, walks cut into chunks: -1 automatic, 0 never, 1 always
+    Tunable attn_pair{-1};      // prefill attention, two blocks per workgroup: -1 automatic, 0 never, 1 always
+    Tunable gemv_half{-1};      // half-unit items of the decode kernel: -1 automatic, 0 never, 1 where possible
 };
 Tuning &tuning();
 
@@ -199,8 +209,13 @@ __device__ __forceinline__ us2 fold_abs(us2 acc, uint32_t d) {
 
 // Gate activations of the fused input act(gate) * x.  Both are g * sigmoid(t): t = g for SiLU,
 // t = 2 sqrt(2/pi) (g + 0.044715 g^3) for the tanh form of GELU (0.5 (1 + tanh z) = sigmoid(2 z)).
-// Written as t = g (c1 + c3 g^2) with the pair (c1, c3) chosen once per kernel, and with the
-// hardware reciprocal (1 ulp) in place of an IEEE division: the result is rounded to binary16.
+// Written as t = g (c1 + c3 g^2) with the pair (c1, c3) chosen once per kernel.  EXACT = false
+// (decode kernels, where every workgroup repeats the evaluation): fast exponential and the hardware
+// reciprocal (1 ulp) in place of an IEEE division; the result is rounded to binary16 anyway.
+// EXACT = true (the quantizer of the int8 prefill path, where the rounded value goes on to decide
+// an 8-bit code): library exponential and an IEEE division, so that the fp32 value is within a
+// few units in the last place of the real one and a code differs from the definition's only when
+// the real value lies that close to a rounding boundary.
 struct GateCoeffs {
     float c1, c3;
 };
@@ -210,20 +225,23 @@ __device__ __forceinline__ GateCoeffs gate_coeffs(int act) {
     c.c3 = act == QFC_ACT_GELU_TANH ? 1.5957691216f * 0.044715f : 0.0f;
     return c;
 }
+template <bool EXACT = false>
 __device__ __forceinline__ float gate_activation(float g, const GateCoeffs &c) {
     const float t = g * fmaf(c.c3, g * g, c.c1);
+    if constexpr (EXACT) return g / (1.0f + expf(-t));
     return g * __builtin_amdgcn_rcpf(1.0f + __expf(-t));
 }
 
 // Eight binary16 pairs (gate, x) -> eight binary16 values fp16(act(gate) * x): fp32 arithmetic,
 // one rounding to binary16.
+template <bool EXACT = false>
 __device__ __forceinline__ uint4 gated_input8_u4(const uint4 &gate, const uint4 &x, int act) {
     typedef _Float16 half8 __attribute__((ext_vector_type(8)));
     const half8 g = __builtin_bit_cast(half8, gate), u = __builtin_bit_cast(half8, x);
     const GateCoeffs c = gate_coeffs(act);
     half8 r;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) r[e] = (_Float16)(gate_activation((float)g[e], c) * (float)u[e]);
+    for (int e = 0; e < 8; ++e) r[e] = (_Float16)(gate_activation<EXACT>((float)g[e], c) * (float)u[e]);
     return __builtin_bit_cast(uint4, r);
 }
 

@@ -4,6 +4,7 @@ device."""
 import ctypes
 import os
 import re
+import subprocess
 
 import pytest
 
@@ -19,12 +20,24 @@ def L():
     return binding.lib()
 
 
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
+    return set(re.findall(r"\b(qfc_[a-z0-9_]+)\s*\(", header))
+
+
 def test_header_symbols_are_exported(L):
-    header = open(os.path.join(ROOT, "include", "qfc.h")).read()
-    declared = set(re.findall(r"\b(qfc_[a-z0-9_]+)\s*\(", header))
+    """qfc.h declares exactly the binding's entry points, and the library's dynamic symbol table
+    holds no qfc_* function beyond what the two headers declare (qfc_experimental.h: the
+    tunables of tests and sweeps, which are not part of the interface)."""
+    declared = _declared("qfc.h")
     assert declared == set(binding.EXPORTS)
     for name in declared:
         assert hasattr(L, name), name
+    experimental = _declared("qfc_experimental.h")
+    assert experimental == {"qfc_tune"}
+    nm = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True)
+    exported = {ln.split()[-1] for ln in nm.stdout.splitlines() if len(ln.split()) >= 3 and ln.split()[-2] in "TW"}
+    assert {e for e in exported if e.startswith("qfc_")} == declared | experimental
 
 
 def test_status_strings(L):
@@ -72,7 +85,7 @@ def test_argument_errors_before_any_launch(L):
     assert L.qfc_pack_weights(ctypes.byref(d), a, a, a, 16, s, ctypes.byref(h)) == 3
     assert h.value is None
     for fn, args in [(L.qfc_forward, (None, a, 1, a, s)), (L.qfc_unpack_weights, (None, a, a, s)),
-                     (L.qfc_bind_workspace, (None, a, 1024, s)), (L.qfc_forward_q8, (None, a, a, 1, a, s)),
+                     (L.qfc_bind_workspace, (None, a, 1024)), (L.qfc_forward_q8, (None, a, a, 1, a, s)),
                      (L.qfc_forward_acc_i32, (None, a, 1, a, s)), (L.qfc_embedding, (None, a, 1, a, s)),
                      (L.qfc_destroy, (None,))]:
         assert fn(*args) == 1

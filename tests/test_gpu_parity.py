@@ -3,6 +3,8 @@ element on the same seeded inputs.  Integer work (packing, quantized
 activations, int32 accumulators) must match bit for bit; floating-point outputs
 must satisfy the floored relative error bound 2e-3 (fp32 accumulation, binary16
 output)."""
+import ctypes
+
 import numpy as np
 import pytest
 import torch
@@ -21,6 +23,15 @@ def _layer(wq, s, fmt, max_m=8, mode=None):
 
 def _group(fmt):
     return 32 if fmt == "w4g32" else 0
+
+
+def _E(y, ref) -> float:
+    """The acceptance metric (floored relative error), and beside it the plain maximum relative
+    error over the entries at or above their row's floor, which the same bound must hold for."""
+    e = oracle.floored_rel_error(y, ref)
+    p = oracle.plain_rel_error_above_floor(y, ref)
+    assert p <= e * (1 + 1e-12) + 1e-300, (p, e)
+    return max(e, p)
 
 
 def _forward(layer, x):
@@ -100,7 +111,7 @@ def test_decode_matches_oracle(fmt, N, K):
         x = synth.activations(2000, N, K + M, M, K)
         y = _forward(layer, x)
         ref = oracle.fc_weight_only(x, wq, s, _group(fmt))
-        err = oracle.floored_rel_error(y, ref)
+        err = _E(y, ref)
         assert err <= TOL, (M, err)
         y2 = _forward(layer, x)
         assert np.array_equal(y.view(np.uint16), y2.view(np.uint16))  # deterministic
@@ -149,7 +160,7 @@ def test_decode_config1():
     x = synth.activations(1001, 0, 0, 1, fc.K)
     layer = _layer(wq, s, fc.fmt)
     y = _forward(layer, x)
-    assert oracle.floored_rel_error(y, oracle.fc_weight_only(x, wq, s)) <= TOL
+    assert _E(y, oracle.fc_weight_only(x, wq, s)) <= TOL
     layer.close()
 
 
@@ -160,7 +171,7 @@ def test_decode_config2_gemma_layer_full():
         x = synth.activations(1002, 0, i, 1, fc.K)
         layer = _layer(wq, s, fc.fmt)
         y = _forward(layer, x)
-        assert oracle.floored_rel_error(y, oracle.fc_weight_only(x, wq, s, 32)) <= TOL
+        assert _E(y, oracle.fc_weight_only(x, wq, s, 32)) <= TOL
         layer.close()
 
 
@@ -179,7 +190,7 @@ def test_decode_config3_llama_shapes_sampled(M):
         rows[:2] = (0, 1)
         rows[-2:] = (fc.N - 2, fc.N - 1)
         ref = oracle.fc_weight_only(x, wq[rows], s[rows], _group(fc.fmt))
-        assert oracle.floored_rel_error(y[:, rows], ref) <= TOL
+        assert _E(y[:, rows], ref) <= TOL
         assert np.all(np.isfinite(y.astype(np.float32)))
         layer.close()
         del wq, s
@@ -223,9 +234,28 @@ def test_int8_prefill_matches_oracle(M, N, K):
     y = torch.empty((M, N), dtype=torch.float16, device=DEV)
     binding.qfc_forward_q8(layer.handle, xq_d, torch.from_numpy(sx_ref).to(DEV), y)
     torch.cuda.synchronize()
-    assert oracle.floored_rel_error(y.cpu().numpy(), y_ref) <= TOL
+    assert _E(y.cpu().numpy(), y_ref) <= TOL
     y2 = _forward(layer, x)  # quantization kernel + product + epilogue in one call
-    assert oracle.floored_rel_error(y2, y_ref) <= TOL
+    assert _E(y2, y_ref) <= TOL
+    layer.close()
+
+
+@pytest.mark.parametrize("M,N,K", [(512, 4096, 4096), (1024, 6144, 4096)])
+def test_int8_prefill_whole_output_against_oracle(M, N, K):
+    """Every element of a mid-size layer and of the QKV layer of the Llama-3.1-8B prefill workload
+    (all workgroups of a real launch, not a sample): quantized activations and int32 accumulators
+    bit for bit, outputs within the tolerance."""
+    print(f"int8 prefill whole output vs oracle M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, "w8c")
+    wq, sw = synth.weights(4100, M, N, fc)
+    x = synth.activations(4100, M, N, M, K)
+    xq_ref, sx_ref, acc_ref, y_ref = oracle.fc_int8_act(x, wq, sw)
+    layer = _layer(wq, sw, "w8c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    binding.qfc_forward_acc_i32(layer.handle, torch.from_numpy(xq_ref).to(DEV), acc)
+    y = _forward(layer, x)
+    assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref)
+    assert _E(y, y_ref) <= TOL
     layer.close()
 
 
@@ -249,7 +279,7 @@ def test_int8_prefill_other_tile_shapes_bit_exact(variant):
             binding.qfc_forward_acc_i32(layer.handle, torch.from_numpy(xq_ref).to(DEV), acc)
             y = _forward(layer, x)
             assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), rep
-            assert oracle.floored_rel_error(y, y_ref) <= TOL, rep
+            assert _E(y, y_ref) <= TOL, rep
     finally:
         binding.qfc_tune(2, 0)
     layer.close()
@@ -283,7 +313,7 @@ def test_int8_prefill_config4_shapes_sampled():
         got = acc.cpu().numpy()[np.ix_(rows, cols)].astype(np.int64)
         assert np.array_equal(got, acc_ref)
         y_ref = oracle.rescale(acc_ref, sx_ref[rows], sw[cols])
-        assert oracle.floored_rel_error(y.cpu().numpy()[np.ix_(rows, cols)], y_ref) <= TOL
+        assert _E(y.cpu().numpy()[np.ix_(rows, cols)], y_ref) <= TOL
         layer.close()
         del wq
 
@@ -316,7 +346,7 @@ def test_int8_prefill_config5_lm_head_sampled():
     acc_ref = oracle.int_contract(xq_ref[rows], wq[cols])
     assert np.array_equal(acc[ri][:, ci].cpu().numpy().astype(np.int64), acc_ref)
     y_ref = oracle.rescale(acc_ref, sx_ref[rows], sw[cols])
-    assert oracle.floored_rel_error(y[ri][:, ci].cpu().numpy(), y_ref) <= TOL
+    assert _E(y[ri][:, ci].cpu().numpy(), y_ref) <= TOL
     layer.close()
 
 
@@ -378,7 +408,21 @@ def test_fp16_prefill_matches_oracle(fmt, M, N, K):
     layer = _layer(wq, s, fmt, max_m=M)
     y = _forward(layer, x)
     ref = oracle.fc_weight_only(x, wq, s, _group(fmt))
-    assert oracle.floored_rel_error(y, ref) <= TOL
+    assert _E(y, ref) <= TOL
+    layer.close()
+
+
+@pytest.mark.parametrize("fmt,M,N,K", [("w4g32", 512, 4096, 4096), ("w4c", 512, 4096, 4096), ("w4g32", 2048, 4096, 2304)])
+def test_fp16_prefill_whole_output_against_oracle(fmt, M, N, K):
+    """Every element of a mid-size layer, and of the QKV layer of the Gemma2-2B prefill workload at
+    its full M = 2048, against the oracle (not a sample)."""
+    print(f"fp16 prefill whole output vs oracle {fmt} M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(5100, M, N, fc)
+    x = synth.activations(5100, M, N, M, K)
+    layer = _layer(wq, s, fmt, max_m=M)
+    y = _forward(layer, x)
+    assert _E(y, oracle.fc_weight_only(x, wq, s, _group(fmt))) <= TOL
     layer.close()
 
 
@@ -395,7 +439,7 @@ def test_fp16_prefill_config5_shapes_sampled():
         cols = np.sort(rng.choice(fc.N, size=512, replace=False))
         rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, fc.N - 1
         ref = oracle.fc_weight_only(x[rows], wq[cols], s[cols], 32)
-        assert oracle.floored_rel_error(y[np.ix_(rows, cols)], ref) <= TOL
+        assert _E(y[np.ix_(rows, cols)], ref) <= TOL
         layer.close()
 
 
@@ -430,7 +474,7 @@ def test_fp16_prefill_whole_output_two_kernels_agree(fmt, M):
     rows = np.sort(rng.choice(M, size=16, replace=False))
     cols = np.sort(rng.choice(fc.N, size=512, replace=False))
     ref = oracle.fc_weight_only(x[rows], wq[cols], s[cols], _group(fmt))
-    assert oracle.floored_rel_error(y.cpu().numpy()[np.ix_(rows, cols)], ref) <= TOL
+    assert _E(y.cpu().numpy()[np.ix_(rows, cols)], ref) <= TOL
     layer.close()
 
 
@@ -458,7 +502,7 @@ def test_decode_int8_activations(fmt, N, K):
         binding.qfc_forward_q8(layer.handle, xq_d, torch.from_numpy(sx_ref).to(DEV), y_q8)
         y = _forward(layer, x)
         assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), M
-        assert oracle.floored_rel_error(y, y_ref) <= TOL, M
+        assert _E(y, y_ref) <= TOL, M
         assert np.array_equal(y.view(np.uint16), y_q8.cpu().numpy().view(np.uint16)), M
     layer.close()
 
@@ -474,7 +518,7 @@ def test_decode_int8_activations_llama_shapes_sampled():
         cols = np.sort(rng.choice(fc.N, size=512, replace=False))
         cols[0], cols[-1] = 0, fc.N - 1
         _, _, _, y_ref = oracle.fc_int8_act(x, wq[cols], sw[cols])
-        assert oracle.floored_rel_error(y[:, cols], y_ref) <= TOL
+        assert _E(y[:, cols], y_ref) <= TOL
         layer.close()
 
 
@@ -496,10 +540,10 @@ def test_dispatch_boundary_m8_m9(fmt):
     else:
         ref9 = oracle.fc_weight_only(x, wq, s, _group(fmt))
     ref8 = oracle.fc_weight_only(x[:8], wq, s, _group(fmt))
-    assert oracle.floored_rel_error(y8, ref8) <= TOL
-    assert oracle.floored_rel_error(y9, ref9) <= TOL
+    assert _E(y8, ref8) <= TOL
+    assert _E(y9, ref9) <= TOL
     if fmt != "w8c":
-        assert oracle.floored_rel_error(y9[:8], ref8) <= TOL
+        assert _E(y9[:8], ref8) <= TOL
     layer.close()
 
 
@@ -564,6 +608,37 @@ def test_error_paths_on_device():
     del x
 
 
+def test_binding_rejects_tensors_the_abi_cannot_check():
+    """The C ABI takes pointers and row counts; the binding refuses tensors whose dtype, strides or
+    dimensions do not match the handle before anything is launched."""
+    fc = synth.FC("t", 128, 64, "w4g32")
+    wq, s = synth.weights(6100, 0, 0, fc)
+    layer = _layer(wq, s, "w4g32")
+    x = torch.zeros((2, 128), dtype=torch.float16, device=DEV)
+    y = torch.zeros((2, 64), dtype=torch.float16, device=DEV)
+    binding.qfc_forward(layer.handle, x, y)
+    bad = [(torch.zeros((2, 96), dtype=torch.float16, device=DEV), y),       # K of x
+           (x, torch.zeros((2, 32), dtype=torch.float16, device=DEV)),       # N of y
+           (x, torch.zeros((3, 64), dtype=torch.float16, device=DEV)),       # M of y
+           (x.float(), y), (x, y.float()),                                   # dtypes
+           (torch.zeros((2, 256), dtype=torch.float16, device=DEV)[:, ::2], y),  # strided view
+           (x.cpu(), y)]
+    for xb, yb in bad:
+        with pytest.raises(ValueError):
+            binding.qfc_forward(layer.handle, xb, yb)
+        with pytest.raises(ValueError):
+            binding.qfc_forward_fused(layer.handle, xb, yb)
+    with pytest.raises(ValueError):
+        binding.ForwardBatch([layer.handle], [x], [torch.zeros((2, 32), dtype=torch.float16, device=DEV)], 2)
+    with pytest.raises(ValueError):
+        binding.qfc_quantize_activations(x, torch.zeros((2, 64), dtype=torch.int8, device=DEV),
+                                         torch.zeros((2,), dtype=torch.float32, device=DEV))
+    layer.close()
+    with pytest.raises(ValueError):
+        binding.qfc_forward(ctypes.c_void_p(12345), x, y)  # not a live handle of this binding
+    torch.cuda.synchronize()
+
+
 # ------------------------------------------------------------------ element-wise operators fused with the layer
 def _fused(layer, x, gate=None, act=binding.QFC_ACT_SILU, residual=None, alias=False):
     xd = torch.from_numpy(x).to(DEV)
@@ -597,14 +672,14 @@ def test_decode_fused_gate_and_residual(fmt, N, K):
         act = binding.QFC_ACT_SILU if M % 2 else binding.QFC_ACT_GELU_TANH
         oact = oracle.SILU if M % 2 else oracle.GELU_TANH
         y = _fused(layer, up, gate, act, res)
-        assert oracle.floored_rel_error(y, _fused_ref(up, wq, s, fmt, gate, oact, res)) <= TOL, M
+        assert _E(y, _fused_ref(up, wq, s, fmt, gate, oact, res)) <= TOL, M
         if M == 3:
             assert np.array_equal(y[1], res[1])
         # each part alone, and the output written over the residual
         y = _fused(layer, up, gate, act, None)
-        assert oracle.floored_rel_error(y, _fused_ref(up, wq, s, fmt, gate, oact, None)) <= TOL, M
+        assert _E(y, _fused_ref(up, wq, s, fmt, gate, oact, None)) <= TOL, M
         y = _fused(layer, up, None, act, res, alias=True)
-        assert oracle.floored_rel_error(y, _fused_ref(up, wq, s, fmt, None, oact, res)) <= TOL, M
+        assert _E(y, _fused_ref(up, wq, s, fmt, None, oact, res)) <= TOL, M
         # no parts: the plain call, bit for bit
         assert np.array_equal(_fused(layer, up), _forward(layer, up))
     layer.close()
@@ -622,7 +697,7 @@ def test_decode_fused_gate_matches_the_unfused_pipeline():
     x_in = oracle.gated_input(gate, up, oracle.SILU)
     y_fused = _fused(layer, up, gate, binding.QFC_ACT_SILU)
     y_plain = _forward(layer, x_in)
-    assert oracle.floored_rel_error(y_fused, y_plain.astype(np.float64)) <= 1e-3
+    assert _E(y_fused, y_plain.astype(np.float64)) <= 1e-3
     layer.close()
 
 
@@ -639,12 +714,15 @@ def test_int8_prefill_fused_gate_and_residual(M, N, K):
     for act, oact in ((binding.QFC_ACT_SILU, oracle.SILU), (binding.QFC_ACT_GELU_TANH, oracle.GELU_TANH)):
         y = _fused(layer, up, gate, act, res)
         ref = _fused_ref(up, wq, sw, "w8c", gate, oact, res, int8_act=True)
-        # the gate activation is evaluated in fp32 on the GPU: where that flips the binary16 rounding
-        # of an input element, its int8 code can move by one, i.e. by sx * |w| in the output
-        assert oracle.floored_rel_error(y, ref) <= 2 * TOL
+        # the quantizer evaluates the gate activation with the library exponential and an IEEE
+        # division (fp32 within a few units in the last place of the real value), so the binary16
+        # input and the 8-bit codes are the definition's
+        e = _E(y, ref)
+        print(f"  act {act}: E = {e:.3e}", flush=True)
+        assert e <= TOL
         assert np.array_equal(y[M // 2], res[M // 2])
     y = _fused(layer, up, None, 0, res)
-    assert oracle.floored_rel_error(y, _fused_ref(up, wq, sw, "w8c", None, 0, res, int8_act=True)) <= TOL
+    assert _E(y, _fused_ref(up, wq, sw, "w8c", None, 0, res, int8_act=True)) <= TOL
     assert np.array_equal(_fused(layer, up), _forward(layer, up))
     layer.close()
 
@@ -659,7 +737,7 @@ def test_fp16_prefill_fused_residual(fmt, M, N, K):
     res = synth.activations(3401, M, N, M, N)
     layer = _layer(wq, s, fmt, max_m=M)
     y = _fused(layer, x, None, 0, res)
-    assert oracle.floored_rel_error(y, _fused_ref(x, wq, s, fmt, None, 0, res)) <= TOL
+    assert _E(y, _fused_ref(x, wq, s, fmt, None, 0, res)) <= TOL
     assert np.array_equal(_fused(layer, x), _forward(layer, x))
     with pytest.raises(binding.QfcError) as e:  # no place for the gate on this path
         _fused(layer, x, x, binding.QFC_ACT_SILU, None)
@@ -681,7 +759,7 @@ def test_fused_mlp_llama_shapes_sampled():
         cols = np.sort(rng.choice(fc.N, size=256, replace=False))
         cols[0], cols[-1] = 0, fc.N - 1
         ref = _fused_ref(up, wq[cols], s[cols], fc.fmt, gate, oracle.SILU, res[:, cols])
-        assert oracle.floored_rel_error(y[:, cols], ref) <= TOL
+        assert _E(y[:, cols], ref) <= TOL
     layer.close()
 
 
@@ -702,7 +780,7 @@ def test_decode_gated_output(fmt, N, K):
         binding.qfc_forward_fused(layer.handle, xd, y, activation=act, gated_output=True)
         torch.cuda.synchronize()
         ref = oracle.gated_output(oracle.fc_weight_only(x, wq, s, _group(fmt)), oact)
-        assert oracle.floored_rel_error(y.cpu().numpy(), ref) <= TOL, M
+        assert _E(y.cpu().numpy(), ref) <= TOL, M
     # combinations the interface excludes
     xd = torch.from_numpy(synth.activations(3500, N, K, 1, K)).to(DEV)
     y = torch.empty((1, N // 2), dtype=torch.float16, device=DEV)
@@ -746,7 +824,7 @@ def test_rmsnorm_residual_quantize(M, K):
         # the residual stream: one correctly rounded binary16 addition, bit for bit
         assert np.array_equal(h_out.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
         y_gpu = y.cpu().numpy()
-        assert oracle.floored_rel_error(y_gpu, y_ref) <= TOL
+        assert _E(y_gpu, y_ref) <= TOL
         # the quantization is the activation quantization of the stored y, bit for bit
         xq_ref, sx_ref = oracle.quantize_activations(y_gpu)
         assert np.array_equal(xq.cpu().numpy(), xq_ref)
@@ -758,7 +836,7 @@ def test_rmsnorm_residual_quantize(M, K):
     binding.qfc_rmsnorm(xd, gd, 1e-5, 0.0, y=y2)
     torch.cuda.synchronize()
     h_ref, y_ref = oracle.rmsnorm(x, gamma, 1e-5, 0.0)
-    assert oracle.floored_rel_error(y2.cpu().numpy(), y_ref) <= TOL
+    assert _E(y2.cpu().numpy(), y_ref) <= TOL
     stream_buf = xd.clone()
     xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
     sx = torch.empty((M,), dtype=torch.float32, device=DEV)
@@ -857,7 +935,7 @@ def test_attention_over_the_cache(B, S, h_q, h_kv, d, C, n_ctx):
     ref = oracle.attention(q, K, V, n_ctx, S)
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got))
-    assert oracle.floored_rel_error(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
+    assert _E(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
 
 
 @pytest.mark.parametrize("B,S,h_q,h_kv,d,C,n_ctx", [(1, 5, 8, 2, 64, 64, 5), (1, 40, 4, 4, 128, 128, 40),
@@ -887,7 +965,7 @@ def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
     ref = oracle.attention(q, K, V, n_ctx, S)
     got = out.cpu().numpy()
     assert np.all(np.isfinite(got))
-    assert oracle.floored_rel_error(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
+    assert _E(got.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
     # the launch form of large grids (a workgroup takes a long and a short block of query rows in
     # turn), forced on this small case: every row is computed as before, so the bits are the same
     out2 = torch.full((G, M, d), 9.0, dtype=torch.float16, device=DEV)
@@ -910,7 +988,7 @@ def test_attention_many_query_rows(B, S, h_q, h_kv, d, C, n_ctx):
         binding.qfc_tune(6, -1)
     got3 = out3.cpu().numpy()
     assert np.all(np.isfinite(got3))
-    assert oracle.floored_rel_error(got3.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
+    assert _E(got3.reshape(G * M, d), ref.reshape(G * M, d)) <= TOL
     # the first token's rows see n_ctx - S + 1 positions only: with one position the output is that value column
     if n_ctx == S:
         assert np.allclose(got[:, :g].astype(np.float64), np.repeat(V[:, None, :, 0], g, axis=1).astype(np.float64), rtol=2e-3, atol=2e-3)
@@ -958,7 +1036,7 @@ def test_rope_then_attention_decode_step():
     K[:, pos0] = k_ref[:, 0]
     V[:, :, pos0] = v_ref[:, 0]
     ref = oracle.attention(q_ref, K, V, pos0 + 1, 1)
-    assert oracle.floored_rel_error(out.cpu().numpy().reshape(G * g, d), ref.reshape(G * g, d)) <= TOL
+    assert _E(out.cpu().numpy().reshape(G * g, d), ref.reshape(G * g, d)) <= TOL
     # [G, g, d] is [B, h_q * d]: query head kv * g + j of batch b at row b, columns (kv * g + j) * d ..
     assert out.reshape(B, h_q * d).shape == (B, h_q * d)
 
@@ -1059,7 +1137,11 @@ def test_decode_norm_merged_into_layer(fmt, N, K):
         x_in = oracle.norm_weighted_input(x, gamma, off)
         rs = oracle.rms_scale(x, eps)
         full = rs[:, None] * oracle.fc_weight_only(x_in, wq, s, _group(fmt))
-        assert oracle.floored_rel_error(y.cpu().numpy(), oracle.add_residual(full, res)) <= TOL, M
+        assert _E(y.cpu().numpy(), oracle.add_residual(full, res)) <= TOL, M
+        # ... and against the plain definition: the layer applied to rmsnorm(x), nothing factored
+        # out and nothing rounded between the normalization and the product
+        plain = oracle.rmsnorm(x, gamma, eps, off)[1] @ oracle.dequantize(wq, s, _group(fmt)).T
+        assert _E(y.cpu().numpy(), oracle.add_residual(plain, res)) <= TOL, M
         if N % 32 == 0:
             yg = torch.empty((M, N // 2), dtype=torch.float16, device=DEV)
             # a normalization weight scaled down (by a power of two) keeps the product of the two halves of order 1..64
@@ -1073,7 +1155,9 @@ def test_decode_norm_merged_into_layer(fmt, N, K):
                                       norm_offset=0.0)
             torch.cuda.synchronize()
             fulls = oracle.rms_scale(xs, eps)[:, None] * oracle.fc_weight_only(oracle.norm_weighted_input(xs, gs, 0.0), wq, s, _group(fmt))
-            assert oracle.floored_rel_error(yg.cpu().numpy(), oracle.gated_output(fulls, oracle.SILU)) <= TOL, M
+            assert _E(yg.cpu().numpy(), oracle.gated_output(fulls, oracle.SILU)) <= TOL, M
+            plains = oracle.rmsnorm(xs, gs, eps, 0.0)[1] @ oracle.dequantize(wq, s, _group(fmt)).T
+            assert _E(yg.cpu().numpy(), oracle.gated_output(plains, oracle.SILU)) <= TOL, M
     # against the unfused sequence on the GPU: norm kernel, then the plain layer
     x = synth.activations(3953, N, K, 3, K)
     xd = torch.from_numpy(x).to(DEV)
@@ -1085,5 +1169,5 @@ def test_decode_norm_merged_into_layer(fmt, N, K):
         binding.qfc_forward(layer.handle, yn, y_a)
         binding.qfc_forward_fused(layer.handle, xd, y_b, norm_gamma=gd, norm_eps=1e-5, norm_offset=0.0)
         torch.cuda.synchronize()
-        assert oracle.floored_rel_error(y_b.cpu().numpy(), y_a.cpu().numpy().astype(np.float64)) <= 2 * TOL
+        assert _E(y_b.cpu().numpy(), y_a.cpu().numpy().astype(np.float64)) <= 2 * TOL
     layer.close()

@@ -275,6 +275,51 @@ def test_error_metric():
     assert abs(oracle.floored_rel_error(y + np.array([[0, 0, 1e-3, 0]]), y) - 1e-3 / rho) < 1e-15
 
 
+def test_error_metric_golden_per_row_and_short_rows():
+    """Both branches of the acceptance metric against hand-worked values: the per-row floor that
+    every parity test of a real layer (N >= 32) goes through, and the whole-output floor of
+    short rows.  The two rows have different scales, so a floor taken per column or over the
+    whole output fails (a) and (b)."""
+    c = _golden()["error_metric_rows"]
+    ref = np.empty((2, 32))
+    ref[0] = float(c["row0_fill"][0])
+    ref[0, int(c["row0_zero_at"][0])] = 0.0
+    ref[1] = float(c["row1_fill"][0])
+    ref[1, int(c["row1_big_at"][0])] = float(c["row1_big"][0])
+
+    def E(m, n, delta):
+        y = ref.copy()
+        y[m, n] += delta
+        return oracle.floored_rel_error(y, ref)
+
+    assert E(0, 5, 1e-3) == pytest.approx(float(c["E_a"][0]), rel=1e-8)
+    assert E(1, 3, 1e-3) == pytest.approx(float(c["E_b"][0]), rel=1e-8)
+    assert E(1, 7, -0.016) == pytest.approx(float(c["E_c"][0]), rel=1e-8)
+    assert E(0, 9, -1e-3) == pytest.approx(float(c["E_d"][0]), rel=1e-8)
+    # the maximum over all entries is reported, whichever row it is in
+    y = ref.copy()
+    y[0, 5] += 1e-3
+    y[1, 3] += 1e-3
+    assert oracle.floored_rel_error(y, ref) == pytest.approx(float(c["E_a"][0]), rel=1e-8)
+    # the plain relative error over the entries at or above their row's floor: (a) and (b) sit
+    # below the floor and do not count, (c) and (d) are plain |delta| / |ref|
+    assert oracle.plain_rel_error_above_floor(y, ref) == 0.0
+    y[1, 7] -= 0.016
+    assert oracle.plain_rel_error_above_floor(y, ref) == pytest.approx(5e-4, rel=1e-8)
+    y[0, 9] -= 1e-3
+    assert oracle.plain_rel_error_above_floor(y, ref) == pytest.approx(1e-3, rel=1e-8)
+
+    s = _golden()["error_metric_short_rows"]
+    ref2 = np.array([[3.0, 4.0], [0.0, 0.0]])
+    y = ref2.copy()
+    y[1, 0] += 0.005
+    assert oracle.floored_rel_error(y, ref2) == pytest.approx(float(s["E_zero_row"][0]), rel=1e-8)
+    y = ref2.copy()
+    y[0, 1] += 0.005
+    assert oracle.floored_rel_error(y, ref2) == pytest.approx(float(s["E_big_entry"][0]), rel=1e-8)
+    assert oracle.plain_rel_error_above_floor(y, ref2) == pytest.approx(float(s["E_big_entry"][0]), rel=1e-8)
+
+
 # ---------------------------------------------------------------- fused element-wise operators
 def test_gate_activations_hand_values_and_identities():
     c = _golden()["gated_activations"]
