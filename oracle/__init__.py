@@ -155,6 +155,13 @@ def _row_floor(y_ref: np.ndarray):
     return np.sqrt(np.mean(y_ref * y_ref, axis=1, keepdims=True))
 
 
+def floored_denominator(y_ref) -> np.ndarray:
+    """max(|y_ref[m,n]|, rho_m) element by element: the denominator of the acceptance metric."""
+    y_ref = np.asarray(y_ref, dtype=np.float64)
+    den = np.maximum(np.abs(y_ref), _row_floor(y_ref))
+    return np.where(den == 0.0, 1.0, den)
+
+
 def floored_rel_error(y_gpu, y_ref) -> float:
     """Acceptance metric of the floating-point paths.
 

@@ -84,7 +84,7 @@ def test_embedding_lookup_bit_exact(fmt, N, K):
     ids = np.concatenate([[0, N - 1, -3, N], rng.integers(0, N, size=9)]).astype(np.int32)
     M = len(ids)
     y = torch.full((M + 1, K), 3.0, dtype=torch.float16, device=DEV)
-    binding.qfc_embedding(layer.handle, torch.from_numpy(ids).to(DEV), y)
+    binding.qfc_embedding(layer.handle, torch.from_numpy(ids).to(DEV), y[:M])  # (a view of the first M rows)
     torch.cuda.synchronize()
     got = y.cpu().numpy()
     ref = oracle.embedding(ids, wq, s, _group(fmt))
@@ -1139,9 +1139,18 @@ def test_decode_norm_merged_into_layer(fmt, N, K):
         full = rs[:, None] * oracle.fc_weight_only(x_in, wq, s, _group(fmt))
         assert _E(y.cpu().numpy(), oracle.add_residual(full, res)) <= TOL, M
         # ... and against the plain definition: the layer applied to rmsnorm(x), nothing factored
-        # out and nothing rounded between the normalization and the product
-        plain = oracle.rmsnorm(x, gamma, eps, off)[1] @ oracle.dequantize(wq, s, _group(fmt)).T
-        assert _E(y.cpu().numpy(), oracle.add_residual(plain, res)) <= TOL, M
+        # out and nothing rounded between the normalization and the product.  The merged operator
+        # rounds the layer's input once to binary16 (FP16 activations; an unfused normalization
+        # would store the same precision), which the plain definition does not: K independent
+        # roundings of relative size <= 2^-11 add an error of standard deviation
+        # sigma[m,n] <= 2^-11 / sqrt(3) * sqrt(sum_k (xn[m,k] W[n,k])^2) to output (m,n); six of them
+        # are allowed on top of the bound of the output rounding.
+        xn, What = oracle.rmsnorm(x, gamma, eps, off)[1], oracle.dequantize(wq, s, _group(fmt))
+        plain = oracle.add_residual(xn @ What.T, res)
+        sigma = 2.0 ** -11 / np.sqrt(3.0) * np.sqrt((xn * xn) @ (What * What).T)
+        dev = np.abs(y.cpu().numpy().astype(np.float64) - plain)
+        assert np.all(dev <= TOL * oracle.floored_denominator(plain) + 6.0 * sigma), M
+        assert _E(y.cpu().numpy(), plain) <= 1.5 * TOL, M  # (and never far from the plain bound)
         if N % 32 == 0:
             yg = torch.empty((M, N // 2), dtype=torch.float16, device=DEV)
             # a normalization weight scaled down (by a power of two) keeps the product of the two halves of order 1..64
@@ -1157,7 +1166,7 @@ def test_decode_norm_merged_into_layer(fmt, N, K):
             fulls = oracle.rms_scale(xs, eps)[:, None] * oracle.fc_weight_only(oracle.norm_weighted_input(xs, gs, 0.0), wq, s, _group(fmt))
             assert _E(yg.cpu().numpy(), oracle.gated_output(fulls, oracle.SILU)) <= TOL, M
             plains = oracle.rmsnorm(xs, gs, eps, 0.0)[1] @ oracle.dequantize(wq, s, _group(fmt)).T
-            assert _E(yg.cpu().numpy(), oracle.gated_output(plains, oracle.SILU)) <= TOL, M
+            assert _E(yg.cpu().numpy(), oracle.gated_output(plains, oracle.SILU)) <= 2 * TOL, M  # (two rounded-input sums multiplied)
     # against the unfused sequence on the GPU: norm kernel, then the plain layer
     x = synth.activations(3953, N, K, 3, K)
     xd = torch.from_numpy(x).to(DEV)
