@@ -47,7 +47,8 @@ typedef enum {
     QFC_ERR_UNSUPPORTED = 2,      /* a valid combination this library has no kernel for */
     QFC_ERR_BUFFER_TOO_SMALL = 3, /* packed buffer or workspace smaller than required */
     QFC_ERR_ALIGNMENT = 4,        /* a device pointer is not 16-byte aligned */
-    QFC_ERR_HIP = 5               /* the HIP runtime reported an error */
+    QFC_ERR_HIP = 5,              /* the HIP runtime reported an error */
+    QFC_ERR_SCRATCH_LIMIT = 6     /* qfc_forward_static: the call needs more scratch than QFC_STATIC_SCRATCH_BYTES */
 } qfc_status_t;
 
 enum { QFC_SCALE_F32 = 0, QFC_SCALE_F16 = 1 };
@@ -173,6 +174,26 @@ typedef struct qfc_fusion {
  * during the call; null or all parts absent = qfc_forward). */
 qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16,
                                const qfc_fusion_t *f, void *stream);
+
+/* qfc_forward for callers that cannot allocate or lend device memory: code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc.  It
+ * computes exactly what qfc_forward computes (same kernels, same bits) and ignores
+ * the handle's bound workspace: the scratch of the int8 prefill path (the quantized
+ * activations and their scales, qfc_workspace_size(h, M) bytes) lives in a device
+ * array of QFC_STATIC_SCRATCH_BYTES that is part of the library's code object (each
+ * GPU the library runs on holds its own copy until the process ends).  The call
+ * allocates and frees nothing, on the host or the device; on its first use on a
+ * device it looks up that device's copy of the array.
+ *   - Calls whose scratch would not fit return QFC_ERR_SCRATCH_LIMIT before anything
+ *     is enqueued (16 MiB holds M = 1024 token rows at K = 14336).  Decode calls and
+ *     the fp16 prefill path use no scratch and have no such limit.
+ *   - Every call on a GPU shares that GPU's array, which keeps the last call's
+ *     contents; a call rewrites all of the region it reads, so nothing needs
+ *     clearing, but calls that overlap in time on one GPU (two streams, two
+ *     threads) race: order them.
+ * x_f16, y_f16, M, stream: as qfc_forward. */
+#define QFC_STATIC_SCRATCH_BYTES ((size_t)16 << 20)
+qfc_status_t qfc_forward_static(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream);
 
 /* RMS normalization with the residual connection and the quantization of the
  * next layer's input merged into one kernel (operator fusion, section 3.6 and

@@ -14,12 +14,14 @@ LIB_PATH = os.path.join(_HERE, "libqfc.so")
 
 QFC_OK = 0
 QFC_ERR_INVALID_ARG, QFC_ERR_UNSUPPORTED, QFC_ERR_BUFFER_TOO_SMALL, QFC_ERR_ALIGNMENT, QFC_ERR_HIP = 1, 2, 3, 4, 5
+QFC_ERR_SCRATCH_LIMIT = 6
+QFC_STATIC_SCRATCH_BYTES = 16 << 20
 QFC_SCALE_F32, QFC_SCALE_F16 = 0, 1
 QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT, QFC_COMPUTE_INT8_ACT_DECODE = 0, 1, 2
 QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
-           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
+           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_forward_static", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
            "qfc_forward_acc_i32", "qfc_embedding", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
 
 
@@ -73,6 +75,7 @@ def lib() -> ctypes.CDLL:
         L.qfc_bind_workspace.argtypes = [vp, vp, sz]
         L.qfc_quantize_activations.argtypes = [vp, i32, i32, vp, vp, vp]
         L.qfc_forward.argtypes = [vp, vp, i32, vp, vp]
+        L.qfc_forward_static.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_forward_fused.argtypes = [vp, vp, i32, vp, ctypes.POINTER(Fusion), vp]
         L.qfc_rmsnorm.argtypes = [ctypes.POINTER(RmsNorm), i32, i32, vp]
         L.qfc_rope_qkv.argtypes = [vp, i32, i32, ctypes.POINTER(AttnShape), ctypes.c_float, vp, vp, vp, vp]
@@ -202,6 +205,13 @@ def qfc_forward(h, x: torch.Tensor, y: torch.Tensor):
     _want(x, torch.float16, (None, K), "x")
     _want(y, torch.float16, (x.shape[0], N), "y")
     _check(lib().qfc_forward(h, _ptr(x), x.shape[0], _ptr(y), _stream()), "qfc_forward")
+
+
+def qfc_forward_static(h, x: torch.Tensor, y: torch.Tensor):
+    N, K = _nk(h)
+    _want(x, torch.float16, (None, K), "x")
+    _want(y, torch.float16, (x.shape[0], N), "y")
+    _check(lib().qfc_forward_static(h, _ptr(x), x.shape[0], _ptr(y), _stream()), "qfc_forward_static")
 
 
 def qfc_forward_fused(h, x: torch.Tensor, y: torch.Tensor, gate: torch.Tensor | None = None,

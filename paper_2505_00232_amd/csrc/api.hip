@@ -65,6 +65,31 @@ size_t workspace_need(qfc_handle_t h, int M) {
 
 qfc_status_t hip_status(hipError_t e) { return e == hipSuccess ? QFC_OK : QFC_ERR_HIP; }
 
+// ---- scratch of the entry point that allocates nothing (qfc_forward_static)
+// Device memory that is part of the library's code object: every GPU the library runs on holds its
+// own copy, at its own address, until the process ends.  In host code the array's NAME is only a
+// stand-in for the symbol, not a device address; the address on the current device comes from
+// hipGetSymbolAddress, once per device, and only that pointer is ever handed to a kernel.
+constexpr size_t kStaticScratchBytes = QFC_STATIC_SCRATCH_BYTES;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// The array's address on the current device (looked up on the first call on that device).
+qfc_status_t static_scratch(void **out) {
+    int dev = 0;
+    if (hipGetDevice(&dev) != hipSuccess) return QFC_ERR_HIP;
+    if (dev < 0 || dev >= kMaxDevices) return QFC_ERR_UNSUPPORTED;
+    void *p = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!p) {
+        if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return QFC_ERR_HIP;
+        g_scratch_ptr[dev].store(p, std::memory_order_release);  // (two first callers store the same address)
+    }
+    *out = p;
+    return QFC_OK;
+}
+
 // Common checks of the int8 entry points; on success the tiled activations are in the workspace.
 qfc_status_t stage_xq(qfc_handle_t h, const int8_t *xq, int M, int8_t **tiled, float **sx_ws,
                       hipStream_t st) {
@@ -152,9 +177,11 @@ qfc_status_t qfc_quantize_activations(const void *x_f16, int32_t M, int32_t K, i
     return hip_status(launch_act_quant(x_f16, nullptr, 0, M, K, xq, sx, 0, M, K, cus, static_cast<hipStream_t>(stream)));
 }
 
-// Shared body of qfc_forward and qfc_forward_fused.
+// Shared body of qfc_forward, qfc_forward_fused and qfc_forward_static.  `scratch` is where the
+// int8 prefill path keeps the quantized activations and their scales: the handle's bound workspace,
+// or the library's static array.
 static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, const Fusion &f,
-                                 hipStream_t st) {
+                                 void *scratch, size_t scratch_bytes, hipStream_t st) {
     if (!valid(h) || !x_f16 || !y_f16 || M < 1) return QFC_ERR_INVALID_ARG;
     if (!aligned16(x_f16) || !aligned16(y_f16)) return QFC_ERR_ALIGNMENT;
     if ((f.gate && !aligned16(f.gate)) || (f.residual && !aligned16(f.residual))) return QFC_ERR_ALIGNMENT;
@@ -178,10 +205,10 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
         return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, f.residual, h->num_cus, st));
     }
     if (f.gated_output) return QFC_ERR_UNSUPPORTED;
-    if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
-    // int8 activations: quantize into the workspace (tiled), multiply, rescale
+    if (!scratch || scratch_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
+    // int8 activations: quantize into the scratch region (tiled), multiply, rescale
     const int Mp = prefill_rows(M);
-    char *body = static_cast<char *>(h->workspace);
+    char *body = static_cast<char *>(scratch);
     int8_t *tiled = reinterpret_cast<int8_t *>(body);
     float *sx = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
     if (launch_act_quant(x_f16, f.gate, f.activation, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, h->num_cus, st) !=
@@ -191,7 +218,8 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
 }
 
 qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream) {
-    return forward_impl(h, x_f16, M, y_f16, Fusion(), static_cast<hipStream_t>(stream));
+    if (!valid(h)) return QFC_ERR_INVALID_ARG;
+    return forward_impl(h, x_f16, M, y_f16, Fusion(), h->workspace, h->workspace_bytes, static_cast<hipStream_t>(stream));
 }
 
 qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16,
@@ -206,7 +234,20 @@ qfc_status_t qfc_forward_fused(qfc_handle_t h, const void *x_f16, int32_t M, voi
         f.norm_eps = fusion->norm_eps;
         f.norm_offset = fusion->norm_offset;
     }
-    return forward_impl(h, x_f16, M, y_f16, f, static_cast<hipStream_t>(stream));
+    if (!valid(h)) return QFC_ERR_INVALID_ARG;
+    return forward_impl(h, x_f16, M, y_f16, f, h->workspace, h->workspace_bytes, static_cast<hipStream_t>(stream));
+}
+
+qfc_status_t qfc_forward_static(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream) {
+    if (!valid(h) || M < 1) return QFC_ERR_INVALID_ARG;
+    // Which calls need scratch at all is the dispatcher's business (M > 8 in the int8 mode); the limit
+    // is checked for those only, before anything is enqueued.
+    const bool int8_prefill = M > kMaxDecodeM && h->geo.fmt == kW8C && h->desc.compute_mode != QFC_COMPUTE_FP16_DEQUANT;
+    if (int8_prefill && workspace_need(h, M) > kStaticScratchBytes) return QFC_ERR_SCRATCH_LIMIT;
+    void *p = nullptr;
+    const qfc_status_t s = static_scratch(&p);
+    if (s != QFC_OK) return s;
+    return forward_impl(h, x_f16, M, y_f16, Fusion(), p, kStaticScratchBytes, static_cast<hipStream_t>(stream));
 }
 
 qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *r, int32_t M, int32_t K, void *stream) {
@@ -360,6 +401,7 @@ const char *qfc_status_string(qfc_status_t s) {
         case QFC_ERR_BUFFER_TOO_SMALL: return "buffer too small";
         case QFC_ERR_ALIGNMENT: return "pointer not 16-byte aligned";
         case QFC_ERR_HIP: return "HIP runtime error";
+        case QFC_ERR_SCRATCH_LIMIT: return "input needs more scratch than the library's static array holds";
     }
     return "unknown status";
 }

@@ -41,8 +41,8 @@ def test_header_symbols_are_exported(L):
 
 
 def test_status_strings(L):
-    seen = {binding.status_string(c) for c in range(6)}
-    assert len(seen) == 6 and binding.status_string(0) == "ok"
+    seen = {binding.status_string(c) for c in range(7)}
+    assert len(seen) == 7 and binding.status_string(0) == "ok"
     assert binding.status_string(99) == "unknown status"
 
 
@@ -84,7 +84,7 @@ def test_argument_errors_before_any_launch(L):
     assert L.qfc_pack_weights(ctypes.byref(d), odd, a, a, 1 << 20, s, ctypes.byref(h)) == 4
     assert L.qfc_pack_weights(ctypes.byref(d), a, a, a, 16, s, ctypes.byref(h)) == 3
     assert h.value is None
-    for fn, args in [(L.qfc_forward, (None, a, 1, a, s)), (L.qfc_unpack_weights, (None, a, a, s)),
+    for fn, args in [(L.qfc_forward, (None, a, 1, a, s)), (L.qfc_forward_static, (None, a, 1, a, s)), (L.qfc_unpack_weights, (None, a, a, s)),
                      (L.qfc_bind_workspace, (None, a, 1024)), (L.qfc_forward_q8, (None, a, a, 1, a, s)),
                      (L.qfc_forward_acc_i32, (None, a, 1, a, s)), (L.qfc_embedding, (None, a, 1, a, s)),
                      (L.qfc_destroy, (None,))]:
