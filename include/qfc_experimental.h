@@ -19,8 +19,8 @@ extern "C" {
 /* Set one process-wide tunable (each is a single atomic integer; a call that is
  * being enqueued on another thread sees either the old or the new value of each
  * key, never a torn one).  Unknown keys are ignored.
- *   key 0  target number of wavefronts of a decode launch (default 8192)
- *   key 1  most row tiles a decode workgroup walks (default 2)
+ *   key 0  target number of wavefronts of a decode launch (0 = automatic: 8192 up to two token rows, 2048 above)
+ *   key 1  most row tiles a decode workgroup walks (0 = automatic: 2 up to two token rows, 4 above)
  *   key 2  prefill kernel variant (0 = automatic)
  *   key 3  token rows per workgroup of the activation quantization kernel (0 = automatic; 2, 4, 8)
  *   key 4  half-unit items of the decode kernel (-1 automatic, 0 never, 1 where possible)

@@ -460,8 +460,10 @@ __global__ __launch_bounds__(64 * PrefillCfg<D>::NW, 2) void attn_prefill_kernel
         }
     }
     auto issue = [&](int blk) {
-        // past the end the walk's first steps are copied again (constant operation counts; distinct
-        // sources, since many copies of the same lines in flight have been seen to land late)
+        // past the end the walk's first steps are copied again (constant operation counts), into one
+        // spare KiB behind the ring that nothing reads (and from distinct sources: many copies of the
+        // same lines in flight had been seen in ring slots after the counter said they were done;
+        // the cause is not known, so a late copy gets no destination that anything reads)
         const int bc = blk < nb ? blk : min(sb + (blk - nb), nb - 1);
         const int p0 = bc * 32;
         const char *ksrc = kbase + (size_t)p0 * (2 * D);
@@ -475,7 +477,7 @@ __global__ __launch_bounds__(64 * PrefillCfg<D>::NW, 2) void attn_prefill_kernel
             const uint32_t lo = __builtin_amdgcn_readfirstlane((uint32_t)addr);
             const uint32_t hi = __builtin_amdgcn_readfirstlane((uint32_t)(addr >> 32));
             copy16_to_lds(reinterpret_cast<const void *>(((uint64_t)hi << 32) | lo), src_off[i],
-                          __builtin_amdgcn_readfirstlane(lds0 + (blk % NS) * Cfg::STAGE + piece * 1024));
+                          __builtin_amdgcn_readfirstlane(lds0 + (blk < nb ? (blk % NS) * Cfg::STAGE + piece * 1024 : NS * Cfg::STAGE)));
         }
     };
 
@@ -719,8 +721,9 @@ __global__ __launch_bounds__(256) void attn_prefill_combine_kernel(AttnArgs a) {
 
 template <int D>
 hipError_t launch_attn_prefill(const AttnArgs &a, int G, hipStream_t st) {
-    constexpr size_t lds = (size_t)PrefillCfg<D>::NS * PrefillCfg<D>::STAGE;
+    constexpr size_t lds = (size_t)PrefillCfg<D>::NS * PrefillCfg<D>::STAGE + 1024;  // the ring and the spare KiB
     static_assert(lds <= 160 * 1024, "LDS budget");
+    static_assert((PrefillCfg<D>::NS - 1) * PrefillCfg<D>::COPIES <= 63, "outstanding copies must fit the 6-bit counter");
     if (const hipError_t e = allow_dynamic_lds<attn_prefill_kernel<D>>(lds); e != hipSuccess) return e;
     const int nblocks = (a.M + 127) / 128;
     if (a.chunk_steps > 0) {

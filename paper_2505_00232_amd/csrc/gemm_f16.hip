@@ -21,6 +21,8 @@
 // (32 rows x 16 k, lane = row + 32 * (k/8)) is two runs of 512 contiguous
 // bytes; the activation tile has a one-vector pad per octet so that its
 // transposing writes are conflict free as well.
+#include <type_traits>
+
 #include "qfc_internal.h"
 
 namespace qfc {
@@ -290,11 +292,15 @@ constexpr int DW_BYTES = 16 * 1024;               // codes of one tile: 16 row t
 constexpr int DS_BYTES = 4 * 1024;                // scales for one tile: 4 channel groups x 64 rows x 16 B
 constexpr int DW_OFF = DRING * DX_BYTES;
 constexpr int DS_OFF = DW_OFF + DRING * DW_BYTES;
-constexpr int kDirectLdsBytes = DS_OFF + DRING * DS_BYTES;
+constexpr int kDirectRingBytes = DS_OFF + DRING * DS_BYTES;
+constexpr int DSPARE_OFF = kDirectRingBytes;          // one spare KiB: destination of the copies past the end of K
+constexpr int kDirectLdsBytes = kDirectRingBytes + 1024;
+static_assert(kDirectLdsBytes <= 160 * 1024, "LDS of a compute unit");
 constexpr int DBATCH = 2 + 1 + 4;                 // copies per wavefront per tile (one fewer without group scales)
 constexpr int DEX_BYTES = 64 * 64 * 4;            // half of a wavefront's accumulators (exchange buffer)
 constexpr int DEPI_PITCH = (64 + 8) * 2;
-static_assert(8 * DEX_BYTES <= kDirectLdsBytes && 32 * DEPI_PITCH <= DEX_BYTES, "exchange and store staging fit in the rings");
+static_assert(8 * DEX_BYTES <= kDirectRingBytes && 32 * DEPI_PITCH <= DEX_BYTES, "exchange and store staging fit in the rings, below the spare KiB");
+static_assert(3 * DBATCH <= 63, "outstanding copies of a wavefront (three batches at most) must fit the 6-bit counter");
 
 // eight biased codes -> eight scaled binary16 values (k ascending) as an MFMA operand
 __device__ __forceinline__ v8h dequant_frag(uint32_t w, h2 s) {
@@ -391,31 +397,40 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     // The 7 copies of a batch, one at a time (they are spread over the MFMA blocks of
     // a tile: issued together by all eight wavefronts right after the barrier they
     // would queue up behind each other in the memory pipeline while the matrix
-    // cores idle).  Past the end of K the copies start over at tile 0, into slots
-    // nobody reads any more, so that the count of outstanding copies is the same on
-    // every iteration (not the last tile again and again: many copies of the same
-    // lines in flight from one wavefront have been seen to reach LDS after the
-    // counter said they were done).
-    auto issue_w = [&](int t, int i) {  // codes of tile t, row tile 2 ks + i of the channel group
-        const int tc = t < KT ? t : min(t - KT, KT - 1);
+    // cores idle).  Past the end of K the copies start over at tile 0, so that the
+    // count of outstanding copies is the same on every iteration, and all land in
+    // one spare KiB behind the rings that nothing reads and the exchange and store
+    // phases never use (distinct sources, not the last tile again and again: many
+    // copies of the same lines in flight from one wavefront had been seen in ring
+    // slots after the counter said they were done; the cause is not known, so no
+    // late copy may have a destination that anything reads or reuses).
+    // (bulk: the caller knows that tile t lies inside K; the tiles of the main loop's bulk part then
+    // carry no end-of-K tests)
+    constexpr bool kBulk = true, kEdge = false;  // (constants at every call site: the tests fold away)
+    auto issue_w = [&](int t, int i, const bool bulk) __attribute__((always_inline)) {  // codes of tile t, row tile 2 ks + i of the channel group
+        const bool real = bulk || t < KT;
+        const int tc = real ? t : min(t - KT, KT - 1);
         const size_t wpos = (size_t)(PC ? tc : tc + (tc >> 3)) * 1024;
-        copy16_to_lds(wbase + i * rt_bytes + wpos, wlane, lds0 + DW_OFF + (t % DRING) * DW_BYTES + (ng * 4 + ks * 2 + i) * 1024);
+        copy16_to_lds(wbase + i * rt_bytes + wpos, wlane,
+                      lds0 + (real ? DW_OFF + (t % DRING) * DW_BYTES + (ng * 4 + ks * 2 + i) * 1024 : DSPARE_OFF));
     };
-    auto issue_s = [&](int t) {  // scales of tile t: vector (t % 8) / 2 * 16 + row of the unit's scale tile (8 groups = 2 tiles)
-        const int tc = t < KT ? t : min(t - KT, KT - 1), u = tc >> 3;
+    auto issue_s = [&](int t, const bool bulk) __attribute__((always_inline)) {  // scales of tile t: vector (t % 8) / 2 * 16 + row of the unit's scale tile (8 groups = 2 tiles)
+        const bool real = bulk || t < KT;
+        const int tc = real ? t : min(t - KT, KT - 1), u = tc >> 3;
         const size_t spos = (size_t)(min(8 * u + 8, KT) + u) * 1024 + (size_t)((tc & 7) >> 1) * 256;
-        copy16_to_lds(sbase + spos, slane, lds0 + DS_OFF + (t % DRING) * DS_BYTES + ng * 1024);
+        copy16_to_lds(sbase + spos, slane, lds0 + (real ? DS_OFF + (t % DRING) * DS_BYTES + ng * 1024 : DSPARE_OFF));
     };
-    auto issue_x = [&](int t, int i) {  // activation stage t, block wave + 8 (i % 2) of half i / 2
-        const int tc = t < KT ? t : min(t - KT, KT - 1);
+    auto issue_x = [&](int t, int i, const bool bulk) __attribute__((always_inline)) {  // activation stage t, block wave + 8 (i % 2) of half i / 2
+        const bool real = bulk || t < KT;
+        const int tc = real ? t : min(t - KT, KT - 1);
         copy16_to_lds(xbase + (size_t)tc * 256 + (i >> 1) * 128, xlane[i & 1],
-                      lds0 + (t % DRING) * DX_BYTES + wave * 1024 + (i >> 1) * (DX_BYTES / 2) + (i & 1) * 8192);
+                      lds0 + (real ? (t % DRING) * DX_BYTES + wave * 1024 + (i >> 1) * (DX_BYTES / 2) + (i & 1) * 8192 : DSPARE_OFF));
     };
     auto issue_batch = [&](int tw, int tx) {
-        issue_w(tw, 0); issue_w(tw, 1);
-        if (!PC) issue_s(tw);
+        issue_w(tw, 0, kEdge); issue_w(tw, 1, kEdge);
+        if (!PC) issue_s(tw, kEdge);
 #pragma unroll
-        for (int i = 0; i < 4; ++i) issue_x(tx, i);
+        for (int i = 0; i < 4; ++i) issue_x(tx, i, kEdge);
     };
 
     v16f acc[2][4];
@@ -481,12 +496,12 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
 
     // Copies in issue order: codes/scales 0, codes/scales 1, stage 0 | codes/scales 2,
     // stage 1 | then during tile t: codes/scales t + 3, stage t + 2.
-    issue_w(0, 0); issue_w(0, 1);
-    if (!PC) issue_s(0);
-    issue_w(1, 0); issue_w(1, 1);
-    if (!PC) issue_s(1);
+    issue_w(0, 0, kEdge); issue_w(0, 1, kEdge);
+    if (!PC) issue_s(0, kEdge);
+    issue_w(1, 0, kEdge); issue_w(1, 1, kEdge);
+    if (!PC) issue_s(1, kEdge);
 #pragma unroll
-    for (int i = 0; i < 4; ++i) issue_x(0, i);
+    for (int i = 0; i < 4; ++i) issue_x(0, i, kEdge);
     issue_batch(2, 1);
 #pragma unroll
     for (int i = 0; i < 2; ++i)
@@ -499,7 +514,7 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     wait_vmcnt<BATCH>();
     asm volatile("s_barrier" ::: "memory");
     read_ws(0);
-    for (int t = 0; t < KT; ++t) {
+    auto tile = [&](int t, const bool bulk) __attribute__((always_inline)) {
         // What was issued two tiles ago has landed once only the newest batch is
         // outstanding: stage t, codes and scales of tile t + 1.  The barrier makes
         // the other wavefronts' copies visible and says that every wavefront is done
@@ -515,7 +530,7 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
             convert(fa0, 0, qb);
             interleave_mfma_valu();
             __builtin_amdgcn_sched_barrier(0);
-            issue_x(t + 2, qb);
+            issue_x(t + 2, qb, bulk);
         }
         read_x(x1, 1, t);
         __builtin_amdgcn_sched_barrier(0);
@@ -525,11 +540,16 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
             convert(fa1, 1, qb);
             interleave_mfma_valu();
             __builtin_amdgcn_sched_barrier(0);
-            if (qb == 0) issue_w(t + 3, 0);
-            if (qb == 1) issue_w(t + 3, 1);
-            if (qb == 2 && !PC) issue_s(t + 3);
+            if (qb == 0) issue_w(t + 3, 0, bulk);
+            if (qb == 1) issue_w(t + 3, 1, bulk);
+            if (qb == 2 && !PC) issue_s(t + 3, bulk);
         }
         read_ws(t + 1);
+    };
+    {
+        int t = 0;
+        for (; t + 3 < KT; ++t) tile(t, kBulk);  // every copy issued during these tiles lies inside K
+        for (; t < KT; ++t) tile(t, kEdge);
     }
 #pragma unroll
     for (int qb = 0; qb < 4; ++qb) multiply(fa1, x1, qb);

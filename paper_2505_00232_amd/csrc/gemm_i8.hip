@@ -295,10 +295,10 @@ __global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_ke
 // 8 KiB (4 KiB for the 64-row tile), CP tile copies per wavefront and stage; the ring is deep (8-14
 // stages) because the wait count that is safe for both kinds of operation grows with it (see below).  Copies and loads past the end of K start
 // over at stage 0, so that every iteration issues the same number of operations and the waits are
-// constants.  They must not all repeat one stage: with about ten copies of the same lines in flight
-// from one wavefront, some of their data reached LDS after the counter had already dropped to zero
-// (measured with a 14-stage ring: the staging area of the store phase, which reuses the ring, came
-// back holding activation bytes of the repeated stage; with distinct sources it does not happen).
+// constants.  Such copies go to a spare KiB behind the ring that is never read (and their sources
+// are distinct stages, not one stage over and over: with about ten copies of the same lines in
+// flight from one wavefront, data had been seen in ring slots after the counter had dropped to zero;
+// the cause is not known, so no late copy may have a destination that anything reads or reuses).
 // The number of stages must be a multiple of PW.
 // TM = 4: 256 x 128 tile; TM = 2: 256 x 64 tile (twice the tiles for small outputs, twice the weight
 // loads per MFMA).
@@ -340,8 +340,8 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
         wsrc[i] = a.w + ((size_t)(nt * (BN / 16) + 4 * wave + (row >> 4)) * KT) * 64 + (lane >> 5) * 16 + (row & 15);
     }
     v4i wreg[PW][TN][2];
-    auto load_w = [&](int slot, int kt) {
-        const int kc = kt < KT ? kt : min(kt - KT, KT - 1);
+    auto load_w = [&](int slot, int kt, const bool bulk) __attribute__((always_inline)) {  // bulk: kt < KT is known
+        const int kc = bulk || kt < KT ? kt : min(kt - KT, KT - 1);
 #pragma unroll
         for (int i = 0; i < TN; ++i)
 #pragma unroll
@@ -354,12 +354,18 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     // activations: tiles wave (and wave + 4) of the XT token-row tiles of a stage
     const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
     const uint4 *xsrc = a.x + ((size_t)(mt * (BM / 16)) * KT) * 64;
-    auto issue_x = [&](int kt) {
-        const int kc = kt < KT ? kt : min(kt - KT, KT - 1);
+    // Copies past the end of K (issued so that every iteration has the same operation count and the
+    // waits stay constants) read the first stages again and all land in one spare KiB behind the
+    // ring that nothing ever reads and the store phase never uses: whatever their timing, they
+    // cannot touch a stage or the staging area of the store phase.
+    constexpr uint32_t kSpare = NS * XT * 1024;
+    auto issue_x = [&](int kt, const bool bulk) __attribute__((always_inline)) {  // bulk: kt < KT is known
+        const bool real = bulk || kt < KT;
+        const int kc = real ? kt : min(kt - KT, KT - 1);
 #pragma unroll
         for (int h = 0; h < CP; ++h) {
             const int t = wave + 4 * h;
-            copy16_to_lds(xsrc + ((size_t)t * KT + kc) * 64, lane * 16, lds0 + ((kt % NS) * XT + t) * 1024);
+            copy16_to_lds(xsrc + ((size_t)t * KT + kc) * 64, lane * 16, lds0 + (real ? ((kt % NS) * XT + t) * 1024 : kSpare));
         }
     };
 
@@ -372,10 +378,11 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
 
     // prologue: PW weight stages, then NS - 1 activation stages
+    constexpr bool kBulk = true, kEdge = false;  // (constants at every call site: the tests fold away)
 #pragma unroll
-    for (int p = 0; p < PW; ++p) load_w(p, p);
+    for (int p = 0; p < PW; ++p) load_w(p, p, kEdge);
 #pragma unroll
-    for (int p = 0; p < NS - 1; ++p) issue_x(p);
+    for (int p = 0; p < NS - 1; ++p) issue_x(p, kEdge);
 
     // Waiting.  Copies into LDS and loads into registers share one counter (vmcnt) but do NOT complete
     // in order relative to each other - only within their own kind (measured: with waits that assumed
@@ -389,6 +396,9 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
     // kt), which has one stage fewer behind it.
     constexpr int kAfterCopies = CP * (NS - (PIPE ? 3 : 2)), kAfterLoads = 4 * (PW - 1);
     constexpr int kAllowed = kAfterCopies < kAfterLoads ? kAfterCopies : kAfterLoads;
+    // The most vector-memory operations a wavefront ever has outstanding: the copies of NS - 1 stages
+    // and the loads of PW stages (right after the refills of an iteration).  The counter has 6 bits.
+    static_assert(kAllowed >= 0 && CP * (NS - 1) + 4 * PW <= 63, "wait counts must fit the 6-bit counter");
     v4i xf[PIPE ? 2 : 1][2][TM];
     auto read_x = [&](int b, int kt) {
         const uint4 *lx = lds + (kt % NS) * (XT * 64);
@@ -405,7 +415,9 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
         asm volatile("s_barrier" ::: "memory");
         read_x(0, 0);
     }
-    for (int kt0 = 0; kt0 < KT; kt0 += PW) {
+    // PW stages per pass.  The passes whose copies and loads all lie inside K come first and carry no
+    // end-of-K tests; the last ones redirect what lies past the end.
+    auto stages_pw = [&](int kt0, const bool bulk) __attribute__((always_inline)) {
 #pragma unroll
         for (int u = 0; u < PW; ++u) {
             const int kt = kt0 + u;
@@ -418,7 +430,7 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
             for (int i = 0; i < TN; ++i)
 #pragma unroll
                 for (int ks = 0; ks < 2; ++ks) asm volatile("" : "+v"(wreg[u][i][ks]));
-            issue_x(kt + NS - 1);
+            issue_x(kt + NS - 1, bulk);
             const int cur = PIPE ? (u & 1) : 0;
             if (!PIPE) read_x(0, kt);
 #pragma unroll
@@ -430,9 +442,13 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
                         acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(wreg[u][i][ks], xf[cur][ks][j], acc[i][j], 0, 0, 0);
                 if (PIPE && ks == 0) read_x(cur ^ 1, kt + 1);
             }
-            load_w(u, kt + PW);
+            load_w(u, kt + PW, bulk);
         }
-    }
+    };
+    static_assert(NS - 1 >= PW, "a pass whose copies lie inside K has its loads inside K too");
+    int kt0 = 0;
+    for (; kt0 + PW - 1 + NS - 1 < KT; kt0 += PW) stages_pw(kt0, kBulk);
+    for (; kt0 < KT; kt0 += PW) stages_pw(kt0, kEdge);
     wait_vmcnt<0>();
     // The loads issued past the end of K are still writing their destination registers until this
     // wait returns, and the compiler does not know (it sees registers that nobody reads any more).
@@ -449,8 +465,9 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_dw_kernel(GemmI8Args a) {
 
 template <int NS, int PW, int TM, int OUT_MODE, bool PIPE = false>
 hipError_t launch_dw(GemmI8Args a, hipStream_t st) {
-    constexpr size_t lds_bytes = (size_t)NS * (2 * TM) * 1024 < 4 * 32 * (64 + 8) * 2 ? 4 * 32 * (64 + 8) * 2 : (size_t)NS * (2 * TM) * 1024;
-    static_assert(lds_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks in the same LDS");
+    constexpr size_t ring_bytes = (size_t)NS * (2 * TM) * 1024;  // + one spare KiB for the copies past the end of K
+    constexpr size_t lds_bytes = ring_bytes + 1024;
+    static_assert(ring_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks inside the ring, below the spare KiB");
     if ((a.Kp / 64) % PW != 0) return hipErrorInvalidValue;
     static_assert(lds_bytes <= 80 * 1024, "two workgroups per compute unit");
     if (const hipError_t e = allow_dynamic_lds<gemm_i8_dw_kernel<NS, PW, TM, OUT_MODE, PIPE>>(lds_bytes); e != hipSuccess) return e;

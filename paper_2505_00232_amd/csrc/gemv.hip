@@ -59,8 +59,16 @@ GemvPlan plan_gemv(const Geometry &g, int M, int num_cus, int pro) {
     const int per_wave = (p.units + cap - 1) / cap;  // items per wavefront and row tile
     p.waves = (p.units + per_wave - 1) / per_wave;
     const long waves_total = (long)g.RT * p.waves;
-    int r = (int)((waves_total + t.gemv_target_waves - 1) / t.gemv_target_waves);
-    if (r > t.gemv_max_row_tiles) r = t.gemv_max_row_tiles;
+    // Row tiles per workgroup (they share the staged token rows).  One or two token rows: launches of
+    // up to 8192 wavefronts, at most two row tiles (more measured slower: gate+up projection of
+    // Llama-3.1-8B at M = 1 13.5 -> 14.3-17.3 us).  From three token rows on, staging the rows costs as
+    // much traffic between L2 and the compute units as the weights themselves, and sharing it among up
+    // to four row tiles wins wherever there are enough row tiles (the same layer at M = 4: 16.6 -> 15.5 us,
+    // at M = 8: 23.3 -> 17.4 us; the narrow projections are level).
+    const int target = t.gemv_target_waves > 0 ? (int)t.gemv_target_waves : (M > 2 ? 2048 : 8192);
+    const int most = t.gemv_max_row_tiles > 0 ? (int)t.gemv_max_row_tiles : (M > 2 ? 4 : 2);
+    int r = (int)((waves_total + target - 1) / target);
+    if (r > most) r = most;
     if (r > 4) r = 4;
     if (r < 1) r = 1;
     p.row_tiles = r;

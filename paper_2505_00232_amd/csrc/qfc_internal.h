@@ -123,8 +123,8 @@ struct Tunable {
     }
 };
 struct Tuning {
-    Tunable gemv_target_waves{8192};
-    Tunable gemv_max_row_tiles{2};
+    Tunable gemv_target_waves{0};   // 0: automatic (8192 up to two token rows, 2048 above)
+    Tunable gemv_max_row_tiles{0};  // 0: automatic (2 up to two token rows, 4 above)
     Tunable gemm_variant{0};
     Tunable act_quant_rows{0};  // 0: automatic
     Tunable attn_chunks{-1};    // prefill attention, walks cut into chunks: -1 automatic, 0 never, 1 always
