@@ -461,11 +461,11 @@ def main():
 
     # ------------------------------------------------------------ prefill (configs 4 and 5)
     if not args.skip_prefill:
-        def prefill(fc_list, M, seed, reps=10):
+        def prefill(fc_list, M, seed, reps=10, mode=None):
             out, tot_ops, tot_ms = {}, 0, 0.0
             for i, fc in enumerate(fc_list):
                 wq, s = synth.weights(seed, 0, i, fc)
-                lay = binding.QuantLinear(wq, s, fc.fmt, max_m=M)
+                lay = binding.QuantLinear(wq, s, fc.fmt, compute_mode=mode, max_m=M)
                 x = torch.from_numpy(synth.activations(seed, 0, i, M, fc.K)).to(dev)
                 y = torch.empty((M, fc.N), dtype=torch.float16, device=dev)
                 run = lambda: binding.qfc_forward(lay.handle, x, y)
@@ -493,6 +493,11 @@ def main():
         p16c = prefill(synth.GEMMA_FCS_W4C, 2048, 1105)
         extra["prefill_fp16_int4_per_channel_m2048"] = {"us": p16c["total"]["us"], "Tops": p16c["total"]["Tops"],
                                                         "frac_mfma_fp16_peak": round(p16c["total"]["Tops"] / MFMA_F16_PEAK_TFLOPS, 4)}
+        # the paper's "8/4/4" feed-forward weights in its prefill stage: int8 activations x int4 per-channel weights
+        p84 = prefill(synth.LLAMA_FCS_W4C, 1024, 1104, mode=binding.QFC_COMPUTE_INT8_ACT)
+        extra["prefill_int8_w4c_m1024"] = {**{k: v for k, v in p84.items()},
+                                           "frac_mfma_int8_peak": round(p84["total"]["Tops"] / MFMA_I8_PEAK_TOPS, 4),
+                                           "note": "int8 activations x int4 per-channel weights -> int32, Llama-3.1-8B layer, M=1024"}
         lm = prefill([synth.GEMMA_LM_HEAD], 2048, 1005, reps=3)
         extra["prefill_int8_lm_head_m2048"] = {"us": lm["total"]["us"], "Tops": lm["total"]["Tops"],
                                                "frac_mfma_int8_peak": round(lm["total"]["Tops"] / MFMA_I8_PEAK_TOPS, 4),

@@ -63,8 +63,10 @@ enum { QFC_COMPUTE_FP16_DEQUANT = 0, QFC_COMPUTE_INT8_ACT = 1, QFC_COMPUTE_INT8_
  *   wbits 4, group_size 0,  scale_dtype F32: int4 codes in [-8,7], one fp32 scale per output
  *                                            channel (the paper's per-channel 4-bit scheme).
  * Any other combination returns QFC_ERR_UNSUPPORTED.
- * compute_mode selects the M > 8 path: QFC_COMPUTE_INT8_ACT (needs 8-bit per-channel weights)
- * or QFC_COMPUTE_FP16_DEQUANT; neither changes M <= 8, which keeps binary16 activations.
+ * compute_mode selects the M > 8 path: QFC_COMPUTE_INT8_ACT (per-channel weights, 8-bit or 4-bit:
+ * the paper's "q8" and "8/4/4" schemes in its prefill stage; group scales cannot leave an integer
+ * accumulator) or QFC_COMPUTE_FP16_DEQUANT (4-bit weights); neither changes M <= 8, which keeps
+ * binary16 activations.
  * QFC_COMPUTE_INT8_ACT_DECODE (per-channel formats only) is the decode design of section 3.7
  * of the paper: for M <= 8 the kernel quantizes the activations itself (one scale per token
  * row, as qfc_quantize_activations does) and accumulates integers; for M > 8 it behaves like

@@ -48,6 +48,32 @@ def gated_input(gate_f16, up_f16, activation: int) -> np.ndarray:
     return (a * u).astype(np.float16)  # fp64 -> binary16, round to nearest even
 
 
+def gated_input_f32(gate_f16, up_f16, activation: int) -> np.ndarray:
+    """gated_input with every step taken in binary32, the precision the kernels evaluate the gate
+    in: t = g (c1 + c3 g^2), a = g / (1 + exp(-t)), fp16(a * up), each operation rounded to binary32
+    (the multiply-add c3 g^2 + c1 rounded once).  For the path where the rounded value goes on to
+    decide an 8-bit code (the row maximum and every code depend on its last bit), so that both
+    sides of a comparison take that decision in the same precision; elsewhere gated_input (fp64)
+    is the reference.  The two agree except where the real value lies within a few binary32 units
+    of a binary16 rounding boundary (pinned in the CPU tests).  Returns float16 [M, K]."""
+    f32 = np.float32
+    g = np.asarray(gate_f16, dtype=np.float16).astype(f32)
+    u = np.asarray(up_f16, dtype=np.float16).astype(f32)
+    if activation == SILU:
+        c1, c3 = f32(1.0), f32(0.0)
+    elif activation == GELU_TANH:
+        c1 = f32(1.5957691216)                      # 2 sqrt(2 / pi)
+        c3 = f32(f32(1.5957691216) * f32(0.044715))
+    else:
+        raise ValueError("unknown activation")
+    gg = (g * g).astype(f32)
+    inner = (c3.astype(np.float64) * gg.astype(np.float64) + np.float64(c1)).astype(f32)  # one rounding, like an fma
+    t = (g * inner).astype(f32)
+    e = np.exp((-t).astype(f32)).astype(f32)
+    a = (g / (f32(1.0) + e).astype(f32)).astype(f32)
+    return (a * u).astype(f32).astype(np.float16)
+
+
 def add_residual(y, residual_f16) -> np.ndarray:
     """y + residual in fp64 (the caller's comparison applies the final binary16 rounding)."""
     return np.asarray(y, dtype=np.float64) + np.asarray(residual_f16, dtype=np.float16).astype(np.float64)

@@ -9,6 +9,13 @@
 // int8 product exactly like the int8 weights: KiB tiles of 16 token rows x 64 k,
 // lane (c, q) of a tile = the 16 codes (row c, k = 16q .. 16q+15), tiles stored
 // [row tile][k tile], padded with zeros to [Mp, Kp].
+//
+// Tiled for the int8 product with 4-bit weights (TILED = 2): the packed 4-bit tiles keep the eight
+// codes of octet q of quantization-group-sized run g of a 128-k block in one dword, so the
+// product takes k in that order, and the activations are laid out to match: the 16 codes of
+// lane (c, q) of tile 2 t + op are k = 128 t + 32 (2 op) + 8 q .. + 7 followed by
+// k = 128 t + 32 (2 op + 1) + 8 q .. + 7 (a permutation of the 8-byte pieces inside each 128-k
+// block; the contraction does not care about the order of k as long as both operands agree).
 #include "qfc_internal.h"
 
 namespace qfc {
@@ -26,11 +33,12 @@ typedef _Float16 h8 __attribute__((ext_vector_type(8)));
 // per workgroup write whole 128-byte lines.
 // `gate` (or null): the row that is quantized is fp16(act(gate) * x), the input of a layer whose
 // two input branches are merged into it (operator fusion, section 3.6 of the paper).
-template <bool kTiled, int ROWS, bool GLU>
+template <int TILED, int ROWS, bool GLU>
 __global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__restrict__ x,
                                                                const uint4 *__restrict__ gate, int act, int M,
                                                                int K, uint4 *__restrict__ xq,
                                                                float *__restrict__ sx, int Kp) {
+    constexpr bool kTiled = TILED != 0;
     constexpr int T = 16 / ROWS;           // tiles per wavefront instruction
     constexpr int NW = 2 * ROWS;           // wavefronts; NW * T = 32 tiles per step
     constexpr int KEEP = 7;
@@ -103,7 +111,13 @@ __global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__re
             v[8 + e] = h1[e];
         }
         const uint4 out = make_uint4(quant4(v, inv), quant4(v + 4, inv), quant4(v + 8, inv), quant4(v + 12, inv));
-        if (kTiled)
+        if (TILED == 2) {
+            // source octets 2 q and 2 q + 1 of tile kt = octets (q & 1) * 2 and (q & 1) * 2 + 1 of run
+            // g = 2 (kt & 1) + (q >> 1): 8-byte half q >> 1 of vectors 2 (q & 1) and 2 (q & 1) + 1
+            uint2 *dst = reinterpret_cast<uint2 *>(xq + ((size_t)(m >> 4) * (Kp / 64) + kt) * 64 + (m & 15)) + (q >> 1);
+            dst[(2 * (q & 1)) * 16 * 2] = make_uint2(out.x, out.y);
+            dst[(2 * (q & 1) + 1) * 16 * 2] = make_uint2(out.z, out.w);
+        } else if (kTiled)
             xq[((size_t)(m >> 4) * (Kp / 64) + kt) * 64 + q * 16 + (m & 15)] = out;
         else if (real && kt * 64 + q * 16 < K)
             xq[(size_t)m * (K / 16) + kt * 4 + q] = out;
@@ -118,6 +132,8 @@ __global__ __launch_bounds__(128 * ROWS) void act_quant_kernel(const uint4 *__re
     }
 }
 
+// PERM: the k order of the product with 4-bit weights (see the head of this file).
+template <bool PERM>
 __global__ __launch_bounds__(256) void retile_xq_kernel(const uint4 *__restrict__ xq, int M, int K,
                                                         uint4 *__restrict__ tiled, int Mp, int Kp) {
     const size_t total = (size_t)Mp * (Kp / 16);
@@ -127,9 +143,21 @@ __global__ __launch_bounds__(256) void retile_xq_kernel(const uint4 *__restrict_
     const size_t tile = v / 64;
     const int kt = (int)(tile % (Kp / 64));
     const int m = (int)(tile / (Kp / 64)) * 16 + (lane & 15);
-    const int c = kt * 4 + (lane >> 4);
     uint4 out = make_uint4(0, 0, 0, 0);
-    if (m < M && c * 16 < K) out = xq[(size_t)m * (K / 16) + c];
+    if (PERM) {
+        const int q = lane >> 4;
+        const uint2 *src = reinterpret_cast<const uint2 *>(xq);
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+            const int k = (kt >> 1) * 128 + 32 * (2 * (kt & 1) + j) + 8 * q;
+            uint2 p = make_uint2(0, 0);
+            if (m < M && k < K) p = src[((size_t)m * K + k) / 8];
+            if (j == 0) { out.x = p.x; out.y = p.y; } else { out.z = p.x; out.w = p.y; }
+        }
+    } else {
+        const int c = kt * 4 + (lane >> 4);
+        if (m < M && c * 16 < K) out = xq[(size_t)m * (K / 16) + c];
+    }
     tiled[v] = out;
 }
 
@@ -141,21 +169,27 @@ void launch_rows(const void *x, const void *gate, int act, int M, int K, int8_t 
     const uint4 *gv = static_cast<const uint4 *>(gate);
     uint4 *qv = reinterpret_cast<uint4 *>(xq);
     const dim3 grid((unsigned)(tiled ? Mp / ROWS : (M + ROWS - 1) / ROWS)), block(128 * ROWS);
-    if (tiled) {
+    if (tiled == 2) {
         if (gate)
-            act_quant_kernel<true, ROWS, true><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
+            act_quant_kernel<2, ROWS, true><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
         else
-            act_quant_kernel<true, ROWS, false><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
+            act_quant_kernel<2, ROWS, false><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
+    } else if (tiled) {
+        if (gate)
+            act_quant_kernel<1, ROWS, true><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
+        else
+            act_quant_kernel<1, ROWS, false><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, Kp);
     } else {
         if (gate)
-            act_quant_kernel<false, ROWS, true><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, K);
+            act_quant_kernel<0, ROWS, true><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, K);
         else
-            act_quant_kernel<false, ROWS, false><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, K);
+            act_quant_kernel<0, ROWS, false><<<grid, block, 0, st>>>(xv, gv, act, M, K, qv, sx, K);
     }
 }
 
 }  // namespace
 
+// tiled: 0 row-major, 1 tiled, 2 tiled in the k order of the product with 4-bit weights (Kp a multiple of 128).
 // Mp (tiled output) must be a multiple of 16.  The most rows per workgroup that still give two
 // workgroups per compute unit, else two.
 hipError_t launch_act_quant(const void *x, const void *gate, int act, int M, int K, int8_t *xq, float *sx,
@@ -173,11 +207,14 @@ hipError_t launch_act_quant(const void *x, const void *gate, int act, int M, int
     return hipGetLastError();
 }
 
-hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp,
+hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp, bool int4_order,
                             hipStream_t st) {
     const size_t total = (size_t)Mp * (Kp / 16);
-    retile_xq_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(
-        reinterpret_cast<const uint4 *>(xq), M, K, reinterpret_cast<uint4 *>(tiled), Mp, Kp);
+    const unsigned grid = (unsigned)((total + 255) / 256);
+    if (int4_order)
+        retile_xq_kernel<true><<<grid, 256, 0, st>>>(reinterpret_cast<const uint4 *>(xq), M, K, reinterpret_cast<uint4 *>(tiled), Mp, Kp);
+    else
+        retile_xq_kernel<false><<<grid, 256, 0, st>>>(reinterpret_cast<const uint4 *>(xq), M, K, reinterpret_cast<uint4 *>(tiled), Mp, Kp);
     return hipGetLastError();
 }
 

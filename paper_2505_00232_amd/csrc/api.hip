@@ -40,7 +40,6 @@ qfc_status_t check_desc(const qfc_desc_t *d, int *fmt) {
         if (d->compute_mode != QFC_COMPUTE_FP16_DEQUANT) return QFC_ERR_UNSUPPORTED;
     } else if (d->wbits == 4 && d->group_size == 0 && d->scale_dtype == QFC_SCALE_F32) {
         *fmt = kW4C;
-        if (d->compute_mode == QFC_COMPUTE_INT8_ACT) return QFC_ERR_UNSUPPORTED;
     } else {
         return QFC_ERR_UNSUPPORTED;
     }
@@ -59,8 +58,15 @@ size_t int8_region(const Geometry &g, int M) {
     return Mp * (size_t)g.Kp + Mp * sizeof(float);
 }
 
+// Formats whose M > 8 path multiplies int8 activations: 8-bit weights unless the handle asks for the
+// fp16 path, 4-bit per-channel weights when it asks for int8 activations.
+bool int8_prefill(qfc_handle_t h) {
+    if (h->geo.fmt == kW8C) return h->desc.compute_mode != QFC_COMPUTE_FP16_DEQUANT;
+    return h->geo.fmt == kW4C && h->desc.compute_mode == QFC_COMPUTE_INT8_ACT;
+}
+
 size_t workspace_need(qfc_handle_t h, int M) {
-    return h->geo.fmt == kW8C ? int8_region(h->geo, M) : 256;
+    return h->geo.fmt == kW8C || int8_prefill(h) ? int8_region(h->geo, M) : 256;
 }
 
 qfc_status_t hip_status(hipError_t e) { return e == hipSuccess ? QFC_OK : QFC_ERR_HIP; }
@@ -94,14 +100,14 @@ qfc_status_t static_scratch(void **out) {
 qfc_status_t stage_xq(qfc_handle_t h, const int8_t *xq, int M, int8_t **tiled, float **sx_ws,
                       hipStream_t st) {
     if (!valid(h) || !xq || M < 1) return QFC_ERR_INVALID_ARG;
-    if (h->geo.fmt != kW8C) return QFC_ERR_UNSUPPORTED;
+    if (h->geo.fmt != kW8C && !int8_prefill(h)) return QFC_ERR_UNSUPPORTED;
     if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
     if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     const int Mp = prefill_rows(M);
     char *body = static_cast<char *>(h->workspace);
     *tiled = reinterpret_cast<int8_t *>(body);
     *sx_ws = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
-    return hip_status(launch_retile_xq(xq, M, h->geo.K, *tiled, Mp, h->geo.Kp, st));
+    return hip_status(launch_retile_xq(xq, M, h->geo.K, *tiled, Mp, h->geo.Kp, h->geo.fmt == kW4C, st));
 }
 
 }  // namespace
@@ -198,7 +204,7 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
         }
         return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, f, h->num_cus, st));
     }
-    if (h->desc.compute_mode == QFC_COMPUTE_FP16_DEQUANT || h->geo.fmt == kW4C) {
+    if (!int8_prefill(h)) {
         if (h->geo.fmt != kW4G32 && h->geo.fmt != kW4C) return QFC_ERR_UNSUPPORTED;
         // activations go from memory to LDS without passing registers; a tile holds one branch
         if (f.gate || f.gated_output) return QFC_ERR_UNSUPPORTED;
@@ -211,7 +217,7 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
     char *body = static_cast<char *>(scratch);
     int8_t *tiled = reinterpret_cast<int8_t *>(body);
     float *sx = reinterpret_cast<float *>(body + (size_t)Mp * h->geo.Kp);
-    if (launch_act_quant(x_f16, f.gate, f.activation, M, h->geo.K, tiled, sx, 1, Mp, h->geo.Kp, h->num_cus, st) !=
+    if (launch_act_quant(x_f16, f.gate, f.activation, M, h->geo.K, tiled, sx, h->geo.fmt == kW4C ? 2 : 1, Mp, h->geo.Kp, h->num_cus, st) !=
         hipSuccess)
         return QFC_ERR_HIP;
     return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, f.residual, h->num_cus, st));
@@ -242,8 +248,7 @@ qfc_status_t qfc_forward_static(qfc_handle_t h, const void *x_f16, int32_t M, vo
     if (!valid(h) || M < 1) return QFC_ERR_INVALID_ARG;
     // Which calls need scratch at all is the dispatcher's business (M > 8 in the int8 mode); the limit
     // is checked for those only, before anything is enqueued.
-    const bool int8_prefill = M > kMaxDecodeM && h->geo.fmt == kW8C && h->desc.compute_mode != QFC_COMPUTE_FP16_DEQUANT;
-    if (int8_prefill && workspace_need(h, M) > kStaticScratchBytes) return QFC_ERR_SCRATCH_LIMIT;
+    if (M > kMaxDecodeM && int8_prefill(h) && workspace_need(h, M) > kStaticScratchBytes) return QFC_ERR_SCRATCH_LIMIT;
     void *p = nullptr;
     const qfc_status_t s = static_scratch(&p);
     if (s != QFC_OK) return s;

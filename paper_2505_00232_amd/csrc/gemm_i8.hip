@@ -40,6 +40,10 @@ struct GemmI8Args {
     const _Float16 *res;  // [M, N] residual added before the rounding, or null
     void *out;
     int M, N, Kp, n_tiles, m_tiles;
+    // 4-bit weights enter the MFMA as 16 q (the code's nibble in the top half of a byte): the sums are
+    // 16 times the definition's, exactly; channel scales are multiplied by 1/16, raw sums shifted by 4
+    float sw_mul = 1.0f;
+    int acc_shift = 0;
 };
 
 // Epilogue shared by the product kernels.
@@ -67,7 +71,11 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
         for (int i = 0; i < TN; ++i)
 #pragma unroll
             for (int q = 0; q < 4; ++q)
-                scw[i][q] = *reinterpret_cast<const float4 *>(a.sw + n0 + i * 32 + 8 * q + 4 * (lane >> 5));
+            {
+                float4 v = *reinterpret_cast<const float4 *>(a.sw + n0 + i * 32 + 8 * q + 4 * (lane >> 5));
+                v.x *= a.sw_mul, v.y *= a.sw_mul, v.z *= a.sw_mul, v.w *= a.sw_mul;  // (1 or 1/16: exact)
+                scw[i][q] = v;
+            }
 #pragma unroll
         for (int j = 0; j < TM; ++j) {
             const int m = m_base + j * 32 + (lane & 31);
@@ -136,7 +144,7 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
                 if (OUT_MODE == 0) {
                     _Float16 *y = static_cast<_Float16 *>(a.out) + (size_t)m * a.N + n;
                     const float4 s = *reinterpret_cast<const float4 *>(a.sw + n);
-                    const float sv[4] = {s.x, s.y, s.z, s.w};
+                    const float sv[4] = {s.x * a.sw_mul, s.y * a.sw_mul, s.z * a.sw_mul, s.w * a.sw_mul};
                     _Float16 h[4];
 #pragma unroll
                     for (int e = 0; e < 4; ++e) {
@@ -154,13 +162,14 @@ __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM
                     }
                 } else {
                     int32_t *o = static_cast<int32_t *>(a.out) + (size_t)m * a.N + n;
+                    const int sh = a.acc_shift;  // (arithmetic shift of an exact multiple: exact)
                     if (vec_ok) {
-                        *reinterpret_cast<int4 *>(o) = make_int4(acc[i][j][4 * q], acc[i][j][4 * q + 1],
-                                                                 acc[i][j][4 * q + 2], acc[i][j][4 * q + 3]);
+                        *reinterpret_cast<int4 *>(o) = make_int4(acc[i][j][4 * q] >> sh, acc[i][j][4 * q + 1] >> sh,
+                                                                 acc[i][j][4 * q + 2] >> sh, acc[i][j][4 * q + 3] >> sh);
                     } else {
 #pragma unroll
                         for (int e = 0; e < 4; ++e)
-                            if (n + e < a.N) o[e] = acc[i][j][4 * q + e];
+                            if (n + e < a.N) o[e] = acc[i][j][4 * q + e] >> sh;
                     }
                 }
             }
@@ -282,6 +291,123 @@ __global__ __launch_bounds__(256, (BN * BM > 128 * 256) ? 1 : 2) void gemm_i8_ke
         }
     }
 
+    epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wn * WN, mt * BM + wm * WM, wave, lane);
+}
+
+// int8 activations x 4-bit per-channel weights (the "8/4/4" scheme of section 4.2 in the prefill
+// stage of section 3.7): the same pipeline as gemm_i8_kernel with stages of 128 k.  A stage holds
+// one packed KiB tile per 16 weight rows (16 rows x 128 k of 4-bit codes, copied verbatim) and
+// two activation tiles per 16 token rows, the latter written by the quantizer in the k order of
+// the packed codes.  A lane reads the two dwords of its packed vector that belong to a k step and
+// expands them in registers: code u = q + 8 in a nibble becomes the byte (u ^ 8) << 4, which the
+// MFMA reads as the signed value 16 q (5 vector instructions per 8 codes), so the int32 sums are
+// exactly 16 times the definition's and the epilogue divides them out (scale * 1/16, or a shift).
+template <int BN, int BM, int NS, int OUT_MODE>
+__global__ __launch_bounds__(256, 2) void gemm_i8_w4_kernel(GemmI8Args a) {
+    constexpr int WN = BN / 2, WM = BM / 2;
+    constexpr int TN = WN / 32, TM = WM / 32;
+    constexpr int W_TILES = BN / 16, X_TILES = BM / 16 * 2;  // KiB tiles per stage
+    constexpr int STAGE_VECS = (W_TILES + X_TILES) * 64;
+    static_assert((W_TILES + X_TILES) % 4 == 0, "tiles of a stage are dealt to four wavefronts");
+    extern __shared__ uint4 lds[];  // NS stages: [stage][W tiles | X tiles][64]
+
+    const int tid = threadIdx.x;
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wn = wave & 1, wm = wave >> 1;
+    const int total = a.n_tiles * a.m_tiles;
+    int logical = blockIdx.x;
+    if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
+    const int nt = logical / a.m_tiles;
+    const int mt = logical % a.m_tiles;
+    const int stages = a.Kp / 128;
+
+    constexpr int NLOAD = (W_TILES + X_TILES) / 4;
+    const uint4 *src0[NLOAD];
+    int adv[NLOAD];  // vectors a tile's source advances per stage
+#pragma unroll
+    for (int i = 0; i < NLOAD; ++i) {
+        const int t = wave + 4 * i;
+        if (t < W_TILES) {
+            src0[i] = a.w + ((size_t)(nt * (BN / 16) + t) * stages) * 64 + lane;
+            adv[i] = 64;
+        } else {
+            const int tx = t - W_TILES;
+            src0[i] = a.x + ((size_t)(mt * (BM / 16) + tx / 2) * (2 * stages) + tx % 2) * 64 + lane;
+            adv[i] = 128;
+        }
+    }
+    auto issue_stage = [&](int kt, int buf) {
+        uint4 *dst = lds + buf * STAGE_VECS + wave * 64;
+#pragma unroll
+        for (int i = 0; i < NLOAD; ++i)
+            __builtin_amdgcn_global_load_lds((gptr_t)(src0[i] + (size_t)kt * adv[i]), (lptr_t)(dst + i * 256), 16, 0, 0);
+    };
+
+    v16i acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+    constexpr int KS = 4;  // k steps of 32 per stage: step ks = (op, half step) = (ks >> 1, ks & 1)
+    auto load_frags = [&](v4i(&fa)[TN], v4i(&fb)[TM], int buf, int ks) {
+        const char *lw = reinterpret_cast<const char *>(lds + buf * STAGE_VECS);
+        const uint4 *lx = lds + buf * STAGE_VECS + W_TILES * 64;
+        const int q = 2 * (ks & 1) + (lane >> 5);  // octet of the runs 2 op, 2 op + 1 this lane takes
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+            const int row = wn * WN + i * 32 + (lane & 31);
+            const uint2 p = *reinterpret_cast<const uint2 *>(lw + ((row >> 4) * 64 + q * 16 + (row & 15)) * 16 + (ks >> 1) * 8);
+            fa[i][0] = (int)(((p.x << 4) & 0xF0F0F0F0u) ^ 0x80808080u);  // codes 0..3 of the first run's octet
+            fa[i][1] = (int)((p.x & 0xF0F0F0F0u) ^ 0x80808080u);         // codes 4..7
+            fa[i][2] = (int)(((p.y << 4) & 0xF0F0F0F0u) ^ 0x80808080u);  // the second run's octet
+            fa[i][3] = (int)((p.y & 0xF0F0F0F0u) ^ 0x80808080u);
+        }
+        const int kc = 2 * ks + (lane >> 5);  // 16-code chunk inside the stage: tile kc >> 2, quarter kc & 3
+        const int koff = (kc >> 2) * 64 + (kc & 3) * 16;
+#pragma unroll
+        for (int j = 0; j < TM; ++j) {
+            const int row = wm * WM + j * 32 + (lane & 31);
+            fb[j] = __builtin_bit_cast(v4i, lx[(row >> 4) * 128 + koff + (row & 15)]);
+        }
+    };
+    auto stage_ready = [&](int kt) {  // stage kt has landed for the whole workgroup
+        if (kt + NS - 2 < stages)
+            wait_vmcnt<(NS - 2) * NLOAD>();
+        else
+            wait_vmcnt<0>();
+        asm volatile("s_barrier" ::: "memory");
+    };
+    static_assert((NS - 1) * NLOAD <= 63, "outstanding copies must fit the 6-bit counter");
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p)
+        if (p < stages) issue_stage(p, p);
+    v4i fa[2][TN], fb[2][TM];
+    stage_ready(0);
+    if (NS - 1 < stages) issue_stage(NS - 1, NS - 1);
+    load_frags(fa[0], fb[0], 0, 0);
+    for (int kt = 0; kt < stages; ++kt) {
+#pragma unroll
+        for (int ks = 0; ks < KS; ++ks) {
+            if (ks < KS - 1) {
+                load_frags(fa[(ks + 1) & 1], fb[(ks + 1) & 1], kt % NS, ks + 1);
+            } else if (kt + 1 < stages) {
+                stage_ready(kt + 1);
+                if (kt + NS < stages) issue_stage(kt + NS, (kt + NS) % NS);
+                load_frags(fa[(ks + 1) & 1], fb[(ks + 1) & 1], (kt + 1) % NS, 0);
+            }
+            __builtin_amdgcn_sched_barrier(0);  // keep the reads ahead of this step's MFMAs
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int j = 0; j < TM; ++j)
+                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks & 1][i], fb[ks & 1][j], acc[i][j], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
     epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wn * WN, mt * BM + wm * WM, wave, lane);
 }
 
@@ -488,6 +614,18 @@ hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
     return hipGetLastError();
 }
 
+template <int BN, int BM, int NS, int OUT_MODE>
+hipError_t launch_w4(GemmI8Args a, hipStream_t st) {
+    constexpr size_t lds_bytes = (size_t)NS * (BN / 16 + BM / 8) * 1024;
+    static_assert(lds_bytes <= 80 * 1024, "two workgroups per compute unit");
+    static_assert(lds_bytes >= 4 * 32 * (BN / 2 + 8) * 2, "the store phase stages its blocks in the same LDS");
+    if (const hipError_t e = allow_dynamic_lds<gemm_i8_w4_kernel<BN, BM, NS, OUT_MODE>>(lds_bytes); e != hipSuccess) return e;
+    a.n_tiles = (a.N + BN - 1) / BN;
+    a.m_tiles = (a.M + BM - 1) / BM;
+    gemm_i8_w4_kernel<BN, BM, NS, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
+    return hipGetLastError();
+}
+
 template <int OUT_MODE>
 hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
     // Tile shapes measured on MI355X.  The direct-weights kernel with the 256 x 128 tile is used
@@ -535,6 +673,11 @@ hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *x
     a.N = g.N;
     a.Kp = g.Kp;
     a.n_tiles = a.m_tiles = 0;
+    if (g.fmt == kW4C) {
+        a.sw_mul = 0.0625f;
+        a.acc_shift = 4;
+        return out_mode == 0 ? launch_w4<128, 128, 3, 0>(a, st) : launch_w4<128, 128, 3, 1>(a, st);
+    }
     return out_mode == 0 ? launch_mode<0>(a, num_cus, st) : launch_mode<1>(a, num_cus, st);
 }
 

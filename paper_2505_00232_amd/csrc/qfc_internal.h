@@ -313,7 +313,7 @@ hipError_t launch_rope_qkv(const void *qkv, int B, int S, int h_q, int h_kv, int
                            void *q_out, void *kc, void *vc, hipStream_t st);
 hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G, int S, int g, int d, int C,
                             int n_ctx, void *workspace, void *out, int num_cus, hipStream_t st);
-hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp,
+hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int Mp, int Kp, bool int4_order,
                             hipStream_t st);
 // out_mode 0: binary16 y with scales; 1: raw int32 accumulators.
 // `residual` (binary16 [M, N] or null) is added before the final rounding (out_mode 0 only).

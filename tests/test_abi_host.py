@@ -64,8 +64,9 @@ def test_packed_size_and_descriptor_checks(L):
     assert binding.qfc_packed_size(binding.Desc(8, 64, 4, 0, 0, 2)) > 0  # int8-activation decode, per-channel int4
     for d in bad:
         assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 1
+    assert binding.qfc_packed_size(binding.Desc(8, 64, 4, 0, 0, 1)) > 0  # int8-activation prefill, per-channel int4 ("8/4/4")
     unsupported = [binding.Desc(8, 64, 8, 32, 0, 1), binding.Desc(8, 64, 4, 32, 1, 1),
-                   binding.Desc(8, 64, 4, 0, 0, 1), binding.Desc(8, 64, 4, 0, 1, 0), binding.Desc(8, 64, 8, 0, 1, 1),
+                   binding.Desc(8, 64, 4, 0, 1, 0), binding.Desc(8, 64, 8, 0, 1, 1),
                    binding.Desc(8, 64, 4, 32, 1, 2)]
     for d in unsupported:
         assert L.qfc_packed_size(ctypes.byref(d), ctypes.byref(out)) == 2

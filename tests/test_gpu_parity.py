@@ -259,6 +259,67 @@ def test_int8_prefill_whole_output_against_oracle(M, N, K):
     layer.close()
 
 
+# The paper's own "8/4/4" scheme in the prefill stage: int8 activations x int4 per-channel weights
+@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (256, 1000, 2304), (130, 64, 14336),
+                                   (513, 264, 128), (300, 4096, 1152)])
+def test_int8_prefill_int4_weights_matches_oracle(M, N, K):
+    print(f"int8 x int4 prefill M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, "w4c")
+    wq, sw = synth.weights(4500, M, N, fc)
+    wq.flat[0], wq.flat[1] = -8, 7
+    x = synth.activations(4500, M, N, M, K)
+    xq_ref, sx_ref, acc_ref, y_ref = oracle.fc_int8_act(x, wq, sw)
+    layer = _layer(wq, sw, "w4c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    xq_d = torch.from_numpy(xq_ref).to(DEV)
+    acc = torch.empty((M, N), dtype=torch.int32, device=DEV)
+    for rep in range(2):
+        acc.fill_(-1)
+        binding.qfc_forward_acc_i32(layer.handle, xq_d, acc)
+        torch.cuda.synchronize()
+        assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), rep
+    y = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    binding.qfc_forward_q8(layer.handle, xq_d, torch.from_numpy(sx_ref).to(DEV), y)
+    torch.cuda.synchronize()
+    assert _E(y.cpu().numpy(), y_ref) <= TOL
+    y2 = _forward(layer, x)  # quantization kernel (codes in the order of the packed weights) + product + epilogue
+    assert _E(y2, y_ref) <= TOL
+    # the two routes to the activations' codes give the same bits
+    assert np.array_equal(y2.view(np.uint16), y.cpu().numpy().view(np.uint16))
+    # decode through the same handle keeps binary16 activations
+    y1 = _forward(layer, x[:3])
+    assert _E(y1, oracle.fc_weight_only(x[:3], wq, sw, 0)) <= TOL
+    # fused input gate and residual, as for 8-bit weights
+    gate = synth.activations(4501, M, N, M, K)
+    res = synth.activations(4502, M, N, M, N)
+    yf = _fused(layer, x, gate, binding.QFC_ACT_SILU, res)
+    assert _E(yf, _fused_ref(x, wq, sw, "w4c", gate, oracle.SILU, res, int8_act=True)) <= TOL
+    layer.close()
+
+
+def test_int8_prefill_int4_weights_llama_ffn_shapes_sampled():
+    """gate+up and down projections of the Llama-3.1-8B layer at M = 1024 with int4 per-channel weights
+    (the "8/4/4" FFN): accumulators of sampled rows and channels bit for bit, outputs within the tolerance."""
+    rng = np.random.default_rng(45)
+    M = 1024
+    for i, fc in enumerate(synth.LLAMA_FCS_W4C[2:], start=2):
+        print(f"int8 x int4 prefill {fc.name} {fc.K}->{fc.N}", flush=True)
+        wq, sw = synth.weights(1104, 0, i, fc)
+        x = synth.activations(1104, 0, i, M, fc.K)
+        layer = _layer(wq, sw, "w4c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+        xq_ref, sx_ref = oracle.quantize_activations(x)
+        acc = torch.empty((M, fc.N), dtype=torch.int32, device=DEV)
+        binding.qfc_forward_acc_i32(layer.handle, torch.from_numpy(xq_ref).to(DEV), acc)
+        y = _forward(layer, x)
+        rows = np.sort(rng.choice(M, size=48, replace=False))
+        cols = np.sort(rng.choice(fc.N, size=384, replace=False))
+        rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, fc.N - 1
+        acc_ref = oracle.int_contract(xq_ref[rows], wq[cols])
+        assert np.array_equal(acc.cpu().numpy()[np.ix_(rows, cols)].astype(np.int64), acc_ref)
+        y_ref = oracle.rescale(acc_ref, sx_ref[rows], sw[cols])
+        assert _E(y[np.ix_(rows, cols)], y_ref) <= TOL
+        layer.close()
+
+
 @pytest.mark.parametrize("variant", [1, 4, 5, 6, 10, 11, 12, 13, 14, 15])
 def test_int8_prefill_other_tile_shapes_bit_exact(variant):
     """The tile shapes the dispatcher picks for larger problems (and the selectable ones),
@@ -651,7 +712,10 @@ def _fused(layer, x, gate=None, act=binding.QFC_ACT_SILU, residual=None, alias=F
 
 
 def _fused_ref(x, wq, s, fmt, gate, act, residual, int8_act=False):
-    x_in = oracle.gated_input(gate, x, act) if gate is not None else x
+    # (int8 activations: the gated input goes on to decide the row maximum and every 8-bit code, so
+    # the reference takes it in binary32 like the quantizer; otherwise in fp64)
+    gated = oracle.gated_input_f32 if int8_act else oracle.gated_input
+    x_in = gated(gate, x, act) if gate is not None else x
     ref = oracle.fc_int8_act(x_in, wq, s)[3] if int8_act else oracle.fc_weight_only(x_in, wq, s, _group(fmt))
     return oracle.add_residual(ref, residual) if residual is not None else ref
 

@@ -321,6 +321,30 @@ def test_error_metric_golden_per_row_and_short_rows():
 
 
 # ---------------------------------------------------------------- fused element-wise operators
+def test_gated_input_binary32_steps_against_fp64():
+    """The gated input evaluated step by step in binary32 (the precision of the quantizer that
+    consumes it) against the fp64 definition: identical binary16 values except where the real
+    value sits within a few binary32 units of a rounding boundary, and never more than one unit in
+    the last place apart; exact cases agree exactly."""
+    rng = np.random.default_rng(7)
+    g = rng.standard_normal((64, 4096)).astype(np.float16)
+    u = rng.standard_normal((64, 4096)).astype(np.float16)
+    for act in (oracle.SILU, oracle.GELU_TANH):
+        a = oracle.gated_input_f32(g, u, act)
+        b = oracle.gated_input(g, u, act)
+        same = a.view(np.uint16) == b.view(np.uint16)
+        assert same.mean() > 0.998
+        # where they differ: neighbouring binary16 values (bit patterns one apart, same sign)
+        d = np.abs(a.view(np.int16).astype(np.int32) - b.view(np.int16).astype(np.int32))
+        assert d.max() <= 1
+    z = np.zeros((1, 8), dtype=np.float16)
+    assert np.array_equal(oracle.gated_input_f32(z, u[:1, :8], oracle.SILU), z)           # act(0) = 0
+    big = np.full((1, 8), 40.0, dtype=np.float16)                                          # act(g) = g for large g
+    two = np.full((1, 8), 2.0, dtype=np.float16)
+    assert np.array_equal(oracle.gated_input_f32(big, two, oracle.SILU), np.full((1, 8), 80.0, dtype=np.float16))
+    assert np.array_equal(oracle.gated_input_f32(big, two, oracle.GELU_TANH), np.full((1, 8), 80.0, dtype=np.float16))
+
+
 def test_gate_activations_hand_values_and_identities():
     c = _golden()["gated_activations"]
     g = np.array([float(v) for v in c["g"]])
