@@ -78,7 +78,17 @@ typedef struct {
     int32_t group_size;
     int32_t scale_dtype;
     int32_t compute_mode;
+    int32_t flags;        /* 0, or QFC_PACK_GATED_PAIRS */
 } qfc_desc_t;
+
+/* flags.  QFC_PACK_GATED_PAIRS: the layer produces the two branches of a gated feed-forward
+ * block (logical rows [0, N/2) = gate, [N/2, N) = the other branch; N a multiple of 32) and is only
+ * ever used with the merged element-wise operators of qfc_fusion_t.gated_output (operator fusion,
+ * section 3.6 and its figure).  Its physical layout interleaves the row tiles of the two branches,
+ * so that every kernel, prefill included, holds both branches of a channel in one place and
+ * multiplies them in its epilogue.  The logical interface (wq_logical, scales, unpack) is
+ * unchanged.  Calls without gated_output on such a handle return QFC_ERR_UNSUPPORTED. */
+enum { QFC_PACK_GATED_PAIRS = 1 };
 
 /* Bytes of the physical (packed) form of a layer, padding included.
  * `desc` and `bytes` are host pointers. */
@@ -159,7 +169,9 @@ qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, in
  * handles (M <= 8; all parts), the int8 prefill path (gate and residual: the gate is
  * applied by the activation quantization kernel) and the fp16 prefill path
  * (residual only: its activations go from memory to LDS without passing through
- * registers); anything else returns QFC_ERR_UNSUPPORTED. */
+ * registers).  gated_output at M > 8 needs a handle packed with QFC_PACK_GATED_PAIRS
+ * (both prefill paths; the fp16 path also needs K to be a multiple of 128); at M <= 8
+ * it works with either packing.  Anything else returns QFC_ERR_UNSUPPORTED. */
 #define QFC_ACT_SILU 0
 #define QFC_ACT_GELU_TANH 1
 typedef struct qfc_fusion {

@@ -19,6 +19,7 @@ QFC_STATIC_SCRATCH_BYTES = 16 << 20
 QFC_SCALE_F32, QFC_SCALE_F16 = 0, 1
 QFC_COMPUTE_FP16_DEQUANT, QFC_COMPUTE_INT8_ACT, QFC_COMPUTE_INT8_ACT_DECODE = 0, 1, 2
 QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
+QFC_PACK_GATED_PAIRS = 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
            "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_forward_static", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
@@ -28,7 +29,7 @@ EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_wor
 class Desc(ctypes.Structure):
     _fields_ = [("N", ctypes.c_int32), ("K", ctypes.c_int32), ("wbits", ctypes.c_int32),
                 ("group_size", ctypes.c_int32), ("scale_dtype", ctypes.c_int32),
-                ("compute_mode", ctypes.c_int32)]
+                ("compute_mode", ctypes.c_int32), ("flags", ctypes.c_int32)]
 
 
 class Fusion(ctypes.Structure):
@@ -138,16 +139,17 @@ def _stream():
     return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
 
 
-def make_desc(N: int, K: int, fmt: str, compute_mode: int | None = None) -> Desc:
+def make_desc(N: int, K: int, fmt: str, compute_mode: int | None = None, gated_pairs: bool = False) -> Desc:
+    flags = QFC_PACK_GATED_PAIRS if gated_pairs else 0
     if fmt == "w8c":
         mode = QFC_COMPUTE_INT8_ACT if compute_mode is None else compute_mode
-        return Desc(N, K, 8, 0, QFC_SCALE_F32, mode)
+        return Desc(N, K, 8, 0, QFC_SCALE_F32, mode, flags)
     if fmt == "w4g32":
         mode = QFC_COMPUTE_FP16_DEQUANT if compute_mode is None else compute_mode
-        return Desc(N, K, 4, 32, QFC_SCALE_F16, mode)
+        return Desc(N, K, 4, 32, QFC_SCALE_F16, mode, flags)
     if fmt == "w4c":
         mode = QFC_COMPUTE_FP16_DEQUANT if compute_mode is None else compute_mode
-        return Desc(N, K, 4, 0, QFC_SCALE_F32, mode)
+        return Desc(N, K, 4, 0, QFC_SCALE_F32, mode, flags)
     raise ValueError(fmt)
 
 
@@ -340,12 +342,12 @@ class QuantLinear:
     """Convenience owner of one packed layer: device buffers + handle."""
 
     def __init__(self, wq, scales, fmt: str, compute_mode: int | None = None, device="cuda", max_m: int = 8,
-                 workspace: torch.Tensor | None = None):
+                 workspace: torch.Tensor | None = None, gated_pairs: bool = False):
         wq_d = torch.as_tensor(wq).to(device).contiguous()
         s_d = torch.as_tensor(scales).to(device).contiguous()
         N, K = wq_d.shape
         self.N, self.K, self.fmt = N, K, fmt
-        self.desc = make_desc(N, K, fmt, compute_mode)
+        self.desc = make_desc(N, K, fmt, compute_mode, gated_pairs)
         self.packed = torch.empty(qfc_packed_size(self.desc), dtype=torch.uint8, device=device)
         self.handle = qfc_pack_weights(self.desc, wq_d, s_d, self.packed)
         need = max(qfc_workspace_size(self.handle, m) for m in sorted({1, min(max_m, 8), max_m}))

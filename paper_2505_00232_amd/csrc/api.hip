@@ -33,6 +33,10 @@ qfc_status_t check_desc(const qfc_desc_t *d, int *fmt) {
     if (d->compute_mode != QFC_COMPUTE_FP16_DEQUANT && d->compute_mode != QFC_COMPUTE_INT8_ACT &&
         d->compute_mode != QFC_COMPUTE_INT8_ACT_DECODE)
         return QFC_ERR_INVALID_ARG;
+    if (d->flags != 0 && d->flags != QFC_PACK_GATED_PAIRS) return QFC_ERR_INVALID_ARG;
+    if (d->flags == QFC_PACK_GATED_PAIRS && d->N % 32 != 0) return QFC_ERR_INVALID_ARG;
+    // (the decode design with in-kernel quantization has no merged gating)
+    if (d->flags == QFC_PACK_GATED_PAIRS && d->compute_mode == QFC_COMPUTE_INT8_ACT_DECODE) return QFC_ERR_UNSUPPORTED;
     if (d->wbits == 8 && d->group_size == 0 && d->scale_dtype == QFC_SCALE_F32) {
         *fmt = kW8C;
     } else if (d->wbits == 4 && d->group_size == 32 && d->scale_dtype == QFC_SCALE_F16) {
@@ -101,6 +105,7 @@ qfc_status_t stage_xq(qfc_handle_t h, const int8_t *xq, int M, int8_t **tiled, f
                       hipStream_t st) {
     if (!valid(h) || !xq || M < 1) return QFC_ERR_INVALID_ARG;
     if (h->geo.fmt != kW8C && !int8_prefill(h)) return QFC_ERR_UNSUPPORTED;
+    if (h->geo.pair_half) return QFC_ERR_UNSUPPORTED;  // a layer packed in pairs only computes the gated output
     if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
     if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     const int Mp = prefill_rows(M);
@@ -119,7 +124,7 @@ qfc_status_t qfc_packed_size(const qfc_desc_t *desc, size_t *bytes) {
     if (!bytes) return QFC_ERR_INVALID_ARG;
     const qfc_status_t s = check_desc(desc, &fmt);
     if (s != QFC_OK) return s;
-    *bytes = make_geometry(desc->N, desc->K, fmt).total_bytes;
+    *bytes = make_geometry(desc->N, desc->K, fmt, desc->flags == QFC_PACK_GATED_PAIRS).total_bytes;
     return QFC_OK;
 }
 
@@ -132,7 +137,7 @@ qfc_status_t qfc_pack_weights(const qfc_desc_t *desc, const int8_t *wq_logical, 
     if (s != QFC_OK) return s;
     if (!wq_logical || !scales || !packed) return QFC_ERR_INVALID_ARG;
     if (!aligned16(wq_logical) || !aligned16(scales) || !aligned16(packed)) return QFC_ERR_ALIGNMENT;
-    const Geometry g = make_geometry(desc->N, desc->K, fmt);
+    const Geometry g = make_geometry(desc->N, desc->K, fmt, desc->flags == QFC_PACK_GATED_PAIRS);
     if (packed_bytes < g.total_bytes) return QFC_ERR_BUFFER_TOO_SMALL;
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return QFC_ERR_HIP;
@@ -197,6 +202,8 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
     if (f.norm_gamma && (f.gate || !aligned16(f.norm_gamma) || !(f.norm_eps >= 0.0f))) return QFC_ERR_INVALID_ARG;
     if (f.norm_gamma && M > kMaxDecodeM) return QFC_ERR_UNSUPPORTED;
     const bool fused = f.gate || f.residual || f.gated_output || f.norm_gamma;
+    if (h->geo.pair_half && !f.gated_output) return QFC_ERR_UNSUPPORTED;  // packed in pairs: gated output only
+    const int gated_act = f.gated_output ? f.activation : -1;
     if (M <= kMaxDecodeM) {
         if (h->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE) {
             if (fused) return QFC_ERR_UNSUPPORTED;
@@ -206,11 +213,14 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
     }
     if (!int8_prefill(h)) {
         if (h->geo.fmt != kW4G32 && h->geo.fmt != kW4C) return QFC_ERR_UNSUPPORTED;
-        // activations go from memory to LDS without passing registers; a tile holds one branch
-        if (f.gate || f.gated_output) return QFC_ERR_UNSUPPORTED;
-        return hip_status(launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, f.residual, h->num_cus, st));
+        // activations go from memory to LDS without passing registers
+        if (f.gate) return QFC_ERR_UNSUPPORTED;
+        // a tile holds both branches only when the layer is packed in pairs
+        if (f.gated_output && !h->geo.pair_half) return QFC_ERR_UNSUPPORTED;
+        const hipError_t e = launch_gemm_f16(h->geo, h->packed, x_f16, M, y_f16, f.residual, gated_act, h->num_cus, st);
+        return e == hipErrorNotSupported ? QFC_ERR_UNSUPPORTED : hip_status(e);
     }
-    if (f.gated_output) return QFC_ERR_UNSUPPORTED;
+    if (f.gated_output && !h->geo.pair_half) return QFC_ERR_UNSUPPORTED;
     if (!scratch || scratch_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
     // int8 activations: quantize into the scratch region (tiled), multiply, rescale
     const int Mp = prefill_rows(M);
@@ -220,7 +230,7 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
     if (launch_act_quant(x_f16, f.gate, f.activation, M, h->geo.K, tiled, sx, h->geo.fmt == kW4C ? 2 : 1, Mp, h->geo.Kp, h->num_cus, st) !=
         hipSuccess)
         return QFC_ERR_HIP;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, f.residual, h->num_cus, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, Mp, y_f16, 0, f.residual, gated_act, h->num_cus, st));
 }
 
 qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f16, void *stream) {
@@ -345,6 +355,7 @@ qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, i
                             void *stream) {
     if (!sx || !y_f16) return QFC_ERR_INVALID_ARG;
     if (!aligned16(y_f16) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return QFC_ERR_ALIGNMENT;
+    if (valid(h) && h->geo.pair_half) return QFC_ERR_UNSUPPORTED;
     if (valid(h) && xq && M >= 1 && M <= kMaxDecodeM && (h->geo.fmt == kW8C || h->geo.fmt == kW4C)) {
         if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
         return hip_status(launch_gemv_q8(h->geo, h->packed, xq, sx, 1, M, y_f16, 0, h->num_cus,
@@ -355,12 +366,13 @@ qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, i
     hipStream_t st = static_cast<hipStream_t>(stream);
     const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
     if (s != QFC_OK) return s;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, prefill_rows(M), y_f16, 0, nullptr, h->num_cus, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, sx, M, prefill_rows(M), y_f16, 0, nullptr, -1, h->num_cus, st));
 }
 
 qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc, void *stream) {
     if (!acc) return QFC_ERR_INVALID_ARG;
     if (!aligned16(acc)) return QFC_ERR_ALIGNMENT;
+    if (valid(h) && h->geo.pair_half) return QFC_ERR_UNSUPPORTED;
     if (valid(h) && xq && M >= 1 && M <= kMaxDecodeM && (h->geo.fmt == kW8C || h->geo.fmt == kW4C)) {
         if (!aligned16(xq)) return QFC_ERR_ALIGNMENT;
         return hip_status(launch_gemv_q8(h->geo, h->packed, xq, nullptr, 1, M, acc, 1, h->num_cus,
@@ -371,13 +383,14 @@ qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, in
     hipStream_t st = static_cast<hipStream_t>(stream);
     const qfc_status_t s = stage_xq(h, xq, M, &tiled, &sx_ws, st);
     if (s != QFC_OK) return s;
-    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, nullptr, h->num_cus, st));
+    return hip_status(launch_gemm_i8(h->geo, h->packed, tiled, nullptr, M, prefill_rows(M), acc, 1, nullptr, -1, h->num_cus, st));
 }
 
 qfc_status_t qfc_embedding(qfc_handle_t h, const int32_t *ids, int32_t M, void *y_f16, void *stream) {
     if (!valid(h) || !ids || !y_f16 || M < 1) return QFC_ERR_INVALID_ARG;
     if (!aligned16(y_f16) || (reinterpret_cast<uintptr_t>(ids) & 3u)) return QFC_ERR_ALIGNMENT;
     if (M > 65535) return QFC_ERR_UNSUPPORTED;  // one grid row per token
+    if (h->geo.pair_half) return QFC_ERR_UNSUPPORTED;
     return hip_status(launch_embedding(h->geo, h->packed, ids, M, y_f16, static_cast<hipStream_t>(stream)));
 }
 

@@ -45,6 +45,7 @@ struct GemmF16Args {
     const _Float16 *res;  // [M, N] residual added before the rounding, or null
     const float *sw;  // W4C: fp32 scale per output channel [Np]
     int M, N, K, KT, rt_stride, n_tiles, m_tiles;
+    int gated_act = -1;  // QFC_ACT_*: the layer is packed in pairs and y [M, N/2] = fp16(act(gate) * other)
 };
 
 __device__ __forceinline__ h2 as_h2(uint32_t u) { return __builtin_bit_cast(h2, u); }
@@ -612,6 +613,45 @@ __global__ __launch_bounds__(512) void gemm_f16_w4_direct_kernel(GemmF16Args a) 
     // consecutive n.  The binary16 values go through a per-wavefront LDS block
     // (32 token rows x 64 channels) and leave as 16-byte stores along n.
     const int n0 = nt * DBN + ng * 64;
+    if (a.gated_act >= 0) {
+        // Layer packed in pairs (operator fusion, section 3.6 of the paper): physical rows 32 t .. + 15
+        // are gate rows and 32 t + 16 .. + 31 the other branch's rows of the same 16 channels, so the
+        // registers 4 qq + e (qq = 0, 1) and 4 (qq + 2) + e of a 32 x 32 tile are the two branches of one
+        // channel.  32 output channels per wavefront, rows of N / 2 values.
+        const GateCoeffs gc = gate_coeffs(a.gated_act);
+        const int half = a.N / 2, o0 = n0 / 2;
+        char *region = lds_b + wave * DEX_BYTES;
+#pragma unroll
+        for (int jj = 0; jj < 2; ++jj) {
+            const int mrow0 = mt * DBM + (keep + jj) * 32;
+#pragma unroll
+            for (int ip = 0; ip < 2; ++ip)
+#pragma unroll
+                for (int qq = 0; qq < 2; ++qq) {
+                    typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                    h4 hv;
+#pragma unroll
+                    for (int e = 0; e < 4; ++e)
+                        hv[e] = (_Float16)(gate_activation(out[ip][jj][4 * qq + e], gc) * out[ip][jj][4 * (qq + 2) + e]);
+                    *reinterpret_cast<h4 *>(region + r * DEPI_PITCH + (ip * 16 + 8 * qq + 4 * kh) * 2) = hv;
+                }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+#pragma unroll
+            for (int it = 0; it < 2; ++it) {  // 32 rows x 4 chunks of 16 bytes
+                const int idx = it * 64 + lane;
+                const int row = idx >> 2, ch = idx & 3;
+                const uint4 v = *reinterpret_cast<const uint4 *>(region + row * DEPI_PITCH + ch * 16);
+                const int mm = mrow0 + row, nn = o0 + ch * 8;
+                if (mm < a.M && nn < half) *reinterpret_cast<uint4 *>(a.y + (size_t)mm * half + nn) = v;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+            __builtin_amdgcn_wave_barrier();
+            __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        }
+        return;
+    }
     if ((a.N % 8) == 0) {
         char *region = lds_b + wave * DEX_BYTES;
 #pragma unroll
@@ -693,8 +733,10 @@ hipError_t launch_fallback(GemmF16Args a, int M, hipStream_t st) {
 }  // namespace
 
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                           const void *residual, int num_cus, hipStream_t st) {
+                           const void *residual, int gated_act, int num_cus, hipStream_t st) {
     if (g.fmt != kW4G32 && g.fmt != kW4C) return hipErrorNotSupported;
+    // only the kernel that converts in registers has the merged gating (K a multiple of 128)
+    if (gated_act >= 0 && (!g.pair_half || (g.K % 128) != 0)) return hipErrorNotSupported;
     (void)num_cus;
     GemmF16Args a;
     a.w = static_cast<const uint4 *>(packed);
@@ -708,8 +750,9 @@ hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x,
     a.KT = g.KT;
     a.rt_stride = g.rt_stride;
     a.n_tiles = a.m_tiles = 0;
+    a.gated_act = gated_act;
     const bool pc = g.fmt == kW4C;
-    if ((g.K % 128) == 0 && tuning().gemm_variant != 9) return pc ? launch_direct<true>(a, M, st) : launch_direct<false>(a, M, st);
+    if ((g.K % 128) == 0 && (tuning().gemm_variant != 9 || gated_act >= 0)) return pc ? launch_direct<true>(a, M, st) : launch_direct<false>(a, M, st);
     return pc ? launch_fallback<true>(a, M, st) : launch_fallback<false>(a, M, st);
 }
 

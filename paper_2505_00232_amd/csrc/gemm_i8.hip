@@ -44,7 +44,83 @@ struct GemmI8Args {
     // 16 times the definition's, exactly; channel scales are multiplied by 1/16, raw sums shifted by 4
     float sw_mul = 1.0f;
     int acc_shift = 0;
+    int gated_act = -1;  // QFC_ACT_*: the layer is packed in pairs and y [M, N/2] = fp16(act(gate) * other)
 };
+
+// Store phase of a layer packed in pairs (operator fusion, section 3.6 of the paper: the element-wise
+// operators of the two branches merged into the fully connected operator that produces them).
+// Physical rows 32 t .. 32 t + 15 are gate rows and 32 t + 16 .. 32 t + 31 the other branch's rows of
+// the same 16 channels, so a lane's accumulator registers 4 q + e (q = 0, 1) and 4 (q + 2) + e of a
+// 32 x 32 tile are the two branches of one channel: scale both, multiply act(gate) with the other
+// in fp32, round once.  16 TN output channels per wavefront, staged through LDS like the plain
+// store phase and written as 16-byte pieces of rows of N / 2 values.
+template <int TN, int TM>
+__device__ __forceinline__ void epilogue_gated(const GemmI8Args &a, v16i (&acc)[TN][TM], uint4 *lds, int n_base,
+                                               int m_base, int wave, int lane) {
+    constexpr int WO = TN * 16;
+    constexpr int PITCH = (WO + 8) * 2;  // bytes per staged row
+    char *region = reinterpret_cast<char *>(lds) + wave * (32 * PITCH);
+    const int half = a.N / 2;
+    const int o0 = n_base / 2;  // first output channel of the wavefront
+    const GateCoeffs gc = gate_coeffs(a.gated_act);
+    float4 scg[TN][2], scu[TN][2];
+    float sxr[TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int q = 0; q < 2; ++q) {
+            float4 g = *reinterpret_cast<const float4 *>(a.sw + n_base + i * 32 + 8 * q + 4 * (lane >> 5));
+            float4 u = *reinterpret_cast<const float4 *>(a.sw + n_base + i * 32 + 16 + 8 * q + 4 * (lane >> 5));
+            g.x *= a.sw_mul, g.y *= a.sw_mul, g.z *= a.sw_mul, g.w *= a.sw_mul;
+            u.x *= a.sw_mul, u.y *= a.sw_mul, u.z *= a.sw_mul, u.w *= a.sw_mul;
+            scg[i][q] = g;
+            scu[i][q] = u;
+        }
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int m = m_base + j * 32 + (lane & 31);
+        sxr[j] = m < a.M ? a.sx[m] : 0.0f;
+    }
+    asm volatile("s_barrier" ::: "memory");  // all wavefronts are done with the stage buffers
+#pragma unroll
+    for (int j = 0; j < TM; ++j) {
+        const int mrow0 = m_base + j * 32;
+        const float sxm = sxr[j];
+#pragma unroll
+        for (int i = 0; i < TN; ++i) {
+#pragma unroll
+            for (int q = 0; q < 2; ++q) {
+                typedef _Float16 h4 __attribute__((ext_vector_type(4)));
+                const float gs[4] = {scg[i][q].x, scg[i][q].y, scg[i][q].z, scg[i][q].w};
+                const float us[4] = {scu[i][q].x, scu[i][q].y, scu[i][q].z, scu[i][q].w};
+                h4 hv;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float g = (float)acc[i][j][4 * q + e] * sxm * gs[e];
+                    const float u = (float)acc[i][j][4 * (q + 2) + e] * sxm * us[e];
+                    hv[e] = (_Float16)(gate_activation(g, gc) * u);
+                }
+                *reinterpret_cast<h4 *>(region + (lane & 31) * PITCH + (i * 16 + 8 * q + 4 * (lane >> 5)) * 2) = hv;
+            }
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+        constexpr int CH = WO / 8;  // 16-byte chunks per staged row
+#pragma unroll
+        for (int it = 0; it < 32 * CH / 64; ++it) {
+            const int idx = it * 64 + lane;
+            const int row = idx / CH, ch = idx % CH;
+            const uint4 v = *reinterpret_cast<const uint4 *>(region + row * PITCH + ch * 16);
+            const int mm = mrow0 + row, nn = o0 + ch * 8;
+            if (mm < a.M && nn < half)
+                *reinterpret_cast<uint4 *>(static_cast<_Float16 *>(a.out) + (size_t)mm * half + nn) = v;
+        }
+        __builtin_amdgcn_fence(__ATOMIC_RELEASE, "wavefront");
+        __builtin_amdgcn_wave_barrier();
+        __builtin_amdgcn_fence(__ATOMIC_ACQUIRE, "wavefront");
+    }
+}
 
 // Epilogue shared by the product kernels.
 // A wavefront holds TN x TM tiles of 32 x 32 outputs whose first weight row is n_base and first
@@ -53,6 +129,10 @@ template <int OUT_MODE, int TN, int TM>
 __device__ __forceinline__ void epilogue(const GemmI8Args &a, v16i (&acc)[TN][TM], uint4 *lds, int n_base, int m_base,
                                          int wave, int lane) {
     constexpr int WN = TN * 32;
+    if (OUT_MODE == 0 && a.gated_act >= 0) {
+        epilogue_gated<TN, TM>(a, acc, lds, n_base, m_base, wave, lane);
+        return;
+    }
     // Epilogue.  After the MFMAs a lane holds one token row m (lane % 32) and, per
     // group of four accumulator registers, four consecutive n: stored as they are,
     // every store instruction would touch 32 different rows of y with 8 bytes
@@ -660,7 +740,7 @@ hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
 
 hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *xq_tiled,
                           const float *sx, int M, int Mp, void *out, int out_mode, const void *residual,
-                          int num_cus, hipStream_t st) {
+                          int gated_act, int num_cus, hipStream_t st) {
     (void)Mp;
     GemmI8Args a;
     a.w = static_cast<const uint4 *>(packed);
@@ -673,6 +753,7 @@ hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *x
     a.N = g.N;
     a.Kp = g.Kp;
     a.n_tiles = a.m_tiles = 0;
+    a.gated_act = out_mode == 0 && g.pair_half ? gated_act : -1;
     if (g.fmt == kW4C) {
         a.sw_mul = 0.0625f;
         a.acc_shift = 4;

@@ -144,6 +144,7 @@ struct GemvArgs {
     int row_tiles;           // R: row tiles per workgroup
     int rt_step;             // distance between a workgroup's row tiles (1; RT / 2 for a gated output)
     int gated_out;           // 1: rows [0, N/2) are the gate, rows [N/2, N) the other branch; y is [M, N/2]
+    int paired;              // 1: the layer is packed in pairs (physical row tiles 2 t, 2 t + 1 = the two branches)
     int units_q, units_rem;  // KU = units_q * waves + units_rem
 };
 
@@ -232,7 +233,8 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
     const int c = lane & 15, q = lane >> 4;
     // Gated output: a workgroup owns the two row tiles (t, t + RT / 2) that hold the gate and the
     // other branch of the same 16 output channels.
-    const int rt0 = a.gated_out ? blockIdx.x : blockIdx.x * a.row_tiles;
+    // (first row tile in the packed buffer: with the branches' tiles interleaved, the pair (2 b, 2 b + 1))
+    const int rt0 = a.gated_out ? (a.paired ? 2 * blockIdx.x : blockIdx.x) : blockIdx.x * a.row_tiles;
     const int R = a.gated_out ? 2 : min(a.row_tiles, a.RT - rt0);
     const int u0 = wave * a.units_q + min(wave, a.units_rem);
     const int u1 = u0 + a.units_q + (wave < a.units_rem ? 1 : 0);
@@ -472,11 +474,11 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
                 sg += red[((w * 4 + 0) * M + m) * 16 + cc];
                 su += red[((w * 4 + 1) * M + m) * 16 + cc];
             }
-            const int n = rt0 * 16 + cc;
+            const int n = (int)blockIdx.x * 16 + cc;  // channel of the gated output
             if (n < half) {
-                if (FMT != kW4G32) {
-                    sg *= a.sw[n];
-                    su *= a.sw[n + half];
+                if (FMT != kW4G32) {  // (the scales follow the packed row order)
+                    sg *= a.sw[a.paired ? rt0 * 16 + cc : n];
+                    su *= a.sw[a.paired ? rt0 * 16 + 16 + cc : n + half];
                 }
                 if constexpr (PRO == 2) {
                     float tot = 0.0f;
@@ -603,7 +605,8 @@ hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int
     a.KU = p.units;
     a.rt_stride = g.rt_stride;
     a.row_tiles = p.row_tiles;
-    a.rt_step = f.gated_output ? g.RT / 2 : 1;
+    a.paired = g.pair_half ? 1 : 0;
+    a.rt_step = f.gated_output && !a.paired ? g.RT / 2 : 1;
     a.gated_out = f.gated_output ? 1 : 0;
     a.units_q = p.units / p.waves;
     a.units_rem = p.units % p.waves;

@@ -7,20 +7,31 @@
 namespace qfc {
 namespace {
 
+// Paired packing of a layer that produces the two branches of a gated feed-forward block (rows
+// [0, N/2) = gate, rows [N/2, N) = the other branch; operator fusion, section 3.6 of the paper):
+// physical row tile 2 t holds gate rows 16 t .. 16 t + 15 and tile 2 t + 1 the other branch's rows
+// of the same 16 channels, so that every 32-row MFMA tile of a product holds both branches of its
+// channels in the same lanes.  `half` = N / 2 for such a layer (N a multiple of 32), 0 otherwise.
+__device__ inline int logical_row(int p, int N, int half) {
+    if (!half || p >= N) return p;
+    const int tp = p >> 4;
+    return (tp & 1) * half + (tp >> 1) * 16 + (p & 15);
+}
+
 // ---------------------------------------------------------------- W8C
 __global__ __launch_bounds__(256) void pack_w8c_kernel(const int8_t *__restrict__ wq,
                                                        const float *__restrict__ scales,
                                                        uint4 *__restrict__ packed, float *__restrict__ ps,
-                                                       int N, int K, int Np, int KT) {
+                                                       int N, int K, int Np, int KT, int half) {
     const size_t total = (size_t)(Np / 16) * KT * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < (size_t)Np) ps[v] = v < (size_t)N ? scales[v] : 0.0f;
+    if (v < (size_t)Np) ps[v] = v < (size_t)N ? scales[logical_row((int)v, N, half)] : 0.0f;
     if (v >= total) return;
     const int lane = (int)(v % 64);
     const size_t tile = v / 64;
     const int kt = (int)(tile % KT);
     const int rt = (int)(tile / KT);
-    const int n = rt * 16 + (lane & 15);
+    const int n = logical_row(rt * 16 + (lane & 15), N, half);
     const int k = kt * 64 + (lane >> 4) * 16;
     uint4 out = make_uint4(0, 0, 0, 0);
     if (n < N && k < K) out = *reinterpret_cast<const uint4 *>(wq + (size_t)n * K + k);
@@ -30,16 +41,16 @@ __global__ __launch_bounds__(256) void pack_w8c_kernel(const int8_t *__restrict_
 __global__ __launch_bounds__(256) void unpack_w8c_kernel(const uint4 *__restrict__ packed,
                                                          const float *__restrict__ ps,
                                                          int8_t *__restrict__ wq, float *__restrict__ scales,
-                                                         int N, int K, int Np, int KT) {
+                                                         int N, int K, int Np, int KT, int half) {
     const size_t total = (size_t)(Np / 16) * KT * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < (size_t)N) scales[v] = ps[v];
+    if (v < (size_t)N) scales[logical_row((int)v, N, half)] = ps[v];
     if (v >= total) return;
     const int lane = (int)(v % 64);
     const size_t tile = v / 64;
     const int kt = (int)(tile % KT);
     const int rt = (int)(tile / KT);
-    const int n = rt * 16 + (lane & 15);
+    const int n = logical_row(rt * 16 + (lane & 15), N, half);
     const int k = kt * 64 + (lane >> 4) * 16;
     if (n < N && k < K) *reinterpret_cast<uint4 *>(wq + (size_t)n * K + k) = packed[v];
 }
@@ -77,7 +88,7 @@ __device__ inline int classify(int pos, int KT) {
 __global__ __launch_bounds__(256) void pack_w4g32_kernel(const int8_t *__restrict__ wq,
                                                          const uint16_t *__restrict__ scales,
                                                          uint4 *__restrict__ packed, int N, int K,
-                                                         int RTp, int KT, int stride) {
+                                                         int RTp, int KT, int stride, int half) {
     const int Kg = K / 32;
     const size_t total = (size_t)RTp * stride * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -89,7 +100,7 @@ __global__ __launch_bounds__(256) void pack_w4g32_kernel(const int8_t *__restric
     const int what = classify(pos, KT);
     uint4 out;
     if (what >= 0) {
-        const int n = rt * 16 + (lane & 15);
+        const int n = logical_row(rt * 16 + (lane & 15), N, half);
         const int q = lane >> 4;
         uint32_t d[4];
 #pragma unroll
@@ -107,7 +118,7 @@ __global__ __launch_bounds__(256) void pack_w4g32_kernel(const int8_t *__restric
         out = make_uint4(d[0], d[1], d[2], d[3]);
     } else {
         const int u = -1 - what;
-        const int n = rt * 16 + (lane & 15);
+        const int n = logical_row(rt * 16 + (lane & 15), N, half);
         const int p = lane >> 4;
         uint32_t s[8];
 #pragma unroll
@@ -123,7 +134,7 @@ __global__ __launch_bounds__(256) void pack_w4g32_kernel(const int8_t *__restric
 __global__ __launch_bounds__(256) void unpack_w4g32_kernel(const uint4 *__restrict__ packed,
                                                            int8_t *__restrict__ wq,
                                                            uint16_t *__restrict__ scales, int N, int K,
-                                                           int RTp, int KT, int stride) {
+                                                           int RTp, int KT, int stride, int half) {
     const int Kg = K / 32;
     const size_t total = (size_t)RTp * stride * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
@@ -133,7 +144,7 @@ __global__ __launch_bounds__(256) void unpack_w4g32_kernel(const uint4 *__restri
     const int pos = (int)(tile % stride);
     const int rt = (int)(tile / stride);
     const int what = classify(pos, KT);
-    const int n = rt * 16 + (lane & 15);
+    const int n = logical_row(rt * 16 + (lane & 15), N, half);
     if (n >= N) return;
     const uint4 in = packed[v];
     const uint32_t w[4] = {in.x, in.y, in.z, in.w};
@@ -165,17 +176,17 @@ __global__ __launch_bounds__(256) void unpack_w4g32_kernel(const uint4 *__restri
 __global__ __launch_bounds__(256) void pack_w4c_kernel(const int8_t *__restrict__ wq,
                                                        const float *__restrict__ scales,
                                                        uint4 *__restrict__ packed, float *__restrict__ ps,
-                                                       int N, int K, int Np, int KT) {
+                                                       int N, int K, int Np, int KT, int half) {
     const int Kg = K / 32;
     const size_t total = (size_t)(Np / 16) * KT * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < (size_t)Np) ps[v] = v < (size_t)N ? scales[v] : 0.0f;
+    if (v < (size_t)Np) ps[v] = v < (size_t)N ? scales[logical_row((int)v, N, half)] : 0.0f;
     if (v >= total) return;
     const int lane = (int)(v % 64);
     const size_t tile = v / 64;
     const int kt = (int)(tile % KT);
     const int rt = (int)(tile / KT);
-    const int n = rt * 16 + (lane & 15);
+    const int n = logical_row(rt * 16 + (lane & 15), N, half);
     const int q = lane >> 4;
     uint32_t d[4];
 #pragma unroll
@@ -195,17 +206,17 @@ __global__ __launch_bounds__(256) void pack_w4c_kernel(const int8_t *__restrict_
 __global__ __launch_bounds__(256) void unpack_w4c_kernel(const uint4 *__restrict__ packed,
                                                          const float *__restrict__ ps,
                                                          int8_t *__restrict__ wq, float *__restrict__ scales,
-                                                         int N, int K, int Np, int KT) {
+                                                         int N, int K, int Np, int KT, int half) {
     const int Kg = K / 32;
     const size_t total = (size_t)(Np / 16) * KT * 64;
     const size_t v = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
-    if (v < (size_t)N) scales[v] = ps[v];
+    if (v < (size_t)N) scales[logical_row((int)v, N, half)] = ps[v];
     if (v >= total) return;
     const int lane = (int)(v % 64);
     const size_t tile = v / 64;
     const int kt = (int)(tile % KT);
     const int rt = (int)(tile / KT);
-    const int n = rt * 16 + (lane & 15);
+    const int n = logical_row(rt * 16 + (lane & 15), N, half);
     if (n >= N) return;
     const int q = lane >> 4;
     const uint4 in = packed[v];
@@ -297,17 +308,17 @@ hipError_t launch_pack(const Geometry &g, const int8_t *wq, const void *scales, 
         const size_t total = (size_t)g.RTp * g.KT * 64;
         pack_w8c_kernel<<<blocks_for(total), 256, 0, st>>>(
             wq, static_cast<const float *>(scales), static_cast<uint4 *>(packed),
-            reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.KT);
+            reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.KT, g.pair_half);
     } else if (g.fmt == kW4C) {
         const size_t total = (size_t)g.RTp * g.KT * 64;
         pack_w4c_kernel<<<blocks_for(total > (size_t)g.Np ? total : (size_t)g.Np), 256, 0, st>>>(
             wq, static_cast<const float *>(scales), static_cast<uint4 *>(packed),
-            reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.KT);
+            reinterpret_cast<float *>(static_cast<char *>(packed) + g.scale_off), g.N, g.K, g.Np, g.KT, g.pair_half);
     } else {
         const size_t total = (size_t)g.RTp * g.rt_stride * 64;
         pack_w4g32_kernel<<<blocks_for(total), 256, 0, st>>>(
             wq, static_cast<const uint16_t *>(scales), static_cast<uint4 *>(packed), g.N, g.K, g.RTp, g.KT,
-            g.rt_stride);
+            g.rt_stride, g.pair_half);
     }
     return hipGetLastError();
 }
@@ -334,18 +345,18 @@ hipError_t launch_unpack(const Geometry &g, const void *packed, int8_t *wq, void
         unpack_w8c_kernel<<<blocks_for(total), 256, 0, st>>>(
             static_cast<const uint4 *>(packed),
             reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off), wq,
-            static_cast<float *>(scales), g.N, g.K, g.Np, g.KT);
+            static_cast<float *>(scales), g.N, g.K, g.Np, g.KT, g.pair_half);
     } else if (g.fmt == kW4C) {
         const size_t total = (size_t)g.RTp * g.KT * 64;
         unpack_w4c_kernel<<<blocks_for(total > (size_t)g.Np ? total : (size_t)g.Np), 256, 0, st>>>(
             static_cast<const uint4 *>(packed),
             reinterpret_cast<const float *>(static_cast<const char *>(packed) + g.scale_off), wq,
-            static_cast<float *>(scales), g.N, g.K, g.Np, g.KT);
+            static_cast<float *>(scales), g.N, g.K, g.Np, g.KT, g.pair_half);
     } else {
         const size_t total = (size_t)g.RTp * g.rt_stride * 64;
         unpack_w4g32_kernel<<<blocks_for(total), 256, 0, st>>>(
             static_cast<const uint4 *>(packed), wq, static_cast<uint16_t *>(scales), g.N, g.K, g.RTp, g.KT,
-            g.rt_stride);
+            g.rt_stride, g.pair_half);
     }
     return hipGetLastError();
 }

@@ -62,6 +62,7 @@ struct Geometry {
     int KU;      // units of 8 tiles per row tile: ceil(KT / 8)
     int rt_stride;       // KiB tiles per row tile (W4G32: KT + KU, else KT)
     int fmt;
+    int pair_half;       // N / 2 for a layer packed with its two branches' row tiles interleaved, else 0
     size_t code_bytes;   // bytes of the code (+ group scale) region
     size_t scale_off;    // W8C, W4C: byte offset of the fp32 scales
     size_t total_bytes;
@@ -69,9 +70,10 @@ struct Geometry {
 
 inline int round_up(int v, int m) { return (v + m - 1) / m * m; }
 
-inline Geometry make_geometry(int N, int K, int fmt) {
+inline Geometry make_geometry(int N, int K, int fmt, bool paired = false) {
     Geometry g;
     g.N = N; g.K = K; g.fmt = fmt;
+    g.pair_half = paired ? N / 2 : 0;
     g.Np = round_up(N, kPadN);
     g.RT = (N + kTileRows - 1) / kTileRows;
     g.RTp = g.Np / kTileRows;
@@ -317,10 +319,13 @@ hipError_t launch_retile_xq(const int8_t *xq, int M, int K, int8_t *tiled, int M
                             hipStream_t st);
 // out_mode 0: binary16 y with scales; 1: raw int32 accumulators.
 // `residual` (binary16 [M, N] or null) is added before the final rounding (out_mode 0 only).
+// gated_act (QFC_ACT_* or -1): the layer is packed in pairs (g.pair_half) and y [M, N/2] is
+// fp16(act(gate) * other) of the fp32 outputs of the two branches (out_mode 0, no residual).
 hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *xq_tiled,
                           const float *sx, int M, int Mp, void *out, int out_mode, const void *residual,
-                          int num_cus, hipStream_t st);
+                          int gated_act, int num_cus, hipStream_t st);
+// Returns hipErrorNotSupported for a gated output when K is not a multiple of 128.
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
-                           const void *residual, int num_cus, hipStream_t st);
+                           const void *residual, int gated_act, int num_cus, hipStream_t st);
 
 }  // namespace qfc

@@ -854,6 +854,135 @@ def test_decode_gated_output(fmt, N, K):
     layer.close()
 
 
+# Layers packed in pairs (the row tiles of the two branches interleaved): the merged gating in every kernel
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
+@pytest.mark.parametrize("N,K", [(32, 32), (160, 96), (1024, 256), (2080, 1152)])
+def test_paired_packing_round_trip_and_decode(fmt, N, K):
+    print(f"paired packing {fmt} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(3600, N, K, fc)
+    layer = binding.QuantLinear(wq, s, fmt, gated_pairs=True)
+    plain = binding.QuantLinear(wq, s, fmt)
+    # the logical interface does not change: unpack returns what pack was given
+    wq_back = torch.empty((N, K), dtype=torch.int8, device=DEV)
+    s_back = torch.empty_like(torch.as_tensor(s)).to(DEV)
+    binding.qfc_unpack_weights(layer.handle, wq_back, s_back)
+    torch.cuda.synchronize()
+    assert np.array_equal(wq_back.cpu().numpy(), wq)
+    assert np.array_equal(s_back.cpu().numpy().view(np.uint8), np.ascontiguousarray(s).view(np.uint8))
+    # and the packed bytes are a permutation of the plain packing's row tiles
+    a, b = layer.packed.cpu().numpy(), plain.packed.cpu().numpy()
+    assert a.shape == b.shape and (N == 32 or not np.array_equal(a, b))  # (two row tiles: nothing to interleave)
+    for M in (1, 3, 8):
+        x = (synth.activations(3600, N, K + M, M, K) * np.float16(0.0625)).astype(np.float16)
+        xd = torch.from_numpy(x).to(DEV)
+        act, oact = (binding.QFC_ACT_SILU, oracle.SILU) if M % 2 else (binding.QFC_ACT_GELU_TANH, oracle.GELU_TANH)
+        y = torch.full((M, N // 2), 77.0, dtype=torch.float16, device=DEV)
+        y_plain = torch.empty_like(y)
+        binding.qfc_forward_fused(layer.handle, xd, y, activation=act, gated_output=True)
+        binding.qfc_forward_fused(plain.handle, xd, y_plain, activation=act, gated_output=True)
+        torch.cuda.synchronize()
+        ref = oracle.gated_output(oracle.fc_weight_only(x, wq, s, _group(fmt)), oact)
+        assert _E(y.cpu().numpy(), ref) <= TOL, M
+        # same row tiles in the same order, wherever they sit in memory: the same bits
+        assert np.array_equal(y.cpu().numpy().view(np.uint16), y_plain.cpu().numpy().view(np.uint16)), M
+    # a layer packed in pairs only computes the gated output
+    xd = torch.from_numpy(synth.activations(3600, N, K, 2, K)).to(DEV)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_forward(layer.handle, xd, torch.empty((2, N), dtype=torch.float16, device=DEV))
+    assert e.value.code == binding.QFC_ERR_UNSUPPORTED
+    layer.close()
+    plain.close()
+
+
+@pytest.mark.parametrize("fmt,mode", [("w8c", None), ("w4c", binding.QFC_COMPUTE_INT8_ACT), ("w4g32", None), ("w4c", None)])
+@pytest.mark.parametrize("M,N,K", [(9, 32, 128), (100, 160, 384), (130, 1024, 256), (300, 2080, 1152), (513, 544, 2304)])
+def test_prefill_gated_output(fmt, mode, M, N, K):
+    """act(gate) * up in the store phase of both prefill kernels (layer packed in pairs) against the
+    oracle: the element-wise product of the two halves of the unrounded outputs."""
+    print(f"prefill gated output {fmt} mode={mode} M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, fmt)
+    wq, s = synth.weights(3700, M, N, fc)
+    x = (synth.activations(3700, M, N, M, K) * np.float16(0.125)).astype(np.float16)
+    layer = binding.QuantLinear(wq, s, fmt, compute_mode=mode, max_m=M, gated_pairs=True)
+    int8 = fmt == "w8c" or mode == binding.QFC_COMPUTE_INT8_ACT
+    full = oracle.fc_int8_act(x, wq, s)[3] if int8 else oracle.fc_weight_only(x, wq, s, _group(fmt))
+    xd = torch.from_numpy(x).to(DEV)
+    for act, oact in ((binding.QFC_ACT_SILU, oracle.SILU), (binding.QFC_ACT_GELU_TANH, oracle.GELU_TANH)):
+        y = torch.full((M, N // 2), 77.0, dtype=torch.float16, device=DEV)
+        binding.qfc_forward_fused(layer.handle, xd, y, activation=act, gated_output=True)
+        torch.cuda.synchronize()
+        e = _E(y.cpu().numpy(), oracle.gated_output(full, oact))
+        print(f"  act {act}: E = {e:.3e}", flush=True)
+        # the product of two outputs, each within the bound of its own path (the fp16 path with group
+        # scales folded into the weights carries ~1e-3 per factor)
+        assert e <= (2 * TOL if fmt == "w4g32" else TOL)
+    layer.close()
+
+
+def test_prefill_gated_output_llama_gate_up_sampled():
+    """The gate+up layer of Llama-3.1-8B at M = 1024 (int8 activations, 8-bit weights) and of Gemma2-2B at
+    M = 2048 (fp16, int4 group-32), packed in pairs: sampled rows and channels against the oracle."""
+    rng = np.random.default_rng(46)
+    for fc, M, seed in ((synth.LLAMA_FCS_W8[2], 1024, 1004), (synth.GEMMA_FCS_W4[2], 2048, 1005)):
+        print(f"prefill gated output {fc.name} {fc.fmt} {fc.K}->{fc.N} M={M}", flush=True)
+        wq, s = synth.weights(seed, 0, 2, fc)
+        x = (synth.activations(seed, 0, 2, M, fc.K) * np.float16(0.125)).astype(np.float16)
+        layer = binding.QuantLinear(wq, s, fc.fmt, max_m=M, gated_pairs=True)
+        y = torch.empty((M, fc.N // 2), dtype=torch.float16, device=DEV)
+        binding.qfc_forward_fused(layer.handle, torch.from_numpy(x).to(DEV), y, activation=binding.QFC_ACT_SILU,
+                                  gated_output=True)
+        torch.cuda.synchronize()
+        half = fc.N // 2
+        rows = np.sort(rng.choice(M, size=32, replace=False))
+        cols = np.sort(rng.choice(half, size=256, replace=False))
+        rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, half - 1
+        both = np.concatenate([cols, cols + half])
+        if fc.fmt == "w8c":
+            full = oracle.fc_int8_act(x[rows], wq[both], s[both])[3]
+        else:
+            full = oracle.fc_weight_only(x[rows], wq[both], s[both], 32)
+        ref = oracle.gated_output(full, oracle.SILU)
+        assert _E(y.cpu().numpy()[np.ix_(rows, cols)], ref) <= (2 * TOL if fc.fmt == "w4g32" else TOL)
+        layer.close()
+
+
+def test_paired_packing_restrictions():
+    fc = synth.FC("t", 96, 64, "w8c")
+    wq, s = synth.weights(3800, 0, 0, fc)
+    with pytest.raises(binding.QfcError) as e:  # the halves must be whole row tiles
+        binding.QuantLinear(wq[:48], s[:48], "w8c", gated_pairs=True)
+    assert e.value.code == binding.QFC_ERR_INVALID_ARG
+    layer = binding.QuantLinear(wq, s, "w8c", max_m=16, gated_pairs=True)
+    plain = binding.QuantLinear(wq, s, "w8c", max_m=16)
+    x = torch.zeros((16, 96), dtype=torch.float16, device=DEV)
+    xq = torch.zeros((16, 96), dtype=torch.int8, device=DEV)
+    sx = torch.zeros((16,), dtype=torch.float32, device=DEV)
+    y = torch.zeros((16, 64), dtype=torch.float16, device=DEV)
+    yh = torch.zeros((16, 32), dtype=torch.float16, device=DEV)
+    for call in (lambda: binding.qfc_forward(layer.handle, x, y),
+                 lambda: binding.qfc_forward_q8(layer.handle, xq, sx, y),
+                 lambda: binding.qfc_forward_acc_i32(layer.handle, xq, torch.zeros((16, 64), dtype=torch.int32, device=DEV)),
+                 lambda: binding.qfc_embedding(layer.handle, torch.zeros(2, dtype=torch.int32, device=DEV),
+                                               torch.zeros((2, 96), dtype=torch.float16, device=DEV)),
+                 # gated output at M > 8 needs the paired packing
+                 lambda: binding.qfc_forward_fused(plain.handle, x, yh, gated_output=True)):
+        with pytest.raises(binding.QfcError) as e:
+            call()
+        assert e.value.code == binding.QFC_ERR_UNSUPPORTED
+    binding.qfc_forward_fused(layer.handle, x, yh, gated_output=True)  # (and works with it)
+    # the fp16 path's merged gating needs K to be a multiple of 128
+    fc4 = synth.FC("t", 96, 64, "w4g32")
+    wq4, s4 = synth.weights(3801, 0, 0, fc4)
+    l4 = binding.QuantLinear(wq4, s4, "w4g32", max_m=16, gated_pairs=True)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_forward_fused(l4.handle, x, yh, gated_output=True)
+    assert e.value.code == binding.QFC_ERR_UNSUPPORTED
+    torch.cuda.synchronize()
+    for l in (layer, plain, l4):
+        l.close()
+
+
 def test_gated_output_needs_even_halves_of_whole_tiles():
     fc = synth.FC("t", 64, 48, "w8c")  # N / 2 = 24 is not a whole number of 16-row tiles
     wq, s = synth.weights(3501, 0, 0, fc)
