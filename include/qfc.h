@@ -65,8 +65,8 @@ enum { QFC_COMPUTE_FP16_DEQUANT = 0, QFC_COMPUTE_INT8_ACT = 1, QFC_COMPUTE_INT8_
  * Any other combination returns QFC_ERR_UNSUPPORTED.
  * compute_mode selects the M > 8 path: QFC_COMPUTE_INT8_ACT (per-channel weights, 8-bit or 4-bit:
  * the paper's "q8" and "8/4/4" schemes in its prefill stage; group scales cannot leave an integer
- * accumulator) or QFC_COMPUTE_FP16_DEQUANT (4-bit weights); neither changes M <= 8, which keeps
- * binary16 activations.
+ * accumulator) or QFC_COMPUTE_FP16_DEQUANT (binary16 activations, weights dequantized on the
+ * fly: every format); neither changes M <= 8, which keeps binary16 activations.
  * QFC_COMPUTE_INT8_ACT_DECODE (per-channel formats only) is the decode design of section 3.7
  * of the paper: for M <= 8 the kernel quantizes the activations itself (one scale per token
  * row, as qfc_quantize_activations does) and accumulates integers; for M > 8 it behaves like

@@ -212,7 +212,6 @@ static qfc_status_t forward_impl(qfc_handle_t h, const void *x_f16, int32_t M, v
         return hip_status(launch_gemv(h->geo, h->packed, x_f16, M, y_f16, f, h->num_cus, st));
     }
     if (!int8_prefill(h)) {
-        if (h->geo.fmt != kW4G32 && h->geo.fmt != kW4C) return QFC_ERR_UNSUPPORTED;
         // activations go from memory to LDS without passing registers
         if (f.gate) return QFC_ERR_UNSUPPORTED;
         // a tile holds both branches only when the layer is packed in pairs

@@ -66,9 +66,25 @@ __device__ __forceinline__ uint4 dequant8_scaled(uint32_t w, uint32_t scale_bits
     return make_uint4(as_u32(p0), as_u32(p1), as_u32(p2), as_u32(p3));
 }
 
-// PC = per-channel scales (W4C): unscaled integer weights in the MFMA, fp32 scale in the epilogue
-template <bool PC>
+// eight int8 codes (two dwords) -> eight binary16 values, exactly (sign bit flipped: b + 128 under the
+// exponent byte 0x64 is 1024 + b + 128)
+__device__ __forceinline__ uint4 dequant_i8x8(uint32_t lo, uint32_t hi) {
+    const h2 c1152 = {(_Float16)1152.0f, (_Float16)1152.0f};
+    const uint32_t a = lo ^ 0x80808080u, b = hi ^ 0x80808080u;
+    const h2 p0 = as_h2(__builtin_amdgcn_perm(0x64646464u, a, 0x04010400u)) - c1152;
+    const h2 p1 = as_h2(__builtin_amdgcn_perm(0x64646464u, a, 0x04030402u)) - c1152;
+    const h2 p2 = as_h2(__builtin_amdgcn_perm(0x64646464u, b, 0x04010400u)) - c1152;
+    const h2 p3 = as_h2(__builtin_amdgcn_perm(0x64646464u, b, 0x04030402u)) - c1152;
+    return make_uint4(as_u32(p0), as_u32(p1), as_u32(p2), as_u32(p3));
+}
+
+// PC = per-channel scales (W4C): unscaled integer weights in the MFMA, fp32 scale in the epilogue.
+// W8 (with PC) = int8 per-channel weights with binary16 activations (the "q8" scheme of section 4.2
+// with FP16 activations at M > 8): two packed KiB tiles of 64 k per row tile and stage, converted
+// exactly to binary16 on their way into LDS, fp32 scale in the epilogue.
+template <bool PC, bool W8 = false>
 __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
+    static_assert(!W8 || PC, "int8 weights carry per-channel scales");
     extern __shared__ uint4 lds[];
     uint4 *lds_w = lds;
     uint4 *lds_x = lds + OCT * LDW;
@@ -100,16 +116,17 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
 #pragma unroll
             for (int e = 0; e < 16; ++e) acc[i][j][e] = 0.0f;
 
-    uint4 wreg[2], xreg[8];
+    uint4 wreg[2], wreg2[W8 ? 2 : 1], xreg[8];
     uint2 sreg[2];
     auto load_stage = [&](int kt) {
         const int u = kt >> 3;
-        const int wpos = PC ? kt : kt + u;                     // weight tile kt of the row tile
+        const int wpos = W8 ? 2 * kt : PC ? kt : kt + u;       // weight tile kt of the row tile (int8: tiles 2 kt, 2 kt + 1)
         const int spos = min(8 * u + 8, a.KT) + u;             // scale tile of its unit
         const int soff = (((kt & 7) >> 1) * 16 + c) * 2 + (kt & 1);  // 8-byte index inside it
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             wreg[i] = w_rt[i][(size_t)wpos * 64 + lane];
+            if (W8) wreg2[i] = w_rt[i][(size_t)(wpos + 1) * 64 + lane];
             sreg[i] = PC ? make_uint2(0x3C003C00u, 0x3C003C00u)  // 1.0: the multiply is exact
                          : reinterpret_cast<const uint2 *>(w_rt[i] + (size_t)spos * 64)[soff];
         }
@@ -122,13 +139,21 @@ __global__ __launch_bounds__(256) void gemm_f16_w4_kernel(GemmF16Args a) {
         }
     };
 
-    const int stages = a.KT;
+    const int stages = W8 ? a.KT / 2 : a.KT;  // (int8 rows are padded to a multiple of 256 k: an even number of tiles)
     load_stage(0);
     for (int kt = 0; kt < stages; ++kt) {
         __syncthreads();
 #pragma unroll
         for (int i = 0; i < 2; ++i) {
             const int row = (wave + 4 * i) * 16 + c;
+            if (W8) {
+                // lane (c, q) of tile h holds the codes k = 64 h + 16 q .. + 15: octets 8 h + 2 q and + 1 of the stage
+                lds_w[(2 * q) * LDW + row] = dequant_i8x8(wreg[i].x, wreg[i].y);
+                lds_w[(2 * q + 1) * LDW + row] = dequant_i8x8(wreg[i].z, wreg[i].w);
+                lds_w[(8 + 2 * q) * LDW + row] = dequant_i8x8(wreg2[i].x, wreg2[i].y);
+                lds_w[(8 + 2 * q + 1) * LDW + row] = dequant_i8x8(wreg2[i].z, wreg2[i].w);
+                continue;
+            }
             const uint32_t wd[4] = {wreg[i].x, wreg[i].y, wreg[i].z, wreg[i].w};
             const uint32_t sc[4] = {sreg[i].x & 0xFFFFu, sreg[i].x >> 16, sreg[i].y & 0xFFFFu, sreg[i].y >> 16};
 #pragma unroll
@@ -721,12 +746,12 @@ hipError_t launch_direct(GemmF16Args a, int M, hipStream_t st) {
     return hipGetLastError();
 }
 
-template <bool PC>
+template <bool PC, bool W8 = false>
 hipError_t launch_fallback(GemmF16Args a, int M, hipStream_t st) {
-    if (const hipError_t e = allow_dynamic_lds<gemm_f16_w4_kernel<PC>>(kLdsBytes); e != hipSuccess) return e;
+    if (const hipError_t e = allow_dynamic_lds<gemm_f16_w4_kernel<PC, W8>>(kLdsBytes); e != hipSuccess) return e;
     a.n_tiles = (a.N + BN - 1) / BN;
     a.m_tiles = (M + BM - 1) / BM;
-    gemm_f16_w4_kernel<PC><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, kLdsBytes, st>>>(a);
+    gemm_f16_w4_kernel<PC, W8><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, kLdsBytes, st>>>(a);
     return hipGetLastError();
 }
 
@@ -734,9 +759,8 @@ hipError_t launch_fallback(GemmF16Args a, int M, hipStream_t st) {
 
 hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x, int M, void *y,
                            const void *residual, int gated_act, int num_cus, hipStream_t st) {
-    if (g.fmt != kW4G32 && g.fmt != kW4C) return hipErrorNotSupported;
-    // only the kernel that converts in registers has the merged gating (K a multiple of 128)
-    if (gated_act >= 0 && (!g.pair_half || (g.K % 128) != 0)) return hipErrorNotSupported;
+    // only the kernel that converts in registers has the merged gating (int4 formats, K a multiple of 128)
+    if (gated_act >= 0 && (!g.pair_half || (g.K % 128) != 0 || g.fmt == kW8C)) return hipErrorNotSupported;
     (void)num_cus;
     GemmF16Args a;
     a.w = static_cast<const uint4 *>(packed);
@@ -751,6 +775,7 @@ hipError_t launch_gemm_f16(const Geometry &g, const void *packed, const void *x,
     a.rt_stride = g.rt_stride;
     a.n_tiles = a.m_tiles = 0;
     a.gated_act = gated_act;
+    if (g.fmt == kW8C) return launch_fallback<true, true>(a, M, st);
     const bool pc = g.fmt == kW4C;
     if ((g.K % 128) == 0 && (tuning().gemm_variant != 9 || gated_act >= 0)) return pc ? launch_direct<true>(a, M, st) : launch_direct<false>(a, M, st);
     return pc ? launch_fallback<true>(a, M, st) : launch_fallback<false>(a, M, st);

@@ -487,6 +487,25 @@ def test_fp16_prefill_whole_output_against_oracle(fmt, M, N, K):
     layer.close()
 
 
+@pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (130, 1000, 2304), (64, 264, 14336)])
+def test_fp16_prefill_int8_weights_matches_oracle(M, N, K):
+    """Per-channel int8 weights with binary16 activations at M > 8 (the "q8" scheme with FP16
+    activations): the weight-only definition, as for the int4 formats; residual merged as there."""
+    print(f"fp16 prefill w8c M={M} N={N} K={K}", flush=True)
+    fc = synth.FC("t", K, N, "w8c")
+    wq, s = synth.weights(5200, M, N, fc)
+    wq.flat[0], wq.flat[1] = -128, 127
+    x = synth.activations(5200, M, N, M, K)
+    layer = _layer(wq, s, "w8c", max_m=M, mode=binding.QFC_COMPUTE_FP16_DEQUANT)
+    ref = oracle.fc_weight_only(x, wq, s, 0)
+    assert _E(_forward(layer, x), ref) <= TOL
+    res = synth.activations(5201, M, N, M, N)
+    assert _E(_fused(layer, x, None, 0, res), oracle.add_residual(ref, res)) <= TOL
+    # decode through the same handle
+    assert _E(_forward(layer, x[:5]), ref[:5]) <= TOL
+    layer.close()
+
+
 def test_fp16_prefill_config5_shapes_sampled():
     rng = np.random.default_rng(5)
     M = 2048
