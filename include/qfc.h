@@ -141,6 +141,9 @@ qfc_status_t qfc_forward(qfc_handle_t h, const void *x_f16, int32_t M, void *y_f
 qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M,
                             void *y_f16, void *stream);
 
+/* (qfc_forward_q8 with xq == NULL and sx == NULL, M > 8: the activations are those a preceding
+ * qfc_rmsnorm with consumer == h and the same M left in h's workspace.) */
+
 /* The raw int32 accumulators of the same product (parity aid): acc int32 [M, N]. */
 qfc_status_t qfc_forward_acc_i32(qfc_handle_t h, const int8_t *xq, int32_t M, int32_t *acc,
                                  void *stream);
@@ -219,7 +222,13 @@ qfc_status_t qfc_forward_static(qfc_handle_t h, const void *x_f16, int32_t M, vo
  * Each of h_out, y, (xq and sx together) is written when given; at least one must be.
  * h_out may be x or residual itself; y may be x when h_out is not x.  gamma_offset is 0
  * for a plain weight and 1 for models that store weight - 1.  K: a multiple of 32, at
- * most 14336 (a row is held in registers), else QFC_ERR_UNSUPPORTED. */
+ * most 14336 (a row is held in registers), else QFC_ERR_UNSUPPORTED.
+ * consumer (or null): a handle whose M > 8 path multiplies int8 activations and whose K is this
+ * K.  The codes and scales are then (also) written into that handle's bound workspace in the
+ * physical order its product kernel reads, and qfc_forward_q8(consumer, NULL, NULL, M, y, stream)
+ * runs the product on them without another pass over the activations (the normalization as the
+ * producer of the next layer's quantized input).  xq and sx may be null when consumer is given.
+ * The workspace must hold qfc_workspace_size(consumer, M) bytes, else QFC_ERR_BUFFER_TOO_SMALL. */
 typedef struct qfc_rmsnorm {
     const void *x;        /* device */
     const void *residual; /* device or null */
@@ -230,6 +239,7 @@ typedef struct qfc_rmsnorm {
     void *y;              /* device or null */
     int8_t *xq;           /* device or null */
     float *sx;            /* device or null (with xq) */
+    qfc_handle_t consumer; /* host handle or null */
 } qfc_rmsnorm_t;
 qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *args, int32_t M, int32_t K, void *stream);
 

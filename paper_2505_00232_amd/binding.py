@@ -43,7 +43,8 @@ class RmsNorm(ctypes.Structure):
     """qfc_rmsnorm_t."""
     _fields_ = [("x", ctypes.c_void_p), ("residual", ctypes.c_void_p), ("gamma", ctypes.c_void_p),
                 ("eps", ctypes.c_float), ("gamma_offset", ctypes.c_float), ("h_out", ctypes.c_void_p),
-                ("y", ctypes.c_void_p), ("xq", ctypes.c_void_p), ("sx", ctypes.c_void_p)]
+                ("y", ctypes.c_void_p), ("xq", ctypes.c_void_p), ("sx", ctypes.c_void_p),
+                ("consumer", ctypes.c_void_p)]
 
 
 class AttnShape(ctypes.Structure):
@@ -237,7 +238,7 @@ def qfc_forward_fused(h, x: torch.Tensor, y: torch.Tensor, gate: torch.Tensor | 
 
 
 def qfc_rmsnorm(x: torch.Tensor, gamma: torch.Tensor, eps: float, gamma_offset: float = 0.0, residual=None,
-                h_out=None, y=None, xq=None, sx=None):
+                h_out=None, y=None, xq=None, sx=None, consumer=None):
     def p(t):
         return t.data_ptr() if t is not None else None
     _want(x, torch.float16, (None, None), "x")
@@ -250,7 +251,10 @@ def qfc_rmsnorm(x: torch.Tensor, gamma: torch.Tensor, eps: float, gamma_offset: 
         _want(xq, torch.int8, (M, K), "xq")
     if sx is not None:
         _want(sx, torch.float32, (M,), "sx")
-    a = RmsNorm(p(x), p(residual), p(gamma), eps, gamma_offset, p(h_out), p(y), p(xq), p(sx))
+    if consumer is not None and _nk(consumer)[1] != K:
+        raise ValueError("consumer: K of the layer differs from the normalized width")
+    a = RmsNorm(p(x), p(residual), p(gamma), eps, gamma_offset, p(h_out), p(y), p(xq), p(sx),
+                consumer.value if consumer is not None else None)
     _check(lib().qfc_rmsnorm(ctypes.byref(a), M, K, _stream()), "qfc_rmsnorm")
 
 
@@ -285,8 +289,13 @@ def qfc_attention(q: torch.Tensor, kcache: torch.Tensor, vcache: torch.Tensor, S
                                workspace.numel() * workspace.element_size(), _ptr(out), _stream()), "qfc_attention")
 
 
-def qfc_forward_q8(h, xq: torch.Tensor, sx: torch.Tensor, y: torch.Tensor):
+def qfc_forward_q8(h, xq: torch.Tensor | None, sx: torch.Tensor | None, y: torch.Tensor):
+    """xq = sx = None: the activations a preceding qfc_rmsnorm(..., consumer=h) left in h's workspace."""
     N, K = _nk(h)
+    if xq is None and sx is None:
+        _want(y, torch.float16, (None, N), "y")
+        _check(lib().qfc_forward_q8(h, None, None, y.shape[0], _ptr(y), _stream()), "qfc_forward_q8")
+        return
     _want(xq, torch.int8, (None, K), "xq")
     _want(sx, torch.float32, (xq.shape[0],), "sx")
     _want(y, torch.float16, (xq.shape[0], N), "y")

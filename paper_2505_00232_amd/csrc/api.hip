@@ -266,7 +266,13 @@ qfc_status_t qfc_forward_static(qfc_handle_t h, const void *x_f16, int32_t M, vo
 
 qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *r, int32_t M, int32_t K, void *stream) {
     if (!r || !r->x || !r->gamma || M < 1 || K < 32 || K % 32 != 0) return QFC_ERR_INVALID_ARG;
-    if (!r->h_out && !r->y && !r->xq) return QFC_ERR_INVALID_ARG;
+    if (!r->h_out && !r->y && !r->xq && !r->consumer) return QFC_ERR_INVALID_ARG;
+    if (r->consumer) {
+        qfc_handle_t c = r->consumer;
+        if (!valid(c) || c->geo.K != K || M <= kMaxDecodeM) return QFC_ERR_INVALID_ARG;
+        if (!int8_prefill(c) || c->geo.pair_half) return QFC_ERR_UNSUPPORTED;
+        if (!c->workspace || c->workspace_bytes < workspace_need(c, M)) return QFC_ERR_BUFFER_TOO_SMALL;
+    }
     if ((r->xq == nullptr) != (r->sx == nullptr)) return QFC_ERR_INVALID_ARG;
     if (!(r->eps >= 0.0f)) return QFC_ERR_INVALID_ARG;
     if (K > 14336) return QFC_ERR_UNSUPPORTED;
@@ -287,6 +293,23 @@ qfc_status_t qfc_rmsnorm(const qfc_rmsnorm_t *r, int32_t M, int32_t K, void *str
     a.sx = r->sx;
     a.eps = r->eps;
     a.gamma_offset = r->gamma_offset;
+    if (r->consumer) {
+        // the row-major outputs, if asked for, by a launch of their own; then the tiled ones
+        qfc_handle_t c = r->consumer;
+        if (r->xq) {
+            RmsNormArgs b = a;
+            b.h_out = nullptr;
+            b.y = nullptr;
+            if (launch_rmsnorm(b, M, K, cus, static_cast<hipStream_t>(stream)) != hipSuccess) return QFC_ERR_HIP;
+        }
+        const int Mp = prefill_rows(M);
+        char *body = static_cast<char *>(c->workspace);
+        a.xq = reinterpret_cast<int8_t *>(body);
+        a.sx = reinterpret_cast<float *>(body + (size_t)Mp * c->geo.Kp);
+        a.tiled = c->geo.fmt == kW4C ? 2 : 1;
+        a.Mp = Mp;
+        a.Kp = c->geo.Kp;
+    }
     return hip_status(launch_rmsnorm(a, M, K, cus, static_cast<hipStream_t>(stream)));
 }
 
@@ -352,6 +375,18 @@ qfc_status_t qfc_attention(const void *q, const void *kcache, const void *vcache
 
 qfc_status_t qfc_forward_q8(qfc_handle_t h, const int8_t *xq, const float *sx, int32_t M, void *y_f16,
                             void *stream) {
+    if (!xq && !sx) {
+        // the activations a preceding qfc_rmsnorm with consumer == h left in the workspace
+        if (!valid(h) || !y_f16 || M <= kMaxDecodeM) return QFC_ERR_INVALID_ARG;
+        if (!aligned16(y_f16)) return QFC_ERR_ALIGNMENT;
+        if (!int8_prefill(h) || h->geo.pair_half) return QFC_ERR_UNSUPPORTED;
+        if (!h->workspace || h->workspace_bytes < workspace_need(h, M)) return QFC_ERR_BUFFER_TOO_SMALL;
+        const int Mp = prefill_rows(M);
+        char *body = static_cast<char *>(h->workspace);
+        return hip_status(launch_gemm_i8(h->geo, h->packed, reinterpret_cast<const int8_t *>(body),
+                                         reinterpret_cast<const float *>(body + (size_t)Mp * h->geo.Kp), M, Mp, y_f16, 0,
+                                         nullptr, -1, h->num_cus, static_cast<hipStream_t>(stream)));
+    }
     if (!sx || !y_f16) return QFC_ERR_INVALID_ARG;
     if (!aligned16(y_f16) || (reinterpret_cast<uintptr_t>(sx) & 3u)) return QFC_ERR_ALIGNMENT;
     if (valid(h) && h->geo.pair_half) return QFC_ERR_UNSUPPORTED;

@@ -303,6 +303,7 @@ struct RmsNormArgs {
     int8_t *xq;
     float *sx;
     float eps, gamma_offset;
+    int tiled = 0, Mp = 0, Kp = 0;  // tiled output for an int8 prefill layer (see the kernel)
 };
 hipError_t launch_rmsnorm(const RmsNormArgs &a, int M, int K, int num_cus, hipStream_t st);
 // Attention-side operators (see qfc_rope_qkv / qfc_attention).  G = batch * h_kv groups.

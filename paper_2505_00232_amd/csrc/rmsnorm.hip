@@ -23,6 +23,10 @@ struct RmsDev {
     float *sx;
     float eps, goff;
     int M, K;
+    // tiled != 0: xq / sx are the tiled activations and scales of an int8 prefill layer (see the
+    // activation quantization kernel: 1 = order of 8-bit weights, 2 = order of 4-bit weights), padded
+    // with zeros to [Mp, Kp]; the grid then covers Mp rows
+    int tiled, Mp, Kp;
 };
 
 template <int ROWS>
@@ -118,22 +122,30 @@ __global__ __launch_bounds__(128 * ROWS) void rmsnorm_kernel(RmsDev a) {
         scale = am / 127.0f;
         inv = 127.0f / am;
     }
-    if (wave == 0 && lane < ROWS && real) a.sx[m] = scale;
+    if (wave == 0 && lane < ROWS && (real || a.tiled)) a.sx[m] = scale;
 #pragma unroll
     for (int i = 0; i < KEEP; ++i) {
         if (i < steps) {
             const int kt = T * (NW * i + wave) + t;
             const int k0 = kt * 64 + q * 16;
-            if (real && k0 < K) {
-                const h8 h0 = __builtin_bit_cast(h8, keep[i][0]), h1 = __builtin_bit_cast(h8, keep[i][1]);
-                _Float16 v[16];
+            const bool in = real && k0 < K;
+            if (!in && !(a.tiled && kt * 64 < a.Kp)) continue;
+            const h8 h0 = __builtin_bit_cast(h8, keep[i][0]), h1 = __builtin_bit_cast(h8, keep[i][1]);  // (zeros outside the row)
+            _Float16 v[16];
 #pragma unroll
-                for (int e = 0; e < 8; ++e) {
-                    v[e] = h0[e];
-                    v[8 + e] = h1[e];
-                }
-                a.xq[(size_t)m * (K / 16) + kt * 4 + q] =
-                    make_uint4(quant4(v, inv), quant4(v + 4, inv), quant4(v + 8, inv), quant4(v + 12, inv));
+            for (int e = 0; e < 8; ++e) {
+                v[e] = h0[e];
+                v[8 + e] = h1[e];
+            }
+            const uint4 out = make_uint4(quant4(v, inv), quant4(v + 4, inv), quant4(v + 8, inv), quant4(v + 12, inv));
+            if (a.tiled == 2) {
+                uint2 *dst = reinterpret_cast<uint2 *>(a.xq + ((size_t)(m >> 4) * (a.Kp / 64) + kt) * 64 + (m & 15)) + (q >> 1);
+                dst[(2 * (q & 1)) * 16 * 2] = make_uint2(out.x, out.y);
+                dst[(2 * (q & 1) + 1) * 16 * 2] = make_uint2(out.z, out.w);
+            } else if (a.tiled) {
+                a.xq[((size_t)(m >> 4) * (a.Kp / 64) + kt) * 64 + q * 16 + (m & 15)] = out;
+            } else {
+                a.xq[(size_t)m * (K / 16) + kt * 4 + q] = out;
             }
         }
     }
@@ -155,8 +167,12 @@ hipError_t launch_rmsnorm(const RmsNormArgs &h, int M, int K, int num_cus, hipSt
     a.goff = h.gamma_offset;
     a.M = M;
     a.K = K;
-    const int rows = M >= 16 * num_cus ? 8 : M >= 8 * num_cus ? 4 : 2;
-    const unsigned grid = (unsigned)((M + rows - 1) / rows);
+    a.tiled = h.tiled;
+    a.Mp = h.Mp;
+    a.Kp = h.Kp;
+    const int rows_total = h.tiled ? h.Mp : M;  // (Mp is a multiple of 16)
+    const int rows = rows_total >= 16 * num_cus ? 8 : rows_total >= 8 * num_cus ? 4 : 2;
+    const unsigned grid = (unsigned)((rows_total + rows - 1) / rows);
     if (rows == 8)
         rmsnorm_kernel<8><<<grid, 1024, 0, st>>>(a);
     else if (rows == 4)

@@ -1083,6 +1083,52 @@ def test_rmsnorm_feeds_the_int8_layer():
     layer.close()
 
 
+@pytest.mark.parametrize("fmt", ["w8c", "w4c"])
+@pytest.mark.parametrize("M,K,N", [(40, 512, 300), (300, 2304, 264), (1024, 4096, 512)])
+def test_rmsnorm_writes_the_next_layers_tiled_activations(fmt, M, K, N):
+    """The normalization as the producer of the int8 layer's input: qfc_rmsnorm(consumer = layer) leaves
+    the codes in the layer's workspace in the order its product kernel reads, and qfc_forward_q8 on
+    them (no pass over the activations in between) gives the bits of the two-step route, which in turn
+    is within the tolerance of the oracle's norm -> quantize -> integer product -> rescale."""
+    print(f"rmsnorm -> tiled activations {fmt} M={M} K={K} N={N}", flush=True)
+    fc = synth.FC("t", K, N, fmt)
+    wq, sw = synth.weights(3750, M, N, fc)
+    layer = _layer(wq, sw, fmt, max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    xh = synth.activations(3750, M, N, M, K)
+    rh = synth.activations(3751, M, N, M, K)
+    gh = synth.activations(3752, M, N, 1, K)[0]
+    x, r, gamma = (torch.from_numpy(t).to(DEV) for t in (xh, rh, gh))
+    xq = torch.empty((M, K), dtype=torch.int8, device=DEV)
+    sx = torch.empty((M,), dtype=torch.float32, device=DEV)
+    h_a = torch.empty((M, K), dtype=torch.float16, device=DEV)
+    h_b = torch.empty((M, K), dtype=torch.float16, device=DEV)
+    out_a = torch.empty((M, N), dtype=torch.float16, device=DEV)
+    out_b = torch.full((M, N), 9.0, dtype=torch.float16, device=DEV)
+    binding.qfc_rmsnorm(x, gamma, 1e-5, 1.0, residual=r, h_out=h_a, xq=xq, sx=sx)
+    binding.qfc_forward_q8(layer.handle, xq, sx, out_a)
+    layer.workspace.fill_(0x55)  # whatever the first route left there
+    binding.qfc_rmsnorm(x, gamma, 1e-5, 1.0, residual=r, h_out=h_b, consumer=layer.handle)
+    binding.qfc_forward_q8(layer.handle, None, None, out_b)
+    torch.cuda.synchronize()
+    assert np.array_equal(h_a.cpu().numpy().view(np.uint16), h_b.cpu().numpy().view(np.uint16))
+    assert np.array_equal(out_a.cpu().numpy().view(np.uint16), out_b.cpu().numpy().view(np.uint16))
+    h_ref, y_ref = oracle.rmsnorm(xh, gh, 1e-5, 1.0, rh)
+    assert np.array_equal(h_b.cpu().numpy().view(np.uint16), h_ref.view(np.uint16))
+    # the layer's input is the stored (binary16) y; where the fp32 evaluation of y rounds to the other
+    # neighbour the 8-bit code may move, so this last comparison is to the bound of the integer path
+    ref = oracle.fc_int8_act(y_ref.astype(np.float16), wq, sw)[3]
+    assert _E(out_b.cpu().numpy(), ref) <= 2 * TOL
+    # both outputs at once (row-major codes and the tiled ones)
+    xq2, sx2 = torch.empty_like(xq), torch.empty_like(sx)
+    binding.qfc_rmsnorm(x, gamma, 1e-5, 1.0, residual=r, xq=xq2, sx=sx2, consumer=layer.handle)
+    torch.cuda.synchronize()
+    assert torch.equal(xq2, xq) and torch.equal(sx2, sx)
+    # a decode-size M or a layer of another width is refused
+    with pytest.raises(binding.QfcError):
+        binding.qfc_rmsnorm(x[:4], gamma, 1e-5, 1.0, consumer=layer.handle)
+    layer.close()
+
+
 # ------------------------------------------------------------------ attention-side operators
 def _attn_shape(B, h_q, h_kv, d, C):
     return binding.AttnShape(B, h_q, h_kv, d, C)
