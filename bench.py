@@ -498,6 +498,32 @@ def main():
         extra["prefill_int8_w4c_m1024"] = {**{k: v for k, v in p84.items()},
                                            "frac_mfma_int8_peak": round(p84["total"]["Tops"] / MFMA_I8_PEAK_TOPS, 4),
                                            "note": "int8 activations x int4 per-channel weights -> int32, Llama-3.1-8B layer, M=1024"}
+        # act(gate) * up merged into the gate+up layer's store phase (layer packed in pairs) against the
+        # plain layer followed by PyTorch's element-wise kernels
+        def gated_line(fc, M, seed, act):
+            wq, s = synth.weights(seed, 0, 2, fc)
+            x = torch.from_numpy((synth.activations(seed, 0, 2, M, fc.K) * np.float16(0.125)).astype(np.float16)).to(dev)
+            plain = binding.QuantLinear(wq, s, fc.fmt, max_m=M)
+            paired = binding.QuantLinear(wq, s, fc.fmt, max_m=M, gated_pairs=True)
+            y = torch.empty((M, fc.N), dtype=torch.float16, device=dev)
+            yg = torch.empty((M, fc.N // 2), dtype=torch.float16, device=dev)
+            out = torch.empty_like(yg)
+            half = fc.N // 2
+
+            def unfused():
+                binding.qfc_forward(plain.handle, x, y)
+                torch.mul(torch.nn.functional.silu(y[:, :half]), y[:, half:], out=out)
+
+            fused = lambda: binding.qfc_forward_fused(paired.handle, x, yg, activation=act, gated_output=True)
+            unfused(); fused()
+            ms_u, ms_f = event_ms(unfused, 10), event_ms(fused, 10)
+            plain.close(); paired.close()
+            return {"fused_us": round(ms_f * 1e3, 1), "unfused_us": round(ms_u * 1e3, 1)}
+
+        extra["prefill_gated_output"] = {
+            "int8_llama_gate_up_m1024": gated_line(synth.LLAMA_FCS_W8[2], 1024, 1004, binding.QFC_ACT_SILU),
+            "fp16_gemma_gate_up_m2048": gated_line(synth.GEMMA_FCS_W4[2], 2048, 1005, binding.QFC_ACT_SILU),
+            "note": "act(gate) * up in the store phase of the product kernel vs product + PyTorch silu and mul kernels"}
         lm = prefill([synth.GEMMA_LM_HEAD], 2048, 1005, reps=3)
         extra["prefill_int8_lm_head_m2048"] = {"us": lm["total"]["us"], "Tops": lm["total"]["Tops"],
                                                "frac_mfma_int8_peak": round(lm["total"]["Tops"] / MFMA_I8_PEAK_TOPS, 4),
