@@ -683,6 +683,150 @@ hipError_t launch_dw(GemmI8Args a, hipStream_t st) {
     return hipGetLastError();
 }
 
+// The same direct-weights form for 4-bit per-channel weights.  A stage is 128 k: a lane's two packed
+// vectors of a row (octets h and 2 + h of the 128 codes, h = lane / 32) feed all four k steps of the
+// stage, so a stage costs 4 loads per wavefront where the 8-bit kernel needs 8 for the same k, and
+// the activations (two KiB tiles per 16 token rows and stage, in the k order of the packed dwords)
+// are the only operand in LDS.  The codes are expanded as in the kernel above.  Waiting, the spare
+// KiB for copies past the end of K and the hand-back of the load destinations are those of the
+// 8-bit kernel; the operand reads of a k step are left to the compiler (they wait on the LDS
+// counter, which no asm here touches).
+template <int NS, int PW, int TM, int OUT_MODE>
+__global__ __launch_bounds__(256, 2) void gemm_i8_dw4_kernel(GemmI8Args a) {
+    constexpr int BN = 256, BM = 32 * TM, TN = 2;
+    constexpr int XT = BM / 16 * 2;  // activation tiles (KiB) per stage
+    constexpr int CP = XT / 4;       // copies per wavefront and stage
+    static_assert(NS >= 3 && (TM == 2 || TM == 4), "tile shapes");
+    extern __shared__ uint4 lds[];  // NS stages of XT tiles x 64 vectors
+    const int lane = threadIdx.x & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
+    const int total = a.n_tiles * a.m_tiles;
+    int logical = blockIdx.x;
+    if (total % 8 == 0) logical = (blockIdx.x % 8) * (total / 8) + blockIdx.x / 8;
+    const int nt = logical / a.m_tiles, mt = logical % a.m_tiles;
+    const int KT = a.Kp / 128;  // stages
+
+    // weights: vector v of operand row tile i = rows 32 i + (lane & 31) of the wavefront's 64, octet 2 v + lane / 32
+    const uint4 *wsrc[TN];
+#pragma unroll
+    for (int i = 0; i < TN; ++i) {
+        const int row = 32 * i + (lane & 31);
+        wsrc[i] = a.w + ((size_t)(nt * (BN / 16) + 4 * wave + (row >> 4)) * KT) * 64 + (lane >> 5) * 16 + (row & 15);
+    }
+    v4i wreg[PW][TN][2];
+    auto load_w = [&](int slot, int kt, const bool bulk) __attribute__((always_inline)) {  // bulk: kt < KT is known
+        const int kc = bulk || kt < KT ? kt : min(kt - KT, KT - 1);
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int v = 0; v < 2; ++v)
+                asm volatile("global_load_dwordx4 %0, %1, off"
+                             : "=&v"(wreg[slot][i][v])
+                             : "v"(wsrc[i] + (size_t)kc * 64 + v * 32)
+                             : "memory");
+    };
+    // activations: tile t = 2 g + e of a stage is half e of the stage's 128 k for token rows 16 g ..
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)lds;
+    const uint4 *xsrc = a.x + ((size_t)(mt * (BM / 16)) * 2 * KT) * 64;
+    constexpr uint32_t kSpare = NS * XT * 1024;  // copies past the end of K land here; nothing reads it
+    auto issue_x = [&](int kt, const bool bulk) __attribute__((always_inline)) {
+        const bool real = bulk || kt < KT;
+        const int kc = real ? kt : min(kt - KT, KT - 1);
+#pragma unroll
+        for (int h = 0; h < CP; ++h) {
+            const int t = wave + 4 * h;
+            copy16_to_lds(xsrc + ((size_t)(t >> 1) * 2 * KT + 2 * kc + (t & 1)) * 64, lane * 16,
+                          lds0 + (real ? ((kt % NS) * XT + t) * 1024 : kSpare));
+        }
+    };
+
+    v16i acc[TN][TM];
+#pragma unroll
+    for (int i = 0; i < TN; ++i)
+#pragma unroll
+        for (int j = 0; j < TM; ++j)
+#pragma unroll
+            for (int e = 0; e < 16; ++e) acc[i][j][e] = 0;
+
+    constexpr bool kBulk = true, kEdge = false;
+#pragma unroll
+    for (int p = 0; p < PW; ++p) load_w(p, p, kEdge);
+#pragma unroll
+    for (int p = 0; p < NS - 1; ++p) issue_x(p, kEdge);
+
+    // (see the 8-bit kernel: at most kAllowed operations outstanding means stage kt's copies and loads are done)
+    constexpr int kAfterCopies = CP * (NS - 2), kAfterLoads = 4 * (PW - 1);
+    constexpr int kAllowed = kAfterCopies < kAfterLoads ? kAfterCopies : kAfterLoads;
+    static_assert(CP * (NS - 1) + 4 * PW <= 63, "wait counts must fit the 6-bit counter");
+
+    auto stages_pw = [&](int kt0, const bool bulk) __attribute__((always_inline)) {
+#pragma unroll
+        for (int u = 0; u < PW; ++u) {
+            const int kt = kt0 + u;
+            wait_vmcnt<kAllowed>();
+            asm volatile("s_barrier" ::: "memory");
+#pragma unroll
+            for (int i = 0; i < TN; ++i)
+#pragma unroll
+                for (int v = 0; v < 2; ++v) asm volatile("" : "+v"(wreg[u][i][v]));
+            issue_x(kt + NS - 1, bulk);
+            const uint4 *lx = lds + (kt % NS) * (XT * 64);
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) {  // k step = (dword pair, vector) = (ks >> 1, ks & 1)
+                v4i fa[TN], fb[TM];
+#pragma unroll
+                for (int i = 0; i < TN; ++i) {
+                    const uint32_t px = (uint32_t)wreg[u][i][ks & 1][2 * (ks >> 1)];
+                    const uint32_t py = (uint32_t)wreg[u][i][ks & 1][2 * (ks >> 1) + 1];
+                    fa[i][0] = (int)(((px << 4) & 0xF0F0F0F0u) ^ 0x80808080u);
+                    fa[i][1] = (int)((px & 0xF0F0F0F0u) ^ 0x80808080u);
+                    fa[i][2] = (int)(((py << 4) & 0xF0F0F0F0u) ^ 0x80808080u);
+                    fa[i][3] = (int)((py & 0xF0F0F0F0u) ^ 0x80808080u);
+                }
+                const int kc = 2 * ks + (lane >> 5);  // 16-code chunk inside the stage: tile kc >> 2, quarter kc & 3
+                const int koff = (kc >> 2) * 64 + (kc & 3) * 16;
+#pragma unroll
+                for (int j = 0; j < TM; ++j) {
+                    const int row = 32 * j + (lane & 31);
+                    fb[j] = __builtin_bit_cast(v4i, lx[(row >> 4) * 128 + koff + (row & 15)]);
+                }
+#pragma unroll
+                for (int i = 0; i < TN; ++i)
+#pragma unroll
+                    for (int j = 0; j < TM; ++j)
+                        acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+            }
+            load_w(u, kt + PW, bulk);
+        }
+    };
+    constexpr int kAhead = NS - 1 > PW ? NS - 1 : PW;  // how far past kt a pass issues
+    int kt0 = 0;
+    for (; kt0 + PW - 1 + kAhead < KT; kt0 += PW) stages_pw(kt0, kBulk);
+    for (; kt0 < KT; kt0 += PW) stages_pw(kt0, kEdge);
+    wait_vmcnt<0>();
+#pragma unroll
+    for (int p = 0; p < PW; ++p)
+#pragma unroll
+        for (int i = 0; i < TN; ++i)
+#pragma unroll
+            for (int v = 0; v < 2; ++v) asm volatile("" ::"v"(wreg[p][i][v]) : "memory");
+    epilogue<OUT_MODE, TN, TM>(a, acc, lds, nt * BN + wave * 64, mt * BM, wave, lane);
+}
+
+template <int NS, int PW, int TM, int OUT_MODE>
+hipError_t launch_dw4(GemmI8Args a, hipStream_t st) {
+    constexpr size_t ring_bytes = (size_t)NS * (4 * TM) * 1024;  // + one spare KiB for the copies past the end of K
+    constexpr size_t lds_bytes = ring_bytes + 1024;
+    static_assert(ring_bytes >= 4 * 32 * (64 + 8) * 2, "the store phase stages its blocks inside the ring, below the spare KiB");
+    static_assert(lds_bytes <= 80 * 1024, "two workgroups per compute unit");
+    if ((a.Kp / 128) % PW != 0) return hipErrorInvalidValue;
+    if (const hipError_t e = allow_dynamic_lds<gemm_i8_dw4_kernel<NS, PW, TM, OUT_MODE>>(lds_bytes); e != hipSuccess) return e;
+    a.n_tiles = (a.N + 255) / 256;
+    a.m_tiles = (a.M + 32 * TM - 1) / (32 * TM);
+    gemm_i8_dw4_kernel<NS, PW, TM, OUT_MODE><<<dim3((unsigned)(a.n_tiles * a.m_tiles)), 256, lds_bytes, st>>>(a);
+    return hipGetLastError();
+}
+
 template <int BN, int BM, int KTS, int NS, int OUT_MODE>
 hipError_t launch_variant(GemmI8Args a, hipStream_t st) {
     constexpr size_t lds_bytes = (size_t)NS * ((BN + BM) / 16 * KTS) * 1024;
@@ -736,6 +880,23 @@ hipError_t launch_mode(const GemmI8Args &a, int num_cus, hipStream_t st) {
     }
 }
 
+template <int OUT_MODE>
+hipError_t launch_mode_w4(const GemmI8Args &a, int num_cus, hipStream_t st) {
+    int variant = tuning().gemm_variant;
+    const int stages = a.Kp / 128;
+    if (variant == 0) {
+        const long big_tiles = (long)((a.N + 255) / 256) * ((a.M + 127) / 128);
+        variant = stages % 2 != 0 ? 20 : 4 * big_tiles >= 3L * num_cus ? 21 : 23;
+    }
+    switch (variant) {
+        case 21: return launch_dw4<4, 2, 4, OUT_MODE>(a, st);
+        case 22: return launch_dw4<4, 4, 4, OUT_MODE>(a, st);
+        case 23: return launch_dw4<8, 2, 2, OUT_MODE>(a, st);
+        case 24: return launch_dw4<8, 4, 2, OUT_MODE>(a, st);
+        default: return launch_w4<128, 128, 3, OUT_MODE>(a, st);
+    }
+}
+
 }  // namespace
 
 hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *xq_tiled,
@@ -757,7 +918,7 @@ hipError_t launch_gemm_i8(const Geometry &g, const void *packed, const int8_t *x
     if (g.fmt == kW4C) {
         a.sw_mul = 0.0625f;
         a.acc_shift = 4;
-        return out_mode == 0 ? launch_w4<128, 128, 3, 0>(a, st) : launch_w4<128, 128, 3, 1>(a, st);
+        return out_mode == 0 ? launch_mode_w4<0>(a, num_cus, st) : launch_mode_w4<1>(a, num_cus, st);
     }
     return out_mode == 0 ? launch_mode<0>(a, num_cus, st) : launch_mode<1>(a, num_cus, st);
 }

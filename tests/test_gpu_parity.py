@@ -346,6 +346,30 @@ def test_int8_prefill_other_tile_shapes_bit_exact(variant):
     layer.close()
 
 
+@pytest.mark.parametrize("variant", [20, 21, 22, 23, 24])
+def test_int8_prefill_int4_weights_tile_shapes_bit_exact(variant):
+    """The kernels of the int8 x int4 product (both operands staged; weights straight into registers
+    with two tile widths and two prefetch depths), forced on a ragged shape."""
+    print(f"int8 x int4 prefill tile variant {variant}", flush=True)
+    M, N, K = 300, 520, 1024
+    fc = synth.FC("t", K, N, "w4c")
+    wq, sw = synth.weights(4600, M, N, fc)
+    x = synth.activations(4600, M, N, M, K)
+    xq_ref, sx_ref, acc_ref, y_ref = oracle.fc_int8_act(x, wq, sw)
+    layer = _layer(wq, sw, "w4c", max_m=M, mode=binding.QFC_COMPUTE_INT8_ACT)
+    binding.qfc_tune(2, variant)
+    try:
+        for rep in range(3):
+            acc = torch.full((M, N), -1, dtype=torch.int32, device=DEV)
+            binding.qfc_forward_acc_i32(layer.handle, torch.from_numpy(xq_ref).to(DEV), acc)
+            y = _forward(layer, x)
+            assert np.array_equal(acc.cpu().numpy().astype(np.int64), acc_ref), rep
+            assert _E(y, y_ref) <= TOL, rep
+    finally:
+        binding.qfc_tune(2, 0)
+    layer.close()
+
+
 def test_int8_prefill_config4_shapes_sampled():
     """Llama layer at M = 1024, int8 per-channel weights: accumulators of a
     sample of (token, channel) pairs against the exact integer contraction."""
