@@ -204,47 +204,55 @@ def main():
             l.close()
         return ms, nbytes
 
-    # ------------------------------------------------------------ the paper's own scheme ("8/4/4", section 4.2)
-    # int4 per-channel weights in the FCs, int8 per-channel LM head: the same decode step with
-    # 0.5 B per weight instead of 0.5625.
+    # ------------------------------------------------------------ the paper's own schemes (section 4.2)
+    # per-channel scales everywhere.  "8/4/4": int8 attention projections, int4 feed-forward and
+    # embedding (= LM head) weights; "q8": int8 everywhere.  The same decode step, other formats.
+    def decode_scheme(fc_list, seed, mode=None, xs=None):
+        ls = []
+        own_xs = xs is None
+        xs = [] if own_xs else xs
+        for layer, i, fc in fc_list:
+            wq, s = synth.weights(seed, layer, i, fc)
+            ls.append(binding.QuantLinear(wq, s, fc.fmt, max_m=8) if mode is None else
+                      binding.QuantLinear(wq, s, fc.fmt, compute_mode=mode, max_m=8))
+            if own_xs:
+                xs.append(torch.from_numpy(synth.activations(seed, layer, i, 1, fc.K)).to(dev))
+            del wq, s
+        ys = [torch.empty((1, l.N), dtype=torch.float16, device=dev) for l in ls]
+        fb = binding.ForwardBatch([l.handle for l in ls], xs, ys, 1)
+        fb.run()
+        ms = event_ms(fb.run, args.steps)
+        nbytes = sum(synth.algorithmic_bytes(fc, 1) for _, _, fc in fc_list)
+        for l in ls:
+            l.close()
+        del ls, ys, fb
+        torch.cuda.empty_cache()
+        return xs, {"ms_per_step": round(ms, 4), "GB/s": round(nbytes / (ms * 1e-3) / 1e9, 1),
+                    "frac_hbm_peak": round(nbytes / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                    "tokens_per_s": round(1 / (ms * 1e-3), 1), "algorithmic_bytes_per_step": nbytes}
+
+    def as_fmt(fc, fmt):
+        return synth.FC(fc.name, fc.K, fc.N, fmt)
+
+    mixed = [(layer, i, as_fmt(fc, "w8c" if fc.name in ("qkv", "o") else "w4c"))
+             for layer in range(args.layers) for i, fc in enumerate(synth.LLAMA_FCS_W4C)]
+    mixed.append((args.layers, 4, as_fmt(synth.LLAMA_LM_HEAD, "w4c")))
+    _, extra["decode_m1_mixed_8_4_4"] = decode_scheme(mixed, SEED + 200)
+    q8 = [(layer, i, as_fmt(fc, "w8c")) for layer, i, fc in mixed]
+    _, extra["decode_m1_q8"] = decode_scheme(q8, SEED + 300)
+    # int4 per-channel weights in all four FCs, int8 per-channel LM head
     fcs_pc = [(layer, i, fc) for layer in range(args.layers) for i, fc in enumerate(synth.LLAMA_FCS_W4C)]
     fcs_pc.append((args.layers, 4, synth.LLAMA_LM_HEAD))
-    ls_pc, xs_pc = [], []
-    for layer, i, fc in fcs_pc:
-        wq, s = synth.weights(SEED + 100, layer, i, fc)
-        ls_pc.append(binding.QuantLinear(wq, s, fc.fmt, max_m=8))
-        xs_pc.append(torch.from_numpy(synth.activations(SEED + 100, layer, i, 1, fc.K)).to(dev))
-        del wq, s
-    ys_pc = [torch.empty((1, l.N), dtype=torch.float16, device=dev) for l in ls_pc]
-    fb_pc = binding.ForwardBatch([l.handle for l in ls_pc], xs_pc, ys_pc, 1)
-    fb_pc.run()
-    ms_pc = event_ms(fb_pc.run, args.steps)
-    bytes_pc = sum(synth.algorithmic_bytes(fc, 1) for _, _, fc in fcs_pc)
-    extra["decode_m1_int4_per_channel"] = {"ms_per_step": round(ms_pc, 4), "GB/s": round(bytes_pc / (ms_pc * 1e-3) / 1e9, 1),
-                                           "frac_hbm_peak": round(bytes_pc / (ms_pc * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
-                                           "tokens_per_s": round(1 / (ms_pc * 1e-3), 1),
-                                           "algorithmic_bytes_per_step": bytes_pc}
-    for l in ls_pc:
-        l.close()
-    del ls_pc, ys_pc, fb_pc
-    torch.cuda.empty_cache()
+    xs_pc, extra["decode_m1_int4_per_channel"] = decode_scheme(fcs_pc, SEED + 100)
     # ... and with the paper's decode design: activations quantized to int8 inside the kernel,
     # integer accumulation (section 3.7)
-    ls_q = []
-    for layer, i, fc in fcs_pc:
-        wq, s = synth.weights(SEED + 100, layer, i, fc)
-        ls_q.append(binding.QuantLinear(wq, s, fc.fmt, compute_mode=binding.QFC_COMPUTE_INT8_ACT_DECODE, max_m=8))
-        del wq, s
-    ys_q = [torch.empty((1, l.N), dtype=torch.float16, device=dev) for l in ls_q]
-    fb_q = binding.ForwardBatch([l.handle for l in ls_q], xs_pc, ys_q, 1)
-    fb_q.run()
-    ms_q = event_ms(fb_q.run, args.steps)
-    extra["decode_m1_int4_per_channel_int8_activations"] = {
-        "ms_per_step": round(ms_q, 4), "GB/s": round(bytes_pc / (ms_q * 1e-3) / 1e9, 1),
-        "frac_hbm_peak": round(bytes_pc / (ms_q * 1e-3) / 1e9 / HBM_PEAK_GBS, 4), "tokens_per_s": round(1 / (ms_q * 1e-3), 1)}
-    for l in ls_q:
-        l.close()
-    del ls_q, xs_pc, ys_q, fb_q
+    _, q = decode_scheme(fcs_pc, SEED + 100, mode=binding.QFC_COMPUTE_INT8_ACT_DECODE, xs=xs_pc)
+    q.pop("algorithmic_bytes_per_step")
+    extra["decode_m1_int4_per_channel_int8_activations"] = q
+    _, q = decode_scheme(mixed, SEED + 200, mode=binding.QFC_COMPUTE_INT8_ACT_DECODE)
+    q.pop("algorithmic_bytes_per_step")
+    extra["decode_m1_mixed_8_4_4_int8_activations"] = q
+    del xs_pc
     torch.cuda.empty_cache()
 
     ms_c1, b_c1 = rotating([synth.CFG1_FC], 1001, 512)
@@ -498,6 +506,12 @@ def main():
         extra["prefill_int8_w4c_m1024"] = {**{k: v for k, v in p84.items()},
                                            "frac_mfma_int8_peak": round(p84["total"]["Tops"] / MFMA_I8_PEAK_TOPS, 4),
                                            "note": "int8 activations x int4 per-channel weights -> int32, Llama-3.1-8B layer, M=1024"}
+        mixed_us = p8["qkv"]["us"] + p8["o"]["us"] + p84["gate_up"]["us"] + p84["down"]["us"]
+        mixed_ops = 2.0 * 1024 * sum(fc.N * fc.K for fc in synth.LLAMA_FCS_W8)
+        extra["prefill_int8_mixed_8_4_4_m1024"] = {
+            "us": round(mixed_us, 1), "Tops": round(mixed_ops / (mixed_us * 1e-6) / 1e12, 1),
+            "frac_mfma_int8_peak": round(mixed_ops / (mixed_us * 1e-6) / 1e12 / MFMA_I8_PEAK_TOPS, 4),
+            "note": "int8 attention projections + int4 feed-forward projections (the two layers above, summed), int8 activations"}
         # act(gate) * up merged into the gate+up layer's store phase (layer packed in pairs) against the
         # plain layer followed by PyTorch's element-wise kernels
         def gated_line(fc, M, seed, act):
