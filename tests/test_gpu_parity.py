@@ -261,7 +261,7 @@ def test_int8_prefill_whole_output_against_oracle(M, N, K):
 
 # The paper's own "8/4/4" scheme in the prefill stage: int8 activations x int4 per-channel weights
 @pytest.mark.parametrize("M,N,K", [(9, 1, 32), (100, 130, 96), (200, 300, 512), (256, 1000, 2304), (130, 64, 14336),
-                                   (513, 264, 128), (300, 4096, 1152)])
+                                   (513, 264, 128), (300, 4096, 1152), (77, 300, 256)])
 def test_int8_prefill_int4_weights_matches_oracle(M, N, K):
     print(f"int8 x int4 prefill M={M} N={N} K={K}", flush=True)
     fc = synth.FC("t", K, N, "w4c")
