@@ -40,6 +40,9 @@ def parse():
     p.add_argument("--traffic-probe", action="store_true",
                    help="for rocprofv3 --pmc runs: a few plain copies of a 1 GiB buffer (calibration of "
                         "FETCH_SIZE / WRITE_SIZE) followed by a few decode steps, then exit")
+    p.add_argument("--probe-mfma", action="store_true",
+                   help="measure what rate and shader clock a register-only MFMA loop holds with constant and "
+                        "with random operands (context for the prefill rooflines), print it as JSON, exit")
     return p.parse_args()
 
 
@@ -59,6 +62,31 @@ def main():
     binding.lib()  # fail loudly if the HIP library is missing
     dev = "cuda"
     SEED = 1003
+
+    if args.probe_mfma:
+        out = {}
+        for kind, name, ops in ((0, "int8 v_mfma_i32_32x32x32_i8", 65536.0), (1, "fp16 v_mfma_f32_32x32x16_f16", 32768.0)):
+            for random_operands in (False, True):
+                wgs, iters = 512, 20000  # two wavefronts per SIMD; about 10 ms per launch at full rate
+                ticks = torch.zeros((wgs, 2), dtype=torch.int64, device=dev)
+                launch = lambda: binding.qfc_probe_mfma(kind, random_operands, iters, wgs, ticks)
+                for _ in range(15):  # 150 ms and more of the same load first
+                    launch()
+                torch.cuda.synchronize()
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                for _ in range(5):
+                    launch()
+                e1.record()
+                torch.cuda.synchronize()
+                ms = e0.elapsed_time(e1) / 5
+                t = ticks.cpu().numpy().astype(np.float64)
+                out[f"{name}, {'random' if random_operands else 'constant'} operands"] = {
+                    "Tops": round(ops * 32 * iters * wgs * 4 / (ms * 1e-3) / 1e12, 1),
+                    "shader_clock_MHz": round(float((t[:, 0] / (t[:, 1] / 100.0)).mean()), 1),
+                    "ms_per_launch": round(ms, 3)}
+        print(json.dumps({"probe": "register-only MFMA loop, 512 workgroups x 4 wavefronts, 640000 MFMAs per wavefront", "results": out}))
+        return
 
     def event_ms(fn, reps):
         e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)

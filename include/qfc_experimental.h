@@ -12,6 +12,8 @@
 
 #include <stdint.h>
 
+#include "qfc.h"
+
 #ifdef __cplusplus
 extern "C" {
 #endif
@@ -28,6 +30,17 @@ extern "C" {
  *   key 6  causal walks of prefill attention cut into chunks (-1 automatic, 0 never, 1 always);
  *          qfc_attention_workspace_size follows the value set when it is called */
 void qfc_tune(int32_t key, int32_t value);
+
+/* Measurement probe (bench.py --probe-mfma): `workgroups` workgroups of four wavefronts each issue
+ * 32 * iters back-to-back MFMAs from registers, no memory traffic (kind 0: v_mfma_i32_32x32x32_i8,
+ * 65536 operations each; kind 1: v_mfma_f32_32x32x16_f16, 32768 each), with constant operands
+ * (random_operands = 0) or operands of random bits used in rotation (1).  ticks (device, 8-byte
+ * aligned, 2 * workgroups entries, written by the kernel): per workgroup the shader-clock ticks
+ * and the ticks of the constant 100 MHz counter over the loop.  The caller times the launch.
+ * Errors: QFC_ERR_INVALID_ARG (kind, iters outside 1 .. 2^22, workgroups outside 1 .. 4096, null),
+ * QFC_ERR_ALIGNMENT, QFC_ERR_HIP. */
+qfc_status_t qfc_probe_mfma(int32_t kind, int32_t random_operands, int32_t iters, int32_t workgroups,
+                            uint64_t *ticks, void *stream);
 
 #ifdef __cplusplus
 }

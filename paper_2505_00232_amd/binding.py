@@ -92,6 +92,8 @@ def lib() -> ctypes.CDLL:
         L.qfc_status_string.restype = ctypes.c_char_p
         L.qfc_tune.argtypes = [i32, i32]
         L.qfc_tune.restype = None
+        L.qfc_probe_mfma.argtypes = [i32, i32, i32, i32, vp, vp]
+        L.qfc_probe_mfma.restype = ctypes.c_int
         for name in EXPORTS:
             if name != "qfc_status_string":
                 getattr(L, name).restype = ctypes.c_int
@@ -345,6 +347,13 @@ def qfc_destroy(h):
 
 def qfc_tune(key: int, value: int):
     lib().qfc_tune(key, value)
+
+
+def qfc_probe_mfma(kind: int, random_operands: bool, iters: int, workgroups: int, ticks):
+    """Measurement probe of qfc_experimental.h: ticks = int64 device tensor [workgroups, 2]."""
+    _want(ticks, torch.int64, (workgroups, 2), "ticks")
+    _check(lib().qfc_probe_mfma(kind, int(bool(random_operands)), iters, workgroups, _ptr(ticks), _stream()),
+           "qfc_probe_mfma")
 
 
 class QuantLinear:

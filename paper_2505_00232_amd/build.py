@@ -13,7 +13,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 LIB = os.path.join(HERE, "libqfc.so")
-SOURCES = ["api.hip", "pack.hip", "gemv.hip", "gemv_q8.hip", "actquant.hip", "rmsnorm.hip", "attention.hip", "gemm_i8.hip", "gemm_f16.hip"]
+SOURCES = ["api.hip", "pack.hip", "gemv.hip", "gemv_q8.hip", "actquant.hip", "rmsnorm.hip", "attention.hip", "gemm_i8.hip", "gemm_f16.hip", "probe.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-unused-function",
          # packed-fp32 code generation is switched off on purpose
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]

@@ -34,7 +34,7 @@ def test_header_symbols_are_exported(L):
     for name in declared:
         assert hasattr(L, name), name
     experimental = _declared("qfc_experimental.h")
-    assert experimental == {"qfc_tune"}
+    assert experimental == {"qfc_tune", "qfc_probe_mfma"}
     nm = subprocess.run(["nm", "-D", "--defined-only", binding.LIB_PATH], capture_output=True, text=True, check=True)
     exported = {ln.split()[-1] for ln in nm.stdout.splitlines() if len(ln.split()) >= 3 and ln.split()[-2] in "TW"}
     assert {e for e in exported if e.startswith("qfc_")} == declared | experimental

@@ -1462,3 +1462,21 @@ def test_decode_norm_merged_into_layer(fmt, N, K):
         torch.cuda.synchronize()
         assert _E(y_b.cpu().numpy(), y_a.cpu().numpy().astype(np.float64)) <= 2 * TOL
     layer.close()
+
+
+def test_probe_mfma_runs_and_rejects_bad_arguments():
+    """The measurement probe of qfc_experimental.h: a short run writes both counters of every
+    workgroup; arguments outside its documented ranges are refused before any launch."""
+    print("mfma probe", flush=True)
+    for kind in (0, 1):
+        ticks = torch.zeros((8, 2), dtype=torch.int64, device=DEV)
+        binding.qfc_probe_mfma(kind, True, 10, 8, ticks)
+        torch.cuda.synchronize()
+        t = ticks.cpu().numpy()
+        assert (t > 0).all()
+    ticks = torch.zeros((8, 2), dtype=torch.int64, device=DEV)
+    for args in ((2, True, 10, 8), (0, True, 0, 8), (0, True, (1 << 22) + 1, 8)):
+        with pytest.raises(binding.QfcError):
+            binding.qfc_probe_mfma(*args, ticks)
+    with pytest.raises(ValueError):
+        binding.qfc_probe_mfma(0, True, 10, 4097, ticks)
