@@ -1,11 +1,12 @@
 /*
- * qfc_experimental - knobs of libqfc.so that are NOT part of its interface.
+ * qfc_experimental - knobs and a probe of libqfc.so that are NOT part of its interface.
  *
- * Used by this repository's tests and parameter sweeps to force a kernel
- * variant that the dispatcher would not pick for a given shape (so that every
- * variant can be checked on small inputs).  Nothing here follows a passage of
- * the paper, nothing here is needed to use the library, and it may change
- * without notice.  Production callers include qfc.h only.
+ * qfc_tune is used by this repository's tests and parameter sweeps to force a
+ * kernel variant that the dispatcher would not pick for a given shape (so that
+ * every variant can be checked on small inputs); qfc_probe_mfma is a
+ * measurement aid of bench.py.  Nothing here follows a passage of the paper,
+ * nothing here is needed to use the library, and it may change without
+ * notice.  Production callers include qfc.h only.
  */
 #ifndef QFC_EXPERIMENTAL_H
 #define QFC_EXPERIMENTAL_H
