@@ -964,14 +964,16 @@ def test_prefill_gated_output(fmt, mode, M, N, K):
 
 
 def test_prefill_gated_output_llama_gate_up_sampled():
-    """The gate+up layer of Llama-3.1-8B at M = 1024 (int8 activations, 8-bit weights) and of Gemma2-2B at
-    M = 2048 (fp16, int4 group-32), packed in pairs: sampled rows and channels against the oracle."""
+    """The gate+up layer of Llama-3.1-8B at M = 1024 (int8 activations, 8-bit and 4-bit per-channel weights)
+    and of Gemma2-2B at M = 2048 (fp16, int4 group-32), packed in pairs: sampled rows and channels
+    against the oracle."""
     rng = np.random.default_rng(46)
-    for fc, M, seed in ((synth.LLAMA_FCS_W8[2], 1024, 1004), (synth.GEMMA_FCS_W4[2], 2048, 1005)):
+    for fc, M, seed, mode in ((synth.LLAMA_FCS_W8[2], 1024, 1004, None), (synth.GEMMA_FCS_W4[2], 2048, 1005, None),
+                              (synth.LLAMA_FCS_W4C[2], 1024, 1104, binding.QFC_COMPUTE_INT8_ACT)):
         print(f"prefill gated output {fc.name} {fc.fmt} {fc.K}->{fc.N} M={M}", flush=True)
         wq, s = synth.weights(seed, 0, 2, fc)
         x = (synth.activations(seed, 0, 2, M, fc.K) * np.float16(0.125)).astype(np.float16)
-        layer = binding.QuantLinear(wq, s, fc.fmt, max_m=M, gated_pairs=True)
+        layer = binding.QuantLinear(wq, s, fc.fmt, compute_mode=mode, max_m=M, gated_pairs=True)
         y = torch.empty((M, fc.N // 2), dtype=torch.float16, device=DEV)
         binding.qfc_forward_fused(layer.handle, torch.from_numpy(x).to(DEV), y, activation=binding.QFC_ACT_SILU,
                                   gated_output=True)
@@ -981,7 +983,7 @@ def test_prefill_gated_output_llama_gate_up_sampled():
         cols = np.sort(rng.choice(half, size=256, replace=False))
         rows[0], rows[-1], cols[0], cols[-1] = 0, M - 1, 0, half - 1
         both = np.concatenate([cols, cols + half])
-        if fc.fmt == "w8c":
+        if fc.fmt == "w8c" or mode == binding.QFC_COMPUTE_INT8_ACT:
             full = oracle.fc_int8_act(x[rows], wq[both], s[both])[3]
         else:
             full = oracle.fc_weight_only(x[rows], wq[both], s[both], 32)
