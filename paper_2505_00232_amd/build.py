@@ -19,6 +19,28 @@ FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wno-u
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops"]
 
 
+# Kernels that load MFMA operands into registers with hand-written asynchronous loads and place the
+# waits themselves: the compiler takes a destination register to be valid right after the load
+# instruction, so if it spilled one it would save the stale value.  The build refuses any spill
+# in these kernels (mangled-name fragments per source file).
+NO_SPILL = {"gemm_i8.hip": ("gemm_i8_dw_kernel", "gemm_i8_dw4_kernel")}
+
+
+def _spilling_kernels(remarks: list[str], fragments: tuple[str, ...]) -> list[str]:
+    """Names of the kernels matching `fragments` whose resource-usage remarks report scratch memory."""
+    import re
+    bad, name = [], None
+    for line in remarks:
+        m = re.search(r"Function Name: (\S+)", line)
+        if m:
+            name = m.group(1)
+            continue
+        m = re.search(r"(ScratchSize \[bytes/lane\]|VGPRs Spill|SGPRs Spill): (\d+)", line)
+        if m and name and any(f in name for f in fragments) and int(m.group(2)) != 0 and name not in bad:
+            bad.append(name)
+    return bad
+
+
 def _hipcc() -> str:
     for c in (os.environ.get("HIPCC"), "/opt/rocm/bin/hipcc", "hipcc"):
         if c and (os.path.isabs(c) and os.path.exists(c) or not os.path.isabs(c)):
@@ -43,8 +65,16 @@ def build(force: bool = False, verbose: bool = False) -> str:
     def compile_one(src: str) -> str:
         obj = os.path.join(OBJ, src.replace(".hip", ".o"))
         cmd = [cc, *FLAGS, "-c", os.path.join(CSRC, src), "-o", obj]
+        if src in NO_SPILL:
+            cmd.append("-Rpass-analysis=kernel-resource-usage")
         r = subprocess.run(cmd, capture_output=True, text=True)
-        err = "\n".join(l for l in r.stderr.splitlines() if "packed-fp32-ops" not in l)
+        lines = r.stderr.splitlines()
+        if src in NO_SPILL:
+            spilled = _spilling_kernels(lines, NO_SPILL[src])
+            lines = [l for l in lines if "-Rpass-analysis=kernel-resource-usage" not in l]
+            if r.returncode == 0 and spilled:
+                raise RuntimeError(f"{src}: register spills in {', '.join(spilled)} (their loads complete behind the compiler's back)")
+        err = "\n".join(l for l in lines if "packed-fp32-ops" not in l)
         if r.returncode != 0:
             raise RuntimeError(f"hipcc failed on {src}:\n{err}")
         if verbose and err.strip():

@@ -128,3 +128,21 @@ def test_argument_errors_before_any_launch(L):
     assert L.qfc_rope_qkv(A, 1, 4096, ctypes.byref(sh), 10000.0, A, A, A, s) == 1           # position past the cache
     assert L.qfc_rope_qkv(A, 1, 0, ctypes.byref(sh), 1.0, A, A, A, s) == 1                  # base must exceed 1
     assert L.qfc_rope_qkv(None, 1, 0, ctypes.byref(sh), 10000.0, A, A, A, s) == 1
+
+
+def test_build_refuses_spills_in_kernels_with_hand_placed_loads():
+    """The build parses the compiler's resource-usage remarks of the kernels whose operand loads are
+    asynchronous assembly (a spilled destination register would be saved before its load lands)."""
+    from paper_2505_00232_amd import build
+    pre = "gemm_i8.hip:527:1: remark: "
+    suf = " [-Rpass-analysis=kernel-resource-usage]"
+    def remarks(name, scratch, vspill):
+        return [pre + f"Function Name: {name}" + suf, pre + "    VGPRs: 220" + suf,
+                pre + f"    ScratchSize [bytes/lane]: {scratch}" + suf, pre + "    SGPRs Spill: 0" + suf,
+                pre + f"    VGPRs Spill: {vspill}" + suf]
+    clean = remarks("_ZN3qfc18gemm_i8_dw4_kernelILi4ELi2ELi4ELi0EEEv", 0, 0)
+    other = remarks("_ZN3qfc14gemm_i8_kernelILi128ELi128EEEv", 76, 18)   # not one of the guarded kernels
+    bad = remarks("_ZN3qfc17gemm_i8_dw_kernelILi9ELi4ELi4ELi0ELb1EEEv", 76, 18)
+    frag = build.NO_SPILL["gemm_i8.hip"]
+    assert build._spilling_kernels(clean + other, frag) == []
+    assert build._spilling_kernels(clean + bad + other, frag) == ["_ZN3qfc17gemm_i8_dw_kernelILi9ELi4ELi4ELi0ELb1EEEv"]
