@@ -513,7 +513,8 @@ __global__ __launch_bounds__(256, 2) void gemm_i8_w4_kernel(GemmI8Args a) {
 // of fragment registers; the ring is one stage deeper because a stage must have landed one step
 // earlier).  A wavefront that is alone on its SIMD (launches of at most one workgroup per compute unit)
 // otherwise spends 180 of its ~640 clocks per stage between the barrier and the first MFMA waiting
-// for LDS (cycle counters inside the kernel); measured 7-10 % on such launches, level elsewhere.
+// for LDS (cycle counters inside the kernel); measured 4-6 % on such launches in the steady state,
+// level elsewhere.
 //
 // The weight loads carry no streaming hint: the workgroups of the same weight tile (one per token tile)
 // run side by side on one XCD, and with the lines marked evict-first the later ones miss in L2
