@@ -269,6 +269,32 @@ typedef struct qfc_attn_shape {
 qfc_status_t qfc_rope_qkv(const void *qkv_f16, int32_t S, int32_t pos0, const qfc_attn_shape_t *shape,
                           float rope_base, void *q_out, void *kcache, void *vcache, void *stream);
 
+/* The rotary angles of the first `positions` positions for this shape's head size, evaluated once
+ * (in fp64, like qfc_rope_qkv): table (device, 8-byte aligned, positions * d_head / 2 * 2 floats) gets
+ * table[(pos * d_head / 2 + i) * 2] = cos and [.. + 1] = sin of pos * rope_base^(-2 i / d_head).
+ * Errors as qfc_rope_qkv; QFC_ERR_INVALID_ARG for positions < 1. */
+qfc_status_t qfc_rope_table(const qfc_attn_shape_t *shape, float rope_base, int32_t positions, float *table,
+                            void *stream);
+
+/* Decode step of the QKV layer with the rotary embedding, the layout transformation and the cache
+ * append merged into its kernel (operator fusion, section 3.6): for the shape's `batch` sequences
+ * (= the layer's M token rows, at most 8), each at position pos0,
+ *   qkv = x W^T (optionally rmsnorm(x) first: fusion->norm_gamma, norm_eps, norm_offset; the other
+ *   members of fusion must be null / 0), never stored; queries and keys rotated on the fp32 sums
+ *   with the table's cos and sin and rounded once to binary16; queries to q_out [G, g, d_head],
+ *   keys to row pos0 of kcache, values to column pos0 of vcache (layouts above).
+ * h: a QKV layer with N = (h_q + 2 h_kv) * d_head output channels (query heads, key heads, value
+ * heads), any weight format, not packed in pairs.  rope_table: from qfc_rope_table with at least
+ * pos0 + 1 positions (table_positions says how many it holds).  Same result as qfc_forward followed
+ * by qfc_rope_qkv up to the rounding of the intermediate qkv, in one launch instead of two.
+ * Errors: QFC_ERR_INVALID_ARG (null pointers, pos0 outside the cache or the table, N not matching
+ * the shape, fusion members other than the normalization), QFC_ERR_ALIGNMENT (16 bytes; the table
+ * 8), QFC_ERR_UNSUPPORTED (batch > 8, a layer packed in pairs or in the 8-bit-activation decode
+ * mode, head sizes other than 64, 128, 256). */
+qfc_status_t qfc_forward_qkv_rope(qfc_handle_t h, const void *x_f16, const qfc_fusion_t *fusion,
+                                  const qfc_attn_shape_t *shape, int32_t pos0, const float *rope_table,
+                                  int32_t table_positions, void *q_out, void *kcache, void *vcache, void *stream);
+
 /* Bytes of scratch qfc_attention needs for this shape and S (host pointer). */
 qfc_status_t qfc_attention_workspace_size(const qfc_attn_shape_t *shape, int32_t S, size_t *bytes);
 

@@ -18,7 +18,7 @@ import subprocess
 import numpy as np
 
 from .elementwise import GELU_TANH, SILU, add_residual, embedding, gated_input, gated_input_f32, gated_output, gelu_tanh, norm_weighted_input, rms_scale, rmsnorm, silu  # noqa: F401
-from .attention import attention, rope, rope_qkv_layout  # noqa: F401
+from .attention import attention, rope, rope_qkv_layout, rope_qkv_layout_exact  # noqa: F401
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
 _SRC = os.path.join(_HERE, "qfc_oracle.c")

@@ -29,14 +29,12 @@ def rope(x, pos, base: float) -> np.ndarray:
     return np.concatenate([a * c - b * s, b * c + a * s], axis=-1)
 
 
-def rope_qkv_layout(qkv_f16, pos0: int, h_q: int, h_kv: int, d: int, base: float):
-    """From the QKV projection's output [B, S, (h_q + 2 h_kv) d] (query heads, then key heads, then
-    value heads) to the attention layouts, all rounded once to binary16:
-      q  [B * h_kv, S * g, d], g = h_q / h_kv, row s * g + j = query head kv * g + j at token s, rotated
-      k  [B * h_kv, S, d]      rotated: the rows appended to the K cache at positions pos0 + s
-      v  [B * h_kv, S, d]      as is: appended to the V cache as columns pos0 + s
-    """
-    x = np.asarray(qkv_f16, dtype=np.float16).astype(np.float64)
+def rope_qkv_layout_exact(qkv, pos0: int, h_q: int, h_kv: int, d: int, base: float):
+    """The same transformation on real (fp64) projection outputs [B, S, (h_q + 2 h_kv) d], nothing
+    rounded: what the merged operator (QKV layer + rotary embedding + layout transformation,
+    section 3.6) computes before its single rounding to binary16.  Returns q [B * h_kv, S * g, d],
+    k [B * h_kv, S, d], v [B * h_kv, S, d] in fp64."""
+    x = np.asarray(qkv, dtype=np.float64)
     B, S, W = x.shape
     g = h_q // h_kv
     assert W == (h_q + 2 * h_kv) * d and h_q == g * h_kv
@@ -49,6 +47,18 @@ def rope_qkv_layout(qkv_f16, pos0: int, h_q: int, h_kv: int, d: int, base: float
     q = q.transpose(0, 2, 1, 3, 4).reshape(B * h_kv, S * g, d)
     k = k.transpose(0, 2, 1, 3).reshape(B * h_kv, S, d)
     v = v.transpose(0, 2, 1, 3).reshape(B * h_kv, S, d)
+    return q, k, v
+
+
+def rope_qkv_layout(qkv_f16, pos0: int, h_q: int, h_kv: int, d: int, base: float):
+    """From the QKV projection's output [B, S, (h_q + 2 h_kv) d] (query heads, then key heads, then
+    value heads) to the attention layouts, all rounded once to binary16:
+      q  [B * h_kv, S * g, d], g = h_q / h_kv, row s * g + j = query head kv * g + j at token s, rotated
+      k  [B * h_kv, S, d]      rotated: the rows appended to the K cache at positions pos0 + s
+      v  [B * h_kv, S, d]      as is: appended to the V cache as columns pos0 + s
+    """
+    x = np.asarray(qkv_f16, dtype=np.float16).astype(np.float64)
+    q, k, v = rope_qkv_layout_exact(x, pos0, h_q, h_kv, d, base)
     return q.astype(np.float16), k.astype(np.float16), v.astype(np.float16)
 
 

@@ -22,7 +22,7 @@ QFC_ACT_SILU, QFC_ACT_GELU_TANH = 0, 1
 QFC_PACK_GATED_PAIRS = 1
 
 EXPORTS = ["qfc_packed_size", "qfc_pack_weights", "qfc_unpack_weights", "qfc_workspace_size",
-           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_forward_static", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
+           "qfc_bind_workspace", "qfc_quantize_activations", "qfc_forward", "qfc_forward_fused", "qfc_forward_static", "qfc_rmsnorm", "qfc_rope_qkv", "qfc_rope_table", "qfc_forward_qkv_rope", "qfc_attention_workspace_size", "qfc_attention", "qfc_forward_q8",
            "qfc_forward_acc_i32", "qfc_embedding", "qfc_forward_batch", "qfc_destroy", "qfc_status_string"]
 
 
@@ -83,6 +83,8 @@ def lib() -> ctypes.CDLL:
         L.qfc_rope_qkv.argtypes = [vp, i32, i32, ctypes.POINTER(AttnShape), ctypes.c_float, vp, vp, vp, vp]
         L.qfc_attention_workspace_size.argtypes = [ctypes.POINTER(AttnShape), i32, ctypes.POINTER(sz)]
         L.qfc_attention.argtypes = [vp, vp, vp, i32, i32, ctypes.POINTER(AttnShape), vp, sz, vp, vp]
+        L.qfc_rope_table.argtypes = [ctypes.POINTER(AttnShape), ctypes.c_float, i32, vp, vp]
+        L.qfc_forward_qkv_rope.argtypes = [vp, vp, ctypes.POINTER(Fusion), ctypes.POINTER(AttnShape), i32, vp, i32, vp, vp, vp, vp]
         L.qfc_forward_q8.argtypes = [vp, vp, vp, i32, vp, vp]
         L.qfc_forward_acc_i32.argtypes = [vp, vp, i32, vp, vp]
         L.qfc_embedding.argtypes = [vp, vp, i32, vp, vp]
@@ -265,6 +267,34 @@ def qfc_rope_qkv(qkv: torch.Tensor, pos0: int, shape: AttnShape, rope_base: floa
     S = qkv.shape[1]
     _check(lib().qfc_rope_qkv(_ptr(qkv), S, pos0, ctypes.byref(shape), rope_base, _ptr(q_out), _ptr(kcache),
                               _ptr(vcache), _stream()), "qfc_rope_qkv")
+
+
+def qfc_rope_table(shape: AttnShape, rope_base: float, positions: int, device="cuda") -> torch.Tensor:
+    """cos and sin of the rotary angles of the first `positions` positions: float32 [positions, d_head / 2, 2]."""
+    table = torch.empty((positions, shape.d_head // 2, 2), dtype=torch.float32, device=device)
+    _check(lib().qfc_rope_table(ctypes.byref(shape), rope_base, positions, _ptr(table), _stream()), "qfc_rope_table")
+    return table
+
+
+def qfc_forward_qkv_rope(h, x: torch.Tensor, pos0: int, shape: AttnShape, rope_table: torch.Tensor, q_out: torch.Tensor,
+                         kcache: torch.Tensor, vcache: torch.Tensor, norm_gamma: torch.Tensor | None = None,
+                         norm_eps: float = 0.0, norm_offset: float = 0.0):
+    """Decode step of the QKV layer with rotary embedding, layout transformation and cache append merged in."""
+    N, K = _nk(h)
+    g = shape.h_q // max(shape.h_kv, 1)
+    G = shape.batch * shape.h_kv
+    _want(x, torch.float16, (shape.batch, K), "x")
+    _want(rope_table, torch.float32, (None, shape.d_head // 2, 2), "rope_table")
+    _want(q_out, torch.float16, (G, g, shape.d_head), "q_out")
+    _want(kcache, torch.float16, (G, shape.cache_size, shape.d_head), "kcache")
+    _want(vcache, torch.float16, (G, shape.cache_size // 64, shape.d_head, 64), "vcache")
+    f = None
+    if norm_gamma is not None:
+        _want(norm_gamma, torch.float16, (K,), "norm_gamma")
+        f = Fusion(None, 0, None, 0, norm_gamma.data_ptr(), norm_eps, norm_offset)
+    _check(lib().qfc_forward_qkv_rope(h, _ptr(x), ctypes.byref(f) if f is not None else None, ctypes.byref(shape), pos0,
+                                      _ptr(rope_table), rope_table.shape[0], _ptr(q_out), _ptr(kcache), _ptr(vcache),
+                                      _stream()), "qfc_forward_qkv_rope")
 
 
 def vcache_physical(v_logical: torch.Tensor) -> torch.Tensor:

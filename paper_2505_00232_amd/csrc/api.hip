@@ -332,6 +332,51 @@ qfc_status_t qfc_rope_qkv(const void *qkv_f16, int32_t S, int32_t pos0, const qf
                                       q_out, kcache, vcache, static_cast<hipStream_t>(stream)));
 }
 
+qfc_status_t qfc_rope_table(const qfc_attn_shape_t *a, float rope_base, int32_t positions, float *table, void *stream) {
+    const qfc_status_t s = check_attn_shape(a, 1);
+    if (s != QFC_OK) return s;
+    if (!table || positions < 1 || !(rope_base > 1.0f)) return QFC_ERR_INVALID_ARG;
+    if (reinterpret_cast<uintptr_t>(table) & 7u) return QFC_ERR_ALIGNMENT;
+    return hip_status(launch_rope_table(a->d_head, rope_base, positions, table, static_cast<hipStream_t>(stream)));
+}
+
+qfc_status_t qfc_forward_qkv_rope(qfc_handle_t h, const void *x_f16, const qfc_fusion_t *fusion,
+                                  const qfc_attn_shape_t *a, int32_t pos0, const float *rope_table,
+                                  int32_t table_positions, void *q_out, void *kcache, void *vcache, void *stream) {
+    if (!valid(h)) return QFC_ERR_INVALID_ARG;
+    const qfc_status_t s = check_attn_shape(a, 1);
+    if (s != QFC_OK) return s;
+    if (!x_f16 || !rope_table || !q_out || !kcache || !vcache || pos0 < 0 || pos0 >= a->cache_size || pos0 >= table_positions)
+        return QFC_ERR_INVALID_ARG;
+    if (h->geo.N != (a->h_q + 2 * a->h_kv) * a->d_head) return QFC_ERR_INVALID_ARG;
+    if (!aligned16(x_f16) || !aligned16(q_out) || !aligned16(kcache) || !aligned16(vcache) ||
+        (reinterpret_cast<uintptr_t>(rope_table) & 7u))
+        return QFC_ERR_ALIGNMENT;
+    // decode only: the batch is the layer's M token rows, one new position per sequence
+    if (a->batch > kMaxDecodeM || h->geo.pair_half || h->desc.compute_mode == QFC_COMPUTE_INT8_ACT_DECODE)
+        return QFC_ERR_UNSUPPORTED;
+    Fusion f;
+    if (fusion) {
+        if (fusion->gate || fusion->residual || fusion->gated_output) return QFC_ERR_INVALID_ARG;
+        f.norm_gamma = fusion->norm_gamma;
+        f.norm_eps = fusion->norm_eps;
+        f.norm_offset = fusion->norm_offset;
+        if (f.norm_gamma && (!aligned16(f.norm_gamma) || !(f.norm_eps >= 0.0f))) return QFC_ERR_INVALID_ARG;
+    }
+    RopeOut r;
+    r.d = a->d_head;
+    r.h_q = a->h_q;
+    r.h_kv = a->h_kv;
+    r.C = a->cache_size;
+    r.pos = pos0;
+    r.table = rope_table;
+    r.q = q_out;
+    r.kc = kcache;
+    r.vc = vcache;
+    f.rope = &r;
+    return hip_status(launch_gemv(h->geo, h->packed, x_f16, a->batch, nullptr, f, h->num_cus, static_cast<hipStream_t>(stream)));
+}
+
 static int device_cus() {
     int dev = 0, cus = 0;
     if (hipGetDevice(&dev) != hipSuccess) return 0;

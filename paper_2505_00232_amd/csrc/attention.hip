@@ -77,6 +77,21 @@ __global__ __launch_bounds__(256) void rope_qkv_kernel(const _Float16 *__restric
     dst[i + half] = y1;
 }
 
+// cos and sin of the rotary angles of `positions` positions: table[(pos * d / 2 + i) * 2] = cos, + 1 = sin
+// of pos * base^(-2 i / d), the angle in fp64 as in the kernel above (long contexts keep its low bits).
+__global__ __launch_bounds__(256) void rope_table_kernel(int d, int positions, double log_base, float *__restrict__ table) {
+    const int half = d / 2;
+    const long idx = (long)blockIdx.x * 256 + threadIdx.x;
+    if (idx >= (long)positions * half) return;
+    const int i = (int)(idx % half);
+    const int pos = (int)(idx / half);
+    const double ang = (double)pos * exp(-2.0 * (double)i / (double)d * log_base);
+    double sn, cs;
+    sincos(ang, &sn, &cs);
+    table[2 * idx] = (float)cs;
+    table[2 * idx + 1] = (float)sn;
+}
+
 // ---------------------------------------------------------------- attention over the cache
 struct AttnArgs {
     const _Float16 *q;   // [G, M, D]
@@ -782,6 +797,12 @@ hipError_t launch_rope_qkv(const void *qkv, int B, int S, int h_q, int h_kv, int
     rope_qkv_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(
         static_cast<const _Float16 *>(qkv), B, S, h_q, h_kv, d, C, pos0, log((double)base),
         static_cast<_Float16 *>(q_out), static_cast<_Float16 *>(kc), static_cast<_Float16 *>(vc));
+    return hipGetLastError();
+}
+
+hipError_t launch_rope_table(int d, float base, int positions, float *table, hipStream_t st) {
+    const long total = (long)positions * (d / 2);
+    rope_table_kernel<<<(unsigned)((total + 255) / 256), 256, 0, st>>>(d, positions, log((double)base), table);
     return hipGetLastError();
 }
 

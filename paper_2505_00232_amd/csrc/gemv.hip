@@ -146,6 +146,11 @@ struct GemvArgs {
     int gated_out;           // 1: rows [0, N/2) are the gate, rows [N/2, N) the other branch; y is [M, N/2]
     int paired;              // 1: the layer is packed in pairs (physical row tiles 2 t, 2 t + 1 = the two branches)
     int units_q, units_rem;  // KU = units_q * waves + units_rem
+    // Rotary embedding + layout transformation + cache append in the final reduction (QKV layer):
+    // rope_per = d / 32 (0: off) is the distance, in row tiles, between the two rows of a rotary pair.
+    int rope_per, rope_d, rope_hq, rope_hkv, rope_C, rope_pos;
+    const float *rope_table;
+    _Float16 *rope_q, *rope_kc, *rope_vc;
 };
 
 // LDS view of one wavefront's staged activations: vector (slot * M + m).
@@ -234,8 +239,11 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
     // Gated output: a workgroup owns the two row tiles (t, t + RT / 2) that hold the gate and the
     // other branch of the same 16 output channels.
     // (first row tile in the packed buffer: with the branches' tiles interleaved, the pair (2 b, 2 b + 1))
-    const int rt0 = a.gated_out ? (a.paired ? 2 * blockIdx.x : blockIdx.x) : blockIdx.x * a.row_tiles;
-    const int R = a.gated_out ? 2 : min(a.row_tiles, a.RT - rt0);
+    // Rotary pairs: a workgroup owns the row tiles (t, t + d / 32) of one head, i.e. rows i and i + d / 2.
+    const int rt0 = a.rope_per    ? (int)(blockIdx.x / a.rope_per) * (2 * a.rope_per) + (int)(blockIdx.x % a.rope_per)
+                    : a.gated_out ? (a.paired ? 2 * blockIdx.x : blockIdx.x)
+                                  : blockIdx.x * a.row_tiles;
+    const int R = a.gated_out || a.rope_per ? 2 : min(a.row_tiles, a.RT - rt0);
     const int u0 = wave * a.units_q + min(wave, a.units_rem);
     const int u1 = u0 + a.units_q + (wave < a.units_rem ? 1 : 0);
     u32x4 *lds_x = lds_all + wave * (OCT * M);
@@ -461,6 +469,53 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
             if (rr < R && m < M) red[((wave * 4 + rr) * M + m) * 16 + c] = acc[rr][i];
         }
     __syncthreads();
+    if (a.rope_per) {
+        // Rotary embedding fused with the layout transformation of the query, key and value
+        // projections (section 3.6 of the paper), here in the final reduction of the layer that
+        // produces them: the workgroup holds the fp32 sums of rows i and i + d / 2 of one head for
+        // every token row (= sequence b at position pos); queries and keys are rotated in fp32 and
+        // rounded once, the results go to the query buffer and into the two caches.
+        const int d = a.rope_d, halfd = d / 2, g = a.rope_hq / a.rope_hkv;
+        const int head = (int)(blockIdx.x / a.rope_per);
+        for (int e = threadIdx.x; e < M * 16; e += blockDim.x) {
+            const int cc = e & 15, m = e >> 4;
+            float s0 = 0.0f, s1 = 0.0f;
+            for (int w = 0; w < nwaves; ++w) {
+                s0 += red[((w * 4 + 0) * M + m) * 16 + cc];
+                s1 += red[((w * 4 + 1) * M + m) * 16 + cc];
+            }
+            const int i = (int)(blockIdx.x % a.rope_per) * 16 + cc;  // index inside the first half of the head
+            const int n0 = head * d + i;                             // output channel of s0; s1 is n0 + d / 2
+            if (FMT != kW4G32) {
+                s0 *= a.sw[n0];
+                s1 *= a.sw[n0 + halfd];
+            }
+            if constexpr (PRO == 2) {
+                float tot = 0.0f;
+                for (int w = 0; w < nwaves; ++w) tot += s_ss[w][m];
+                const float rs = 1.0f / sqrtf(tot / (float)a.K + a.norm_eps);
+                s0 *= rs;
+                s1 *= rs;
+            }
+            if (head >= a.rope_hq + a.rope_hkv) {  // value head: column pos of the transposed cache
+                const int kv = head - a.rope_hq - a.rope_hkv;
+                _Float16 *dst = a.rope_vc + (((size_t)(m * a.rope_hkv + kv) * (a.rope_C / 64) + a.rope_pos / 64) * d) * 64 + a.rope_pos % 64;
+                dst[(size_t)i * 64] = (_Float16)s0;
+                dst[(size_t)(i + halfd) * 64] = (_Float16)s1;
+                continue;
+            }
+            const float cs = a.rope_table[((size_t)a.rope_pos * halfd + i) * 2];
+            const float sn = a.rope_table[((size_t)a.rope_pos * halfd + i) * 2 + 1];
+            _Float16 *dst;
+            if (head < a.rope_hq)
+                dst = a.rope_q + ((size_t)(m * a.rope_hkv + head / g) * g + head % g) * d;
+            else
+                dst = a.rope_kc + ((size_t)(m * a.rope_hkv + head - a.rope_hq) * a.rope_C + a.rope_pos) * d;
+            dst[i] = (_Float16)(s0 * cs - s1 * sn);
+            dst[i + halfd] = (_Float16)(s1 * cs + s0 * sn);
+        }
+        return;
+    }
     if (a.gated_out) {
         // y[m, n] = fp16(act(gate) * other), both fp32 sums of this workgroup (operator fusion,
         // section 3.6 of the paper: the element-wise operators of the two branches are merged
@@ -513,14 +568,14 @@ __global__ __launch_bounds__(BIG ? 1024 : PRO && M > 4 ? 256 : 512) void gemv_ke
 template <int M, int PRO>
 hipError_t launch_m(const Geometry &g, const GemvArgs &a, const GemvPlan &p, hipStream_t st) {
     const int waves = p.waves;
-    const dim3 grid((unsigned)(a.gated_out ? g.RT / 2 : (g.RT + a.row_tiles - 1) / a.row_tiles));
+    const dim3 grid((unsigned)(a.gated_out || a.rope_per ? g.RT / 2 : (g.RT + a.row_tiles - 1) / a.row_tiles));
     const dim3 block((unsigned)(waves * 64));
     const int oct = g.fmt == kW8C || p.half ? 64 : 128;
     size_t lds = (size_t)waves * oct * M * 16;
     const size_t red = (size_t)waves * 4 * M * 16 * sizeof(float);
     if (red > lds) lds = red;
     // long-lived wavefronts (>= 3 items each) get the double-buffered variant
-    const int items = ((p.units + waves - 1) / waves) * (a.gated_out ? 2 : a.row_tiles);
+    const int items = ((p.units + waves - 1) / waves) * (a.gated_out || a.rope_per ? 2 : a.row_tiles);
     if constexpr (PRO == 0 && M > 4) {
         if (p.half && p.copy) {
             if (g.fmt == kW4C)
@@ -608,6 +663,24 @@ hipError_t launch_gemv(const Geometry &g, const void *packed, const void *x, int
     a.paired = g.pair_half ? 1 : 0;
     a.rt_step = f.gated_output && !a.paired ? g.RT / 2 : 1;
     a.gated_out = f.gated_output ? 1 : 0;
+    a.rope_per = 0;
+    a.rope_d = a.rope_hq = a.rope_hkv = a.rope_C = a.rope_pos = 0;
+    a.rope_table = nullptr;
+    a.rope_q = a.rope_kc = a.rope_vc = nullptr;
+    if (f.rope) {
+        const RopeOut &r = *f.rope;
+        a.rope_per = r.d / 32;
+        a.rt_step = a.rope_per;
+        a.rope_d = r.d;
+        a.rope_hq = r.h_q;
+        a.rope_hkv = r.h_kv;
+        a.rope_C = r.C;
+        a.rope_pos = r.pos;
+        a.rope_table = r.table;
+        a.rope_q = static_cast<_Float16 *>(r.q);
+        a.rope_kc = static_cast<_Float16 *>(r.kc);
+        a.rope_vc = static_cast<_Float16 *>(r.vc);
+    }
     a.units_q = p.units / p.waves;
     a.units_rem = p.units % p.waves;
     a.norm_eps = f.norm_eps;

@@ -278,7 +278,16 @@ __device__ __forceinline__ void staged_residual4(const char *region, int off, fl
 }
 
 // Element-wise parts fused with the layer (null pointer = absent), see qfc_fusion_t.
+// Rotary embedding, QKV layout transformation and KV-cache append merged into the decode kernel of
+// the QKV layer (the M token rows are M sequences at the same position `pos`).
+struct RopeOut {
+    int d = 0, h_q = 0, h_kv = 0, C = 0, pos = 0;
+    const float *table = nullptr;  // [positions][d / 2][2]: cos, sin of pos * base^(-2 i / d)
+    void *q = nullptr, *kc = nullptr, *vc = nullptr;  // binary16, layouts of the attention operators
+};
+
 struct Fusion {
+    const RopeOut *rope = nullptr;   // decode only; y is not written
     const void *gate = nullptr;      // binary16 [M, K]
     int activation = 0;              // QFC_ACT_*
     const void *residual = nullptr;  // binary16 [M, N]
@@ -312,6 +321,8 @@ constexpr int kPrefillMaxChunks = 8;  // chunks a block's walk is cut into at mo
 // Bytes of workspace the many-query-rows path needs for G groups of M query rows of d values.
 size_t attn_prefill_workspace(int G, int M, int d, int num_cus);
 int attn_splits(int G, int n_ctx, int num_cus);
+// cos and sin of pos * base^(-2 i / d) for pos < positions, i < d / 2, evaluated in fp64: [positions][d / 2][2] floats
+hipError_t launch_rope_table(int d, float base, int positions, float *table, hipStream_t st);
 hipError_t launch_rope_qkv(const void *qkv, int B, int S, int h_q, int h_kv, int d, int C, int pos0, float base,
                            void *q_out, void *kc, void *vc, hipStream_t st);
 hipError_t launch_attention(const void *q, const void *kc, const void *vc, int G, int S, int g, int d, int C,

@@ -1325,6 +1325,102 @@ def test_rope_then_attention_decode_step():
     assert out.reshape(B, h_q * d).shape == (B, h_q * d)
 
 
+@pytest.mark.parametrize("fmt", ["w8c", "w4g32", "w4c"])
+@pytest.mark.parametrize("B,h_q,h_kv,d,C,pos0,K,norm", [(1, 4, 2, 64, 64, 0, 128, False), (2, 8, 2, 128, 128, 77, 1152, True),
+                                                         (1, 32, 8, 128, 8192, 8191, 4096, True), (8, 8, 4, 256, 192, 130, 2304, False),
+                                                         (3, 2, 1, 128, 131072, 131071, 256, False)])
+def test_qkv_layer_with_rotary_embedding_merged(fmt, B, h_q, h_kv, d, C, pos0, K, norm):
+    """QKV layer + rotary embedding + layout transformation + cache append in one decode launch against
+    the oracle's pipeline on the unrounded projection outputs, and against the two-launch route."""
+    print(f"qkv+rope {fmt} B={B} h_q={h_q} h_kv={h_kv} d={d} C={C} pos0={pos0} K={K} norm={norm}", flush=True)
+    base = 500000.0 if d == 128 else 10000.0
+    N = (h_q + 2 * h_kv) * d
+    G, g = B * h_kv, h_q // h_kv
+    fc = synth.FC("qkv", K, N, fmt)
+    wq, s = synth.weights(3950, B, d, fc)
+    x = synth.activations(3950, B, d, B, K)
+    gamma = (1.0 + 0.1 * synth.activations(3951, B, d, 1, K)[0].astype(np.float32)).astype(np.float16)
+    layer = _layer(wq, s, fmt)
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+    table = binding.qfc_rope_table(shape, base, pos0 + 1)
+    # the table is the fp64 cosine and sine, rounded to binary32
+    i = np.arange(d // 2, dtype=np.float64)
+    ang = float(pos0) * base ** (-2.0 * i / d)
+    t = table.cpu().numpy()
+    assert np.allclose(t[pos0, :, 0], np.cos(ang), rtol=0, atol=2.0 ** -23) and np.allclose(t[pos0, :, 1], np.sin(ang), rtol=0, atol=2.0 ** -23)
+    assert np.array_equal(t[0, :, 0], np.ones(d // 2, dtype=np.float32)) and not t[0, :, 1].any()
+    xd = torch.from_numpy(x).to(DEV)
+    gd = torch.from_numpy(gamma).to(DEV)
+    q_out = torch.zeros((G, g, d), dtype=torch.float16, device=DEV)
+    kc = torch.full((G, C, d), 3.0, dtype=torch.float16, device=DEV)
+    vc = torch.full((G, C // 64, d, 64), 5.0, dtype=torch.float16, device=DEV)
+    kw = dict(norm_gamma=gd, norm_eps=1e-5) if norm else {}
+    binding.qfc_forward_qkv_rope(layer.handle, xd, pos0, shape, table, q_out, kc, vc, **kw)
+    torch.cuda.synchronize()
+    # oracle: the real projection (with the merged normalization in its factorised form, as for the
+    # plain layer: rs * fc(fp16(x * weight))), then the real rotation; one rounding at the end
+    if norm:
+        y_ref = oracle.rms_scale(x, 1e-5)[:, None] * oracle.fc_weight_only(oracle.norm_weighted_input(x, gamma, 0.0), wq, s, _group(fmt))
+    else:
+        y_ref = oracle.fc_weight_only(x, wq, s, _group(fmt))
+    q_ref, k_ref, v_ref = oracle.rope_qkv_layout_exact(y_ref.reshape(B, 1, N), pos0, h_q, h_kv, d, base)
+    kcn, vcn = kc.cpu().numpy(), binding.vcache_logical(vc).cpu().numpy()
+    got = np.concatenate([q_out.cpu().numpy().reshape(B, h_kv, g * d), kcn[:, pos0].reshape(B, h_kv, d),
+                          vcn[:, :, pos0].reshape(B, h_kv, d)], axis=2).reshape(B, -1)
+    ref = np.concatenate([q_ref.reshape(B, h_kv, g * d), k_ref.reshape(B, h_kv, d), v_ref.reshape(B, h_kv, d)], axis=2).reshape(B, -1)
+    assert _E(got, ref) <= TOL
+    # nothing but position pos0 of the caches changed
+    kcn[:, pos0] = 3.0
+    vcn[:, :, pos0] = 5.0
+    assert np.all(kcn == 3.0) and np.all(vcn == 5.0)
+    # the two-launch route (layer, then the rotary kernel) rounds the projection to binary16 in between
+    y = torch.empty((B, N), dtype=torch.float16, device=DEV)
+    if norm:
+        binding.qfc_forward_fused(layer.handle, xd, y, norm_gamma=gd, norm_eps=1e-5)
+    else:
+        binding.qfc_forward(layer.handle, xd, y)
+    q2 = torch.zeros_like(q_out)
+    kc2 = torch.full_like(kc, 3.0)
+    vc2 = torch.full_like(vc, 5.0)
+    binding.qfc_rope_qkv(y.view(B, 1, N), pos0, shape, base, q2, kc2, vc2)
+    torch.cuda.synchronize()
+    got2 = np.concatenate([q2.cpu().numpy().reshape(B, h_kv, g * d), kc2.cpu().numpy()[:, pos0].reshape(B, h_kv, d),
+                           binding.vcache_logical(vc2).cpu().numpy()[:, :, pos0].reshape(B, h_kv, d)], axis=2).reshape(B, -1)
+    assert _E(got, got2.astype(np.float64)) <= 2 * TOL
+    # values are not rotated: the same sums, the same single rounding, the same bits
+    assert np.array_equal(binding.vcache_logical(vc).cpu().numpy()[:, :, pos0].view(np.uint16),
+                          binding.vcache_logical(vc2).cpu().numpy()[:, :, pos0].view(np.uint16))
+    layer.close()
+
+
+def test_qkv_layer_with_rotary_embedding_rejects_what_it_cannot_do():
+    B, h_q, h_kv, d, C = 1, 4, 2, 64, 64
+    N, K = (h_q + 2 * h_kv) * d, 128
+    fc = synth.FC("qkv", K, N, "w8c")
+    wq, s = synth.weights(3960, 0, 0, fc)
+    layer = _layer(wq, s, "w8c")
+    shape = _attn_shape(B, h_q, h_kv, d, C)
+    table = binding.qfc_rope_table(shape, 10000.0, 8)
+    x = torch.zeros((B, K), dtype=torch.float16, device=DEV)
+    q = torch.zeros((B * h_kv, h_q // h_kv, d), dtype=torch.float16, device=DEV)
+    kc = torch.zeros((B * h_kv, C, d), dtype=torch.float16, device=DEV)
+    vc = torch.zeros((B * h_kv, C // 64, d, 64), dtype=torch.float16, device=DEV)
+    for pos in (-1, 8, 64):  # before the cache, beyond the table, beyond the cache
+        with pytest.raises(binding.QfcError) as e:
+            binding.qfc_forward_qkv_rope(layer.handle, x, pos, shape, table, q, kc, vc)
+        assert e.value.code == binding.QFC_ERR_INVALID_ARG
+    wrong = _attn_shape(B, h_q + 2, h_kv, d, C)  # N does not match the shape
+    with pytest.raises((binding.QfcError, ValueError)):
+        binding.qfc_forward_qkv_rope(layer.handle, x, 0, wrong, table,
+                                     torch.zeros((B * h_kv, (h_q + 2) // h_kv, d), dtype=torch.float16, device=DEV), kc, vc)
+    layer.close()
+    l8 = _layer(wq, s, "w8c", mode=binding.QFC_COMPUTE_INT8_ACT_DECODE)
+    with pytest.raises(binding.QfcError) as e:
+        binding.qfc_forward_qkv_rope(l8.handle, x, 0, shape, table, q, kc, vc)
+    assert e.value.code == binding.QFC_ERR_UNSUPPORTED
+    l8.close()
+
+
 # ------------------------------------------------------------------ one decoder layer, decode step, every operator chained
 def test_decoder_layer_decode_step_chain():
     """rmsnorm -> QKV layer -> rotary + layouts + cache append -> attention -> O layer + residual ->
@@ -1395,6 +1491,23 @@ def test_decoder_layer_decode_step_chain():
     h2_ref = oracle.add_residual(oracle.fc_weight_only(N(a), wq_dn, s_dn, 32), N(h1))
     assert err(N(h2), h2_ref) <= TOL
     assert np.all(np.isfinite(N(h2)))
+
+    # The same layer in six launches: both normalizations merged into the layers that follow them, the
+    # rotary kernel merged into the QKV layer.  Fewer roundings on the way, so the end of the layer
+    # is compared with the eight-launch result (each differs from the real chain by its own roundings).
+    table = binding.qfc_rope_table(shape, 10000.0, pos0 + 1)
+    kc6, vc6 = T(K0), binding.vcache_physical(T(V0))
+    q6, att6, h16, a6, h26 = E(G, g, d), E(G, g, d), E(B, hidden), E(B, ffn), E(B, hidden)
+    binding.qfc_forward_qkv_rope(l_qkv.handle, h_d, pos0, shape, table, q6, kc6, vc6, norm_gamma=g1_d, norm_eps=eps)
+    binding.qfc_attention(q6, kc6, vc6, 1, pos0 + 1, shape, ws, att6)
+    binding.qfc_forward_fused(l_o.handle, att6.view(B, h_q * d), h16, residual=h_d)
+    binding.qfc_forward_fused(l_gu.handle, h16, a6, activation=binding.QFC_ACT_SILU, gated_output=True, norm_gamma=g2_d, norm_eps=eps)
+    binding.qfc_forward_fused(l_dn.handle, a6, h26, residual=h16)
+    torch.cuda.synchronize()
+    assert err(N(q6).reshape(G * g, d), N(q).reshape(G * g, d).astype(np.float64)) <= 2 * TOL
+    assert err(N(kc6)[:, pos0], N(kc)[:, pos0].astype(np.float64)) <= 2 * TOL
+    assert err(N(att6).reshape(G * g, d), N(att).reshape(G * g, d).astype(np.float64)) <= 2 * TOL
+    assert err(N(h26), N(h2).astype(np.float64)) <= 4 * TOL  # (five stages, each within its own bound of the real chain)
     for l in (l_qkv, l_o, l_gu, l_dn):
         l.close()
 

@@ -492,6 +492,31 @@ def test_rope_qkv_layout_places_heads():
                     assert np.allclose(got, oracle.rope(src_q, 5 + s, 10000.0), rtol=2e-3, atol=1e-3)
 
 
+def test_rope_qkv_layout_exact_places_heads_without_rounding():
+    """The unrounded form (what the merged QKV + rotary operator computes before its one rounding): every
+    output element is the rotation of the right source pair, to the last bit of fp64, for inputs that
+    binary16 cannot hold."""
+    B, S, h_q, h_kv, d = 2, 1, 4, 2, 8
+    W = (h_q + 2 * h_kv) * d
+    rng = np.random.default_rng(12)
+    x = rng.standard_normal((B, S, W)) * (1.0 + 2.0 ** -30)
+    q, k, v = oracle.rope_qkv_layout_exact(x, 9, h_q, h_kv, d, 500000.0)
+    assert q.dtype == np.float64 and q.shape == (B * h_kv, S * (h_q // h_kv), d) and k.shape == (B * h_kv, S, d)
+    g = h_q // h_kv
+    for b in range(B):
+        for kv in range(h_kv):
+            assert np.array_equal(v[b * h_kv + kv, 0], x[b, 0, (h_q + h_kv + kv) * d: (h_q + h_kv + kv + 1) * d])
+            assert np.array_equal(k[b * h_kv + kv, 0], oracle.rope(x[b, 0, (h_q + kv) * d: (h_q + kv + 1) * d], 9, 500000.0))
+            for j in range(g):
+                head = kv * g + j
+                assert np.array_equal(q[b * h_kv + kv, j], oracle.rope(x[b, 0, head * d: (head + 1) * d], 9, 500000.0))
+    # rounding its outputs gives the binary16 form when the inputs are binary16
+    xf = x.astype(np.float16)
+    qe, ke, ve = oracle.rope_qkv_layout_exact(xf.astype(np.float64), 9, h_q, h_kv, d, 500000.0)
+    qr, kr, vr = oracle.rope_qkv_layout(xf, 9, h_q, h_kv, d, 500000.0)
+    assert np.array_equal(qe.astype(np.float16), qr) and np.array_equal(ke.astype(np.float16), kr) and np.array_equal(ve.astype(np.float16), vr)
+
+
 def test_attention_hand_case_library_routine_and_special_cases():
     c = _golden()["attention"]
     q = np.array([[[2.0, 0.0]]], dtype=np.float16)
